@@ -1,0 +1,311 @@
+"""Pins for the CPU oracle: each test derives its expected value from the paper's equations,
+from brute force, from float64 / exact rational arithmetic or from a library routine --
+never from the oracle itself.  All of them run without a GPU."""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import (bf16_bits_from_f32, bf16_bits_to_f32, brute_topk, load_golden, mag_key,
+                     round_fraction_to_f32)
+
+
+def f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+# ---------------------------------------------------------------- hand-worked examples (Eq. 2, 3, 5)
+@pytest.mark.parametrize("name", ["e1_step0.txt", "e2_step1.txt", "e3_lr.txt"])
+def test_hand_worked_examples(golden_dir, name):
+    g = load_golden(os.path.join(golden_dir, name))
+    mem = [f32(g["mem_0"]), f32(g["mem_1"])]
+    grad = [f32(g["grad_0"]), f32(g["grad_1"])]
+    idx, red = oracle.step(mem, grad, g["k"], g["beta"], g["lr"], g["step"])
+    assert idx.tolist() == g["idx"].astype(int).tolist()
+    assert red.tolist() == g["reduced"].tolist()
+    assert mem[0].tolist() == g["mem_0_out"].tolist()
+    assert mem[1].tolist() == g["mem_1_out"].tolist()
+
+
+def test_hand_worked_example_beta_one(golden_dir):
+    g = load_golden(os.path.join(golden_dir, "e1_step0.txt"))
+    mem = [f32(g["mem_0"]), f32(g["mem_1"])]
+    grad = [f32(g["grad_0"]), f32(g["grad_1"])]
+    idx, red = oracle.step(mem, grad, g["k"], 1.0, g["lr"], g["step"])
+    assert idx.tolist() == [1, 4] and red.tolist() == [-7.0, -5.0]
+    assert mem[0].tolist() == g["mem_0_out_beta1"].tolist()
+    assert mem[1].tolist() == g["mem_1_out_beta1"].tolist()
+
+
+def test_two_examples_chain(golden_dir):
+    """Running e1 then e2 on carried memory gives e2's result (memory is the only state)."""
+    g1 = load_golden(os.path.join(golden_dir, "e1_step0.txt"))
+    g2 = load_golden(os.path.join(golden_dir, "e2_step1.txt"))
+    mem = [f32(g1["mem_0"]), f32(g1["mem_1"])]
+    oracle.step(mem, [f32(g1["grad_0"]), f32(g1["grad_1"])], 2, 0.5, 1.0, 0)
+    idx, red = oracle.step(mem, [f32(g2["grad_0"]), f32(g2["grad_1"])], 2, 0.5, 1.0, 1)
+    assert idx.tolist() == [3, 4] and red.tolist() == [3.25, 3.0]
+    assert mem[0].tolist() == g2["mem_0_out"].tolist() and mem[1].tolist() == g2["mem_1_out"].tolist()
+
+
+# ---------------------------------------------------------------- top-k index set (Eq. 2)
+def _adversarial_vectors(rng):
+    yield f32([0.0])
+    yield f32([-0.0, 0.0, -0.0, 0.0])
+    yield f32([1.0] * 17)
+    yield f32([1.0, -1.0] * 9)
+    yield f32([2.0, 1.0] * 8 + [2.0])
+    yield f32([0.0] * 10 + [1e-45, -1e-45] + [0.0] * 5)              # denormals beat zeros
+    yield f32([np.inf, -np.inf, 3.0e38, 1.0, np.nan, -2.0])           # non-finite: order by bit pattern
+    for n in (1, 2, 3, 7, 8, 31, 64):
+        yield f32(rng.choice([-2.0, -1.0, -0.5, 0.0, 0.5, 1.0, 2.0], size=n))   # heavy ties
+        yield f32(rng.standard_normal(n))
+        yield f32(rng.standard_normal(n) * 10.0 ** rng.integers(-30, 30, size=n))  # wide exponent range
+
+
+def test_topk_matches_brute_force_all_k():
+    rng = np.random.default_rng(20201)
+    for x in _adversarial_vectors(rng):
+        for k in range(0, x.size + 1):
+            want = brute_topk(x, k)
+            assert oracle.topk_sort(x, k).tolist() == want.tolist(), (x, k)
+            assert oracle.topk_select(x, k).tolist() == want.tolist(), (x, k)
+
+
+def test_topk_select_matches_library_argsort():
+    """Against NumPy's stable argsort of -|x| (a different routine from the oracle's)."""
+    rng = np.random.default_rng(7)
+    for n, k in ((1000, 10), (65_537, 655), (200_000, 1786), (200_000, 200_000), (200_000, 1)):
+        x = f32(rng.standard_normal(n) * 1e-3)
+        x[rng.integers(0, n, size=n // 50)] = x[0]          # plant equal magnitudes
+        x[rng.integers(0, n, size=n // 50)] = -x[0]
+        want = np.sort(np.argsort(-np.abs(x.astype(np.float64)), kind="stable")[:k])
+        got = oracle.topk_select(x, k)
+        assert np.array_equal(got, want.astype(np.int32))
+        if n <= 70_000:
+            assert np.array_equal(oracle.topk_sort(x, k), got)
+
+
+def test_topk_tie_straddling_cut_takes_lowest_positions():
+    x = f32([5, 3, 3, 3, 3, 1])
+    assert oracle.topk_select(x, 3).tolist() == [0, 1, 2]
+    x = f32([1, -3, 3, 5, -3, 3])
+    assert oracle.topk_select(x, 3).tolist() == [1, 2, 3]
+
+
+def test_topk_energy_is_maximal_over_all_subsets():
+    """Top-k keeps the most energy of any k-subset (contraction property, Sec. 3 / Lemma 1)."""
+    rng = np.random.default_rng(3)
+    x = f32(rng.standard_normal(9))
+    for k in (1, 3, 5):
+        sel = oracle.topk_select(x, k)
+        best = max(sum(float(x[j]) ** 2 for j in c) for c in itertools.combinations(range(9), k))
+        assert sum(float(x[j]) ** 2 for j in sel) == pytest.approx(best, rel=1e-12)
+
+
+def test_topk_contraction_no_worse_than_random_k():
+    rng = np.random.default_rng(4)
+    x = f32(rng.standard_normal(50_000))
+    k = 500
+    sel = oracle.topk_select(x, k)
+    e_sel = float(np.sum(x[sel].astype(np.float64) ** 2))
+    e_all = float(np.sum(x.astype(np.float64) ** 2))
+    assert e_all - e_sel <= (1.0 - k / x.size) * e_all
+
+
+# ---------------------------------------------------------------- accumulate (Alg. 1 line 6)
+def test_accumulate_is_single_rounding_of_exact_value():
+    rng = np.random.default_rng(11)
+    m = f32(rng.standard_normal(300))
+    g = f32(rng.standard_normal(300) * 3.0)
+    lr = np.float32(0.1)
+    acc = oracle.accumulate(m, g, float(lr))
+    two_roundings_differ = 0
+    for j in range(m.size):
+        exact = Fraction(float(m[j])) + Fraction(float(lr)) * Fraction(float(g[j]))
+        assert acc[j] == round_fraction_to_f32(exact), j
+        two_roundings_differ += acc[j] != np.float32(np.float32(lr * g[j]) + m[j])
+    assert two_roundings_differ > 0      # the sample does tell fused from unfused evaluation
+
+
+def test_accumulate_lr_one_is_plain_sum_and_zero_memory_is_scaling():
+    rng = np.random.default_rng(12)
+    m, g = f32(rng.standard_normal(1000)), f32(rng.standard_normal(1000))
+    assert np.array_equal(oracle.accumulate(m, g, 1.0), m + g)
+    z = np.zeros(1000, np.float32)
+    assert np.array_equal(oracle.accumulate(z, g, 0.25), g * np.float32(0.25))
+
+
+def test_accumulate_bf16_gradients_widen_exactly():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(13)
+    g32 = f32(rng.standard_normal(4096) * 1e-3)
+    tb = torch.from_numpy(g32).to(torch.bfloat16)
+    bits = tb.view(torch.int16).numpy().view(np.uint16).copy()
+    assert np.array_equal(bits, bf16_bits_from_f32(g32))               # helper agrees with the library's rounding
+    widened = tb.to(torch.float32).numpy()
+    assert np.array_equal(widened, bf16_bits_to_f32(bits))
+    m = f32(rng.standard_normal(4096) * 1e-3)
+    assert np.array_equal(oracle.accumulate(m, bits, 0.5), oracle.accumulate(m, widened, 0.5))
+
+
+# ---------------------------------------------------------------- whole step: closed forms and invariants
+def _random_problem(rng, n, numel, scale=1e-3, mem_scale=1e-3):
+    shared = rng.standard_normal(numel)
+    grad = [f32(scale * (shared + 0.5 * rng.standard_normal(numel))) for _ in range(n)]
+    mem = [f32(mem_scale * rng.standard_normal(numel)) for _ in range(n)]
+    return mem, grad
+
+
+def test_step_against_float64_closed_form():
+    """Everything recomputed in float64 from Eq. 2, 3, 5 with NumPy; the oracle's binary32
+    results must agree to rounding, and its index set must be a valid top-k of the float64
+    leader vector up to a 1-ulp tie."""
+    rng = np.random.default_rng(21)
+    n, numel, k, beta, lr, step = 5, 20_000, 200, 0.3, 0.1, 7
+    mem, grad = _random_problem(rng, n, numel)
+    mem0 = [m.copy() for m in mem]
+    idx, red = oracle.step(mem, grad, k, beta, lr, step)
+    lr64, beta64 = float(np.float32(lr)), float(np.float32(beta))
+    acc = [mem0[i].astype(np.float64) + lr64 * grad[i].astype(np.float64) for i in range(n)]
+    leader = step % n
+    assert leader == 2
+    mag = np.abs(acc[leader])
+    assert idx.size == k and np.all(np.diff(idx) > 0)
+    rest = np.setdiff1d(np.arange(numel), idx)
+    assert mag[idx].min() >= mag[rest].max() * (1 - 2.0 ** -22)
+    want_red = sum(a[idx] for a in acc)
+    assert np.allclose(red, want_red, rtol=1e-6, atol=1e-6 * np.abs(want_red).max())
+    for i in range(n):
+        m64 = mem0[i].astype(np.float64)
+        resid = acc[i].copy()
+        resid[idx] = 0.0
+        want = (1 - beta64) * m64 + beta64 * resid                   # Eq. 5 as printed
+        other = m64 + beta64 * (lr64 * grad[i].astype(np.float64) - (acc[i] - resid))   # m + beta (grad - g)
+        assert np.allclose(want, other, rtol=0, atol=1e-15)
+        assert np.allclose(mem[i], want, rtol=1e-6, atol=1e-6 * np.abs(want).max())
+        # selected entries keep (1 - beta) of their old memory: not zero
+        assert np.allclose(mem[i][idx], (1 - beta64) * m64[idx], rtol=1e-6, atol=1e-12)
+        assert np.count_nonzero(mem[i][idx]) == k
+
+
+def test_leader_follows_step_mod_n():
+    """The index set at step t is the plain top-k of learner (t mod n)'s own vector (Remark 1),
+    and of nobody else's."""
+    rng = np.random.default_rng(22)
+    n, numel, k = 4, 4096, 40
+    for step in range(0, 9):
+        mem, grad = _random_problem(rng, n, numel)
+        grad = [f32(rng.standard_normal(numel)) for _ in range(n)]     # independent: sets differ
+        accs = [oracle.accumulate(mem[i], grad[i], 0.5) for i in range(n)]
+        idx, _ = oracle.step([m.copy() for m in mem], grad, k, 0.5, 0.5, step)
+        for i in range(n):
+            same = np.array_equal(idx, brute_topk(accs[i], k))
+            assert same == (i == step % n)
+
+
+def test_reduction_commutes_with_sparsification():
+    """Eq. 1: sparsify-then-sum equals sum-then-sparsify; with the same order of additions the
+    two are the same binary32 numbers."""
+    rng = np.random.default_rng(23)
+    n, numel, k = 6, 5000, 77
+    mem, grad = _random_problem(rng, n, numel)
+    accs = [oracle.accumulate(mem[i], grad[i], 0.1) for i in range(n)]
+    dense = accs[0].copy()
+    for i in range(1, n):
+        dense = dense + accs[i]
+    idx, red = oracle.step(mem, grad, k, 0.2, 0.1, 3)
+    assert np.array_equal(red, dense[idx])
+
+
+def test_beta_one_is_plain_error_feedback():
+    rng = np.random.default_rng(24)
+    n, numel, k = 3, 3000, 30
+    mem, grad = _random_problem(rng, n, numel)
+    accs = [oracle.accumulate(mem[i], grad[i], 0.1) for i in range(n)]
+    idx, red = oracle.step(mem, grad, k, 1.0, 0.1, 1)
+    total = np.zeros(k, np.float32)
+    for i in range(n):
+        assert np.all(mem[i][idx] == 0.0)
+        sent = np.zeros(numel, np.float32)
+        sent[idx] = accs[i][idx]
+        assert np.array_equal(mem[i] + sent, accs[i])                  # nothing lost: memory + sent = x
+    assert np.array_equal(red, oracle.reduce([a[idx] for a in accs]))
+
+
+def test_residual_energy_identity():
+    """||x - CLT(x)||^2 = ||x||^2 - sum of squares of the kept values (used in Lemma 1)."""
+    rng = np.random.default_rng(25)
+    n, numel, k = 3, 3000, 50
+    mem, grad = _random_problem(rng, n, numel)
+    accs = [oracle.accumulate(mem[i], grad[i], 1.0).astype(np.float64) for i in range(n)]
+    idx, _ = oracle.step(mem, grad, k, 1.0, 1.0, 0)
+    for i in range(n):
+        lhs = float(np.sum(mem[i].astype(np.float64) ** 2))           # beta = 1: memory is the residual
+        rhs = float(np.sum(accs[i] ** 2) - np.sum(accs[i][idx] ** 2))
+        assert lhs == pytest.approx(rhs, rel=1e-9)
+
+
+def test_memory_telescopes_over_steps():
+    """Summing Eq. 5 over iterations: mean_i m_i^T = beta * sum_t (mean_i lr grad_i^t - g^t / n),
+    the identity behind theta^t - v^t = (alpha / beta) mean memory in Appendix C."""
+    rng = np.random.default_rng(26)
+    n, numel, k, beta, lr, T = 4, 2048, 20, 0.25, 0.5, 9
+    mem = [np.zeros(numel, np.float32) for _ in range(n)]
+    acc64 = np.zeros(numel)
+    for t in range(T):
+        _, grad = _random_problem(rng, n, numel)
+        idx, red = oracle.step(mem, grad, k, beta, lr, t)
+        sent = np.zeros(numel)
+        sent[idx] = red.astype(np.float64)
+        acc64 += float(np.float32(lr)) * np.mean([g.astype(np.float64) for g in grad], axis=0) - sent / n
+    mean_mem = np.mean([m.astype(np.float64) for m in mem], axis=0)
+    assert np.allclose(mean_mem, float(np.float32(beta)) * acc64, rtol=0, atol=5e-6 * np.abs(acc64).max())
+
+
+def test_per_tensor_index_sets():
+    """Per-layer mode: every segment gets its own top-k of the same leader, positions are
+    reported in the whole vector; equals running the whole-vector step on each slice."""
+    rng = np.random.default_rng(27)
+    n = 3
+    sizes = [1, 64, 5, 1000, 333, 2]
+    ks = [1, 1, 5, 10, 4, 0]
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    numel = int(offsets[-1])
+    mem, grad = _random_problem(rng, n, numel)
+    mem_ref = [m.copy() for m in mem]
+    idx, red = oracle.step_layers(mem, grad, offsets, ks, 0.5, 0.1, 4)
+    pos = 0
+    for s, (size, k) in enumerate(zip(sizes, ks)):
+        a, b = int(offsets[s]), int(offsets[s + 1])
+        sub_mem = [m[a:b].copy() for m in mem_ref]
+        sub_idx, sub_red = oracle.step(sub_mem, [f32(g[a:b]) for g in grad], k, 0.5, 0.1, 4)
+        leader_acc = oracle.accumulate(f32(mem_ref[1][a:b]), f32(grad[1][a:b]), 0.1)   # 4 mod 3 = 1
+        assert np.array_equal(sub_idx, brute_topk(leader_acc, k))
+        assert np.array_equal(idx[pos:pos + k], sub_idx + a)
+        assert np.array_equal(red[pos:pos + k], sub_red)
+        for i in range(n):
+            assert np.array_equal(mem[i][a:b], sub_mem[i])
+        pos += k
+    assert pos == idx.size
+
+
+def test_degenerate_sizes():
+    z = [np.zeros(16, np.float32) for _ in range(2)]
+    g = [np.zeros(16, np.float32) for _ in range(2)]
+    idx, red = oracle.step(z, g, 4, 0.1, 0.1, 0)                       # all zero: lowest positions
+    assert idx.tolist() == [0, 1, 2, 3] and red.tolist() == [0, 0, 0, 0]
+    idx, red = oracle.step(z, g, 0, 0.1, 0.1, 0)                       # k = 0: nothing selected
+    assert idx.size == 0 and red.size == 0
+    m = [f32([1, 2, 3]), f32([4, 5, 6])]
+    g = [f32([1, 1, 1]), f32([2, 2, 2])]
+    idx, red = oracle.step(m, g, 3, 0.5, 1.0, 1)                       # k = numel: everything selected
+    assert idx.tolist() == [0, 1, 2] and red.tolist() == [8, 10, 12]
+    assert m[0].tolist() == [0.5, 1.0, 1.5] and m[1].tolist() == [2.0, 2.5, 3.0]
+    with pytest.raises(ValueError):
+        oracle.step(m, g, 4, 0.5, 1.0, 0)                              # k > numel
+    with pytest.raises(ValueError):
+        oracle.step(m, g, 1, 0.0, 1.0, 0)                              # beta outside (0, 1]
