@@ -1,0 +1,133 @@
+/*
+ * scalecom.h -- C-ABI of the MI355X (gfx950) implementation of ScaleCom's per-step gradient
+ * compression path: the cyclic local top-k compressor (CLT-k) with low-pass-filtered error
+ * feedback (ScaleCom, arXiv 2104.11125, Algorithm 1 lines 6, 7 and 10; Eq. 2, 3, 5).
+ *
+ * n learners are simulated as n separate buffers on ONE GPU.  One call to scalecom_step
+ * performs, for iteration `step`:
+ *
+ *   x_i   = mem_i + lr * grad_i                  for every learner i        (Alg. 1 line 6)
+ *   I     = positions of the k largest |x_L|,    L = step mod n_learners    (Eq. 2, leader rule)
+ *           ties ordered by position, lowest first; reported ascending
+ *   v_i   = x_i restricted to I                  (CLT-k, Eq. 3)
+ *   out   = sum_i v_i, added in the order i = 0, 1, ..., n-1   (Alg. 1 line 10 without 1/n)
+ *   mem_i = (1-beta) * mem_i + beta * (x_i - CLT-k(x_i))       (Eq. 5, Alg. 1 line 7)
+ *
+ * All arithmetic is IEEE binary32: x = fma(lr, grad, mem); the update is
+ * fma(beta, r, (1-beta)*mem) with r = 0 on I and r = x elsewhere.  bfloat16 gradients are
+ * widened exactly.  |x| is compared on the bit pattern with the sign bit cleared, so the
+ * index set is a pure function of the input bits (NaN patterns rank above infinity).
+ *
+ * Conventions
+ *  - Pointers marked [device] are GPU global memory of the device given to scalecom_init;
+ *    pointers marked [host] are ordinary process memory, read before the call returns.
+ *  - The caller owns every buffer, including the workspace; the library allocates no
+ *    device memory.  It keeps a few KB of pinned host memory per context.
+ *  - All work is enqueued on the HIP stream given to scalecom_init; calls do not wait for
+ *    the GPU.  Outputs are valid once that stream has reached the end of the call's work.
+ *    A context must not be used from two threads at once.
+ *  - Errors are return codes; nothing is thrown.  scalecom_last_error gives the detail.
+ */
+#ifndef SCALECOM_H
+#define SCALECOM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct scalecom_ctx scalecom_ctx; /* opaque */
+
+typedef enum {
+    SCALECOM_OK = 0,
+    SCALECOM_EINVAL = 1,      /* an argument is outside what the header allows          */
+    SCALECOM_ENOMEM = 2,      /* host allocation failed, or the workspace is too small  */
+    SCALECOM_EHIP = 3,        /* a HIP runtime call failed (text in scalecom_last_error) */
+    SCALECOM_EUNSUPPORTED = 4 /* the device is not a gfx950 GPU                          */
+} scalecom_status;
+
+typedef enum {
+    SCALECOM_GRAD_F32 = 0, /* gradients are binary32                          */
+    SCALECOM_GRAD_BF16 = 1 /* gradients are bfloat16 (upper half of binary32) */
+} scalecom_grad_dtype;
+
+/* Largest n_learners accepted (the paper scales to 64 learners, abstract and Table 3). */
+#define SCALECOM_MAX_LEARNERS 64
+
+/*
+ * Bytes of device workspace needed for vectors of up to numel_max elements per learner,
+ * split into at most n_tensors_max segments (1 for whole-vector use).  Pure host
+ * arithmetic.  Returns 0 if an argument is out of range (numel_max < 0 or > 2^31 - 1,
+ * n_tensors_max < 1).
+ */
+size_t scalecom_workspace_bytes(int64_t numel_max, int n_tensors_max);
+
+/*
+ * Create a context bound to one device and one stream.
+ *   out             [host]   receives the context
+ *   device                   HIP device ordinal
+ *   hip_stream               hipStream_t on that device, as void* (NULL = the default stream)
+ *   workspace       [device] at least scalecom_workspace_bytes(numel_max, n_tensors_max) bytes,
+ *                            256-byte aligned; stays the caller's, must outlive the context,
+ *                            contents are scratch
+ *   n_learners_max           1 .. SCALECOM_MAX_LEARNERS
+ *   grad_dtype               element type of every grad buffer passed later
+ * EINVAL for bad arguments, ENOMEM for a short workspace, EHIP / EUNSUPPORTED for device trouble.
+ */
+scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, void* workspace,
+                              size_t workspace_bytes, int n_learners_max, int64_t numel_max,
+                              int n_tensors_max, scalecom_grad_dtype grad_dtype);
+
+/*
+ * One iteration over whole vectors (the operation stated at the top of this file).
+ *   mem              [host] array of n_learners [device] pointers, each float[numel], 16-byte
+ *                    aligned; read and overwritten in place (Eq. 5)
+ *   grad             [host] array of n_learners [device] pointers, each numel gradients of the
+ *                    context's grad_dtype, 16-byte aligned (8 for bfloat16); never written
+ *   n_learners       1 .. n_learners_max
+ *   numel            0 .. numel_max      (0: nothing is done)
+ *   k                0 .. numel          (0: the index set is empty, memories still updated)
+ *   beta             0 < beta <= 1       (Eq. 5; beta = 1 is plain error feedback)
+ *   lr               finite; multiplies the gradient before it is added to the memory
+ *   step             >= 0; the leader is learner step mod n_learners
+ *   idx_out          [device] int32[k]: the index set, ascending
+ *   reduced_vals_out [device] float[k]: reduced_vals_out[t] = sum over learners of x_i[idx_out[t]]
+ * Buffers must not overlap each other.  EINVAL if any rule above is broken.
+ */
+scalecom_status scalecom_step(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                              int64_t numel, int64_t k, float beta, float lr, int64_t step,
+                              int32_t* idx_out, float* reduced_vals_out);
+
+/*
+ * One iteration with a separate index set per tensor (per-layer compression rates, Sec. 4):
+ * each learner's vector is cut into n_tensors consecutive segments
+ * [offsets[s], offsets[s+1]), and segment s gets the ks[s] largest-magnitude positions of
+ * the leader's x inside that segment.  The leader is the same for all segments of a step.
+ *   offsets          [host] int64[n_tensors + 1], non-decreasing, offsets[0] >= 0,
+ *                    offsets[n_tensors] <= numel_max; elements outside the segments are untouched
+ *   ks               [host] int64[n_tensors], 0 <= ks[s] <= length of segment s
+ *   idx_out          [device] int32[sum ks]: positions in the whole vector, segment after
+ *                    segment, ascending inside a segment
+ *   reduced_vals_out [device] float[sum ks], paired with idx_out
+ * Other arguments as for scalecom_step; 1 <= n_tensors <= n_tensors_max.
+ */
+scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const void* const* grad,
+                                     int n_learners, int n_tensors, const int64_t* offsets,
+                                     const int64_t* ks, float beta, float lr, int64_t step,
+                                     int32_t* idx_out, float* reduced_vals_out);
+
+/* Static text for a status code. */
+const char* scalecom_strerror(scalecom_status status);
+
+/* Detail of the last failure on this context ("" if none); valid until the next call on it. */
+const char* scalecom_last_error(const scalecom_ctx* ctx);
+
+/* Waits for the context's stream, frees the context's host memory.  NULL is allowed. */
+void scalecom_destroy(scalecom_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCALECOM_H */

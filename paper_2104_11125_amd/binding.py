@@ -1,0 +1,155 @@
+"""Thin Python layer over the C-ABI in ``include/scalecom.h``: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of ``csrc/libscalecom.so``.  PyTorch is used
+for device memory and the stream.  If the library has not been built this module raises:
+there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "libscalecom.so")
+
+SCALECOM_OK, SCALECOM_EINVAL, SCALECOM_ENOMEM, SCALECOM_EHIP, SCALECOM_EUNSUPPORTED = range(5)
+SCALECOM_GRAD_F32, SCALECOM_GRAD_BF16 = 0, 1
+SCALECOM_MAX_LEARNERS = 64
+
+_lib = None
+
+
+class ScaleComError(RuntimeError):
+    def __init__(self, status: int, detail: str = ""):
+        self.status = status
+        text = lib().scalecom_strerror(status).decode()
+        super().__init__(f"scalecom status {status} ({text})" + (f": {detail}" if detail else ""))
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library (built by ``paper_2104_11125_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2104_11125_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+        L.scalecom_workspace_bytes.argtypes = [i64, i32]
+        L.scalecom_workspace_bytes.restype = sz
+        L.scalecom_init.argtypes = [ctypes.POINTER(vp), i32, vp, vp, sz, i32, i64, i32, i32]
+        L.scalecom_init.restype = i32
+        L.scalecom_step.argtypes = [vp, vp, vp, i32, i64, i64, f32, f32, i64, vp, vp]
+        L.scalecom_step.restype = i32
+        L.scalecom_step_layers.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, f32, i64, vp, vp]
+        L.scalecom_step_layers.restype = i32
+        L.scalecom_strerror.argtypes = [i32]
+        L.scalecom_strerror.restype = ctypes.c_char_p
+        L.scalecom_last_error.argtypes = [vp]
+        L.scalecom_last_error.restype = ctypes.c_char_p
+        L.scalecom_destroy.argtypes = [vp]
+        L.scalecom_destroy.restype = None
+        _lib = L
+    return _lib
+
+
+def scalecom_workspace_bytes(numel_max: int, n_tensors_max: int = 1) -> int:
+    return int(lib().scalecom_workspace_bytes(numel_max, n_tensors_max))
+
+
+def _ptrs(tensors: Sequence[torch.Tensor]):
+    return (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+class ScaleCom:
+    """One context: a device, a stream and a caller-owned workspace (a torch tensor held here)."""
+
+    def __init__(self, numel_max: int, n_learners_max: int, grad_dtype: torch.dtype = torch.float32,
+                 n_tensors_max: int = 1, device: Optional[torch.device] = None,
+                 stream: Optional[torch.cuda.Stream] = None):
+        L = lib()
+        self.device = torch.device(device if device is not None else "cuda:0")
+        if grad_dtype not in (torch.float32, torch.bfloat16):
+            raise TypeError("grad_dtype must be torch.float32 or torch.bfloat16")
+        self.grad_dtype = grad_dtype
+        nbytes = scalecom_workspace_bytes(numel_max, n_tensors_max)
+        if nbytes == 0:
+            raise ScaleComError(SCALECOM_EINVAL, "numel_max / n_tensors_max out of range")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self._ctx = ctypes.c_void_p()
+        index = self.device.index if self.device.index is not None else torch.cuda.current_device()
+        st = L.scalecom_init(ctypes.byref(self._ctx), index, ctypes.c_void_p(self.stream.cuda_stream),
+                             ctypes.c_void_p(self.workspace.data_ptr()), nbytes, n_learners_max, numel_max,
+                             n_tensors_max,
+                             SCALECOM_GRAD_BF16 if grad_dtype == torch.bfloat16 else SCALECOM_GRAD_F32)
+        if st != SCALECOM_OK:
+            self._ctx = ctypes.c_void_p()
+            raise ScaleComError(st)
+
+    def _check(self, st: int):
+        if st != SCALECOM_OK:
+            raise ScaleComError(st, lib().scalecom_last_error(self._ctx).decode())
+
+    def _check_buffers(self, mem, grad):
+        for m, g in zip(mem, grad):
+            if m.dtype != torch.float32 or g.dtype != self.grad_dtype:
+                raise TypeError("mem must be float32 and grad must have the context's grad_dtype")
+            if not (m.is_contiguous() and g.is_contiguous() and m.device == self.device and g.device == self.device):
+                raise ValueError("buffers must be contiguous tensors on the context's device")
+
+    def scalecom_step(self, mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor], k: int, beta: float,
+                      lr: float, step: int, idx_out: Optional[torch.Tensor] = None,
+                      reduced_vals_out: Optional[torch.Tensor] = None):
+        """``scalecom_step`` of the C-ABI; allocates the two outputs if they are not given."""
+        self._check_buffers(mem, grad)
+        numel = mem[0].numel()
+        if idx_out is None:
+            idx_out = torch.empty(max(k, 0), dtype=torch.int32, device=self.device)
+        if reduced_vals_out is None:
+            reduced_vals_out = torch.empty(max(k, 0), dtype=torch.float32, device=self.device)
+        st = lib().scalecom_step(self._ctx, _ptrs(mem), _ptrs(grad), len(mem), numel, k, beta, lr, step,
+                                 ctypes.c_void_p(idx_out.data_ptr()), ctypes.c_void_p(reduced_vals_out.data_ptr()))
+        self._check(st)
+        return idx_out, reduced_vals_out
+
+    def scalecom_step_layers(self, mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor],
+                             offsets: Sequence[int], ks: Sequence[int], beta: float, lr: float, step: int,
+                             idx_out: Optional[torch.Tensor] = None,
+                             reduced_vals_out: Optional[torch.Tensor] = None):
+        """``scalecom_step_layers`` of the C-ABI."""
+        self._check_buffers(mem, grad)
+        n_tensors = len(ks)
+        if len(offsets) != n_tensors + 1:
+            raise ValueError("offsets must have len(ks) + 1 entries")
+        c_off = (ctypes.c_int64 * (n_tensors + 1))(*[int(o) for o in offsets])
+        c_ks = (ctypes.c_int64 * n_tensors)(*[int(v) for v in ks])
+        total = max(int(sum(int(v) for v in ks)), 0)
+        if idx_out is None:
+            idx_out = torch.empty(total, dtype=torch.int32, device=self.device)
+        if reduced_vals_out is None:
+            reduced_vals_out = torch.empty(total, dtype=torch.float32, device=self.device)
+        st = lib().scalecom_step_layers(self._ctx, _ptrs(mem), _ptrs(grad), len(mem), n_tensors, c_off, c_ks, beta,
+                                        lr, step, ctypes.c_void_p(idx_out.data_ptr()),
+                                        ctypes.c_void_p(reduced_vals_out.data_ptr()))
+        self._check(st)
+        return idx_out, reduced_vals_out
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx:
+            lib().scalecom_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def scalecom_init(numel_max: int, n_learners_max: int, grad_dtype: torch.dtype = torch.float32,
+                  n_tensors_max: int = 1, device=None, stream=None) -> ScaleCom:
+    """``scalecom_init`` of the C-ABI, with the workspace taken from torch."""
+    return ScaleCom(numel_max, n_learners_max, grad_dtype, n_tensors_max, device, stream)

@@ -1,0 +1,860 @@
+// HIP kernels (gfx950 / CDNA4, 64-lane wavefronts) and C-ABI of ScaleCom's per-step
+// compression path: CLT-k with low-pass-filtered error feedback (arXiv 2104.11125, Alg. 1
+// lines 6, 7, 10; Eq. 2, 3, 5).  See include/scalecom.h for the contract of each entry point.
+//
+// Structure of one step (all on the context's stream, no host synchronisation):
+//
+//   init        zero the digit histograms and per-segment selection state
+//   hist<0..2>  leader only: x_L = fma(lr, grad_L, mem_L) is recomputed on the fly (never
+//               stored) and the 31-bit magnitude key |x_L| is histogrammed 12 + 12 + 7 bits at
+//               a time, each level restricted to the bucket the previous level chose
+//   find<0..2>  per segment: walk the histogram from the top to the bucket holding the k-th
+//               largest key; after level 2 the exact threshold key T and the number q of
+//               keys equal to T that still belong to the set are known  (Eq. 2)
+//   tilecount   leader only: per 256-element wave tile, how many keys are > T and == T
+//   scan        exclusive prefix of those counts over the tiles of each segment
+//   fused       every learner, one read of (mem, grad) and one write of mem:
+//               membership = key > T, or key == T and rank among equal keys (by position) < q;
+//               gather + sum over learners at the members (Eq. 3, Alg. 1 line 10), residual and
+//               low-pass update for everybody (Eq. 5), index/value written at the slot given by
+//               the prefix counts, so the output is ascending by position and deterministic.
+//
+// Nothing here is a dense contraction, so there is no MFMA; the kernels are bound by HBM
+// traffic (fused) and by LDS atomics + HBM (hist).
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "scalecom.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// geometry
+// ------------------------------------------------------------------------------------------
+constexpr int kLanes = 64;                       // wavefront width on CDNA
+constexpr int kVec = 4;                          // elements per lane per access (16 B of fp32)
+constexpr int kWaveTile = kLanes * kVec;         // 256 consecutive positions handled by one wave
+constexpr int kTilesPerSuper = 32;               // wave tiles per supertile (unit of the prefix scan)
+constexpr int kSuper = kWaveTile * kTilesPerSuper;   // 8192 positions
+constexpr int kBlock = 256;                      // threads per block in the streaming kernels
+constexpr int kWaves = kBlock / kLanes;          // 4
+constexpr int kFusedTiles = 8;                   // wave tiles per block of the fused kernel
+constexpr int kFusedBlocksPerSuper = kTilesPerSuper / kFusedTiles;
+
+constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
+constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
+constexpr int kHistGridMax = 2048;
+
+struct SegDesc {          // one per tensor (segment of the flat vector)
+    int32_t begin, end;   // positions [begin, end)
+    int32_t k;            // size of this segment's index set
+    int32_t out_base;     // first output slot of this segment
+    int32_t st_first;     // first supertile
+    int32_t st_count;     // number of supertiles
+    int32_t pad0, pad1;
+};
+
+struct StDesc {           // one per supertile
+    int32_t seg;
+    int32_t a0;           // first position, a multiple of 4 (may lie up to 3 before seg.begin)
+};
+
+struct SegState {         // selection state of one segment, written by find<>
+    uint32_t prefix;      // key bits fixed so far (level 0: 12 bits, level 1: 24 bits)
+    uint32_t k_rem;       // members still to be found inside the current bucket
+    uint32_t T;           // threshold key (after level 2)
+    uint32_t q;           // number of keys == T that are members (the lowest positions)
+    uint32_t done;        // 1: empty index set, nothing to refine
+    uint32_t pad[3];
+};
+
+struct LearnerPtrs {
+    float* mem[SCALECOM_MAX_LEARNERS];
+    const void* grad[SCALECOM_MAX_LEARNERS];
+};
+
+// ------------------------------------------------------------------------------------------
+// device helpers
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t magnitude_key(float x) { return __float_as_uint(x) & 0x7fffffffu; }
+
+__device__ __forceinline__ float widen(float g) { return g; }
+__device__ __forceinline__ float widen(uint16_t g) { return __uint_as_float(static_cast<uint32_t>(g) << 16); }
+
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const uint16_t* p)
+{
+    const uint2 v = *reinterpret_cast<const uint2*>(p);
+    float4 r;
+    r.x = __uint_as_float(v.x << 16);
+    r.y = __uint_as_float(v.x & 0xffff0000u);
+    r.z = __uint_as_float(v.y << 16);
+    r.w = __uint_as_float(v.y & 0xffff0000u);
+    return r;
+}
+__device__ __forceinline__ void store4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+
+// number of set bits of a wave-wide ballot that belong to lanes below the calling lane
+__device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
+{
+    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(ballot >> 32),
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ballot), 0u));
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kLanes);
+    return v;
+}
+
+// 4 consecutive values starting at position p0 (a multiple of 4) of one learner's array;
+// positions outside [begin, end) read as 0 and are never touched in memory.
+template <typename T>
+__device__ __forceinline__ float4 load_guarded(const T* base, int64_t p0, int64_t begin, int64_t end, bool full)
+{
+    if (full) return load4(base + p0);
+    float v[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int64_t p = p0 + c;
+        v[c] = (p >= begin && p < end) ? widen(base[p]) : 0.0f;
+    }
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+
+__device__ __forceinline__ void store_guarded(float* base, int64_t p0, int64_t begin, int64_t end, bool full,
+                                              const float4& v)
+{
+    if (full) {
+        store4(base + p0, v);
+        return;
+    }
+    const float a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int64_t p = p0 + c;
+        if (p >= begin && p < end) base[p] = a[c];
+    }
+}
+
+// x = fma(lr, grad, mem): the error-feedback gradient of Alg. 1 line 6, one rounding.
+__device__ __forceinline__ float4 accumulate4(const float4& m, const float4& g, float lr)
+{
+    return make_float4(fmaf(lr, g.x, m.x), fmaf(lr, g.y, m.y), fmaf(lr, g.z, m.z), fmaf(lr, g.w, m.w));
+}
+
+// Magnitude keys of the leader's x at the 4 positions of this lane; ok[c] tells whether the
+// position belongs to the segment.
+template <typename G>
+__device__ __forceinline__ void leader_keys(const float* mem, const G* grad, float lr, int64_t p0, int64_t begin,
+                                            int64_t end, uint32_t key[4], bool ok[4])
+{
+    const bool full = p0 >= begin && p0 + 3 < end;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) ok[c] = (p0 + c >= begin) && (p0 + c < end);
+    if (!(ok[0] | ok[1] | ok[2] | ok[3])) {
+        key[0] = key[1] = key[2] = key[3] = 0;
+        return;
+    }
+    const float4 m = load_guarded(mem, p0, begin, end, full);
+    const float4 g = load_guarded(grad, p0, begin, end, full);
+    const float4 x = accumulate4(m, g, lr);
+    key[0] = magnitude_key(x.x);
+    key[1] = magnitude_key(x.y);
+    key[2] = magnitude_key(x.z);
+    key[3] = magnitude_key(x.w);
+}
+
+// ------------------------------------------------------------------------------------------
+// kernels
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock) k_init(uint32_t* zero_from, size_t n_words)
+{
+    for (size_t i = blockIdx.x * static_cast<size_t>(kBlock) + threadIdx.x; i < n_words;
+         i += static_cast<size_t>(gridDim.x) * kBlock)
+        zero_from[i] = 0u;
+}
+
+// Histogram of one digit of the leader's magnitude keys (Eq. 2: finding the k-th largest
+// magnitude), per segment.  LEVEL 0: top 12 bits of every key; LEVEL 1: next 12 bits of keys
+// whose top 12 bits equal the chosen bucket; LEVEL 2: last 7 bits of keys matching 24 bits.
+template <typename G, int LEVEL>
+__global__ void __launch_bounds__(kBlock)
+k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+       const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state, uint32_t* __restrict__ hist)
+{
+    constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
+    __shared__ uint32_t lh[NB];
+    for (int b = threadIdx.x; b < NB; b += kBlock) lh[b] = 0u;
+    __syncthreads();
+
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
+    const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
+
+    int cur = -1;
+    int64_t begin = 0, end = 0;
+    uint32_t prefix = 0;
+    bool skip = false;
+    for (int st = st_lo; st < st_hi; ++st) {
+        const StDesc d = sts[st];
+        if (d.seg != cur) {
+            if (cur >= 0) {   // flush the finished segment's counts
+                __syncthreads();
+                for (int b = threadIdx.x; b < NB; b += kBlock) {
+                    const uint32_t v = lh[b];
+                    if (v) {
+                        atomicAdd(&hist[static_cast<size_t>(cur) * NB + b], v);
+                        lh[b] = 0u;
+                    }
+                }
+                __syncthreads();
+            }
+            cur = d.seg;
+            begin = segs[cur].begin;
+            end = segs[cur].end;
+            if (LEVEL > 0) {
+                prefix = state[cur].prefix;
+                skip = state[cur].done != 0;
+            }
+        }
+        if (skip) continue;
+#pragma unroll 2
+        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+            const int64_t p0 = static_cast<int64_t>(d.a0) + (it * kWaves + wave) * kWaveTile + lane * kVec;
+            if (p0 >= end) continue;
+            uint32_t key[4];
+            bool ok[4];
+            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (!ok[c]) continue;
+                if (LEVEL == 0) {
+                    atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
+                } else if (LEVEL == 1) {
+                    if ((key[c] >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key[c] >> kBits2) & (kBins1 - 1)], 1u);
+                } else {
+                    if ((key[c] >> kBits2) == prefix) atomicAdd(&lh[key[c] & (kBins2 - 1)], 1u);
+                }
+            }
+        }
+    }
+    if (cur >= 0) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < NB; b += kBlock) {
+            const uint32_t v = lh[b];
+            if (v) atomicAdd(&hist[static_cast<size_t>(cur) * NB + b], v);
+        }
+    }
+}
+
+// One block per segment: locate, from the top of the histogram, the bucket that holds the
+// k_rem-th largest key of the current bucket, and narrow the state to it.
+template <int LEVEL>
+__global__ void __launch_bounds__(kBlock)
+k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uint32_t* __restrict__ hist)
+{
+    constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
+    constexpr int BITS = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
+    constexpr int CH = NB >= kBlock ? NB / kBlock : 1;     // bins per thread
+    constexpr int ACTIVE = NB >= kBlock ? kBlock : NB;     // threads that own bins
+    const int seg = blockIdx.x;
+    const uint32_t* h = hist + static_cast<size_t>(seg) * NB;
+    __shared__ uint32_t above[kBlock];   // keys in the chunks of higher threads
+
+    SegState s = state[seg];
+    if (LEVEL == 0) {
+        s.prefix = 0;
+        s.k_rem = static_cast<uint32_t>(segs[seg].k);
+        s.done = s.k_rem == 0 ? 1u : 0u;
+        s.T = 0xffffffffu;     // above every key: nothing is a member
+        s.q = 0;
+        if (s.done) {
+            if (threadIdx.x == 0) state[seg] = s;
+            return;
+        }
+    } else if (s.done) {
+        return;
+    }
+
+    const int t = threadIdx.x;
+    uint32_t mine = 0;
+    if (t < ACTIVE)
+        for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
+    // inclusive suffix sums over threads (Hillis-Steele on the reversed order)
+    above[t] = t < ACTIVE ? mine : 0u;
+    __syncthreads();
+    for (int off = 1; off < kBlock; off <<= 1) {
+        const uint32_t add = (t + off < kBlock) ? above[t + off] : 0u;
+        __syncthreads();
+        above[t] += add;
+        __syncthreads();
+    }
+    const uint32_t incl = above[t];          // keys in my chunk and all higher chunks
+    const uint32_t excl = incl - mine;       // keys strictly above my chunk
+    if (t < ACTIVE && excl < s.k_rem && s.k_rem <= incl) {
+        uint32_t c = excl;
+        for (int b = CH - 1; b >= 0; --b) {
+            const uint32_t n = h[t * CH + b];
+            if (c + n >= s.k_rem) {
+                const uint32_t digit = static_cast<uint32_t>(t * CH + b);
+                s.prefix = (s.prefix << BITS) | digit;
+                s.k_rem -= c;
+                if (LEVEL == 2) {
+                    s.T = s.prefix;
+                    s.q = s.k_rem;
+                }
+                state[seg] = s;
+                break;
+            }
+            c += n;
+        }
+    }
+}
+
+// Per wave tile of the leader's vector: number of keys above the threshold and equal to it.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+            const StDesc* __restrict__ sts, const SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt,
+            uint2* __restrict__ st_sum)
+{
+    const int st = blockIdx.x;
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const StDesc d = sts[st];
+    const int64_t begin = segs[d.seg].begin, end = segs[d.seg].end;
+    const uint32_t T = state[d.seg].T;
+    __shared__ uint32_t part[kWaves][2];
+
+    uint32_t tot_gt = 0, tot_eq = 0;
+    for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+        const int wt = it * kWaves + wave;
+        const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
+        uint32_t gt = 0, eq = 0;
+        if (p0 < end) {
+            uint32_t key[4];
+            bool ok[4];
+            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                gt += (ok[c] && key[c] > T) ? 1u : 0u;
+                eq += (ok[c] && key[c] == T) ? 1u : 0u;
+            }
+        }
+        const uint32_t s = wave_sum(gt | (eq << 16));     // at most 256 each: no carry between halves
+        if (lane == 0) wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt] = s;
+        tot_gt += s & 0xffffu;
+        tot_eq += s >> 16;
+    }
+    if (lane == 0) {
+        part[wave][0] = tot_gt;
+        part[wave][1] = tot_eq;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = 0, b = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            a += part[w][0];
+            b += part[w][1];
+        }
+        st_sum[st] = make_uint2(a, b);
+    }
+}
+
+// One block per segment: exclusive prefix sums of (above, equal) over its supertiles.
+constexpr int kScanBlock = 1024;
+__global__ void __launch_bounds__(kScanBlock)
+k_scan(const SegDesc* __restrict__ segs, const uint2* __restrict__ st_sum, uint2* __restrict__ st_prefix)
+{
+    const SegDesc sd = segs[blockIdx.x];
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    __shared__ uint2 wtot[kScanBlock / kLanes];
+    uint2 carry = make_uint2(0, 0);
+    for (int base = 0; base < sd.st_count; base += kScanBlock) {
+        const int i = base + threadIdx.x;
+        uint2 v = i < sd.st_count ? st_sum[sd.st_first + i] : make_uint2(0, 0);
+        uint2 inc = v;
+#pragma unroll
+        for (int off = 1; off < kLanes; off <<= 1) {
+            const uint32_t ax = __shfl_up(inc.x, off, kLanes), ay = __shfl_up(inc.y, off, kLanes);
+            if (lane >= off) {
+                inc.x += ax;
+                inc.y += ay;
+            }
+        }
+        if (lane == kLanes - 1) wtot[wave] = inc;
+        __syncthreads();
+        uint2 before = carry, total = carry;
+        for (int w = 0; w < kScanBlock / kLanes; ++w) {
+            const uint2 t = wtot[w];
+            if (w < wave) {
+                before.x += t.x;
+                before.y += t.y;
+            }
+            total.x += t.x;
+            total.y += t.y;
+        }
+        if (i < sd.st_count) st_prefix[sd.st_first + i] = make_uint2(before.x + inc.x - v.x, before.y + inc.y - v.y);
+        carry = total;
+        __syncthreads();
+    }
+}
+
+// The all-learner pass: CLT-k gather and sum (Eq. 3, Alg. 1 line 10) and the low-pass memory
+// update (Eq. 5) in one read of (mem, grad) and one write of mem per learner.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_fused(LearnerPtrs lp, int n_learners, int leader, float lr, float beta, float one_minus_beta,
+        const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, const SegState* __restrict__ state,
+        const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_prefix, int32_t* __restrict__ idx_out,
+        float* __restrict__ red_out)
+{
+    const int st = blockIdx.x / kFusedBlocksPerSuper;
+    const int part = blockIdx.x % kFusedBlocksPerSuper;
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const StDesc d = sts[st];
+    const SegDesc sd = segs[d.seg];
+    const int64_t begin = sd.begin, end = sd.end;
+    const uint32_t T = state[d.seg].T, q = state[d.seg].q;
+    const uint2 stp = st_prefix[st];
+    const uint32_t slot_end = static_cast<uint32_t>(sd.out_base) + static_cast<uint32_t>(sd.k);
+
+#pragma unroll 1
+    for (int r = 0; r < kFusedTiles / kWaves; ++r) {
+        const int wt = part * kFusedTiles + r * kWaves + wave;
+        const int64_t tile0 = static_cast<int64_t>(d.a0) + wt * kWaveTile;
+        if (tile0 >= end) continue;                       // wave-uniform
+        const int64_t p0 = tile0 + lane * kVec;
+        const bool full = p0 >= begin && p0 + 3 < end;
+        bool ok[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ok[c] = (p0 + c >= begin) && (p0 + c < end);
+        const bool any_ok = ok[0] | ok[1] | ok[2] | ok[3];
+
+        // leader first: membership of my 4 positions
+        float4 mL = make_float4(0, 0, 0, 0), xL = mL;
+        if (any_ok) {
+            mL = load_guarded(lp.mem[leader], p0, begin, end, full);
+            const float4 gL = load_guarded(static_cast<const G*>(lp.grad[leader]), p0, begin, end, full);
+            xL = accumulate4(mL, gL, lr);
+        }
+        const uint32_t key[4] = {magnitude_key(xL.x), magnitude_key(xL.y), magnitude_key(xL.z), magnitude_key(xL.w)};
+        bool sel[4], eq[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sel[c] = ok[c] && key[c] > T;
+            eq[c] = ok[c] && key[c] == T;
+        }
+
+        // members and ties in earlier tiles of this segment
+        const uint32_t packed = lane < wt ? wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + lane] : 0u;
+        const uint32_t psum = wave_sum(packed);           // <= 31 * 256 per half
+        const uint32_t gt_before = stp.x + (psum & 0xffffu);
+        const uint32_t eq_before = stp.y + (psum >> 16);
+
+        // keys equal to the threshold are members while their rank by position is below q
+        if (__ballot(eq[0] | eq[1] | eq[2] | eq[3]) != 0ull) {
+            uint32_t rank = eq_before;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) rank += lanes_below(__ballot(eq[c]));
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (eq[c]) {
+                    sel[c] = rank < q;
+                    ++rank;
+                }
+            }
+        }
+
+        // output slot of my first member: everything selected before me, by position
+        uint32_t slot = static_cast<uint32_t>(sd.out_base) + gt_before + (eq_before < q ? eq_before : q);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) slot += lanes_below(__ballot(sel[c]));
+
+        float4 sum = make_float4(0, 0, 0, 0);
+        if (any_ok) {
+#pragma unroll 1
+            for (int i0 = 0; i0 < n_learners; i0 += 4) {
+                float4 m[4], g[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u;
+                    if (i < n_learners && i != leader) {
+                        m[u] = load_guarded(lp.mem[i], p0, begin, end, full);
+                        g[u] = load_guarded(static_cast<const G*>(lp.grad[i]), p0, begin, end, full);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u;
+                    if (i >= n_learners) break;
+                    float4 mi, x;
+                    if (i == leader) {
+                        mi = mL;
+                        x = xL;
+                    } else {
+                        mi = m[u];
+                        x = accumulate4(mi, g[u], lr);
+                    }
+                    if (i == 0) {
+                        sum = x;
+                    } else {
+                        sum.x = sum.x + x.x;
+                        sum.y = sum.y + x.y;
+                        sum.z = sum.z + x.z;
+                        sum.w = sum.w + x.w;
+                    }
+                    // Eq. 5: residual is x off the index set, 0 on it
+                    float4 out;
+                    out.x = fmaf(beta, sel[0] ? 0.0f : x.x, one_minus_beta * mi.x);
+                    out.y = fmaf(beta, sel[1] ? 0.0f : x.y, one_minus_beta * mi.y);
+                    out.z = fmaf(beta, sel[2] ? 0.0f : x.z, one_minus_beta * mi.z);
+                    out.w = fmaf(beta, sel[3] ? 0.0f : x.w, one_minus_beta * mi.w);
+                    store_guarded(lp.mem[i], p0, begin, end, full, out);
+                }
+            }
+        }
+
+        const float s4[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (sel[c] && slot < slot_end) {   // the bound only matters if the counts were corrupted
+                idx_out[slot] = static_cast<int32_t>(p0 + c);
+                red_out[slot] = s4[c];
+                ++slot;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline int64_t max_supertiles(int64_t numel_max, int n_tensors_max)
+{
+    return numel_max / kSuper + 2 * static_cast<int64_t>(n_tensors_max) + 2;
+}
+
+struct WsLayout {
+    size_t segs, sts, state, hist0, hist1, hist2, wt_cnt, st_sum, st_prefix, total;
+    size_t zero_words;   // state + histograms are contiguous and zeroed every step
+};
+
+WsLayout layout_for(int64_t numel_max, int n_tensors_max)
+{
+    const size_t nt = static_cast<size_t>(n_tensors_max);
+    const size_t nst = static_cast<size_t>(max_supertiles(numel_max, n_tensors_max));
+    WsLayout l{};
+    size_t o = 0;
+    l.segs = o;      o = align_up(o + nt * sizeof(SegDesc), 256);
+    l.sts = o;       o = align_up(o + nst * sizeof(StDesc), 256);
+    l.state = o;     o = align_up(o + nt * sizeof(SegState), 256);
+    l.hist0 = o;     o = align_up(o + nt * kBins0 * sizeof(uint32_t), 256);
+    l.hist1 = o;     o = align_up(o + nt * kBins1 * sizeof(uint32_t), 256);
+    l.hist2 = o;     o = align_up(o + nt * kBins2 * sizeof(uint32_t), 256);
+    l.zero_words = (o - l.state) / sizeof(uint32_t);
+    l.wt_cnt = o;    o = align_up(o + nst * kTilesPerSuper * sizeof(uint32_t), 256);
+    l.st_sum = o;    o = align_up(o + nst * sizeof(uint2), 256);
+    l.st_prefix = o; o = align_up(o + nst * sizeof(uint2), 256);
+    l.total = o;
+    return l;
+}
+
+}  // namespace
+
+struct scalecom_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    char* ws = nullptr;
+    int n_learners_max = 0;
+    int64_t numel_max = 0;
+    int n_tensors_max = 0;
+    scalecom_grad_dtype gdt = SCALECOM_GRAD_F32;
+    WsLayout lay{};
+    // tables of the layout used last, kept on the device until the layout changes
+    std::vector<int64_t> cached_offsets, cached_ks;
+    int n_st = 0;
+    char* pinned = nullptr;          // staging for the table upload
+    size_t pinned_bytes = 0;
+    hipEvent_t upload_done = nullptr;
+    bool upload_pending = false;
+    std::string last_error;
+};
+
+namespace {
+
+scalecom_status fail(scalecom_ctx* ctx, scalecom_status st, const std::string& msg)
+{
+    if (ctx) ctx->last_error = msg;
+    return st;
+}
+
+#define SC_HIP(ctx, call)                                                                              \
+    do {                                                                                               \
+        hipError_t e_ = (call);                                                                        \
+        if (e_ != hipSuccess)                                                                          \
+            return fail((ctx), SCALECOM_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));      \
+    } while (0)
+
+struct DeviceGuard {   // make the context's device current for the duration of a call
+    int prev = -1;
+    bool changed = false;
+    hipError_t enter(int device)
+    {
+        hipError_t e = hipGetDevice(&prev);
+        if (e != hipSuccess) return e;
+        if (prev != device) {
+            e = hipSetDevice(device);
+            changed = e == hipSuccess;
+        }
+        return e;
+    }
+    ~DeviceGuard()
+    {
+        if (changed) (void)hipSetDevice(prev);
+    }
+};
+
+// Rebuild and upload the segment and supertile tables if the layout differs from the cached one.
+scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* offsets, const int64_t* ks)
+{
+    const bool same = ctx->cached_ks.size() == static_cast<size_t>(n_tensors) &&
+                      std::memcmp(ctx->cached_offsets.data(), offsets, sizeof(int64_t) * (n_tensors + 1)) == 0 &&
+                      std::memcmp(ctx->cached_ks.data(), ks, sizeof(int64_t) * n_tensors) == 0;
+    if (same) return SCALECOM_OK;
+
+    if (ctx->upload_pending) {   // staging memory may still be read by an earlier copy
+        SC_HIP(ctx, hipEventSynchronize(ctx->upload_done));
+        ctx->upload_pending = false;
+    }
+    SegDesc* segs = reinterpret_cast<SegDesc*>(ctx->pinned);
+    const size_t st_off = align_up(sizeof(SegDesc) * static_cast<size_t>(n_tensors), 256);
+    StDesc* sts = reinterpret_cast<StDesc*>(ctx->pinned + st_off);
+    const int64_t st_cap = max_supertiles(ctx->numel_max, ctx->n_tensors_max);
+    int64_t n_st = 0, out = 0;
+    for (int s = 0; s < n_tensors; ++s) {
+        const int64_t b = offsets[s], e = offsets[s + 1];
+        const int64_t a_first = b & ~static_cast<int64_t>(kVec - 1);
+        const int64_t count = e > b ? (e - a_first + kSuper - 1) / kSuper : 0;
+        if (n_st + count > st_cap) return fail(ctx, SCALECOM_ENOMEM, "supertile table overflow");
+        segs[s] = SegDesc{static_cast<int32_t>(b), static_cast<int32_t>(e), static_cast<int32_t>(ks[s]),
+                          static_cast<int32_t>(out), static_cast<int32_t>(n_st), static_cast<int32_t>(count), 0, 0};
+        for (int64_t j = 0; j < count; ++j)
+            sts[n_st + j] = StDesc{s, static_cast<int32_t>(a_first + j * kSuper)};
+        n_st += count;
+        out += ks[s];
+    }
+    SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.segs, segs, sizeof(SegDesc) * n_tensors, hipMemcpyHostToDevice,
+                               ctx->stream));
+    if (n_st > 0)
+        SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.sts, sts, sizeof(StDesc) * n_st, hipMemcpyHostToDevice,
+                                   ctx->stream));
+    SC_HIP(ctx, hipEventRecord(ctx->upload_done, ctx->stream));
+    ctx->upload_pending = true;
+    ctx->n_st = static_cast<int>(n_st);
+    ctx->cached_offsets.assign(offsets, offsets + n_tensors + 1);
+    ctx->cached_ks.assign(ks, ks + n_tensors);
+    return SCALECOM_OK;
+}
+
+template <typename G>
+scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, float beta,
+                            float lr, int leader, int32_t* idx_out, float* red_out)
+{
+    char* ws = ctx->ws;
+    const WsLayout& l = ctx->lay;
+    const SegDesc* segs = reinterpret_cast<const SegDesc*>(ws + l.segs);
+    const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
+    SegState* state = reinterpret_cast<SegState*>(ws + l.state);
+    uint32_t* hist0 = reinterpret_cast<uint32_t*>(ws + l.hist0);
+    uint32_t* hist1 = reinterpret_cast<uint32_t*>(ws + l.hist1);
+    uint32_t* hist2 = reinterpret_cast<uint32_t*>(ws + l.hist2);
+    uint32_t* wt_cnt = reinterpret_cast<uint32_t*>(ws + l.wt_cnt);
+    uint2* st_sum = reinterpret_cast<uint2*>(ws + l.st_sum);
+    uint2* st_prefix = reinterpret_cast<uint2*>(ws + l.st_prefix);
+    hipStream_t s = ctx->stream;
+    const int n_st = ctx->n_st;
+    const float* memL = lp.mem[leader];
+    const G* gradL = static_cast<const G*>(lp.grad[leader]);
+
+    // selection state and the three histogram arrays start every step at zero
+    {
+        const size_t words = l.zero_words;
+        const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
+        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.state), words);
+    }
+    if (n_st > 0) {
+        const int hgrid = std::min(n_st, kHistGridMax);
+        k_hist<G, 0><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist0);
+        k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0);
+        k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist1);
+        k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1);
+        k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2);
+        k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2);
+        k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, st_sum);
+        k_scan<<<n_tensors, kScanBlock, 0, s>>>(segs, st_sum, st_prefix);
+        k_fused<G><<<n_st * kFusedBlocksPerSuper, kBlock, 0, s>>>(lp, n_learners, leader, lr, beta, 1.0f - beta, segs,
+                                                                  sts, state, wt_cnt, st_prefix, idx_out, red_out);
+    }
+    SC_HIP(ctx, hipGetLastError());
+    return SCALECOM_OK;
+}
+
+scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                            int n_tensors, const int64_t* offsets, const int64_t* ks, float beta, float lr,
+                            int64_t step, int32_t* idx_out, float* red_out)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    ctx->last_error.clear();
+    if (!mem || !grad || !offsets || !ks) return fail(ctx, SCALECOM_EINVAL, "null argument");
+    if (n_learners < 1 || n_learners > ctx->n_learners_max) return fail(ctx, SCALECOM_EINVAL, "n_learners out of range");
+    if (n_tensors < 1 || n_tensors > ctx->n_tensors_max) return fail(ctx, SCALECOM_EINVAL, "n_tensors out of range");
+    if (!(beta > 0.0f && beta <= 1.0f)) return fail(ctx, SCALECOM_EINVAL, "beta must satisfy 0 < beta <= 1");
+    if (!std::isfinite(lr)) return fail(ctx, SCALECOM_EINVAL, "lr must be finite");
+    if (step < 0) return fail(ctx, SCALECOM_EINVAL, "step must be >= 0");
+    if (offsets[0] < 0 || offsets[n_tensors] > ctx->numel_max) return fail(ctx, SCALECOM_EINVAL, "offsets out of range");
+    int64_t k_total = 0;
+    for (int s = 0; s < n_tensors; ++s) {
+        const int64_t len = offsets[s + 1] - offsets[s];
+        if (len < 0) return fail(ctx, SCALECOM_EINVAL, "offsets must be non-decreasing");
+        if (ks[s] < 0 || ks[s] > len) return fail(ctx, SCALECOM_EINVAL, "k must satisfy 0 <= k <= segment length");
+        k_total += ks[s];
+    }
+    if (offsets[n_tensors] == offsets[0]) return SCALECOM_OK;   // nothing to do
+    if (k_total > 0 && (!idx_out || !red_out)) return fail(ctx, SCALECOM_EINVAL, "null output");
+    const uintptr_t galign = ctx->gdt == SCALECOM_GRAD_BF16 ? 8 : 16;
+    LearnerPtrs lp;
+    for (int i = 0; i < n_learners; ++i) {
+        if (!mem[i] || !grad[i]) return fail(ctx, SCALECOM_EINVAL, "null learner buffer");
+        if (reinterpret_cast<uintptr_t>(mem[i]) % 16 || reinterpret_cast<uintptr_t>(grad[i]) % galign)
+            return fail(ctx, SCALECOM_EINVAL, "learner buffer is not aligned");
+        lp.mem[i] = mem[i];
+        lp.grad[i] = grad[i];
+    }
+    for (int i = n_learners; i < SCALECOM_MAX_LEARNERS; ++i) {
+        lp.mem[i] = nullptr;
+        lp.grad[i] = nullptr;
+    }
+
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    scalecom_status st = ensure_tables(ctx, n_tensors, offsets, ks);
+    if (st != SCALECOM_OK) return st;
+    const int leader = static_cast<int>(step % n_learners);    // Alg. 1 line 6: CLT-k of learner mod(t, n)
+    if (ctx->gdt == SCALECOM_GRAD_BF16)
+        return launch_step<uint16_t>(ctx, lp, n_learners, n_tensors, beta, lr, leader, idx_out, red_out);
+    return launch_step<float>(ctx, lp, n_learners, n_tensors, beta, lr, leader, idx_out, red_out);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t scalecom_workspace_bytes(int64_t numel_max, int n_tensors_max)
+{
+    if (numel_max < 0 || numel_max > INT32_MAX || n_tensors_max < 1) return 0;
+    return layout_for(numel_max, n_tensors_max).total;
+}
+
+scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, void* workspace,
+                              size_t workspace_bytes, int n_learners_max, int64_t numel_max, int n_tensors_max,
+                              scalecom_grad_dtype grad_dtype)
+{
+    if (!out) return SCALECOM_EINVAL;
+    *out = nullptr;
+    if (device < 0 || n_learners_max < 1 || n_learners_max > SCALECOM_MAX_LEARNERS || numel_max < 0 ||
+        numel_max > INT32_MAX || n_tensors_max < 1 ||
+        (grad_dtype != SCALECOM_GRAD_F32 && grad_dtype != SCALECOM_GRAD_BF16))
+        return SCALECOM_EINVAL;
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return SCALECOM_EINVAL;
+    const WsLayout lay = layout_for(numel_max, n_tensors_max);
+    if (workspace_bytes < lay.total) return SCALECOM_ENOMEM;
+
+    scalecom_ctx* ctx = new (std::nothrow) scalecom_ctx;
+    if (!ctx) return SCALECOM_ENOMEM;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->ws = static_cast<char*>(workspace);
+    ctx->n_learners_max = n_learners_max;
+    ctx->numel_max = numel_max;
+    ctx->n_tensors_max = n_tensors_max;
+    ctx->gdt = grad_dtype;
+    ctx->lay = lay;
+
+    auto bail = [&](scalecom_status st) {
+        scalecom_destroy(ctx);
+        return st;
+    };
+    DeviceGuard guard;
+    if (guard.enter(device) != hipSuccess) return bail(SCALECOM_EHIP);
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return bail(SCALECOM_EHIP);
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return bail(SCALECOM_EUNSUPPORTED);
+    ctx->pinned_bytes = align_up(sizeof(SegDesc) * static_cast<size_t>(n_tensors_max), 256) +
+                        sizeof(StDesc) * static_cast<size_t>(max_supertiles(numel_max, n_tensors_max));
+    if (hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), ctx->pinned_bytes, hipHostMallocDefault) != hipSuccess)
+        return bail(SCALECOM_ENOMEM);
+    if (hipEventCreateWithFlags(&ctx->upload_done, hipEventDisableTiming) != hipSuccess) return bail(SCALECOM_EHIP);
+    *out = ctx;
+    return SCALECOM_OK;
+}
+
+scalecom_status scalecom_step(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                              int64_t numel, int64_t k, float beta, float lr, int64_t step, int32_t* idx_out,
+                              float* reduced_vals_out)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    if (numel < 0 || numel > ctx->numel_max) return fail(ctx, SCALECOM_EINVAL, "numel out of range");
+    const int64_t offsets[2] = {0, numel};
+    return step_common(ctx, mem, grad, n_learners, 1, offsets, &k, beta, lr, step, idx_out, reduced_vals_out);
+}
+
+scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                                     int n_tensors, const int64_t* offsets, const int64_t* ks, float beta, float lr,
+                                     int64_t step, int32_t* idx_out, float* reduced_vals_out)
+{
+    return step_common(ctx, mem, grad, n_learners, n_tensors, offsets, ks, beta, lr, step, idx_out,
+                       reduced_vals_out);
+}
+
+const char* scalecom_strerror(scalecom_status status)
+{
+    switch (status) {
+        case SCALECOM_OK: return "ok";
+        case SCALECOM_EINVAL: return "invalid argument";
+        case SCALECOM_ENOMEM: return "out of memory or workspace too small";
+        case SCALECOM_EHIP: return "HIP runtime error";
+        case SCALECOM_EUNSUPPORTED: return "unsupported device (gfx950 required)";
+    }
+    return "unknown status";
+}
+
+const char* scalecom_last_error(const scalecom_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }
+
+void scalecom_destroy(scalecom_ctx* ctx)
+{
+    if (!ctx) return;
+    if (ctx->pinned || ctx->upload_done) {
+        DeviceGuard guard;
+        if (guard.enter(ctx->device) == hipSuccess) {
+            (void)hipStreamSynchronize(ctx->stream);
+            if (ctx->upload_done) (void)hipEventDestroy(ctx->upload_done);
+            if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+        }
+    }
+    delete ctx;
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+"""Shared machinery of the GPU parity tests: run the HIP library (through its C-ABI binding)
+and the CPU oracle on the same bytes and compare every output.
+
+Bars (from the benchmark spec): index set bit-exact; per-learner memory within 1e-6 and the
+cross-learner sum within 1e-5, both measured as |a-b| <= rtol*|b| + rtol*max|b|.  Because both
+sides evaluate the same binary32 operations in the same order (x = fma(lr, g, m); sum over
+learners 0..n-1; m' = fma(beta, r, (1-beta)*m)), the tests first ask for bit equality and
+report the tolerance check only as the fallback bar.
+"""
+import numpy as np
+import torch
+
+import oracle
+from paper_2104_11125_amd import binding, workloads
+
+DEV = torch.device("cuda:0")
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def close(a, b, rtol):
+    b64 = b.astype(np.float64)
+    scale = np.abs(b64).max() if b64.size else 0.0
+    return bool(np.all(np.abs(a.astype(np.float64) - b64) <= rtol * np.abs(b64) + rtol * scale))
+
+
+def assert_same(kind, got: np.ndarray, want: np.ndarray, rtol=None, what=""):
+    if got.shape == want.shape and got.tobytes() == want.tobytes():
+        return
+    if got.shape == want.shape and got.dtype == np.float32:
+        # the sign and payload of a NaN are not fixed by IEEE 754: compare NaNs by position only
+        nan_g, nan_w = np.isnan(got), np.isnan(want)
+        if nan_g.any() and np.array_equal(nan_g, nan_w) and \
+                np.where(nan_g, np.float32(0), got).tobytes() == np.where(nan_w, np.float32(0), want).tobytes():
+            return
+    if rtol is None:
+        bad = np.flatnonzero(got != want)[:5] if got.shape == want.shape else "shape"
+        raise AssertionError(f"{kind} {what}: not bit-exact; first differences at {bad}")
+    assert got.shape == want.shape, f"{kind} {what}: shape {got.shape} vs {want.shape}"
+    # NaN patterns must match exactly; everything else within the bar
+    nan_g, nan_w = np.isnan(got), np.isnan(want)
+    assert np.array_equal(nan_g, nan_w), f"{kind} {what}: NaN pattern differs"
+    assert close(np.where(nan_g, 0, got), np.where(nan_w, 0, want), rtol), f"{kind} {what}: outside rtol={rtol}"
+    raise AssertionError(f"{kind} {what}: within rtol={rtol} but not bit-exact (the arithmetic is meant to be pinned)")
+
+
+def compare_step(ctx, mem_dev, grad_dev, mem_ref, step, beta, lr, k=None, offsets=None, ks=None, what=""):
+    """Run one step on both sides; mem_dev / mem_ref are updated in place."""
+    grad_host = [to_host(g) for g in grad_dev]
+    if offsets is None:
+        idx, red = ctx.scalecom_step(mem_dev, grad_dev, k, beta, lr, step)
+        want_idx, want_red = oracle.step(mem_ref, grad_host, k, beta, lr, step)
+    else:
+        idx, red = ctx.scalecom_step_layers(mem_dev, grad_dev, offsets, ks, beta, lr, step)
+        want_idx, want_red = oracle.step_layers(mem_ref, grad_host, offsets, ks, beta, lr, step)
+    torch.cuda.synchronize()
+    assert_same("idx", idx.cpu().numpy(), want_idx, None, f"{what} step {step}")
+    assert_same("reduced", red.cpu().numpy(), want_red, 1e-5, f"{what} step {step}")
+    for i, (m, r) in enumerate(zip(mem_dev, mem_ref)):
+        assert_same("mem", m.cpu().numpy(), r, 1e-6, f"{what} step {step} learner {i}")
+    return idx, red
+
+
+def run_workload(w: workloads.Workload, steps=None, what=None):
+    """The workload's recipe for `steps` iterations, memory carried, all outputs compared."""
+    steps = w.steps if steps is None else steps
+    gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, w.n_tensors, DEV)
+    mem = workloads.zero_memories(w, DEV)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    for step in range(steps):
+        grad = workloads.gradients(w, step, DEV)
+        print(f"[parity] {w.name} n={w.n_learners} numel={w.numel} k={w.k} step={step}", flush=True)
+        if w.n_tensors == 1:
+            compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, k=w.k, what=what or w.name)
+        else:
+            compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, offsets=w.offsets, ks=w.ks, what=what or w.name)
+        del grad
+    ctx.close()

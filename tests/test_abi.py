@@ -1,0 +1,60 @@
+"""Host-only checks of the boundary: the C-ABI library loads without a GPU, exports every
+symbol the header declares, and its pure-host entry points behave as documented."""
+import ctypes
+import os
+import re
+
+from paper_2104_11125_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "scalecom.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(scalecom_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = _declared_symbols()
+    assert {"scalecom_init", "scalecom_step", "scalecom_step_layers", "scalecom_workspace_bytes",
+            "scalecom_strerror", "scalecom_last_error", "scalecom_destroy"} <= set(names)
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_workspace_bytes_is_host_arithmetic():
+    small = binding.scalecom_workspace_bytes(1_048_576, 1)
+    large = binding.scalecom_workspace_bytes(1_000_000_000, 1)
+    layered = binding.scalecom_workspace_bytes(1_048_576, 200)
+    assert 0 < small < large and small < layered
+    assert large < 64 * 2 ** 20                       # tens of MB even for 1e9 elements
+    assert binding.scalecom_workspace_bytes(-1, 1) == 0
+    assert binding.scalecom_workspace_bytes(2 ** 31, 1) == 0     # positions are int32
+    assert binding.scalecom_workspace_bytes(10, 0) == 0
+
+
+def test_argument_checks_that_need_no_device():
+    L = binding.lib()
+    out = ctypes.c_void_p()
+    assert L.scalecom_init(None, 0, None, None, 0, 1, 10, 1, 0) == binding.SCALECOM_EINVAL
+    assert L.scalecom_init(ctypes.byref(out), 0, None, None, 0, 1, 10, 1, 0) == binding.SCALECOM_EINVAL   # no workspace
+    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 1 << 30, 65, 10, 1, 0) == binding.SCALECOM_EINVAL
+    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 16, 1, 10, 1, 0) == binding.SCALECOM_ENOMEM
+    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 1 << 30, 1, 10, 1, 7) == binding.SCALECOM_EINVAL
+    assert out.value is None
+    assert L.scalecom_step(None, None, None, 1, 1, 1, 0.5, 0.1, 0, None, None) == binding.SCALECOM_EINVAL
+    assert L.scalecom_strerror(0) == b"ok" and b"invalid" in L.scalecom_strerror(1)
+    assert L.scalecom_last_error(None) == b""
+    L.scalecom_destroy(None)
+
+
+def test_workloads_match_the_benchmark_table():
+    from paper_2104_11125_amd import workloads
+    cfg = {w.name: w for w in workloads.configs()}
+    assert cfg["tiny"].k == 10_485 and cfg["resnet50_sized"].k == 228_187
+    assert cfg["transformer_base_sized"].k == 275_000 and cfg["large_bf16"].k == 2_500_000
+    pl = cfg["per_layer"]
+    assert pl.n_tensors == 200 and len(pl.offsets) == 201 and all(64 <= b - a <= 4_194_304 for a, b in zip(pl.offsets, pl.offsets[1:]))
+    assert all(k == -(-(b - a) // 100) for k, a, b in zip(pl.ks, pl.offsets, pl.offsets[1:]))

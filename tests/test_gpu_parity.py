@@ -1,0 +1,210 @@
+"""GPU parity: the HIP library, called through its C-ABI, against the CPU oracle, element by
+element on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2104_11125_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+# ------------------------------------------------------------------ workload recipes at oracle-friendly sizes
+def test_tiny_config_full(gu):
+    gu.run_workload(workloads.by_name("tiny"))
+
+
+@pytest.mark.parametrize("numel", [1_000_003, 262_144 + 8192 * 3 + 5])
+def test_resnet_recipe_ragged(gu, numel):
+    # several supertiles (8192 positions each) and a tail that is not a multiple of 4
+    gu.run_workload(workloads.scaled(workloads.by_name("resnet50_sized"), numel, steps=3))
+
+
+def test_transformer_recipe_heavy_tails(gu):
+    gu.run_workload(workloads.scaled(workloads.by_name("transformer_base_sized"), 700_001, steps=3))
+
+
+def test_bf16_recipe(gu):
+    gu.run_workload(workloads.scaled(workloads.by_name("large_bf16"), 600_002, steps=3))
+
+
+def test_many_learners(gu):
+    gu.run_workload(workloads.scaled(workloads.by_name("tiny"), 50_001, n_learners=64, steps=2))
+
+
+def test_single_learner(gu):
+    gu.run_workload(workloads.scaled(workloads.by_name("tiny"), 70_000, n_learners=1, steps=2))
+
+
+# ------------------------------------------------------------------ per-tensor index sets
+def test_per_layer_small_odd_layout(gu):
+    w = workloads.per_layer_workload(name="per_layer_small", n_learners=5, n_tensors=40, lo=1, hi=40_000, rate=100,
+                                     steps=3, seed=77)
+    gu.run_workload(w)
+
+
+def test_per_layer_empty_and_full_segments(gu):
+    n = 3
+    sizes = [0, 1, 7, 0, 8192, 8193, 300, 2, 0]
+    ks = [0, 1, 7, 0, 1, 8193, 0, 1, 0]
+    offsets = np.concatenate([[3], 3 + np.cumsum(sizes)]).tolist()     # the first segment does not start at 0
+    numel = offsets[-1] + 5                                            # and the last one stops before the end
+    g = torch.Generator(device="cpu").manual_seed(5)
+    mem = [torch.randn(numel, generator=g).to(gu.DEV) for _ in range(n)]
+    grad = [torch.randn(numel, generator=g).to(gu.DEV) for _ in range(n)]
+    ref = [m.cpu().numpy().copy() for m in mem]
+    untouched = [m.cpu().numpy().copy() for m in mem]
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(ks), gu.DEV)
+    for step in range(3):
+        gu.compare_step(ctx, mem, grad, ref, step, 0.5, 0.25, offsets=offsets, ks=ks, what="segments")
+    for i in range(n):   # outside the segments nothing is written
+        assert np.array_equal(mem[i].cpu().numpy()[:3], untouched[i][:3])
+        assert np.array_equal(mem[i].cpu().numpy()[offsets[-1]:], untouched[i][offsets[-1]:])
+    ctx.close()
+
+
+# ------------------------------------------------------------------ degenerate and adversarial inputs
+def _adversarial(numel, kind, rng):
+    if kind == "all_equal":
+        return np.full(numel, 0.5, np.float32)
+    if kind == "two_valued":
+        return rng.choice(np.array([1.0, -1.0, 2.0, -2.0], np.float32), size=numel)
+    if kind == "zeros":
+        return np.zeros(numel, np.float32)
+    if kind == "signed_zeros":
+        return rng.choice(np.array([0.0, -0.0], np.float32), size=numel)
+    if kind == "denormals":
+        return (rng.integers(-40, 40, size=numel).astype(np.float32) * np.float32(1e-45)).astype(np.float32)
+    if kind == "few_levels":   # many ties at every level of the key
+        return rng.choice(np.array([1.0, 1.0000001, 1.0000002, 0.99999994, -1.0, 3.0], np.float32), size=numel)
+    if kind == "nonfinite":
+        x = rng.standard_normal(numel).astype(np.float32)
+        x[rng.integers(0, numel, size=max(1, numel // 50))] = np.inf
+        x[rng.integers(0, numel, size=max(1, numel // 50))] = -np.inf
+        x[rng.integers(0, numel, size=max(1, numel // 70))] = np.nan
+        return x
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind", ["all_equal", "two_valued", "zeros", "signed_zeros", "denormals", "few_levels",
+                                  "nonfinite"])
+def test_adversarial_values(gu, kind):
+    rng = np.random.default_rng(hash(kind) % 1000)
+    n = 3
+    for numel in (1, 3, 255, 256, 257, 8191, 8192, 8193, 40_003):
+        ks = sorted({0, 1, numel // 3, numel - 1, numel} - {-1})
+        ctx = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV)
+        for k in ks:
+            grads = [_adversarial(numel, kind, rng) for _ in range(n)]
+            mems = [_adversarial(numel, kind, rng) if kind != "nonfinite" else np.zeros(numel, np.float32)
+                    for _ in range(n)]
+            mem = [torch.from_numpy(m.copy()).to(gu.DEV) for m in mems]
+            grad = [torch.from_numpy(g).to(gu.DEV) for g in grads]
+            ref = [m.copy() for m in mems]
+            for step in range(2):
+                gu.compare_step(ctx, mem, grad, ref, step, 0.25, 1.0, k=k, what=f"{kind} numel={numel} k={k}")
+        ctx.close()
+
+
+def test_threshold_ties_across_tiles(gu):
+    """The threshold value repeated in every wave tile and supertile: members among the equal
+    keys are the lowest positions, wherever the tile boundaries fall."""
+    numel, n = 3 * 8192 + 777, 2
+    x = np.full(numel, 1.0, np.float32)
+    x[::5] = 2.0                                   # above the threshold
+    x[3::7] = 0.5                                  # below
+    above = int(np.count_nonzero(x == 2.0))
+    ties = int(np.count_nonzero(x == 1.0))
+    ctx = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV)
+    for take in (0, 1, 255, 256, 257, 8192, ties - 1, ties):
+        mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+        grad = [torch.from_numpy(x.copy()).to(gu.DEV), torch.from_numpy(-x).to(gu.DEV)]
+        ref = [np.zeros(numel, np.float32) for _ in range(n)]
+        gu.compare_step(ctx, mem, grad, ref, 0, 1.0, 1.0, k=above + take, what=f"ties take={take}")
+    ctx.close()
+
+
+# ------------------------------------------------------------------ behaviour of the boundary
+def test_deterministic_and_resumable(gu):
+    """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
+    continuing in a fresh context equals 4 steps in a row (memory is the only state)."""
+    w = workloads.scaled(workloads.by_name("resnet50_sized"), 123_457, n_learners=4, steps=4)
+
+    def run(first, last, mem):
+        ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV)
+        outs = []
+        for step in range(first, last):
+            idx, red = ctx.scalecom_step(mem, workloads.gradients(w, step, gu.DEV), w.k, w.beta, w.lr, step)
+            outs.append((idx.cpu().numpy().copy(), red.cpu().numpy().copy()))
+        ctx.close()
+        return outs
+
+    mem_a = workloads.zero_memories(w, gu.DEV)
+    outs_a = run(0, 4, mem_a)
+    mem_b = workloads.zero_memories(w, gu.DEV)
+    outs_b = run(0, 2, mem_b)
+    saved = [m.cpu() for m in mem_b]
+    mem_c = [s.to(gu.DEV) for s in saved]
+    outs_b += run(2, 4, mem_c)
+    for (ia, ra), (ib, rb) in zip(outs_a, outs_b):
+        assert ia.tobytes() == ib.tobytes() and ra.tobytes() == rb.tobytes()
+    for a, c in zip(mem_a, mem_c):
+        assert torch.equal(a, c)
+
+
+def test_side_stream_and_changing_k(gu):
+    """A context bound to a non-default stream; k and numel change between calls on one context."""
+    w = workloads.scaled(workloads.by_name("tiny"), 90_001, n_learners=3, steps=1)
+    stream = torch.cuda.Stream(device=gu.DEV)
+    grad = workloads.gradients(w, 0, gu.DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV, stream=stream)
+        for step, (numel, k) in enumerate([(90_001, 900), (90_001, 17), (4097, 4097), (90_001, 900), (12, 0)]):
+            mem = [torch.zeros(numel, device=gu.DEV) for _ in range(w.n_learners)]
+            g = [x[:numel].clone() for x in grad]
+            ref = [np.zeros(numel, np.float32) for _ in range(w.n_learners)]
+            stream.synchronize()
+            gu.compare_step(ctx, mem, g, ref, step, 0.5, 0.5, k=k, what=f"numel={numel} k={k}")
+        ctx.close()
+
+
+def test_argument_errors(gu):
+    numel, n = 1000, 2
+    ctx = binding.scalecom_init(numel, n, torch.float32, 2, gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    grad = [torch.ones(numel, device=gu.DEV) for _ in range(n)]
+    before = [m.clone() for m in mem]
+
+    def status(fn):
+        with pytest.raises(binding.ScaleComError) as e:
+            fn()
+        return e.value.status
+
+    E = binding.SCALECOM_EINVAL
+    assert status(lambda: ctx.scalecom_step(mem, grad, numel + 1, 0.5, 0.1, 0)) == E      # k > numel
+    assert status(lambda: ctx.scalecom_step(mem, grad, -1, 0.5, 0.1, 0)) == E
+    assert status(lambda: ctx.scalecom_step(mem, grad, 10, 0.0, 0.1, 0)) == E             # beta outside (0, 1]
+    assert status(lambda: ctx.scalecom_step(mem, grad, 10, 1.5, 0.1, 0)) == E
+    assert status(lambda: ctx.scalecom_step(mem, grad, 10, float("nan"), 0.1, 0)) == E
+    assert status(lambda: ctx.scalecom_step(mem, grad, 10, 0.5, float("inf"), 0)) == E
+    assert status(lambda: ctx.scalecom_step(mem, grad, 10, 0.5, 0.1, -1)) == E
+    assert status(lambda: ctx.scalecom_step(mem * 2, grad * 2, 10, 0.5, 0.1, 0)) == E     # more learners than the context allows
+    big = [torch.zeros(numel + 1, device=gu.DEV) for _ in range(n)]
+    assert status(lambda: ctx.scalecom_step(big, big, 10, 0.5, 0.1, 0)) == E              # numel > numel_max
+    odd = [m[1:] for m in big]                                                            # 4-byte aligned only
+    assert status(lambda: ctx.scalecom_step(odd, odd, 10, 0.5, 0.1, 0)) == E
+    assert status(lambda: ctx.scalecom_step_layers(mem, grad, [0, 600, 500], [1, 0], 0.5, 0.1, 0)) == E
+    assert status(lambda: ctx.scalecom_step_layers(mem, grad, [0, 10, 20, 30], [1, 1, 1], 0.5, 0.1, 0)) == E
+    torch.cuda.synchronize()
+    for m, b in zip(mem, before):
+        assert torch.equal(m, b)                                                          # a rejected call changes nothing
+    with pytest.raises(binding.ScaleComError):
+        binding.scalecom_init(numel, 65, torch.float32, 1, gu.DEV)
+    ctx.close()
