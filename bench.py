@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the CLT-k + low-pass error-feedback step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+A "step" is one call of scalecom_step (scalecom_step_layers for the per-layer workload): the
+whole path -- accumulate, exact top-k on the cyclic leader, gather, sum over learners,
+low-pass memory update -- over one batch of synthetic gradients that already sit in HBM.
+Memories are carried from step to step, the leader rotates with the step index.
+
+Prints ONE JSON line.  `value` is gradient elements per second (n_learners * numel / step
+time).  `roofline` is for the dominant kernel (the all-learner fused pass), timed with HIP
+events recorded by the library on its own stream inside the timed region.  `cpu_baseline` is
+the single-threaded CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(w):
+    """Bytes one step must move (stated in the design doc): read every learner's mem and grad,
+    write every mem, one extra look at the leader's (mem, grad) to find the threshold, write
+    idx + reduced values."""
+    gb = 2 if w.grad_dtype == "bf16" else 4
+    n, N, k = w.n_learners, w.numel, w.k
+    fused = n * N * (4 + gb) + n * N * 4 + k * 8
+    leader = N * (4 + gb)
+    return fused, fused + leader
+
+
+def recorded_traffic(workload_name):
+    """HBM bytes per launch of the fused kernel from the committed rocprofv3 --pmc summary
+    (line `traffic_bytes_per_launch[<workload>]: <number>`), or None if there is none."""
+    path = os.path.join(ROOT, "profiles", "k_fused_pmc.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch\[" + re.escape(workload_name) + r"\]:\s*([0-9.eE+]+)", text)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The oracle as it stands, single thread, on host copies of the first steps' inputs."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2104_11125_amd import workloads
+
+    oracle.build(force=False)
+    dev = torch.device("cuda:0")
+    mem = [np.zeros(w.numel, np.float32) for _ in range(w.n_learners)]
+    done, spent = 0, 0.0
+    while done < w.steps and (done == 0 or spent + spent / done < budget_s):
+        grad = []
+        for g in workloads.gradients(w, done, dev):
+            grad.append(g.view(torch.int16).cpu().numpy().view(np.uint16) if g.dtype == torch.bfloat16
+                        else g.cpu().numpy())
+        t0 = time.perf_counter()
+        if w.n_tensors == 1:
+            oracle.step(mem, grad, w.k, w.beta, w.lr, done)
+        else:
+            oracle.step_layers(mem, grad, w.offsets, w.ks, w.beta, w.lr, done)
+        spent += time.perf_counter() - t0
+        done += 1
+    per_step = spent / done
+    return {
+        "value": w.n_learners * w.numel / per_step,
+        "unit": "elements/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"first {done} step(s) of the full workload ({w.n_learners} learners x {w.numel} elements, "
+                  f"k={w.k}), memory carried; {per_step * 1e3:.0f} ms/step; host has {os.cpu_count()} logical cores",
+        "ms_per_step": per_step * 1e3,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50_sized")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pool", type=int, default=8, help="distinct gradient batches kept in HBM and cycled")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all learners are buffers on one MI355X); "
+              "--gpus > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2104_11125_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    w = workloads.by_name(args.workload)
+    gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, w.n_tensors, dev)
+
+    # inputs resident in HBM before the timed region: a pool of gradient batches, zero memories
+    gbytes = w.n_learners * w.numel * (2 if w.grad_dtype == "bf16" else 4)
+    pool_n = max(1, min(args.pool, args.steps + args.warmup, int(40e9 // gbytes)))
+    pool = [workloads.gradients(w, t, dev) for t in range(pool_n)]
+    mem = workloads.zero_memories(w, dev)
+    idx = torch.empty(w.k, dtype=torch.int32, device=dev)
+    red = torch.empty(w.k, dtype=torch.float32, device=dev)
+
+    def one_step(t):
+        g = pool[t % pool_n]
+        if w.n_tensors == 1:
+            ctx.scalecom_step(mem, g, w.k, w.beta, w.lr, t, idx, red)
+        else:
+            ctx.scalecom_step_layers(mem, g, w.offsets, w.ks, w.beta, w.lr, t, idx, red)
+
+    for t in range(args.warmup):
+        one_step(t)
+    torch.cuda.synchronize()
+    ctx.scalecom_timing_begin(args.steps)
+    t0 = time.perf_counter()
+    for t in range(args.warmup, args.warmup + args.steps):
+        one_step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    phases = ctx.scalecom_timing_read(args.steps)
+
+    ms_per_step = elapsed / args.steps * 1e3
+    elements = w.n_learners * w.numel
+    fused_bytes, step_bytes = algorithmic_bytes(w)
+    n_ph = len(phases)
+    phase_avg = [sum(p[j] for p in phases) / n_ph for j in range(binding.SCALECOM_N_PHASES)] if n_ph else None
+    fused_ms = phase_avg[4] if phase_avg else None
+    achieved = fused_bytes / (fused_ms * 1e-3) / 1e9 if fused_ms else None
+
+    # practical ceiling: the library's plain copy kernel over 1 GiB (read + write)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        ctx.scalecom_stream_copy(dst, src)
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    for _ in range(10):
+        ctx.scalecom_stream_copy(dst, src)
+    torch.cuda.synchronize()
+    copy_gbps = 10 * 2 * (1 << 30) / (time.perf_counter() - c0) / 1e9
+    del src, dst
+
+    out = {
+        "metric": "clt_k_gradient_elements_per_s",
+        "value": elements / (ms_per_step * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "n_learners": w.n_learners, "numel": w.numel, "k": w.k, "grad_dtype": w.grad_dtype,
+            "n_tensors": w.n_tensors, "beta": w.beta, "lr": w.lr, "gradient_pool": pool_n,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "k_fused",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS if achieved else None,
+            "traffic": recorded_traffic(w.name),
+            "algorithmic_bytes_per_launch": fused_bytes,
+            "avg_launch_ms": fused_ms,
+        },
+        "step_roofline": {
+            "algorithmic_bytes_per_step": step_bytes,
+            "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+            "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "copy_kernel_GBps": copy_gbps,
+            "phase_ms": dict(zip(["hist0_find", "collect", "refine", "tilecount_scan", "fused"], phase_avg)) if phase_avg else None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        del pool
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

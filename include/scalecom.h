@@ -22,7 +22,8 @@
  *  - Pointers marked [device] are GPU global memory of the device given to scalecom_init;
  *    pointers marked [host] are ordinary process memory, read before the call returns.
  *  - The caller owns every buffer, including the workspace; the library allocates no
- *    device memory.  It keeps a few KB of pinned host memory per context.
+ *    device memory.  Per context it keeps pinned host staging for its tile tables
+ *    (about numel_max / 1000 + 64 * n_tensors_max bytes).
  *  - All work is enqueued on the HIP stream given to scalecom_init; calls do not wait for
  *    the GPU.  Outputs are valid once that stream has reached the end of the call's work.
  *    A context must not be used from two threads at once.
@@ -117,6 +118,37 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
                                      int n_learners, int n_tensors, const int64_t* offsets,
                                      const int64_t* ks, float beta, float lr, int64_t step,
                                      int32_t* idx_out, float* reduced_vals_out);
+
+/*
+ * Optional per-phase GPU timing, for benchmarks.  Not part of the paper's method: it only
+ * records HIP events on the context's stream between the kernel groups of a step.
+ * Phases of one step, in order:
+ *   0  leader pass 1: histogram of the top 12 bits of the magnitude keys + bucket search (Eq. 2)
+ *   1  leader pass 2: per-tile counts of keys above the bucket, bucket keys copied to the
+ *      candidate list
+ *   2  remaining 19 key bits resolved on the candidate list: exact threshold and tie quota
+ *   3  per-tile counts of keys above / equal to the threshold + prefix sums
+ *   4  all-learner fused pass: gather, sum over learners, low-pass memory update (Eq. 3, 5)
+ *
+ * scalecom_timing_begin: the next max_steps (0 .. 4096) calls of scalecom_step /
+ * scalecom_step_layers on this context record their phase boundaries (later calls are not
+ * recorded).  scalecom_timing_read: waits for the stream, writes
+ * phase_ms[t * SCALECOM_N_PHASES + p] = milliseconds of phase p of recorded step t for at most
+ * capacity_steps steps, stores the number of steps written in *n_steps_out, and stops recording.
+ *   phase_ms     [host] float[capacity_steps * SCALECOM_N_PHASES]
+ *   n_steps_out  [host]
+ */
+#define SCALECOM_N_PHASES 5
+scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps);
+scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int capacity_steps, int* n_steps_out);
+
+/*
+ * Measurement aid, not part of the paper's method: copy `bytes` bytes from src to dst
+ * [device, 16-byte aligned, bytes a multiple of 16, not overlapping] with a plain streaming
+ * kernel on the context's stream.  Its bandwidth is the practical ceiling the other kernels
+ * are compared with, and its known traffic calibrates the profiler's byte counters.
+ */
+scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* src, size_t bytes);
 
 /* Static text for a status code. */
 const char* scalecom_strerror(scalecom_status status);

@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 SCALECOM_OK, SCALECOM_EINVAL, SCALECOM_ENOMEM, SCALECOM_EHIP, SCALECOM_EUNSUPPORTED = range(5)
 SCALECOM_GRAD_F32, SCALECOM_GRAD_BF16 = 0, 1
 SCALECOM_MAX_LEARNERS = 64
+SCALECOM_N_PHASES = 5
 
 _lib = None
 
@@ -45,6 +46,12 @@ def lib() -> ctypes.CDLL:
         L.scalecom_step.restype = i32
         L.scalecom_step_layers.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, f32, i64, vp, vp]
         L.scalecom_step_layers.restype = i32
+        L.scalecom_timing_begin.argtypes = [vp, i32]
+        L.scalecom_timing_begin.restype = i32
+        L.scalecom_timing_read.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
+        L.scalecom_timing_read.restype = i32
+        L.scalecom_stream_copy.argtypes = [vp, vp, vp, sz]
+        L.scalecom_stream_copy.restype = i32
         L.scalecom_strerror.argtypes = [i32]
         L.scalecom_strerror.restype = ctypes.c_char_p
         L.scalecom_last_error.argtypes = [vp]
@@ -136,6 +143,23 @@ class ScaleCom:
                                         ctypes.c_void_p(reduced_vals_out.data_ptr()))
         self._check(st)
         return idx_out, reduced_vals_out
+
+    def scalecom_timing_begin(self, max_steps: int) -> None:
+        self._check(lib().scalecom_timing_begin(self._ctx, max_steps))
+
+    def scalecom_timing_read(self, capacity_steps: int):
+        """Per-step lists of SCALECOM_N_PHASES phase durations in milliseconds."""
+        buf = (ctypes.c_float * (max(capacity_steps, 1) * SCALECOM_N_PHASES))()
+        n = ctypes.c_int(0)
+        self._check(lib().scalecom_timing_read(self._ctx, buf, capacity_steps, ctypes.byref(n)))
+        return [[buf[t * SCALECOM_N_PHASES + p] for p in range(SCALECOM_N_PHASES)] for t in range(n.value)]
+
+    def scalecom_stream_copy(self, dst: torch.Tensor, src: torch.Tensor) -> None:
+        nbytes = src.numel() * src.element_size()
+        if dst.numel() * dst.element_size() != nbytes:
+            raise ValueError("dst and src must have the same size in bytes")
+        self._check(lib().scalecom_stream_copy(self._ctx, ctypes.c_void_p(dst.data_ptr()),
+                                               ctypes.c_void_p(src.data_ptr()), nbytes))
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx:

@@ -5,14 +5,20 @@
 // Structure of one step (all on the context's stream, no host synchronisation):
 //
 //   init        zero the digit histograms and per-segment selection state
-//   hist<0..2>  leader only: x_L = fma(lr, grad_L, mem_L) is recomputed on the fly (never
-//               stored) and the 31-bit magnitude key |x_L| is histogrammed 12 + 12 + 7 bits at
-//               a time, each level restricted to the bucket the previous level chose
-//   find<0..2>  per segment: walk the histogram from the top to the bucket holding the k-th
-//               largest key; after level 2 the exact threshold key T and the number q of
-//               keys equal to T that still belong to the set are known  (Eq. 2)
-//   tilecount   leader only: per 256-element wave tile, how many keys are > T and == T
+//   hist<0>     leader only: x_L = fma(lr, grad_L, mem_L) is recomputed on the fly (never
+//               stored) and the top 12 bits of the 31-bit magnitude key |x_L| are histogrammed
+//   find<0>     per segment: walk the histogram from the top to the bucket holding the k-th
+//               largest key  (Eq. 2)
+//   collect     leader only, second and last full pass: keys above the bucket are counted per
+//               256-element wave tile; keys inside the bucket (a fraction of a percent of the
+//               vector) are copied, with their positions, into a small candidate list
+//   hist<1,2>   the remaining 12 + 7 key bits, histogrammed over the candidate list only
+//   find<1,2>   after level 2 the exact threshold key T and the number q of keys equal to T
+//               that still belong to the set are known
+//   tilecount   candidates above / equal to T are added to the per-tile counts
 //   scan        exclusive prefix of those counts over the tiles of each segment
+//               (a segment whose bucket does not fit the candidate list -- many equal keys --
+//               takes the same steps with full leader passes instead of the list)
 //   fused       every learner, one read of (mem, grad) and one write of mem:
 //               membership = key > T, or key == T and rank among equal keys (by position) < q;
 //               gather + sum over learners at the members (Eq. 3, Alg. 1 line 10), residual and
@@ -47,12 +53,21 @@ constexpr int kTilesPerSuper = 32;               // wave tiles per supertile (un
 constexpr int kSuper = kWaveTile * kTilesPerSuper;   // 8192 positions
 constexpr int kBlock = 256;                      // threads per block in the streaming kernels
 constexpr int kWaves = kBlock / kLanes;          // 4
-constexpr int kFusedTiles = 8;                   // wave tiles per block of the fused kernel
+#ifndef SC_FUSED_TILES
+#define SC_FUSED_TILES 8
+#endif
+constexpr int kFusedTiles = SC_FUSED_TILES;                   // wave tiles per block of the fused kernel
+#ifndef SC_LCHUNK
+#define SC_LCHUNK 1
+#endif
+constexpr int kLearnerChunk = SC_LCHUNK;        // learners whose loads are in flight together
 constexpr int kFusedBlocksPerSuper = kTilesPerSuper / kFusedTiles;
 
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
 constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
 constexpr int kHistGridMax = 2048;
+constexpr int kCandSlice = 512;                  // candidate slots per supertile (1/16 of its positions)
+constexpr uint32_t kModeFull = 0, kModeCand = 1;
 
 struct SegDesc {          // one per tensor (segment of the flat vector)
     int32_t begin, end;   // positions [begin, end)
@@ -74,7 +89,8 @@ struct SegState {         // selection state of one segment, written by find<>
     uint32_t T;           // threshold key (after level 2)
     uint32_t q;           // number of keys == T that are members (the lowest positions)
     uint32_t done;        // 1: empty index set, nothing to refine
-    uint32_t pad[3];
+    uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
+    uint32_t pad[2];
 };
 
 struct LearnerPtrs {
@@ -90,10 +106,27 @@ __device__ __forceinline__ uint32_t magnitude_key(float x) { return __float_as_u
 __device__ __forceinline__ float widen(float g) { return g; }
 __device__ __forceinline__ float widen(uint16_t g) { return __uint_as_float(static_cast<uint32_t>(g) << 16); }
 
-__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+#ifndef SC_NT
+#define SC_NT 1
+#endif
+typedef float vf4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t vu2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 load4(const float* p)
+{
+#if SC_NT
+    const vf4_t v = __builtin_nontemporal_load(reinterpret_cast<const vf4_t*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+#else
+    return *reinterpret_cast<const float4*>(p);
+#endif
+}
 __device__ __forceinline__ float4 load4(const uint16_t* p)
 {
+#if SC_NT
+    const vu2_t v = __builtin_nontemporal_load(reinterpret_cast<const vu2_t*>(p));
+#else
     const uint2 v = *reinterpret_cast<const uint2*>(p);
+#endif
     float4 r;
     r.x = __uint_as_float(v.x << 16);
     r.y = __uint_as_float(v.x & 0xffff0000u);
@@ -101,7 +134,16 @@ __device__ __forceinline__ float4 load4(const uint16_t* p)
     r.w = __uint_as_float(v.y & 0xffff0000u);
     return r;
 }
-__device__ __forceinline__ void store4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void store4(float* p, const float4& v)
+{
+#if SC_NT
+    vf4_t w;
+    w.x = v.x; w.y = v.y; w.z = v.z; w.w = v.w;
+    __builtin_nontemporal_store(w, reinterpret_cast<vf4_t*>(p));
+#else
+    *reinterpret_cast<float4*>(p) = v;
+#endif
+}
 
 // number of set bits of a wave-wide ballot that belong to lanes below the calling lane
 __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
@@ -191,7 +233,8 @@ __global__ void __launch_bounds__(kBlock) k_init(uint32_t* zero_from, size_t n_w
 template <typename G, int LEVEL>
 __global__ void __launch_bounds__(kBlock)
 k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-       const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state, uint32_t* __restrict__ hist)
+       const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state, uint32_t* __restrict__ hist,
+       const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt)
 {
     constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
     __shared__ uint32_t lh[NB];
@@ -205,7 +248,7 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
     int cur = -1;
     int64_t begin = 0, end = 0;
     uint32_t prefix = 0;
-    bool skip = false;
+    bool skip = false, from_list = false;
     for (int st = st_lo; st < st_hi; ++st) {
         const StDesc d = sts[st];
         if (d.seg != cur) {
@@ -226,9 +269,23 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
             if (LEVEL > 0) {
                 prefix = state[cur].prefix;
                 skip = state[cur].done != 0;
+                from_list = state[cur].mode == kModeCand;
             }
         }
         if (skip) continue;
+        if (LEVEL > 0 && from_list) {   // keys of this supertile that fell into the level-0 bucket
+            const uint32_t cnt = st_cand_cnt[st];
+            const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+            for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) {
+                const uint32_t key = slice[e].x;
+                if (LEVEL == 1) {
+                    atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
+                } else {
+                    if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
+                }
+            }
+            continue;
+        }
 #pragma unroll 2
         for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
             const int64_t p0 = static_cast<int64_t>(d.a0) + (it * kWaves + wave) * kWaveTile + lane * kVec;
@@ -279,6 +336,7 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
         s.done = s.k_rem == 0 ? 1u : 0u;
         s.T = 0xffffffffu;     // above every key: nothing is a member
         s.q = 0;
+        s.mode = kModeFull;
         if (s.done) {
             if (threadIdx.x == 0) state[seg] = s;
             return;
@@ -310,6 +368,11 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
                 const uint32_t digit = static_cast<uint32_t>(t * CH + b);
                 s.prefix = (s.prefix << BITS) | digit;
                 s.k_rem -= c;
+                if (LEVEL == 0) {
+                    // the bucket's keys go to the candidate list if its slots can hold them
+                    const uint64_t slots = static_cast<uint64_t>(segs[seg].st_count) * kCandSlice;
+                    s.mode = n <= slots ? kModeCand : kModeFull;
+                }
                 if (LEVEL == 2) {
                     s.T = s.prefix;
                     s.q = s.k_rem;
@@ -322,21 +385,97 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     }
 }
 
-// Per wave tile of the leader's vector: number of keys above the threshold and equal to it.
+// Second full pass over the leader's vector, for segments in candidate mode.  Per wave tile:
+// the number of keys above the level-0 bucket (members for sure) goes to wt_cnt; keys inside
+// the bucket are appended, with their positions, to this supertile's slice of the candidate
+// list.  A slice that overflows (bucket keys clustered in one place) sends the whole segment
+// back to full-pass mode.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+          const StDesc* __restrict__ sts, SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt,
+          uint2* __restrict__ cand, uint32_t* __restrict__ st_cand_cnt)
+{
+    const int st = blockIdx.x;
+    const StDesc d = sts[st];
+    const SegState ss = state[d.seg];
+    if (ss.done || ss.mode != kModeCand) return;
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int64_t begin = segs[d.seg].begin, end = segs[d.seg].end;
+    const uint32_t bucket = ss.prefix;
+    uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+    __shared__ uint32_t fill;
+    if (threadIdx.x == 0) fill = 0u;
+    __syncthreads();
+
+    for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+        const int wt = it * kWaves + wave;
+        const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
+        uint32_t key[4] = {0, 0, 0, 0};
+        bool ok[4] = {false, false, false, false};
+        if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+        uint32_t above = 0, mine = 0;
+        bool in[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t digit = key[c] >> (kBits1 + kBits2);
+            above += (ok[c] && digit > bucket) ? 1u : 0u;
+            in[c] = ok[c] && digit == bucket;
+            mine += in[c] ? 1u : 0u;
+        }
+        const uint32_t s2 = wave_sum(above | (mine << 16));
+        if (lane == 0) wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt] = s2 & 0xffffu;
+        const uint32_t n_in = s2 >> 16;
+        if (n_in == 0) continue;                           // wave-uniform
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&fill, n_in);
+        base = __shfl(base, 0, kLanes);
+        uint32_t rank = base;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) rank += lanes_below(__ballot(in[c]));
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (in[c]) {
+                if (rank < kCandSlice) slice[rank] = make_uint2(key[c], static_cast<uint32_t>(p0 + c));
+                ++rank;
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t n = fill;
+        st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
+        if (n > kCandSlice) state[d.seg].mode = kModeFull;   // every overflowing block stores the same value
+    }
+}
+
+// Per wave tile of the leader's vector: number of keys above the threshold (low half of the
+// packed counter) and equal to it (high half).  Full-pass mode recomputes every key; candidate
+// mode adds the listed keys to the counts that k_collect started.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
             const StDesc* __restrict__ sts, const SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt,
-            uint2* __restrict__ st_sum)
+            const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt)
 {
     const int st = blockIdx.x;
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
     const StDesc d = sts[st];
+    const SegState ss = state[d.seg];
+    const uint32_t T = ss.T;
+    if (!ss.done && ss.mode == kModeCand) {
+        const uint32_t cnt = st_cand_cnt[st];
+        const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+        for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) {
+            const uint2 ce = slice[e];
+            if (ce.x >= T) {
+                const uint32_t wt = (ce.y - static_cast<uint32_t>(d.a0)) / kWaveTile;
+                atomicAdd(&wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt], ce.x > T ? 1u : 0x10000u);
+            }
+        }
+        return;
+    }
     const int64_t begin = segs[d.seg].begin, end = segs[d.seg].end;
-    const uint32_t T = state[d.seg].T;
-    __shared__ uint32_t part[kWaves][2];
-
-    uint32_t tot_gt = 0, tot_eq = 0;
     for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
         const int wt = it * kWaves + wave;
         const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
@@ -351,30 +490,16 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                 eq += (ok[c] && key[c] == T) ? 1u : 0u;
             }
         }
-        const uint32_t s = wave_sum(gt | (eq << 16));     // at most 256 each: no carry between halves
-        if (lane == 0) wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt] = s;
-        tot_gt += s & 0xffffu;
-        tot_eq += s >> 16;
-    }
-    if (lane == 0) {
-        part[wave][0] = tot_gt;
-        part[wave][1] = tot_eq;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t a = 0, b = 0;
-        for (int w = 0; w < kWaves; ++w) {
-            a += part[w][0];
-            b += part[w][1];
-        }
-        st_sum[st] = make_uint2(a, b);
+        const uint32_t s2 = wave_sum(gt | (eq << 16));     // at most 256 each: no carry between halves
+        if (lane == 0) wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt] = s2;
     }
 }
 
-// One block per segment: exclusive prefix sums of (above, equal) over its supertiles.
+// One block per segment: exclusive prefix sums of (above, equal) over its supertiles; a
+// supertile's own total is the sum of its 32 packed tile counters.
 constexpr int kScanBlock = 1024;
 __global__ void __launch_bounds__(kScanBlock)
-k_scan(const SegDesc* __restrict__ segs, const uint2* __restrict__ st_sum, uint2* __restrict__ st_prefix)
+k_scan(const SegDesc* __restrict__ segs, const uint32_t* __restrict__ wt_cnt, uint2* __restrict__ st_prefix)
 {
     const SegDesc sd = segs[blockIdx.x];
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
@@ -382,7 +507,16 @@ k_scan(const SegDesc* __restrict__ segs, const uint2* __restrict__ st_sum, uint2
     uint2 carry = make_uint2(0, 0);
     for (int base = 0; base < sd.st_count; base += kScanBlock) {
         const int i = base + threadIdx.x;
-        uint2 v = i < sd.st_count ? st_sum[sd.st_first + i] : make_uint2(0, 0);
+        uint2 v = make_uint2(0, 0);
+        if (i < sd.st_count) {
+            const uint4* row = reinterpret_cast<const uint4*>(wt_cnt + static_cast<size_t>(sd.st_first + i) * kTilesPerSuper);
+#pragma unroll
+            for (int j = 0; j < kTilesPerSuper / 4; ++j) {
+                const uint4 w = row[j];
+                v.x += (w.x & 0xffffu) + (w.y & 0xffffu) + (w.z & 0xffffu) + (w.w & 0xffffu);
+                v.y += (w.x >> 16) + (w.y >> 16) + (w.z >> 16) + (w.w >> 16);
+            }
+        }
         uint2 inc = v;
 #pragma unroll
         for (int off = 1; off < kLanes; off <<= 1) {
@@ -484,10 +618,10 @@ k_fused(LearnerPtrs lp, int n_learners, int leader, float lr, float beta, float 
         float4 sum = make_float4(0, 0, 0, 0);
         if (any_ok) {
 #pragma unroll 1
-            for (int i0 = 0; i0 < n_learners; i0 += 4) {
-                float4 m[4], g[4];
+            for (int i0 = 0; i0 < n_learners; i0 += kLearnerChunk) {
+                float4 m[kLearnerChunk], g[kLearnerChunk];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kLearnerChunk; ++u) {
                     const int i = i0 + u;
                     if (i < n_learners && i != leader) {
                         m[u] = load_guarded(lp.mem[i], p0, begin, end, full);
@@ -495,7 +629,7 @@ k_fused(LearnerPtrs lp, int n_learners, int leader, float lr, float beta, float 
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kLearnerChunk; ++u) {
                     const int i = i0 + u;
                     if (i >= n_learners) break;
                     float4 mi, x;
@@ -537,6 +671,14 @@ k_fused(LearnerPtrs lp, int n_learners, int leader, float lr, float beta, float 
     }
 }
 
+// Plain streaming copy (16 bytes per lane per access): the yardstick the other kernels'
+// bandwidth and the profiler's byte counters are compared with.
+__global__ void __launch_bounds__(kBlock) k_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * kBlock;
+    for (size_t i = blockIdx.x * static_cast<size_t>(kBlock) + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
@@ -548,7 +690,7 @@ inline int64_t max_supertiles(int64_t numel_max, int n_tensors_max)
 }
 
 struct WsLayout {
-    size_t segs, sts, state, hist0, hist1, hist2, wt_cnt, st_sum, st_prefix, total;
+    size_t segs, sts, state, hist0, hist1, hist2, wt_cnt, st_prefix, st_cand_cnt, cand, total;
     size_t zero_words;   // state + histograms are contiguous and zeroed every step
 };
 
@@ -566,8 +708,9 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max)
     l.hist2 = o;     o = align_up(o + nt * kBins2 * sizeof(uint32_t), 256);
     l.zero_words = (o - l.state) / sizeof(uint32_t);
     l.wt_cnt = o;    o = align_up(o + nst * kTilesPerSuper * sizeof(uint32_t), 256);
-    l.st_sum = o;    o = align_up(o + nst * sizeof(uint2), 256);
     l.st_prefix = o; o = align_up(o + nst * sizeof(uint2), 256);
+    l.st_cand_cnt = o; o = align_up(o + nst * sizeof(uint32_t), 256);
+    l.cand = o;      o = align_up(o + nst * kCandSlice * sizeof(uint2), 256);
     l.total = o;
     return l;
 }
@@ -590,6 +733,9 @@ struct scalecom_ctx {
     size_t pinned_bytes = 0;
     hipEvent_t upload_done = nullptr;
     bool upload_pending = false;
+    // optional per-phase timing: events recorded on the context's stream between kernel groups
+    std::vector<hipEvent_t> prof_events;     // (SCALECOM_N_PHASES + 1) per recorded step
+    int prof_cap = 0, prof_steps = 0;
     std::string last_error;
 };
 
@@ -682,13 +828,21 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     uint32_t* hist1 = reinterpret_cast<uint32_t*>(ws + l.hist1);
     uint32_t* hist2 = reinterpret_cast<uint32_t*>(ws + l.hist2);
     uint32_t* wt_cnt = reinterpret_cast<uint32_t*>(ws + l.wt_cnt);
-    uint2* st_sum = reinterpret_cast<uint2*>(ws + l.st_sum);
+    uint32_t* st_cand_cnt = reinterpret_cast<uint32_t*>(ws + l.st_cand_cnt);
+    uint2* cand = reinterpret_cast<uint2*>(ws + l.cand);
     uint2* st_prefix = reinterpret_cast<uint2*>(ws + l.st_prefix);
     hipStream_t s = ctx->stream;
     const int n_st = ctx->n_st;
     const float* memL = lp.mem[leader];
     const G* gradL = static_cast<const G*>(lp.grad[leader]);
 
+    // phase boundaries for scalecom_timing_*: one event before the first kernel, one after each phase
+    const bool timed = ctx->prof_steps < ctx->prof_cap;
+    hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
+    auto mark = [&](int boundary) {
+        if (timed) (void)hipEventRecord(ev[boundary], s);
+    };
+    mark(0);
     // selection state and the three histogram arrays start every step at zero
     {
         const size_t words = l.zero_words;
@@ -697,16 +851,23 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     }
     if (n_st > 0) {
         const int hgrid = std::min(n_st, kHistGridMax);
-        k_hist<G, 0><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist0);
+        k_hist<G, 0><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist0, cand, st_cand_cnt);
         k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0);
-        k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist1);
+        mark(1);
+        k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt);
+        mark(2);
+        k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist1, cand, st_cand_cnt);
         k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1);
-        k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2);
+        k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2, cand, st_cand_cnt);
         k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2);
-        k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, st_sum);
-        k_scan<<<n_tensors, kScanBlock, 0, s>>>(segs, st_sum, st_prefix);
+        mark(3);
+        k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt);
+        k_scan<<<n_tensors, kScanBlock, 0, s>>>(segs, wt_cnt, st_prefix);
+        mark(4);
         k_fused<G><<<n_st * kFusedBlocksPerSuper, kBlock, 0, s>>>(lp, n_learners, leader, lr, beta, 1.0f - beta, segs,
                                                                   sts, state, wt_cnt, st_prefix, idx_out, red_out);
+        mark(5);
+        if (timed) ++ctx->prof_steps;
     }
     SC_HIP(ctx, hipGetLastError());
     return SCALECOM_OK;
@@ -829,6 +990,58 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
                        reduced_vals_out);
 }
 
+scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* src, size_t bytes)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    if (!dst || !src || bytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16)
+        return fail(ctx, SCALECOM_EINVAL, "copy needs 16-byte aligned pointers and size");
+    if (bytes == 0) return SCALECOM_OK;
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    const size_t n16 = bytes / 16;
+    const int grid = static_cast<int>(std::min<size_t>((n16 + kBlock - 1) / kBlock, 256 * 32));
+    k_copy<<<grid, kBlock, 0, ctx->stream>>>(static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
+    SC_HIP(ctx, hipGetLastError());
+    return SCALECOM_OK;
+}
+
+scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    if (max_steps < 0 || max_steps > 4096) return fail(ctx, SCALECOM_EINVAL, "max_steps out of range");
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    const size_t need = static_cast<size_t>(max_steps) * (SCALECOM_N_PHASES + 1);
+    while (ctx->prof_events.size() < need) {
+        hipEvent_t e;
+        SC_HIP(ctx, hipEventCreate(&e));
+        ctx->prof_events.push_back(e);
+    }
+    ctx->prof_cap = max_steps;
+    ctx->prof_steps = 0;
+    return SCALECOM_OK;
+}
+
+scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int capacity_steps, int* n_steps_out)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    if (!n_steps_out || capacity_steps < 0 || (capacity_steps > 0 && !phase_ms))
+        return fail(ctx, SCALECOM_EINVAL, "null argument");
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    SC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const int n = std::min(ctx->prof_steps, capacity_steps);
+    for (int t = 0; t < n; ++t) {
+        hipEvent_t* ev = &ctx->prof_events[static_cast<size_t>(t) * (SCALECOM_N_PHASES + 1)];
+        for (int p = 0; p < SCALECOM_N_PHASES; ++p)
+            SC_HIP(ctx, hipEventElapsedTime(&phase_ms[t * SCALECOM_N_PHASES + p], ev[p], ev[p + 1]));
+    }
+    *n_steps_out = n;
+    ctx->prof_cap = 0;   // recording stops until the next scalecom_timing_begin
+    ctx->prof_steps = 0;
+    return SCALECOM_OK;
+}
+
 const char* scalecom_strerror(scalecom_status status)
 {
     switch (status) {
@@ -846,11 +1059,12 @@ const char* scalecom_last_error(const scalecom_ctx* ctx) { return ctx ? ctx->las
 void scalecom_destroy(scalecom_ctx* ctx)
 {
     if (!ctx) return;
-    if (ctx->pinned || ctx->upload_done) {
+    if (ctx->pinned || ctx->upload_done || !ctx->prof_events.empty()) {
         DeviceGuard guard;
         if (guard.enter(ctx->device) == hipSuccess) {
             (void)hipStreamSynchronize(ctx->stream);
             if (ctx->upload_done) (void)hipEventDestroy(ctx->upload_done);
+            for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
             if (ctx->pinned) (void)hipHostFree(ctx->pinned);
         }
     }

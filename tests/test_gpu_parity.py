@@ -130,6 +130,23 @@ def test_threshold_ties_across_tiles(gu):
     ctx.close()
 
 
+def test_bucket_keys_clustered_in_one_place(gu):
+    """Leader vector sorted by magnitude: the keys around the threshold sit next to each other,
+    which overflows the per-supertile candidate slots and must fall back to full passes."""
+    numel, n = 40 * 8192 + 123, 3
+    rng = np.random.default_rng(99)
+    base = np.sort(np.abs(rng.standard_normal(numel).astype(np.float32)))
+    grads = [base * np.float32(1e-3), (base[::-1] * np.float32(1e-3)).copy(),
+             rng.standard_normal(numel).astype(np.float32)]
+    ctx = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    grad = [torch.from_numpy(g).to(gu.DEV) for g in grads]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    for step in range(3):                       # leaders: ascending, descending, random
+        gu.compare_step(ctx, mem, grad, ref, step, 0.5, 1.0, k=numel // 100, what="clustered")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
