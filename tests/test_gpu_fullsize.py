@@ -1,0 +1,103 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(same entry points, same buffer shapes, workspace from scalecom_workspace_bytes).
+
+Memories start from a seeded random vector (not zero) so that one checked step exercises the
+whole of Eq. 5; they never come from a previous GPU step.  The ResNet-50-sized and per-layer
+workloads are compared element by element with oracle.step / oracle.step_layers.  The two
+largest workloads do not fit the oracle's whole-step call in host memory, so the same oracle
+primitives are applied learner by learner (accumulate -> top-k on the leader -> gather ->
+reduce -> memory update): every output element is still compared.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2104_11125_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+def _random_memories(w, dev, seed):
+    gen = torch.Generator(device=dev)
+    out = []
+    for i in range(w.n_learners):
+        gen.manual_seed(seed + i)
+        out.append(torch.randn(w.numel, generator=gen, device=dev, dtype=torch.float32).mul_(2e-4))
+    return out
+
+
+def test_resnet50_sized_full(gu):
+    w = workloads.by_name("resnet50_sized")
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV)
+    mem = _random_memories(w, gu.DEV, 910)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    for step in (0, 3):                                  # leaders 0 and 3, memory carried on both sides
+        print(f"[fullsize] {w.name} step {step}", flush=True)
+        grad = workloads.gradients(w, step, gu.DEV)
+        gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, k=w.k, what=w.name)
+    ctx.close()
+
+
+def test_per_layer_full(gu):
+    w = workloads.by_name("per_layer")
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, w.n_tensors, gu.DEV)
+    mem = _random_memories(w, gu.DEV, 920)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    for step in (0, 5):
+        print(f"[fullsize] {w.name} step {step}", flush=True)
+        grad = workloads.gradients(w, step, gu.DEV)
+        gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, offsets=w.offsets, ks=w.ks, what=w.name)
+    ctx.close()
+
+
+def _streamed_parity(gu, w, step, seed):
+    """One full-size step checked learner by learner with the oracle's primitives."""
+    dev = gu.DEV
+    gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, 1, dev)
+    mem = _random_memories(w, dev, seed)
+    shared = workloads.shared_component(w, step, dev)
+    grad = [workloads.learner_gradient(w, step, i, dev, shared=shared) for i in range(w.n_learners)]
+    del shared
+    before = [m.clone() for m in mem]                    # the GPU step overwrites mem in place
+    t0 = time.time()
+    idx, red = ctx.scalecom_step(mem, grad, w.k, w.beta, w.lr, step)
+    torch.cuda.synchronize()
+    idx_h, red_h = idx.cpu().numpy(), red.cpu().numpy()
+    print(f"[fullsize] {w.name}: GPU step done in {time.time() - t0:.2f}s, checking on the host", flush=True)
+
+    leader = step % w.n_learners
+    acc = oracle.accumulate(before[leader].cpu().numpy(), gu.to_host(grad[leader]), w.lr)
+    want_idx = oracle.topk_select(acc, w.k)
+    del acc
+    print(f"[fullsize] {w.name}: oracle top-k done at {time.time() - t0:.0f}s", flush=True)
+    gu.assert_same("idx", idx_h, want_idx, None, w.name)
+    vals = []
+    for i in range(w.n_learners):
+        m_i = before[i].cpu().numpy()
+        acc = oracle.accumulate(m_i, gu.to_host(grad[i]), w.lr)
+        vals.append(oracle.gather(acc, want_idx))
+        oracle.memory_update(m_i, acc, want_idx, w.beta)
+        del acc
+        gu.assert_same("mem", mem[i].cpu().numpy(), m_i, 1e-6, f"{w.name} learner {i}")
+        del m_i
+        print(f"[fullsize] {w.name}: learner {i} memory checked at {time.time() - t0:.0f}s", flush=True)
+    gu.assert_same("reduced", red_h, oracle.reduce(vals), 1e-5, w.name)
+    ctx.close()
+
+
+def test_transformer_base_sized_full(gu):
+    _streamed_parity(gu, workloads.by_name("transformer_base_sized"), step=5, seed=930)
+
+
+def test_large_bf16_full(gu):
+    _streamed_parity(gu, workloads.by_name("large_bf16"), step=2, seed=940)
