@@ -9,7 +9,7 @@ low-pass memory update -- over one batch of synthetic gradients that already sit
 Memories are carried from step to step, the leader rotates with the step index.
 
 Prints ONE JSON line.  `value` is gradient elements per second (n_learners * numel / step
-time).  `roofline` is for the dominant kernel (the all-learner fused pass), timed with HIP
+time).  `roofline` is for the dominant kernel (the all-learner pass k_update), timed with HIP
 events recorded by the library on its own stream inside the timed region.  `cpu_baseline` is
 the single-threaded CPU oracle on a bounded sample of the same workload.
 """
@@ -35,15 +35,15 @@ def algorithmic_bytes(w):
     idx + reduced values."""
     gb = 2 if w.grad_dtype == "bf16" else 4
     n, N, k = w.n_learners, w.numel, w.k
-    fused = n * N * (4 + gb) + n * N * 4 + k * 8
+    update = n * N * (4 + gb) + n * N * 4 + k * 8      # the all-learner pass (k_update) and its outputs
     leader = N * (4 + gb)
-    return fused, fused + leader
+    return update, update + leader
 
 
 def recorded_traffic(workload_name):
     """HBM bytes per launch of the fused kernel from the committed rocprofv3 --pmc summary
     (line `traffic_bytes_per_launch[<workload>]: <number>`), or None if there is none."""
-    path = os.path.join(ROOT, "profiles", "k_fused_pmc.txt")
+    path = os.path.join(ROOT, "profiles", "k_update_pmc.txt")
     try:
         text = open(path).read()
     except OSError:
@@ -112,7 +112,7 @@ def main():
     dev = torch.device("cuda:0")
     w = workloads.by_name(args.workload)
     gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
-    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, w.n_tensors, dev)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, w.n_tensors, dev, k_max=w.k)
 
     # inputs resident in HBM before the timed region: a pool of gradient batches, zero memories
     gbytes = w.n_learners * w.numel * (2 if w.grad_dtype == "bf16" else 4)
@@ -145,7 +145,7 @@ def main():
     fused_bytes, step_bytes = algorithmic_bytes(w)
     n_ph = len(phases)
     phase_avg = [sum(p[j] for p in phases) / n_ph for j in range(binding.SCALECOM_N_PHASES)] if n_ph else None
-    fused_ms = phase_avg[4] if phase_avg else None
+    fused_ms = phase_avg[4] if phase_avg else None      # phase 4 = the all-learner pass k_update
     achieved = fused_bytes / (fused_ms * 1e-3) / 1e9 if fused_ms else None
 
     # practical ceiling: the library's plain copy kernel over 1 GiB (read + write)
@@ -180,7 +180,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "k_fused",
+            "kernel": "k_update",
             "achieved": achieved,
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
@@ -194,7 +194,7 @@ def main():
             "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
             "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "copy_kernel_GBps": copy_gbps,
-            "phase_ms": dict(zip(["hist0_find", "collect", "refine", "tilecount_scan", "fused"], phase_avg)) if phase_avg else None,
+            "phase_ms": dict(zip(["hist0_find", "collect", "refine", "counts_scan_slots", "update", "reduce"], phase_avg)) if phase_avg else None,
         },
     }
     if not args.no_cpu_baseline:

@@ -58,27 +58,30 @@ typedef enum {
 #define SCALECOM_MAX_LEARNERS 64
 
 /*
- * Bytes of device workspace needed for vectors of up to numel_max elements per learner,
- * split into at most n_tensors_max segments (1 for whole-vector use).  Pure host
- * arithmetic.  Returns 0 if an argument is out of range (numel_max < 0 or > 2^31 - 1,
- * n_tensors_max < 1).
+ * Bytes of device workspace needed for up to n_learners_max learners with vectors of up to
+ * numel_max elements each, split into at most n_tensors_max segments (1 for whole-vector
+ * use), with index sets of at most k_max positions in total per step.  Pure host arithmetic
+ * (about 0.8 * numel_max + 4 * n_learners_max * k_max + 33 KB * n_tensors_max bytes).
+ * Returns 0 if an argument is out of range (numel_max < 0 or > 2^31 - 1, n_tensors_max < 1,
+ * n_learners_max outside 1 .. SCALECOM_MAX_LEARNERS, k_max < 0 or > numel_max).
  */
-size_t scalecom_workspace_bytes(int64_t numel_max, int n_tensors_max);
+size_t scalecom_workspace_bytes(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max);
 
 /*
  * Create a context bound to one device and one stream.
  *   out             [host]   receives the context
  *   device                   HIP device ordinal
  *   hip_stream               hipStream_t on that device, as void* (NULL = the default stream)
- *   workspace       [device] at least scalecom_workspace_bytes(numel_max, n_tensors_max) bytes,
- *                            256-byte aligned; stays the caller's, must outlive the context,
- *                            contents are scratch
+ *   workspace       [device] at least scalecom_workspace_bytes(numel_max, n_tensors_max,
+ *                            n_learners_max, k_max) bytes, 256-byte aligned; stays the caller's,
+ *                            must outlive the context, contents are scratch
  *   n_learners_max           1 .. SCALECOM_MAX_LEARNERS
+ *   k_max                    0 .. numel_max: largest k (sum of ks for scalecom_step_layers) used later
  *   grad_dtype               element type of every grad buffer passed later
  * EINVAL for bad arguments, ENOMEM for a short workspace, EHIP / EUNSUPPORTED for device trouble.
  */
 scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, void* workspace,
-                              size_t workspace_bytes, int n_learners_max, int64_t numel_max,
+                              size_t workspace_bytes, int n_learners_max, int64_t numel_max, int64_t k_max,
                               int n_tensors_max, scalecom_grad_dtype grad_dtype);
 
 /*
@@ -89,7 +92,7 @@ scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, 
  *                    context's grad_dtype, 16-byte aligned (8 for bfloat16); never written
  *   n_learners       1 .. n_learners_max
  *   numel            0 .. numel_max      (0: nothing is done)
- *   k                0 .. numel          (0: the index set is empty, memories still updated)
+ *   k                0 .. min(numel, k_max)   (0: the index set is empty, memories still updated)
  *   beta             0 < beta <= 1       (Eq. 5; beta = 1 is plain error feedback)
  *   lr               finite; multiplies the gradient before it is added to the memory
  *   step             >= 0; the leader is learner step mod n_learners
@@ -108,7 +111,7 @@ scalecom_status scalecom_step(scalecom_ctx* ctx, float* const* mem, const void* 
  * the leader's x inside that segment.  The leader is the same for all segments of a step.
  *   offsets          [host] int64[n_tensors + 1], non-decreasing, offsets[0] >= 0,
  *                    offsets[n_tensors] <= numel_max; elements outside the segments are untouched
- *   ks               [host] int64[n_tensors], 0 <= ks[s] <= length of segment s
+ *   ks               [host] int64[n_tensors], 0 <= ks[s] <= length of segment s, sum <= k_max
  *   idx_out          [device] int32[sum ks]: positions in the whole vector, segment after
  *                    segment, ascending inside a segment
  *   reduced_vals_out [device] float[sum ks], paired with idx_out
@@ -124,11 +127,12 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
  * records HIP events on the context's stream between the kernel groups of a step.
  * Phases of one step, in order:
  *   0  leader pass 1: histogram of the top 12 bits of the magnitude keys + bucket search (Eq. 2)
- *   1  leader pass 2: per-tile counts of keys above the bucket, bucket keys copied to the
- *      candidate list
+ *   1  leader pass 2: keys above the bucket counted and marked as members, bucket keys copied
+ *      to the candidate list
  *   2  remaining 19 key bits resolved on the candidate list: exact threshold and tie quota
- *   3  per-tile counts of keys above / equal to the threshold + prefix sums
- *   4  all-learner fused pass: gather, sum over learners, low-pass memory update (Eq. 3, 5)
+ *   3  per-tile member counts, prefix sums, output slot of every tile, ties resolved
+ *   4  all-learner pass: accumulate, low-pass memory update, members' values staged (Eq. 3, 5)
+ *   5  sum of the staged values over learners (Alg. 1 line 10)
  *
  * scalecom_timing_begin: the next max_steps (0 .. 4096) calls of scalecom_step /
  * scalecom_step_layers on this context record their phase boundaries (later calls are not
@@ -138,7 +142,7 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
  *   phase_ms     [host] float[capacity_steps * SCALECOM_N_PHASES]
  *   n_steps_out  [host]
  */
-#define SCALECOM_N_PHASES 5
+#define SCALECOM_N_PHASES 6
 scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps);
 scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int capacity_steps, int* n_steps_out);
 

@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 SCALECOM_OK, SCALECOM_EINVAL, SCALECOM_ENOMEM, SCALECOM_EHIP, SCALECOM_EUNSUPPORTED = range(5)
 SCALECOM_GRAD_F32, SCALECOM_GRAD_BF16 = 0, 1
 SCALECOM_MAX_LEARNERS = 64
-SCALECOM_N_PHASES = 5
+SCALECOM_N_PHASES = 6
 
 _lib = None
 
@@ -38,9 +38,9 @@ def lib() -> ctypes.CDLL:
                                "(there is no fallback path)")
         L = ctypes.CDLL(_LIB_PATH)
         vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
-        L.scalecom_workspace_bytes.argtypes = [i64, i32]
+        L.scalecom_workspace_bytes.argtypes = [i64, i32, i32, i64]
         L.scalecom_workspace_bytes.restype = sz
-        L.scalecom_init.argtypes = [ctypes.POINTER(vp), i32, vp, vp, sz, i32, i64, i32, i32]
+        L.scalecom_init.argtypes = [ctypes.POINTER(vp), i32, vp, vp, sz, i32, i64, i64, i32, i32]
         L.scalecom_init.restype = i32
         L.scalecom_step.argtypes = [vp, vp, vp, i32, i64, i64, f32, f32, i64, vp, vp]
         L.scalecom_step.restype = i32
@@ -62,8 +62,8 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-def scalecom_workspace_bytes(numel_max: int, n_tensors_max: int = 1) -> int:
-    return int(lib().scalecom_workspace_bytes(numel_max, n_tensors_max))
+def scalecom_workspace_bytes(numel_max: int, n_tensors_max: int, n_learners_max: int, k_max: int) -> int:
+    return int(lib().scalecom_workspace_bytes(numel_max, n_tensors_max, n_learners_max, k_max))
 
 
 def _ptrs(tensors: Sequence[torch.Tensor]):
@@ -75,22 +75,23 @@ class ScaleCom:
 
     def __init__(self, numel_max: int, n_learners_max: int, grad_dtype: torch.dtype = torch.float32,
                  n_tensors_max: int = 1, device: Optional[torch.device] = None,
-                 stream: Optional[torch.cuda.Stream] = None):
+                 stream: Optional[torch.cuda.Stream] = None, k_max: Optional[int] = None):
         L = lib()
         self.device = torch.device(device if device is not None else "cuda:0")
         if grad_dtype not in (torch.float32, torch.bfloat16):
             raise TypeError("grad_dtype must be torch.float32 or torch.bfloat16")
         self.grad_dtype = grad_dtype
-        nbytes = scalecom_workspace_bytes(numel_max, n_tensors_max)
+        k_max = numel_max if k_max is None else k_max
+        nbytes = scalecom_workspace_bytes(numel_max, n_tensors_max, n_learners_max, k_max)
         if nbytes == 0:
-            raise ScaleComError(SCALECOM_EINVAL, "numel_max / n_tensors_max out of range")
+            raise ScaleComError(SCALECOM_EINVAL, "numel_max / n_tensors_max / n_learners_max / k_max out of range")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self._ctx = ctypes.c_void_p()
         index = self.device.index if self.device.index is not None else torch.cuda.current_device()
         st = L.scalecom_init(ctypes.byref(self._ctx), index, ctypes.c_void_p(self.stream.cuda_stream),
                              ctypes.c_void_p(self.workspace.data_ptr()), nbytes, n_learners_max, numel_max,
-                             n_tensors_max,
+                             k_max, n_tensors_max,
                              SCALECOM_GRAD_BF16 if grad_dtype == torch.bfloat16 else SCALECOM_GRAD_F32)
         if st != SCALECOM_OK:
             self._ctx = ctypes.c_void_p()
@@ -174,6 +175,7 @@ class ScaleCom:
 
 
 def scalecom_init(numel_max: int, n_learners_max: int, grad_dtype: torch.dtype = torch.float32,
-                  n_tensors_max: int = 1, device=None, stream=None) -> ScaleCom:
-    """``scalecom_init`` of the C-ABI, with the workspace taken from torch."""
-    return ScaleCom(numel_max, n_learners_max, grad_dtype, n_tensors_max, device, stream)
+                  n_tensors_max: int = 1, device=None, stream=None, k_max: Optional[int] = None) -> ScaleCom:
+    """``scalecom_init`` of the C-ABI, with the workspace taken from torch (``k_max`` defaults to
+    ``numel_max``: any k is then accepted, at the price of a larger workspace)."""
+    return ScaleCom(numel_max, n_learners_max, grad_dtype, n_tensors_max, device, stream, k_max)

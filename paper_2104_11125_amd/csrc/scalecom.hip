@@ -9,24 +9,26 @@
 //               stored) and the top 12 bits of the 31-bit magnitude key |x_L| are histogrammed
 //   find<0>     per segment: walk the histogram from the top to the bucket holding the k-th
 //               largest key  (Eq. 2)
-//   collect     leader only, second and last full pass: keys above the bucket are counted per
-//               256-element wave tile; keys inside the bucket (a fraction of a percent of the
-//               vector) are copied, with their positions, into a small candidate list
+//   collect     leader only, second and last full pass: keys above the bucket are members for
+//               sure: counted per 256-element wave tile and marked in the membership bitmask;
+//               keys inside the bucket (a fraction of a percent of the vector) are copied, with
+//               their positions, into a small candidate list
 //   hist<1,2>   the remaining 12 + 7 key bits, histogrammed over the candidate list only
 //   find<1,2>   after level 2 the exact threshold key T and the number q of keys equal to T
 //               that still belong to the set are known
-//   tilecount   candidates above / equal to T are added to the per-tile counts
-//   scan        exclusive prefix of those counts over the tiles of each segment
+//   tilecount   candidates above / equal to T are added to the per-tile counts and bitmasks
 //               (a segment whose bucket does not fit the candidate list -- many equal keys --
-//               takes the same steps with full leader passes instead of the list)
-//   fused       every learner, one read of (mem, grad) and one write of mem:
-//               membership = key > T, or key == T and rank among equal keys (by position) < q;
-//               gather + sum over learners at the members (Eq. 3, Alg. 1 line 10), residual and
-//               low-pass update for everybody (Eq. 5), index/value written at the slot given by
-//               the prefix counts, so the output is ascending by position and deterministic.
+//               takes levels 1, 2 and this step as full leader passes instead of the list)
+//   scan, slots prefix sums of the counts over tiles: first output slot of every wave tile;
+//               keys equal to T become members in position order until q are taken
+//   update      every learner, one (learner, 1024 positions) pair per block: one read of
+//               (mem, grad), one write of mem (Eq. 5); members also store x_i into a small
+//               [learner][slot] staging array and learner 0 writes the index (Eq. 3)
+//   reduce      reduced[t] = x_0[t] + x_1[t] + ... in learner order  (Alg. 1 line 10)
 //
-// Nothing here is a dense contraction, so there is no MFMA; the kernels are bound by HBM
-// traffic (fused) and by LDS atomics + HBM (hist).
+// The output is ascending by position and deterministic.  Nothing here is a dense
+// contraction, so there is no MFMA; the kernels are bound by HBM traffic (update, collect)
+// and by LDS atomics + HBM (hist<0>).
 
 #include <hip/hip_runtime.h>
 
@@ -49,19 +51,12 @@ namespace {
 constexpr int kLanes = 64;                       // wavefront width on CDNA
 constexpr int kVec = 4;                          // elements per lane per access (16 B of fp32)
 constexpr int kWaveTile = kLanes * kVec;         // 256 consecutive positions handled by one wave
-constexpr int kTilesPerSuper = 32;               // wave tiles per supertile (unit of the prefix scan)
+constexpr int kTilesPerSuper = 32;               // wave tiles per supertile
 constexpr int kSuper = kWaveTile * kTilesPerSuper;   // 8192 positions
 constexpr int kBlock = 256;                      // threads per block in the streaming kernels
 constexpr int kWaves = kBlock / kLanes;          // 4
-#ifndef SC_FUSED_TILES
-#define SC_FUSED_TILES 8
-#endif
-constexpr int kFusedTiles = SC_FUSED_TILES;                   // wave tiles per block of the fused kernel
-#ifndef SC_LCHUNK
-#define SC_LCHUNK 1
-#endif
-constexpr int kLearnerChunk = SC_LCHUNK;        // learners whose loads are in flight together
-constexpr int kFusedBlocksPerSuper = kTilesPerSuper / kFusedTiles;
+constexpr int kUpdateBlocksPerSuper = kTilesPerSuper / kWaves;   // update: one wave tile per wave
+constexpr int kChunk = 1024;                     // supertiles per chunk of the prefix scan
 
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
 constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
@@ -75,12 +70,23 @@ struct SegDesc {          // one per tensor (segment of the flat vector)
     int32_t out_base;     // first output slot of this segment
     int32_t st_first;     // first supertile
     int32_t st_count;     // number of supertiles
-    int32_t pad0, pad1;
+    int32_t chunk_first;  // first scan chunk
+    int32_t chunk_count;
 };
 
-struct StDesc {           // one per supertile
+struct StDesc {           // one per supertile; carries what the streaming kernels need of its segment
     int32_t seg;
-    int32_t a0;           // first position, a multiple of 4 (may lie up to 3 before seg.begin)
+    int32_t a0;           // first position, a multiple of 4 (may lie up to 3 before begin)
+    int32_t begin, end;   // the segment's positions [begin, end)
+    int32_t slot_end;     // one past the segment's last output slot
+    int32_t pad[3];
+};
+
+struct ChunkDesc {        // one per scan chunk: up to kChunk consecutive supertiles of one segment
+    int32_t seg;
+    int32_t st_begin;
+    int32_t st_count;
+    int32_t pad;
 };
 
 struct SegState {         // selection state of one segment, written by find<>
@@ -264,8 +270,8 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
                 __syncthreads();
             }
             cur = d.seg;
-            begin = segs[cur].begin;
-            end = segs[cur].end;
+            begin = d.begin;
+            end = d.end;
             if (LEVEL > 0) {
                 prefix = state[cur].prefix;
                 skip = state[cur].done != 0;
@@ -279,7 +285,7 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
             for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) {
                 const uint32_t key = slice[e].x;
                 if (LEVEL == 1) {
-                    atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
+                    if ((key >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
                 } else {
                     if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
                 }
@@ -385,23 +391,33 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     }
 }
 
+// Membership bitmask layout: per wave tile four 64-bit words; bit l of word c belongs to
+// position tile0 + 4*l + c, i.e. word c is the wave ballot of "element c of my lane is a member".
+__device__ __forceinline__ void store_tile_masks(uint64_t* mask, size_t tile, const uint64_t b[4])
+{
+    ulonglong2* dst = reinterpret_cast<ulonglong2*>(mask + tile * 4);
+    dst[0] = make_ulonglong2(b[0], b[1]);
+    dst[1] = make_ulonglong2(b[2], b[3]);
+}
+
 // Second full pass over the leader's vector, for segments in candidate mode.  Per wave tile:
-// the number of keys above the level-0 bucket (members for sure) goes to wt_cnt; keys inside
-// the bucket are appended, with their positions, to this supertile's slice of the candidate
-// list.  A slice that overflows (bucket keys clustered in one place) sends the whole segment
-// back to full-pass mode.
+// keys above the level-0 bucket are members for sure: their count goes to wt_cnt and their
+// ballots to the membership mask; keys inside the bucket are appended, with their positions,
+// to this supertile's slice of the candidate list.  A slice that overflows (bucket keys
+// clustered in one place) sends the whole segment back to full-pass mode.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
           const StDesc* __restrict__ sts, SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt,
-          uint2* __restrict__ cand, uint32_t* __restrict__ st_cand_cnt)
+          uint2* __restrict__ cand, uint32_t* __restrict__ st_cand_cnt, uint64_t* __restrict__ sel_mask,
+          uint64_t* __restrict__ eq_mask)
 {
     const int st = blockIdx.x;
     const StDesc d = sts[st];
     const SegState ss = state[d.seg];
     if (ss.done || ss.mode != kModeCand) return;
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
-    const int64_t begin = segs[d.seg].begin, end = segs[d.seg].end;
+    const int64_t begin = d.begin, end = d.end;
     const uint32_t bucket = ss.prefix;
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
     __shared__ uint32_t fill;
@@ -410,22 +426,30 @@ k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, c
 
     for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
         const int wt = it * kWaves + wave;
+        const size_t tile = static_cast<size_t>(st) * kTilesPerSuper + wt;
         const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
         uint32_t key[4] = {0, 0, 0, 0};
         bool ok[4] = {false, false, false, false};
         if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-        uint32_t above = 0, mine = 0;
+        uint32_t mine = 0;
         bool in[4];
+        uint64_t above[4];
+        uint32_t n_above = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const uint32_t digit = key[c] >> (kBits1 + kBits2);
-            above += (ok[c] && digit > bucket) ? 1u : 0u;
+            above[c] = __ballot(ok[c] && digit > bucket);
+            n_above += __popcll(above[c]);
             in[c] = ok[c] && digit == bucket;
             mine += in[c] ? 1u : 0u;
         }
-        const uint32_t s2 = wave_sum(above | (mine << 16));
-        if (lane == 0) wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt] = s2 & 0xffffu;
-        const uint32_t n_in = s2 >> 16;
+        if (lane == 0) {
+            wt_cnt[tile] = n_above;
+            store_tile_masks(sel_mask, tile, above);
+            const uint64_t zero[4] = {0, 0, 0, 0};
+            store_tile_masks(eq_mask, tile, zero);
+        }
+        const uint32_t n_in = wave_sum(mine);
         if (n_in == 0) continue;                           // wave-uniform
         uint32_t base = 0;
         if (lane == 0) base = atomicAdd(&fill, n_in);
@@ -450,225 +474,300 @@ k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, c
 }
 
 // Per wave tile of the leader's vector: number of keys above the threshold (low half of the
-// packed counter) and equal to it (high half).  Full-pass mode recomputes every key; candidate
-// mode adds the listed keys to the counts that k_collect started.
+// packed counter) and equal to it (high half), and the two bitmasks that go with them.
+// Full-pass mode recomputes every key; candidate mode adds the listed keys to what k_collect
+// started.  Also leaves the supertile's totals for the prefix scan.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
             const StDesc* __restrict__ sts, const SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt,
-            const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt)
+            const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt, uint64_t* __restrict__ sel_mask,
+            uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
 {
     const int st = blockIdx.x;
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
     const StDesc d = sts[st];
     const SegState ss = state[d.seg];
     const uint32_t T = ss.T;
+    const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper;
+    __shared__ uint32_t cnt[kTilesPerSuper];
+
     if (!ss.done && ss.mode == kModeCand) {
-        const uint32_t cnt = st_cand_cnt[st];
+        if (threadIdx.x < kTilesPerSuper) cnt[threadIdx.x] = wt_cnt[tile0 + threadIdx.x];
+        __syncthreads();
+        const uint32_t n = st_cand_cnt[st];
         const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-        for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) {
+        uint32_t* sel32 = reinterpret_cast<uint32_t*>(sel_mask);
+        uint32_t* eq32 = reinterpret_cast<uint32_t*>(eq_mask);
+        for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
             const uint2 ce = slice[e];
             if (ce.x >= T) {
-                const uint32_t wt = (ce.y - static_cast<uint32_t>(d.a0)) / kWaveTile;
-                atomicAdd(&wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt], ce.x > T ? 1u : 0x10000u);
+                const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
+                const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
+                const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
+                if (ce.x > T) {
+                    atomicAdd(&cnt[wt], 1u);
+                    atomicOr(&sel32[word], 1u << (l & 31));
+                } else {
+                    atomicAdd(&cnt[wt], 0x10000u);
+                    atomicOr(&eq32[word], 1u << (l & 31));
+                }
             }
         }
-        return;
-    }
-    const int64_t begin = segs[d.seg].begin, end = segs[d.seg].end;
-    for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-        const int wt = it * kWaves + wave;
-        const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
-        uint32_t gt = 0, eq = 0;
-        if (p0 < end) {
-            uint32_t key[4];
-            bool ok[4];
-            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+        __syncthreads();
+    } else {
+        const int64_t begin = d.begin, end = d.end;
+        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+            const int wt = it * kWaves + wave;
+            const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
+            uint32_t key[4] = {0, 0, 0, 0};
+            bool ok[4] = {false, false, false, false};
+            if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+            uint64_t gt[4], eq[4];
+            uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                gt += (ok[c] && key[c] > T) ? 1u : 0u;
-                eq += (ok[c] && key[c] == T) ? 1u : 0u;
+                gt[c] = __ballot(ok[c] && key[c] > T);
+                eq[c] = __ballot(ok[c] && key[c] == T);
+                n_gt += __popcll(gt[c]);
+                n_eq += __popcll(eq[c]);
+            }
+            if (lane == 0) {
+                cnt[wt] = n_gt | (n_eq << 16);             // at most 256 each
+                store_tile_masks(sel_mask, tile0 + wt, gt);
+                store_tile_masks(eq_mask, tile0 + wt, eq);
             }
         }
-        const uint32_t s2 = wave_sum(gt | (eq << 16));     // at most 256 each: no carry between halves
-        if (lane == 0) wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + wt] = s2;
+        __syncthreads();
+    }
+    if (threadIdx.x < kLanes) {
+        const uint32_t v = threadIdx.x < kTilesPerSuper ? cnt[threadIdx.x] : 0u;
+        if (threadIdx.x < kTilesPerSuper) wt_cnt[tile0 + threadIdx.x] = v;
+        const uint32_t s2 = wave_sum(v);                   // at most 8192 each: no carry between halves
+        if (threadIdx.x == 0) st_sum[st] = make_uint2(s2 & 0xffffu, s2 >> 16);
     }
 }
 
-// One block per segment: exclusive prefix sums of (above, equal) over its supertiles; a
-// supertile's own total is the sum of its 32 packed tile counters.
-constexpr int kScanBlock = 1024;
-__global__ void __launch_bounds__(kScanBlock)
-k_scan(const SegDesc* __restrict__ segs, const uint32_t* __restrict__ wt_cnt, uint2* __restrict__ st_prefix)
+// Prefix scan, level 1: one block per chunk of up to 1024 supertiles of one segment; exclusive
+// prefix of (above, equal) inside the chunk and the chunk's totals.
+__global__ void __launch_bounds__(kChunk)
+k_scan(const ChunkDesc* __restrict__ chunks, const uint2* __restrict__ st_sum, uint2* __restrict__ st_prefix,
+       uint2* __restrict__ chunk_tot)
 {
-    const SegDesc sd = segs[blockIdx.x];
+    const ChunkDesc cd = chunks[blockIdx.x];
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
-    __shared__ uint2 wtot[kScanBlock / kLanes];
-    uint2 carry = make_uint2(0, 0);
-    for (int base = 0; base < sd.st_count; base += kScanBlock) {
-        const int i = base + threadIdx.x;
-        uint2 v = make_uint2(0, 0);
-        if (i < sd.st_count) {
-            const uint4* row = reinterpret_cast<const uint4*>(wt_cnt + static_cast<size_t>(sd.st_first + i) * kTilesPerSuper);
+    __shared__ uint2 wtot[kChunk / kLanes];
+    const int i = threadIdx.x;
+    const uint2 v = i < cd.st_count ? st_sum[cd.st_begin + i] : make_uint2(0, 0);
+    uint2 inc = v;
 #pragma unroll
-            for (int j = 0; j < kTilesPerSuper / 4; ++j) {
-                const uint4 w = row[j];
-                v.x += (w.x & 0xffffu) + (w.y & 0xffffu) + (w.z & 0xffffu) + (w.w & 0xffffu);
-                v.y += (w.x >> 16) + (w.y >> 16) + (w.z >> 16) + (w.w >> 16);
-            }
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t ax = __shfl_up(inc.x, off, kLanes), ay = __shfl_up(inc.y, off, kLanes);
+        if (lane >= off) {
+            inc.x += ax;
+            inc.y += ay;
         }
-        uint2 inc = v;
-#pragma unroll
-        for (int off = 1; off < kLanes; off <<= 1) {
-            const uint32_t ax = __shfl_up(inc.x, off, kLanes), ay = __shfl_up(inc.y, off, kLanes);
-            if (lane >= off) {
-                inc.x += ax;
-                inc.y += ay;
-            }
-        }
-        if (lane == kLanes - 1) wtot[wave] = inc;
-        __syncthreads();
-        uint2 before = carry, total = carry;
-        for (int w = 0; w < kScanBlock / kLanes; ++w) {
-            const uint2 t = wtot[w];
-            if (w < wave) {
-                before.x += t.x;
-                before.y += t.y;
-            }
-            total.x += t.x;
-            total.y += t.y;
-        }
-        if (i < sd.st_count) st_prefix[sd.st_first + i] = make_uint2(before.x + inc.x - v.x, before.y + inc.y - v.y);
-        carry = total;
-        __syncthreads();
     }
+    if (lane == kLanes - 1) wtot[wave] = inc;
+    __syncthreads();
+    uint2 before = make_uint2(0, 0), total = make_uint2(0, 0);
+    for (int w = 0; w < kChunk / kLanes; ++w) {
+        const uint2 t = wtot[w];
+        if (w < wave) {
+            before.x += t.x;
+            before.y += t.y;
+        }
+        total.x += t.x;
+        total.y += t.y;
+    }
+    if (i < cd.st_count) st_prefix[cd.st_begin + i] = make_uint2(before.x + inc.x - v.x, before.y + inc.y - v.y);
+    if (i == 0) chunk_tot[blockIdx.x] = total;
 }
 
-// The all-learner pass: CLT-k gather and sum (Eq. 3, Alg. 1 line 10) and the low-pass memory
-// update (Eq. 5) in one read of (mem, grad) and one write of mem per learner.
-template <typename G>
+// Prefix scan, level 2, one wave per supertile: first output slot of each of its 32 wave tiles
+// = members in earlier chunks + earlier supertiles of the chunk + earlier tiles of the
+// supertile.  Keys equal to the threshold become members here, in position order, until the
+// segment's quota q is used up (Eq. 2 with ties resolved towards the lowest positions).
 __global__ void __launch_bounds__(kBlock)
-k_fused(LearnerPtrs lp, int n_learners, int leader, float lr, float beta, float one_minus_beta,
-        const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, const SegState* __restrict__ state,
-        const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_prefix, int32_t* __restrict__ idx_out,
-        float* __restrict__ red_out)
+k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state,
+        const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_prefix, const uint2* __restrict__ chunk_tot,
+        uint64_t* __restrict__ sel_mask, const uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ tile_slot)
 {
-    const int st = blockIdx.x / kFusedBlocksPerSuper;
-    const int part = blockIdx.x % kFusedBlocksPerSuper;
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int st = blockIdx.x * kWaves + threadIdx.x / kLanes;
+    const int lane = threadIdx.x % kLanes;
+    if (st >= n_st) return;                                 // whole wave
     const StDesc d = sts[st];
     const SegDesc sd = segs[d.seg];
-    const int64_t begin = sd.begin, end = sd.end;
-    const uint32_t T = state[d.seg].T, q = state[d.seg].q;
-    const uint2 stp = st_prefix[st];
-    const uint32_t slot_end = static_cast<uint32_t>(sd.out_base) + static_cast<uint32_t>(sd.k);
+    const uint32_t q = state[d.seg].q;
 
-#pragma unroll 1
-    for (int r = 0; r < kFusedTiles / kWaves; ++r) {
-        const int wt = part * kFusedTiles + r * kWaves + wave;
-        const int64_t tile0 = static_cast<int64_t>(d.a0) + wt * kWaveTile;
-        if (tile0 >= end) continue;                       // wave-uniform
-        const int64_t p0 = tile0 + lane * kVec;
-        const bool full = p0 >= begin && p0 + 3 < end;
-        bool ok[4];
+    // totals of the segment's earlier chunks
+    const int my_chunk = (st - sd.st_first) / kChunk;
+    uint32_t cx = 0, cy = 0;
+    for (int c = lane; c < my_chunk; c += kLanes) {
+        const uint2 t = chunk_tot[sd.chunk_first + c];
+        cx += t.x;
+        cy += t.y;
+    }
+    cx = wave_sum(cx);
+    cy = wave_sum(cy);
+    const uint2 sp = st_prefix[st];
+
+    const size_t tile = static_cast<size_t>(st) * kTilesPerSuper + lane;   // lanes 0..31 own one tile each
+    const uint32_t packed = lane < kTilesPerSuper ? wt_cnt[tile] : 0u;
+    uint32_t inc = packed;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) ok[c] = (p0 + c >= begin) && (p0 + c < end);
-        const bool any_ok = ok[0] | ok[1] | ok[2] | ok[3];
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t a = __shfl_up(inc, off, kLanes);
+        if (lane >= off) inc += a;
+    }
+    const uint32_t excl = inc - packed;                     // halves stay below 8192: no carry
+    const uint32_t gt_before = cx + sp.x + (excl & 0xffffu);
+    const uint32_t eq_before = cy + sp.y + (excl >> 16);
+    if (lane >= kTilesPerSuper) return;
+    tile_slot[tile] = static_cast<uint32_t>(sd.out_base) + gt_before + (eq_before < q ? eq_before : q);
 
-        // leader first: membership of my 4 positions
-        float4 mL = make_float4(0, 0, 0, 0), xL = mL;
-        if (any_ok) {
-            mL = load_guarded(lp.mem[leader], p0, begin, end, full);
-            const float4 gL = load_guarded(static_cast<const G*>(lp.grad[leader]), p0, begin, end, full);
-            xL = accumulate4(mL, gL, lr);
-        }
-        const uint32_t key[4] = {magnitude_key(xL.x), magnitude_key(xL.y), magnitude_key(xL.z), magnitude_key(xL.w)};
-        bool sel[4], eq[4];
+    const uint32_t own_eq = packed >> 16;
+    uint32_t take = q > eq_before ? q - eq_before : 0u;     // ties of this tile that are members
+    if (take > own_eq) take = own_eq;
+    if (take == 0) return;
+    uint64_t s4[4], e4[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            sel[c] = ok[c] && key[c] > T;
-            eq[c] = ok[c] && key[c] == T;
-        }
-
-        // members and ties in earlier tiles of this segment
-        const uint32_t packed = lane < wt ? wt_cnt[static_cast<size_t>(st) * kTilesPerSuper + lane] : 0u;
-        const uint32_t psum = wave_sum(packed);           // <= 31 * 256 per half
-        const uint32_t gt_before = stp.x + (psum & 0xffffu);
-        const uint32_t eq_before = stp.y + (psum >> 16);
-
-        // keys equal to the threshold are members while their rank by position is below q
-        if (__ballot(eq[0] | eq[1] | eq[2] | eq[3]) != 0ull) {
-            uint32_t rank = eq_before;
+    for (int c = 0; c < 4; ++c) {
+        s4[c] = sel_mask[tile * 4 + c];
+        e4[c] = eq_mask[tile * 4 + c];
+    }
+    if (take == own_eq) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) rank += lanes_below(__ballot(eq[c]));
+        for (int c = 0; c < 4; ++c) s4[c] |= e4[c];
+    } else {                                                // the one tile where the quota runs out
+        for (int l = 0; l < kLanes && take > 0; ++l) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                if (eq[c]) {
-                    sel[c] = rank < q;
-                    ++rank;
+                if (take > 0 && ((e4[c] >> l) & 1ull)) {
+                    s4[c] |= 1ull << l;
+                    --take;
                 }
-            }
-        }
-
-        // output slot of my first member: everything selected before me, by position
-        uint32_t slot = static_cast<uint32_t>(sd.out_base) + gt_before + (eq_before < q ? eq_before : q);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) slot += lanes_below(__ballot(sel[c]));
-
-        float4 sum = make_float4(0, 0, 0, 0);
-        if (any_ok) {
-#pragma unroll 1
-            for (int i0 = 0; i0 < n_learners; i0 += kLearnerChunk) {
-                float4 m[kLearnerChunk], g[kLearnerChunk];
-#pragma unroll
-                for (int u = 0; u < kLearnerChunk; ++u) {
-                    const int i = i0 + u;
-                    if (i < n_learners && i != leader) {
-                        m[u] = load_guarded(lp.mem[i], p0, begin, end, full);
-                        g[u] = load_guarded(static_cast<const G*>(lp.grad[i]), p0, begin, end, full);
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < kLearnerChunk; ++u) {
-                    const int i = i0 + u;
-                    if (i >= n_learners) break;
-                    float4 mi, x;
-                    if (i == leader) {
-                        mi = mL;
-                        x = xL;
-                    } else {
-                        mi = m[u];
-                        x = accumulate4(mi, g[u], lr);
-                    }
-                    if (i == 0) {
-                        sum = x;
-                    } else {
-                        sum.x = sum.x + x.x;
-                        sum.y = sum.y + x.y;
-                        sum.z = sum.z + x.z;
-                        sum.w = sum.w + x.w;
-                    }
-                    // Eq. 5: residual is x off the index set, 0 on it
-                    float4 out;
-                    out.x = fmaf(beta, sel[0] ? 0.0f : x.x, one_minus_beta * mi.x);
-                    out.y = fmaf(beta, sel[1] ? 0.0f : x.y, one_minus_beta * mi.y);
-                    out.z = fmaf(beta, sel[2] ? 0.0f : x.z, one_minus_beta * mi.z);
-                    out.w = fmaf(beta, sel[3] ? 0.0f : x.w, one_minus_beta * mi.w);
-                    store_guarded(lp.mem[i], p0, begin, end, full, out);
-                }
-            }
-        }
-
-        const float s4[4] = {sum.x, sum.y, sum.z, sum.w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (sel[c] && slot < slot_end) {   // the bound only matters if the counts were corrupted
-                idx_out[slot] = static_cast<int32_t>(p0 + c);
-                red_out[slot] = s4[c];
-                ++slot;
             }
         }
     }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sel_mask[tile * 4 + c] = s4[c];
+}
+
+// The all-learner pass, one (learner, 4 wave tiles) pair per block and consecutive blocks on
+// consecutive learners: accumulate (Alg. 1 line 6), low-pass memory update with the residual
+// zeroed on the index set (Eq. 5), and for members the learner's own value x_i (Eq. 3) into
+// vals[learner][slot].  Membership and slots come from the leader's bitmask and prefix
+// counts, so no learner's block reads another learner's data.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDesc* __restrict__ sts, int n_st,
+         const uint64_t* __restrict__ sel_mask, const uint32_t* __restrict__ tile_slot, float* __restrict__ vals,
+         int64_t k_total, int32_t* __restrict__ idx_out)
+{
+    // grid = (learners, groups of 4 wave tiles split over y and z): x runs fastest, so blocks that
+    // are scheduled together work on the same positions of different learners
+    const int learner = blockIdx.x;
+    const int group = blockIdx.y + blockIdx.z * gridDim.y;
+    const int st = group / kUpdateBlocksPerSuper;
+    if (st >= n_st) return;                                 // padding of the 3-d grid (whole block)
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int wt0 = (group % kUpdateBlocksPerSuper) * kWaves;   // the block's first wave tile
+    const int wt = wt0 + wave;
+    const StDesc d = sts[st];
+    const int64_t begin = d.begin, end = d.end;
+    const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
+    const bool full = p0 >= begin && p0 + 3 < end;
+    const bool any_ok = p0 + 3 >= begin && p0 < end;
+
+    // membership of the block's 4 tiles (128 bytes) and the block's first output slot: small,
+    // cache-resident, issued together with the streaming loads so that nothing waits on a
+    // second round trip.  Tiles past the end of the segment have empty masks.
+    const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper + wt0;
+    const ulonglong2* mw = reinterpret_cast<const ulonglong2*>(sel_mask + tile0 * 4);
+    ulonglong2 w[2 * kWaves];
+#pragma unroll
+    for (int j = 0; j < 2 * kWaves; ++j) w[j] = mw[j];
+    const uint32_t slot0 = tile_slot[tile0];
+
+    float* mem = lp.mem[learner];
+    const G* grad = static_cast<const G*>(lp.grad[learner]);
+    float4 m = make_float4(0, 0, 0, 0), x = m;
+    if (any_ok) {
+        m = load_guarded(mem, p0, begin, end, full);
+        const float4 g = load_guarded(grad, p0, begin, end, full);
+        x = accumulate4(m, g, lr);
+    }
+
+    // my tile's ballots, and how many members the block's earlier tiles and the whole block hold
+    uint64_t S[4] = {0, 0, 0, 0};
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int t = 0; t < kWaves; ++t) {
+        const uint32_t n = __popcll(w[2 * t].x) + __popcll(w[2 * t].y) + __popcll(w[2 * t + 1].x) + __popcll(w[2 * t + 1].y);
+        if (t < wave) before += n;
+        total += n;
+        if (t == wave) {
+            S[0] = w[2 * t].x;
+            S[1] = w[2 * t].y;
+            S[2] = w[2 * t + 1].x;
+            S[3] = w[2 * t + 1].y;
+        }
+    }
+    bool sel[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sel[c] = (S[c] >> lane) & 1ull;
+
+    if (any_ok) {
+        // Eq. 5: residual is x off the index set, 0 on it
+        float4 out;
+        out.x = fmaf(beta, sel[0] ? 0.0f : x.x, one_minus_beta * m.x);
+        out.y = fmaf(beta, sel[1] ? 0.0f : x.y, one_minus_beta * m.y);
+        out.z = fmaf(beta, sel[2] ? 0.0f : x.z, one_minus_beta * m.z);
+        out.w = fmaf(beta, sel[3] ? 0.0f : x.w, one_minus_beta * m.w);
+        store_guarded(mem, p0, begin, end, full, out);
+    }
+
+    if (total == 0) return;                                 // no member in the block's tiles (block-uniform)
+#ifdef SC_EXP_NOVALS
+    return;
+#endif
+    // The block's members occupy consecutive output slots (tiles are consecutive): compact them
+    // through LDS and write them with one contiguous store.
+    __shared__ float stage_val[kWaves * kWaveTile];
+    __shared__ int32_t stage_pos[kWaves * kWaveTile];
+    uint32_t rank = before;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) rank += lanes_below(S[c]);
+    const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (sel[c]) {
+            stage_val[rank] = xs[c];
+            if (learner == 0) stage_pos[rank] = static_cast<int32_t>(p0 + c);
+            ++rank;
+        }
+    }
+    __syncthreads();
+    const uint32_t slot_end = static_cast<uint32_t>(d.slot_end);
+    float* my_vals = vals + static_cast<size_t>(learner) * static_cast<size_t>(k_total);
+    for (uint32_t j = threadIdx.x; j < total; j += kBlock) {
+        if (slot0 + j < slot_end) {                         // the bound only matters if the counts were corrupted
+            my_vals[slot0 + j] = stage_val[j];
+            if (learner == 0) idx_out[slot0 + j] = stage_pos[j];
+        }
+    }
+}
+
+// Sum of the learners' values at the index set, learner 0 first (Alg. 1 line 10 without 1/n).
+__global__ void __launch_bounds__(kBlock)
+k_reduce(const float* __restrict__ vals, int n_learners, int64_t k_total, float* __restrict__ red_out)
+{
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (t >= k_total) return;
+    float s = vals[t];
+    for (int i = 1; i < n_learners; ++i) s = s + vals[static_cast<size_t>(i) * static_cast<size_t>(k_total) + t];
+    red_out[t] = s;
 }
 
 // Plain streaming copy (16 bytes per lane per access): the yardstick the other kernels'
@@ -689,30 +788,56 @@ inline int64_t max_supertiles(int64_t numel_max, int n_tensors_max)
     return numel_max / kSuper + 2 * static_cast<int64_t>(n_tensors_max) + 2;
 }
 
+inline int64_t max_chunks(int64_t numel_max, int n_tensors_max)
+{
+    return max_supertiles(numel_max, n_tensors_max) / kChunk + static_cast<int64_t>(n_tensors_max) + 1;
+}
+
 struct WsLayout {
-    size_t segs, sts, state, hist0, hist1, hist2, wt_cnt, st_prefix, st_cand_cnt, cand, total;
+    size_t segs, sts, chunks, state, hist0, hist1, hist2, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand,
+        sel_mask, eq_mask, tile_slot, vals, total;
     size_t zero_words;   // state + histograms are contiguous and zeroed every step
 };
 
-WsLayout layout_for(int64_t numel_max, int n_tensors_max)
+WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
 {
     const size_t nt = static_cast<size_t>(n_tensors_max);
     const size_t nst = static_cast<size_t>(max_supertiles(numel_max, n_tensors_max));
+    const size_t nch = static_cast<size_t>(max_chunks(numel_max, n_tensors_max));
+    const size_t ntile = nst * kTilesPerSuper;
     WsLayout l{};
     size_t o = 0;
-    l.segs = o;      o = align_up(o + nt * sizeof(SegDesc), 256);
-    l.sts = o;       o = align_up(o + nst * sizeof(StDesc), 256);
-    l.state = o;     o = align_up(o + nt * sizeof(SegState), 256);
-    l.hist0 = o;     o = align_up(o + nt * kBins0 * sizeof(uint32_t), 256);
-    l.hist1 = o;     o = align_up(o + nt * kBins1 * sizeof(uint32_t), 256);
-    l.hist2 = o;     o = align_up(o + nt * kBins2 * sizeof(uint32_t), 256);
+    auto take = [&](size_t bytes) {
+        const size_t at = o;
+        o = align_up(o + bytes, 256);
+        return at;
+    };
+    l.segs = take(nt * sizeof(SegDesc));
+    l.sts = take(nst * sizeof(StDesc));
+    l.chunks = take(nch * sizeof(ChunkDesc));
+    l.state = take(nt * sizeof(SegState));
+    l.hist0 = take(nt * kBins0 * sizeof(uint32_t));
+    l.hist1 = take(nt * kBins1 * sizeof(uint32_t));
+    l.hist2 = take(nt * kBins2 * sizeof(uint32_t));
     l.zero_words = (o - l.state) / sizeof(uint32_t);
-    l.wt_cnt = o;    o = align_up(o + nst * kTilesPerSuper * sizeof(uint32_t), 256);
-    l.st_prefix = o; o = align_up(o + nst * sizeof(uint2), 256);
-    l.st_cand_cnt = o; o = align_up(o + nst * sizeof(uint32_t), 256);
-    l.cand = o;      o = align_up(o + nst * kCandSlice * sizeof(uint2), 256);
+    l.wt_cnt = take(ntile * sizeof(uint32_t));
+    l.st_sum = take(nst * sizeof(uint2));
+    l.st_prefix = take(nst * sizeof(uint2));
+    l.chunk_tot = take(nch * sizeof(uint2));
+    l.st_cand_cnt = take(nst * sizeof(uint32_t));
+    l.cand = take(nst * kCandSlice * sizeof(uint2));
+    l.sel_mask = take(ntile * 4 * sizeof(uint64_t));
+    l.eq_mask = take(ntile * 4 * sizeof(uint64_t));
+    l.tile_slot = take(ntile * sizeof(uint32_t));
+    l.vals = take(static_cast<size_t>(n_learners_max) * static_cast<size_t>(k_max) * sizeof(float));
     l.total = o;
     return l;
+}
+
+bool sizes_ok(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
+{
+    return numel_max >= 0 && numel_max <= INT32_MAX && n_tensors_max >= 1 && n_learners_max >= 1 &&
+           n_learners_max <= SCALECOM_MAX_LEARNERS && k_max >= 0 && k_max <= numel_max;
 }
 
 }  // namespace
@@ -723,12 +848,13 @@ struct scalecom_ctx {
     char* ws = nullptr;
     int n_learners_max = 0;
     int64_t numel_max = 0;
+    int64_t k_max = 0;
     int n_tensors_max = 0;
     scalecom_grad_dtype gdt = SCALECOM_GRAD_F32;
     WsLayout lay{};
     // tables of the layout used last, kept on the device until the layout changes
     std::vector<int64_t> cached_offsets, cached_ks;
-    int n_st = 0;
+    int n_st = 0, n_chunks = 0;
     char* pinned = nullptr;          // staging for the table upload
     size_t pinned_bytes = 0;
     hipEvent_t upload_done = nullptr;
@@ -773,7 +899,14 @@ struct DeviceGuard {   // make the context's device current for the duration of 
     }
 };
 
-// Rebuild and upload the segment and supertile tables if the layout differs from the cached one.
+size_t pinned_bytes_for(int64_t numel_max, int n_tensors_max)
+{
+    return align_up(sizeof(SegDesc) * static_cast<size_t>(n_tensors_max), 256) +
+           align_up(sizeof(StDesc) * static_cast<size_t>(max_supertiles(numel_max, n_tensors_max)), 256) +
+           sizeof(ChunkDesc) * static_cast<size_t>(max_chunks(numel_max, n_tensors_max));
+}
+
+// Rebuild and upload the segment, supertile and chunk tables if the layout differs from the cached one.
 scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* offsets, const int64_t* ks)
 {
     const bool same = ctx->cached_ks.size() == static_cast<size_t>(n_tensors) &&
@@ -785,52 +918,73 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
         SC_HIP(ctx, hipEventSynchronize(ctx->upload_done));
         ctx->upload_pending = false;
     }
-    SegDesc* segs = reinterpret_cast<SegDesc*>(ctx->pinned);
-    const size_t st_off = align_up(sizeof(SegDesc) * static_cast<size_t>(n_tensors), 256);
-    StDesc* sts = reinterpret_cast<StDesc*>(ctx->pinned + st_off);
     const int64_t st_cap = max_supertiles(ctx->numel_max, ctx->n_tensors_max);
-    int64_t n_st = 0, out = 0;
+    const int64_t ch_cap = max_chunks(ctx->numel_max, ctx->n_tensors_max);
+    SegDesc* segs = reinterpret_cast<SegDesc*>(ctx->pinned);
+    const size_t st_off = align_up(sizeof(SegDesc) * static_cast<size_t>(ctx->n_tensors_max), 256);
+    StDesc* sts = reinterpret_cast<StDesc*>(ctx->pinned + st_off);
+    const size_t ch_off = st_off + align_up(sizeof(StDesc) * static_cast<size_t>(st_cap), 256);
+    ChunkDesc* chunks = reinterpret_cast<ChunkDesc*>(ctx->pinned + ch_off);
+    int64_t n_st = 0, n_ch = 0, out = 0;
     for (int s = 0; s < n_tensors; ++s) {
         const int64_t b = offsets[s], e = offsets[s + 1];
         const int64_t a_first = b & ~static_cast<int64_t>(kVec - 1);
         const int64_t count = e > b ? (e - a_first + kSuper - 1) / kSuper : 0;
-        if (n_st + count > st_cap) return fail(ctx, SCALECOM_ENOMEM, "supertile table overflow");
-        segs[s] = SegDesc{static_cast<int32_t>(b), static_cast<int32_t>(e), static_cast<int32_t>(ks[s]),
-                          static_cast<int32_t>(out), static_cast<int32_t>(n_st), static_cast<int32_t>(count), 0, 0};
+        const int64_t n_chunks = (count + kChunk - 1) / kChunk;
+        if (n_st + count > st_cap || n_ch + n_chunks > ch_cap) return fail(ctx, SCALECOM_ENOMEM, "tile table overflow");
+        segs[s] = SegDesc{static_cast<int32_t>(b),    static_cast<int32_t>(e),     static_cast<int32_t>(ks[s]),
+                          static_cast<int32_t>(out),  static_cast<int32_t>(n_st),  static_cast<int32_t>(count),
+                          static_cast<int32_t>(n_ch), static_cast<int32_t>(n_chunks)};
         for (int64_t j = 0; j < count; ++j)
-            sts[n_st + j] = StDesc{s, static_cast<int32_t>(a_first + j * kSuper)};
+            sts[n_st + j] = StDesc{s, static_cast<int32_t>(a_first + j * kSuper), static_cast<int32_t>(b),
+                                   static_cast<int32_t>(e), static_cast<int32_t>(out + ks[s]), {0, 0, 0}};
+        for (int64_t c = 0; c < n_chunks; ++c)
+            chunks[n_ch + c] = ChunkDesc{s, static_cast<int32_t>(n_st + c * kChunk),
+                                         static_cast<int32_t>(std::min<int64_t>(kChunk, count - c * kChunk)), 0};
         n_st += count;
+        n_ch += n_chunks;
         out += ks[s];
     }
     SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.segs, segs, sizeof(SegDesc) * n_tensors, hipMemcpyHostToDevice,
                                ctx->stream));
-    if (n_st > 0)
+    if (n_st > 0) {
         SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.sts, sts, sizeof(StDesc) * n_st, hipMemcpyHostToDevice,
                                    ctx->stream));
+        SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.chunks, chunks, sizeof(ChunkDesc) * n_ch, hipMemcpyHostToDevice,
+                                   ctx->stream));
+    }
     SC_HIP(ctx, hipEventRecord(ctx->upload_done, ctx->stream));
     ctx->upload_pending = true;
     ctx->n_st = static_cast<int>(n_st);
+    ctx->n_chunks = static_cast<int>(n_ch);
     ctx->cached_offsets.assign(offsets, offsets + n_tensors + 1);
     ctx->cached_ks.assign(ks, ks + n_tensors);
     return SCALECOM_OK;
 }
 
 template <typename G>
-scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, float beta,
-                            float lr, int leader, int32_t* idx_out, float* red_out)
+scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, int64_t k_total,
+                            float beta, float lr, int leader, int32_t* idx_out, float* red_out)
 {
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
     const SegDesc* segs = reinterpret_cast<const SegDesc*>(ws + l.segs);
     const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
+    const ChunkDesc* chunks = reinterpret_cast<const ChunkDesc*>(ws + l.chunks);
     SegState* state = reinterpret_cast<SegState*>(ws + l.state);
     uint32_t* hist0 = reinterpret_cast<uint32_t*>(ws + l.hist0);
     uint32_t* hist1 = reinterpret_cast<uint32_t*>(ws + l.hist1);
     uint32_t* hist2 = reinterpret_cast<uint32_t*>(ws + l.hist2);
     uint32_t* wt_cnt = reinterpret_cast<uint32_t*>(ws + l.wt_cnt);
+    uint2* st_sum = reinterpret_cast<uint2*>(ws + l.st_sum);
+    uint2* st_prefix = reinterpret_cast<uint2*>(ws + l.st_prefix);
+    uint2* chunk_tot = reinterpret_cast<uint2*>(ws + l.chunk_tot);
     uint32_t* st_cand_cnt = reinterpret_cast<uint32_t*>(ws + l.st_cand_cnt);
     uint2* cand = reinterpret_cast<uint2*>(ws + l.cand);
-    uint2* st_prefix = reinterpret_cast<uint2*>(ws + l.st_prefix);
+    uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
+    uint64_t* eq_mask = reinterpret_cast<uint64_t*>(ws + l.eq_mask);
+    uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
+    float* vals = reinterpret_cast<float*>(ws + l.vals);
     hipStream_t s = ctx->stream;
     const int n_st = ctx->n_st;
     const float* memL = lp.mem[leader];
@@ -854,19 +1008,31 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
         k_hist<G, 0><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist0, cand, st_cand_cnt);
         k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0);
         mark(1);
-        k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt);
+        k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask,
+                                             eq_mask);
         mark(2);
         k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist1, cand, st_cand_cnt);
         k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1);
         k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2, cand, st_cand_cnt);
         k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2);
         mark(3);
-        k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt);
-        k_scan<<<n_tensors, kScanBlock, 0, s>>>(segs, wt_cnt, st_prefix);
+        k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask,
+                                               eq_mask, st_sum);
+        k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
+        k_slots<<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot,
+                                                                sel_mask, eq_mask, tile_slot);
         mark(4);
-        k_fused<G><<<n_st * kFusedBlocksPerSuper, kBlock, 0, s>>>(lp, n_learners, leader, lr, beta, 1.0f - beta, segs,
-                                                                  sts, state, wt_cnt, st_prefix, idx_out, red_out);
+        // groups of 4 wave tiles over grid y and z (y is limited to 65535); surplus groups find no supertile
+        const int64_t groups = static_cast<int64_t>(n_st) * kUpdateBlocksPerSuper;
+        const unsigned gz = static_cast<unsigned>((groups + 65534) / 65535);
+        const unsigned gy = static_cast<unsigned>((groups + gz - 1) / gz);
+        k_update<G><<<dim3(n_learners, gy, gz), kBlock, 0, s>>>(lp, lr, beta, 1.0f - beta, sts, n_st, sel_mask, tile_slot,
+                                                               vals, k_total, idx_out);
         mark(5);
+        if (k_total > 0)
+            k_reduce<<<static_cast<unsigned>((k_total + kBlock - 1) / kBlock), kBlock, 0, s>>>(vals, n_learners, k_total,
+                                                                                               red_out);
+        mark(6);
         if (timed) ++ctx->prof_steps;
     }
     SC_HIP(ctx, hipGetLastError());
@@ -893,6 +1059,7 @@ scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* co
         if (ks[s] < 0 || ks[s] > len) return fail(ctx, SCALECOM_EINVAL, "k must satisfy 0 <= k <= segment length");
         k_total += ks[s];
     }
+    if (k_total > ctx->k_max) return fail(ctx, SCALECOM_EINVAL, "k exceeds the context's k_max");
     if (offsets[n_tensors] == offsets[0]) return SCALECOM_OK;   // nothing to do
     if (k_total > 0 && (!idx_out || !red_out)) return fail(ctx, SCALECOM_EINVAL, "null output");
     const uintptr_t galign = ctx->gdt == SCALECOM_GRAD_BF16 ? 8 : 16;
@@ -915,32 +1082,31 @@ scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* co
     if (st != SCALECOM_OK) return st;
     const int leader = static_cast<int>(step % n_learners);    // Alg. 1 line 6: CLT-k of learner mod(t, n)
     if (ctx->gdt == SCALECOM_GRAD_BF16)
-        return launch_step<uint16_t>(ctx, lp, n_learners, n_tensors, beta, lr, leader, idx_out, red_out);
-    return launch_step<float>(ctx, lp, n_learners, n_tensors, beta, lr, leader, idx_out, red_out);
+        return launch_step<uint16_t>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
+    return launch_step<float>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
 }
 
 }  // namespace
 
 extern "C" {
 
-size_t scalecom_workspace_bytes(int64_t numel_max, int n_tensors_max)
+size_t scalecom_workspace_bytes(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
 {
-    if (numel_max < 0 || numel_max > INT32_MAX || n_tensors_max < 1) return 0;
-    return layout_for(numel_max, n_tensors_max).total;
+    if (!sizes_ok(numel_max, n_tensors_max, n_learners_max, k_max)) return 0;
+    return layout_for(numel_max, n_tensors_max, n_learners_max, k_max).total;
 }
 
 scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, void* workspace,
-                              size_t workspace_bytes, int n_learners_max, int64_t numel_max, int n_tensors_max,
-                              scalecom_grad_dtype grad_dtype)
+                              size_t workspace_bytes, int n_learners_max, int64_t numel_max, int64_t k_max,
+                              int n_tensors_max, scalecom_grad_dtype grad_dtype)
 {
     if (!out) return SCALECOM_EINVAL;
     *out = nullptr;
-    if (device < 0 || n_learners_max < 1 || n_learners_max > SCALECOM_MAX_LEARNERS || numel_max < 0 ||
-        numel_max > INT32_MAX || n_tensors_max < 1 ||
+    if (device < 0 || !sizes_ok(numel_max, n_tensors_max, n_learners_max, k_max) ||
         (grad_dtype != SCALECOM_GRAD_F32 && grad_dtype != SCALECOM_GRAD_BF16))
         return SCALECOM_EINVAL;
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return SCALECOM_EINVAL;
-    const WsLayout lay = layout_for(numel_max, n_tensors_max);
+    const WsLayout lay = layout_for(numel_max, n_tensors_max, n_learners_max, k_max);
     if (workspace_bytes < lay.total) return SCALECOM_ENOMEM;
 
     scalecom_ctx* ctx = new (std::nothrow) scalecom_ctx;
@@ -950,6 +1116,7 @@ scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, 
     ctx->ws = static_cast<char*>(workspace);
     ctx->n_learners_max = n_learners_max;
     ctx->numel_max = numel_max;
+    ctx->k_max = k_max;
     ctx->n_tensors_max = n_tensors_max;
     ctx->gdt = grad_dtype;
     ctx->lay = lay;
@@ -963,8 +1130,7 @@ scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, 
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return bail(SCALECOM_EHIP);
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return bail(SCALECOM_EUNSUPPORTED);
-    ctx->pinned_bytes = align_up(sizeof(SegDesc) * static_cast<size_t>(n_tensors_max), 256) +
-                        sizeof(StDesc) * static_cast<size_t>(max_supertiles(numel_max, n_tensors_max));
+    ctx->pinned_bytes = pinned_bytes_for(numel_max, n_tensors_max);
     if (hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), ctx->pinned_bytes, hipHostMallocDefault) != hipSuccess)
         return bail(SCALECOM_ENOMEM);
     if (hipEventCreateWithFlags(&ctx->upload_done, hipEventDisableTiming) != hipSuccess) return bail(SCALECOM_EHIP);

@@ -25,24 +25,28 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_workspace_bytes_is_host_arithmetic():
-    small = binding.scalecom_workspace_bytes(1_048_576, 1)
-    large = binding.scalecom_workspace_bytes(1_000_000_000, 1)
-    layered = binding.scalecom_workspace_bytes(1_048_576, 200)
-    assert 0 < small < large and small < layered
+    small = binding.scalecom_workspace_bytes(1_048_576, 1, 4, 10_485)
+    large = binding.scalecom_workspace_bytes(1_000_000_000, 1, 8, 2_500_000)
+    layered = binding.scalecom_workspace_bytes(1_048_576, 200, 4, 10_485)
+    more_k = binding.scalecom_workspace_bytes(1_048_576, 1, 4, 1_048_576)
+    assert 0 < small < large and small < layered and small < more_k
     assert large < 1_000_000_000                      # below one byte per element
-    assert binding.scalecom_workspace_bytes(-1, 1) == 0
-    assert binding.scalecom_workspace_bytes(2 ** 31, 1) == 0     # positions are int32
-    assert binding.scalecom_workspace_bytes(10, 0) == 0
+    assert binding.scalecom_workspace_bytes(-1, 1, 1, 0) == 0
+    assert binding.scalecom_workspace_bytes(2 ** 31, 1, 1, 0) == 0     # positions are int32
+    assert binding.scalecom_workspace_bytes(10, 0, 1, 0) == 0
+    assert binding.scalecom_workspace_bytes(10, 1, 65, 0) == 0
+    assert binding.scalecom_workspace_bytes(10, 1, 1, 11) == 0
 
 
 def test_argument_checks_that_need_no_device():
     L = binding.lib()
     out = ctypes.c_void_p()
-    assert L.scalecom_init(None, 0, None, None, 0, 1, 10, 1, 0) == binding.SCALECOM_EINVAL
-    assert L.scalecom_init(ctypes.byref(out), 0, None, None, 0, 1, 10, 1, 0) == binding.SCALECOM_EINVAL   # no workspace
-    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 1 << 30, 65, 10, 1, 0) == binding.SCALECOM_EINVAL
-    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 16, 1, 10, 1, 0) == binding.SCALECOM_ENOMEM
-    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 1 << 30, 1, 10, 1, 7) == binding.SCALECOM_EINVAL
+    assert L.scalecom_init(None, 0, None, None, 0, 1, 10, 10, 1, 0) == binding.SCALECOM_EINVAL
+    assert L.scalecom_init(ctypes.byref(out), 0, None, None, 0, 1, 10, 10, 1, 0) == binding.SCALECOM_EINVAL   # no workspace
+    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 1 << 30, 65, 10, 10, 1, 0) == binding.SCALECOM_EINVAL
+    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 1 << 30, 1, 10, 11, 1, 0) == binding.SCALECOM_EINVAL
+    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 16, 1, 10, 10, 1, 0) == binding.SCALECOM_ENOMEM
+    assert L.scalecom_init(ctypes.byref(out), 0, None, ctypes.c_void_p(256), 1 << 30, 1, 10, 10, 1, 7) == binding.SCALECOM_EINVAL
     assert out.value is None
     assert L.scalecom_step(None, None, None, 1, 1, 1, 0.5, 0.1, 0, None, None) == binding.SCALECOM_EINVAL
     assert L.scalecom_strerror(0) == b"ok" and b"invalid" in L.scalecom_strerror(1)

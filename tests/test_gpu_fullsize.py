@@ -37,7 +37,7 @@ def _random_memories(w, dev, seed):
 
 def test_resnet50_sized_full(gu):
     w = workloads.by_name("resnet50_sized")
-    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV, k_max=w.k)
     mem = _random_memories(w, gu.DEV, 910)
     ref = [m.cpu().numpy().copy() for m in mem]
     for step in (0, 3):                                  # leaders 0 and 3, memory carried on both sides
@@ -49,7 +49,7 @@ def test_resnet50_sized_full(gu):
 
 def test_per_layer_full(gu):
     w = workloads.by_name("per_layer")
-    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, w.n_tensors, gu.DEV)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, w.n_tensors, gu.DEV, k_max=w.k)
     mem = _random_memories(w, gu.DEV, 920)
     ref = [m.cpu().numpy().copy() for m in mem]
     for step in (0, 5):
@@ -63,7 +63,7 @@ def _streamed_parity(gu, w, step, seed):
     """One full-size step checked learner by learner with the oracle's primitives."""
     dev = gu.DEV
     gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
-    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, 1, dev)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, 1, dev, k_max=w.k)
     mem = _random_memories(w, dev, seed)
     shared = workloads.shared_component(w, step, dev)
     grad = [workloads.learner_gradient(w, step, i, dev, shared=shared) for i in range(w.n_learners)]
