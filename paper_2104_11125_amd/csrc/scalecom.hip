@@ -89,15 +89,23 @@ struct ChunkDesc {        // one per scan chunk: up to kChunk consecutive supert
     int32_t pad;
 };
 
-struct SegState {         // selection state of one segment, written by find<>
+struct SegState {         // selection state of one segment; zeroed at the start of every step
     uint32_t prefix;      // key bits fixed so far (level 0: 12 bits, level 1: 24 bits)
     uint32_t k_rem;       // members still to be found inside the current bucket
     uint32_t T;           // threshold key (after level 2)
     uint32_t q;           // number of keys == T that are members (the lowest positions)
     uint32_t done;        // 1: empty index set, nothing to refine
     uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
-    uint32_t pad[2];
+    uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
+    uint32_t spec_overflow;   // 1: a candidate slice overflowed during the predicted pass
 };
+
+constexpr uint32_t kWindow = 5;                  // predicted window: previous bucket +- 2 digits
+// Counts of the predicted pass, per segment: [0] keys above the window, [1 + d] keys with the
+// d-th digit of the window.  Blocks add into one of kPartSlots copies (same-address atomics from
+// thousands of blocks would serialise); readers sum the copies.
+constexpr int kPartSlots = 64;
+constexpr int kPartWords = 8;
 
 struct LearnerPtrs {
     float* mem[SCALECOM_MAX_LEARNERS];
@@ -201,26 +209,77 @@ __device__ __forceinline__ float4 accumulate4(const float4& m, const float4& g, 
     return make_float4(fmaf(lr, g.x, m.x), fmaf(lr, g.y, m.y), fmaf(lr, g.z, m.z), fmaf(lr, g.w, m.w));
 }
 
-// Magnitude keys of the leader's x at the 4 positions of this lane; ok[c] tells whether the
-// position belongs to the segment.
+// The leader's (mem, grad) at the 4 positions of this lane (zeros where outside the segment).
 template <typename G>
-__device__ __forceinline__ void leader_keys(const float* mem, const G* grad, float lr, int64_t p0, int64_t begin,
-                                            int64_t end, uint32_t key[4], bool ok[4])
+__device__ __forceinline__ void leader_load(const float* mem, const G* grad, int64_t p0, int64_t begin, int64_t end,
+                                            float4& m, float4& g)
 {
+    m = make_float4(0, 0, 0, 0);
+    g = m;
+    if (p0 >= end || p0 + 3 < begin) return;
     const bool full = p0 >= begin && p0 + 3 < end;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) ok[c] = (p0 + c >= begin) && (p0 + c < end);
-    if (!(ok[0] | ok[1] | ok[2] | ok[3])) {
-        key[0] = key[1] = key[2] = key[3] = 0;
-        return;
-    }
-    const float4 m = load_guarded(mem, p0, begin, end, full);
-    const float4 g = load_guarded(grad, p0, begin, end, full);
+    m = load_guarded(mem, p0, begin, end, full);
+    g = load_guarded(grad, p0, begin, end, full);
+}
+
+// Magnitude keys of x = fma(lr, grad, mem) (Alg. 1 line 6) for those 4 positions; ok[c] tells
+// whether the position belongs to the segment.
+__device__ __forceinline__ void keys_from(const float4& m, const float4& g, float lr, int64_t p0, int64_t begin,
+                                          int64_t end, uint32_t key[4], bool ok[4])
+{
     const float4 x = accumulate4(m, g, lr);
     key[0] = magnitude_key(x.x);
     key[1] = magnitude_key(x.y);
     key[2] = magnitude_key(x.z);
     key[3] = magnitude_key(x.w);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) ok[c] = (p0 + c >= begin) && (p0 + c < end);
+}
+
+template <typename G>
+__device__ __forceinline__ void leader_keys(const float* mem, const G* grad, float lr, int64_t p0, int64_t begin,
+                                            int64_t end, uint32_t key[4], bool ok[4])
+{
+    float4 m, g;
+    leader_load(mem, grad, p0, begin, end, m, g);
+    keys_from(m, g, lr, p0, begin, end, key, ok);
+}
+
+// first and last top digit of the window collected around a predicted bucket (p = bucket + 1)
+__device__ __forceinline__ uint32_t window_lo(uint32_t p) { return p >= 3 ? p - 3 : 0u; }
+__device__ __forceinline__ uint32_t window_hi(uint32_t p) { return p + 1 < static_cast<uint32_t>(kBins0) ? p + 1 : kBins0 - 1u; }
+
+// Totals of the predicted pass for one segment: tot[0] keys above the window, tot[1 + d] keys with
+// the window's d-th digit.
+__device__ __forceinline__ void spec_totals(const uint32_t* __restrict__ part, int seg, uint32_t tot[1 + kWindow])
+{
+    const uint32_t* base = part + static_cast<size_t>(seg) * kPartSlots * kPartWords;
+#pragma unroll
+    for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = 0;
+    for (int sl = 0; sl < kPartSlots; ++sl)
+#pragma unroll
+        for (uint32_t j = 0; j <= kWindow; ++j) tot[j] += base[sl * kPartWords + j];
+}
+
+// Did the predicted single pass see the k-th largest key inside its window?  If so: the key's
+// top digit and how many members remain to be found inside that digit's bucket.  Exact: uses
+// only counts gathered over the whole segment.
+__device__ __forceinline__ bool spec_resolve(const uint32_t tot[1 + kWindow], bool overflow, uint32_t p, uint32_t k,
+                                             uint32_t& digit, uint32_t& k_rem)
+{
+    if (p == 0 || overflow || k <= tot[0]) return false;
+    const uint32_t lo = window_lo(p), hi = window_hi(p);
+    uint32_t c = tot[0];
+    for (uint32_t d = hi + 1; d-- > lo;) {
+        const uint32_t n = tot[1 + d - lo];
+        if (c + n >= k) {
+            digit = d;
+            k_rem = k - c;
+            return true;
+        }
+        c += n;
+    }
+    return false;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -233,16 +292,207 @@ __global__ void __launch_bounds__(kBlock) k_init(uint32_t* zero_from, size_t n_w
         zero_from[i] = 0u;
 }
 
-// Histogram of one digit of the leader's magnitude keys (Eq. 2: finding the k-th largest
-// magnitude), per segment.  LEVEL 0: top 12 bits of every key; LEVEL 1: next 12 bits of keys
-// whose top 12 bits equal the chosen bucket; LEVEL 2: last 7 bits of keys matching 24 bits.
+// Membership bitmask layout: per wave tile four 64-bit words; bit l of word c belongs to
+// position tile0 + 4*l + c, i.e. word c is the wave ballot of "element c of my lane is a member".
+__device__ __forceinline__ void store_tile_masks(uint64_t* mask, size_t tile, const uint64_t b[4])
+{
+    ulonglong2* dst = reinterpret_cast<ulonglong2*>(mask + tile * 4);
+    dst[0] = make_ulonglong2(b[0], b[1]);
+    dst[1] = make_ulonglong2(b[2], b[3]);
+}
+
+// The per-tile work of the "collect" pass, given the tile's keys: keys whose top digit lies above
+// `hi` are members for sure (count to wt_cnt, ballots to the membership mask); keys with a top
+// digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice
+// (slots handed out through the block's LDS counter `fill`) and, if `wc` is given, counted per
+// digit there.  Called by all lanes of a wave; n_above is the same in every lane.
+__device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], int64_t p0, uint32_t lo,
+                                             uint32_t hi, size_t tile, int lane, uint32_t* __restrict__ wt_cnt,
+                                             uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
+                                             uint2* __restrict__ slice, uint32_t* fill, uint32_t* wc, uint32_t& n_above)
+{
+    uint32_t mine = 0;
+    n_above = 0;
+    bool in[4];
+    uint64_t above[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t digit = key[c] >> (kBits1 + kBits2);
+        above[c] = __ballot(ok[c] && digit > hi);
+        n_above += __popcll(above[c]);
+        in[c] = ok[c] && digit >= lo && digit <= hi;
+        mine += in[c] ? 1u : 0u;
+    }
+    if (lane == 0) {
+        wt_cnt[tile] = n_above;
+        store_tile_masks(sel_mask, tile, above);
+        const uint64_t zero[4] = {0, 0, 0, 0};
+        store_tile_masks(eq_mask, tile, zero);
+    }
+    const uint32_t n_in = wave_sum(mine);
+    if (n_in == 0) return;                                 // wave-uniform
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(fill, n_in);
+    base = __shfl(base, 0, kLanes);
+    uint32_t rank = base;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) rank += lanes_below(__ballot(in[c]));
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (in[c]) {
+            if (rank < kCandSlice) slice[rank] = make_uint2(key[c], static_cast<uint32_t>(p0 + c));
+            if (wc) atomicAdd(&wc[(key[c] >> (kBits1 + kBits2)) - lo], 1u);
+            ++rank;
+        }
+    }
+}
+
+// First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
+// that carry a prediction of their threshold bucket (the bucket found in the previous step).
+// ONE pass, no histogram: keys whose top digit lies above a 5-digit window around the
+// prediction are members for sure (counted per tile, marked in the mask), keys inside the
+// window go to the candidate list and are counted per digit.  If the counts show afterwards
+// that the k-th largest key fell inside the window, the threshold bucket is known exactly and
+// no other full pass over the leader is needed.  The prediction only decides how much work is
+// done, never what is selected.  One block per supertile.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+            const StDesc* __restrict__ sts, SegState* __restrict__ state, uint2* __restrict__ cand,
+            uint32_t* __restrict__ st_cand_cnt, const uint32_t* __restrict__ preds, uint32_t* __restrict__ wt_cnt,
+            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part)
+{
+    const int st = blockIdx.x;
+    const StDesc d = sts[st];
+    const uint32_t p = preds[d.seg];                        // 0: none, else predicted bucket + 1
+    if (p == 0 || segs[d.seg].k == 0) return;
+    const uint32_t lo = window_lo(p), hi = window_hi(p);
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int64_t begin = d.begin, end = d.end;
+    __shared__ uint32_t fill;
+    __shared__ uint32_t acc[kPartWords];                    // [0] above the window, [1 + d] per window digit
+    if (threadIdx.x == 0) fill = 0u;
+    if (threadIdx.x < kPartWords) acc[threadIdx.x] = 0u;
+    __syncthreads();
+
+    uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+    // software pipeline: the next tile's loads are in flight while this tile is processed
+    float4 m_cur, g_cur, m_nxt, g_nxt;
+    int64_t p_cur = static_cast<int64_t>(d.a0) + wave * kWaveTile + lane * kVec;
+    leader_load(mem, grad, p_cur, begin, end, m_cur, g_cur);
+    uint32_t above_acc = 0;
+#pragma unroll 1
+    for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+        const int wt = it * kWaves + wave;
+        const int64_t p_nxt = p_cur + kWaves * kWaveTile;
+        if (it + 1 < kTilesPerSuper / kWaves) leader_load(mem, grad, p_nxt, begin, end, m_nxt, g_nxt);
+        uint32_t key[4];
+        bool ok[4];
+        keys_from(m_cur, g_cur, lr, p_cur, begin, end, key, ok);
+        uint32_t n_above;
+        collect_tile(key, ok, p_cur, lo, hi, static_cast<size_t>(st) * kTilesPerSuper + wt, lane, wt_cnt, sel_mask, eq_mask,
+                     slice, &fill, acc + 1, n_above);
+        above_acc += n_above;
+        m_cur = m_nxt;
+        g_cur = g_nxt;
+        p_cur = p_nxt;
+    }
+    if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t n = fill;
+        st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
+        if (n > kCandSlice) state[d.seg].spec_overflow = 1u;   // every overflowing block stores the same value
+    }
+    if (threadIdx.x <= kWindow) {
+        const uint32_t v = acc[threadIdx.x];
+        if (v)
+            atomicAdd(&part[(static_cast<size_t>(d.seg) * kPartSlots + st % kPartSlots) * kPartWords + threadIdx.x], v);
+    }
+}
+
+// Histogram of the top 12 key bits of the leader's vector, for the segments that need it: those
+// without a prediction, and those whose prediction failed (the k-th largest key was not inside
+// the window k_predicted collected).
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_hist0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+        const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state, uint32_t* __restrict__ hist,
+        const uint32_t* __restrict__ preds, const uint32_t* __restrict__ part)
+{
+    __shared__ uint32_t lh[kBins0];
+    __shared__ int needed;
+    for (int b = threadIdx.x; b < kBins0; b += kBlock) lh[b] = 0u;
+    __syncthreads();
+
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
+    const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
+
+    int cur = -1;
+    bool histogram = false, dirty = false;
+    auto flush = [&]() {
+        if (!dirty) return;
+        __syncthreads();
+        for (int b = threadIdx.x; b < kBins0; b += kBlock) {
+            const uint32_t v = lh[b];
+            if (v) {
+                atomicAdd(&hist[static_cast<size_t>(cur) * kBins0 + b], v);
+                lh[b] = 0u;
+            }
+        }
+        __syncthreads();
+        dirty = false;
+    };
+    for (int st = st_lo; st < st_hi; ++st) {
+        const StDesc d = sts[st];
+        if (d.seg != cur) {
+            if (cur >= 0) flush();
+            cur = d.seg;
+            if (threadIdx.x == 0) {
+                const uint32_t p = preds[cur];
+                const uint32_t k = static_cast<uint32_t>(segs[cur].k);
+                needed = k != 0;
+                if (k != 0 && p != 0) {                     // did the prediction hold?
+                    uint32_t tot[1 + kWindow], digit, k_rem;
+                    spec_totals(part, cur, tot);
+                    needed = !spec_resolve(tot, state[cur].spec_overflow != 0, p, k, digit, k_rem);
+                }
+            }
+            __syncthreads();
+            histogram = needed != 0;
+            __syncthreads();
+        }
+        if (!histogram) continue;
+        dirty = true;
+        const int64_t begin = d.begin, end = d.end;
+#pragma unroll 2
+        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+            const int64_t p0 = static_cast<int64_t>(d.a0) + (it * kWaves + wave) * kWaveTile + lane * kVec;
+            if (p0 >= end) continue;
+            uint32_t key[4];
+            bool ok[4];
+            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
+        }
+    }
+    if (cur >= 0) flush();
+}
+
+// Histogram of the next digit of the leader's magnitude keys, per segment.  LEVEL 1: bits 18..7
+// of keys whose top 12 bits equal the chosen bucket; LEVEL 2: last 7 bits of keys matching 24
+// bits.  Candidate mode reads the keys from the candidate list, full mode recomputes them from
+// the leader's vector.
 template <typename G, int LEVEL>
 __global__ void __launch_bounds__(kBlock)
-k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-       const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state, uint32_t* __restrict__ hist,
-       const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt)
+k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const StDesc* __restrict__ sts, int n_st,
+       const SegState* __restrict__ state, uint32_t* __restrict__ hist, const uint2* __restrict__ cand,
+       const uint32_t* __restrict__ st_cand_cnt)
 {
-    constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
+    static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_hist0");
+    constexpr int NB = LEVEL == 1 ? kBins1 : kBins2;
     __shared__ uint32_t lh[NB];
     for (int b = threadIdx.x; b < NB; b += kBlock) lh[b] = 0u;
     __syncthreads();
@@ -251,8 +501,15 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
     const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
     const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
 
+    auto count = [&](uint32_t key, uint32_t prefix) {
+        if (LEVEL == 1) {
+            if ((key >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
+        } else {
+            if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
+        }
+    };
+
     int cur = -1;
-    int64_t begin = 0, end = 0;
     uint32_t prefix = 0;
     bool skip = false, from_list = false;
     for (int st = st_lo; st < st_hi; ++st) {
@@ -270,28 +527,18 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
                 __syncthreads();
             }
             cur = d.seg;
-            begin = d.begin;
-            end = d.end;
-            if (LEVEL > 0) {
-                prefix = state[cur].prefix;
-                skip = state[cur].done != 0;
-                from_list = state[cur].mode == kModeCand;
-            }
+            prefix = state[cur].prefix;
+            skip = state[cur].done != 0;
+            from_list = state[cur].mode == kModeCand;
         }
         if (skip) continue;
-        if (LEVEL > 0 && from_list) {   // keys of this supertile that fell into the level-0 bucket
+        if (from_list) {   // keys of this supertile that were copied to the candidate list
             const uint32_t cnt = st_cand_cnt[st];
             const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-            for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) {
-                const uint32_t key = slice[e].x;
-                if (LEVEL == 1) {
-                    if ((key >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
-                } else {
-                    if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
-                }
-            }
+            for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) count(slice[e].x, prefix);
             continue;
         }
+        const int64_t begin = d.begin, end = d.end;
 #pragma unroll 2
         for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
             const int64_t p0 = static_cast<int64_t>(d.a0) + (it * kWaves + wave) * kWaveTile + lane * kVec;
@@ -300,16 +547,8 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
             bool ok[4];
             leader_keys(mem, grad, lr, p0, begin, end, key, ok);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (!ok[c]) continue;
-                if (LEVEL == 0) {
-                    atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
-                } else if (LEVEL == 1) {
-                    if ((key[c] >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key[c] >> kBits2) & (kBins1 - 1)], 1u);
-                } else {
-                    if ((key[c] >> kBits2) == prefix) atomicAdd(&lh[key[c] & (kBins2 - 1)], 1u);
-                }
-            }
+            for (int c = 0; c < 4; ++c)
+                if (ok[c]) count(key[c], prefix);
         }
     }
     if (cur >= 0) {
@@ -325,7 +564,8 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
 // k_rem-th largest key of the current bucket, and narrow the state to it.
 template <int LEVEL>
 __global__ void __launch_bounds__(kBlock)
-k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uint32_t* __restrict__ hist)
+k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uint32_t* __restrict__ hist,
+       uint32_t* __restrict__ preds, const uint32_t* __restrict__ part)
 {
     constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
     constexpr int BITS = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
@@ -343,10 +583,32 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
         s.T = 0xffffffffu;     // above every key: nothing is a member
         s.q = 0;
         s.mode = kModeFull;
+        s.collected = 0;
         if (s.done) {
             if (threadIdx.x == 0) state[seg] = s;
             return;
         }
+        // a prediction that held: the single pass already produced everything level 0 gives
+        __shared__ int resolved;
+        if (threadIdx.x == 0) {
+            uint32_t tot[1 + kWindow], digit, k_rem;
+            const uint32_t p = preds[seg];
+            resolved = 0;
+            if (p != 0) {
+                spec_totals(part, seg, tot);
+                if (spec_resolve(tot, s.spec_overflow != 0, p, s.k_rem, digit, k_rem)) {
+                    resolved = 1;
+                    s.prefix = digit;
+                    s.k_rem = k_rem;
+                    s.mode = kModeCand;
+                    s.collected = 1;
+                    state[seg] = s;
+                    preds[seg] = digit + 1;
+                }
+            }
+        }
+        __syncthreads();
+        if (resolved) return;
     } else if (s.done) {
         return;
     }
@@ -378,6 +640,7 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
                     // the bucket's keys go to the candidate list if its slots can hold them
                     const uint64_t slots = static_cast<uint64_t>(segs[seg].st_count) * kCandSlice;
                     s.mode = n <= slots ? kModeCand : kModeFull;
+                    preds[seg] = digit + 1;                 // prediction for the next step
                 }
                 if (LEVEL == 2) {
                     s.T = s.prefix;
@@ -391,31 +654,21 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     }
 }
 
-// Membership bitmask layout: per wave tile four 64-bit words; bit l of word c belongs to
-// position tile0 + 4*l + c, i.e. word c is the wave ballot of "element c of my lane is a member".
-__device__ __forceinline__ void store_tile_masks(uint64_t* mask, size_t tile, const uint64_t b[4])
-{
-    ulonglong2* dst = reinterpret_cast<ulonglong2*>(mask + tile * 4);
-    dst[0] = make_ulonglong2(b[0], b[1]);
-    dst[1] = make_ulonglong2(b[2], b[3]);
-}
-
-// Second full pass over the leader's vector, for segments in candidate mode.  Per wave tile:
-// keys above the level-0 bucket are members for sure: their count goes to wt_cnt and their
-// ballots to the membership mask; keys inside the bucket are appended, with their positions,
-// to this supertile's slice of the candidate list.  A slice that overflows (bucket keys
-// clustered in one place) sends the whole segment back to full-pass mode.
+// Second full pass over the leader's vector, for segments in candidate mode whose list was not
+// already filled during the histogram pass.  Per wave tile: keys above the level-0 bucket are
+// members for sure; keys inside the bucket go to this supertile's slice of the candidate list.
+// A slice that overflows (bucket keys clustered in one place) sends the whole segment back to
+// full-pass mode.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
-k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-          const StDesc* __restrict__ sts, SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt,
-          uint2* __restrict__ cand, uint32_t* __restrict__ st_cand_cnt, uint64_t* __restrict__ sel_mask,
-          uint64_t* __restrict__ eq_mask)
+k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const StDesc* __restrict__ sts,
+          SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt, uint2* __restrict__ cand,
+          uint32_t* __restrict__ st_cand_cnt, uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask)
 {
     const int st = blockIdx.x;
     const StDesc d = sts[st];
     const SegState ss = state[d.seg];
-    if (ss.done || ss.mode != kModeCand) return;
+    if (ss.done || ss.mode != kModeCand || ss.collected) return;
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
     const int64_t begin = d.begin, end = d.end;
     const uint32_t bucket = ss.prefix;
@@ -426,44 +679,13 @@ k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, c
 
     for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
         const int wt = it * kWaves + wave;
-        const size_t tile = static_cast<size_t>(st) * kTilesPerSuper + wt;
         const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
         uint32_t key[4] = {0, 0, 0, 0};
         bool ok[4] = {false, false, false, false};
         if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-        uint32_t mine = 0;
-        bool in[4];
-        uint64_t above[4];
-        uint32_t n_above = 0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t digit = key[c] >> (kBits1 + kBits2);
-            above[c] = __ballot(ok[c] && digit > bucket);
-            n_above += __popcll(above[c]);
-            in[c] = ok[c] && digit == bucket;
-            mine += in[c] ? 1u : 0u;
-        }
-        if (lane == 0) {
-            wt_cnt[tile] = n_above;
-            store_tile_masks(sel_mask, tile, above);
-            const uint64_t zero[4] = {0, 0, 0, 0};
-            store_tile_masks(eq_mask, tile, zero);
-        }
-        const uint32_t n_in = wave_sum(mine);
-        if (n_in == 0) continue;                           // wave-uniform
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(&fill, n_in);
-        base = __shfl(base, 0, kLanes);
-        uint32_t rank = base;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) rank += lanes_below(__ballot(in[c]));
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (in[c]) {
-                if (rank < kCandSlice) slice[rank] = make_uint2(key[c], static_cast<uint32_t>(p0 + c));
-                ++rank;
-            }
-        }
+        uint32_t n_above;
+        collect_tile(key, ok, p0, bucket, bucket, static_cast<size_t>(st) * kTilesPerSuper + wt, lane, wt_cnt, sel_mask,
+                     eq_mask, slice, &fill, nullptr, n_above);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -794,7 +1016,7 @@ inline int64_t max_chunks(int64_t numel_max, int n_tensors_max)
 }
 
 struct WsLayout {
-    size_t segs, sts, chunks, state, hist0, hist1, hist2, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand,
+    size_t segs, sts, chunks, preds, state, part, hist0, hist1, hist2, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand,
         sel_mask, eq_mask, tile_slot, vals, total;
     size_t zero_words;   // state + histograms are contiguous and zeroed every step
 };
@@ -815,7 +1037,9 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.segs = take(nt * sizeof(SegDesc));
     l.sts = take(nst * sizeof(StDesc));
     l.chunks = take(nch * sizeof(ChunkDesc));
+    l.preds = take(nt * sizeof(uint32_t));
     l.state = take(nt * sizeof(SegState));
+    l.part = take(nt * kPartSlots * kPartWords * sizeof(uint32_t));
     l.hist0 = take(nt * kBins0 * sizeof(uint32_t));
     l.hist1 = take(nt * kBins1 * sizeof(uint32_t));
     l.hist2 = take(nt * kBins2 * sizeof(uint32_t));
@@ -953,6 +1177,9 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
         SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.chunks, chunks, sizeof(ChunkDesc) * n_ch, hipMemcpyHostToDevice,
                                    ctx->stream));
     }
+    // predictions of the previous layout's buckets mean nothing for this one
+    k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds),
+                                          static_cast<size_t>(ctx->n_tensors_max));
     SC_HIP(ctx, hipEventRecord(ctx->upload_done, ctx->stream));
     ctx->upload_pending = true;
     ctx->n_st = static_cast<int>(n_st);
@@ -972,6 +1199,8 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
     const ChunkDesc* chunks = reinterpret_cast<const ChunkDesc*>(ws + l.chunks);
     SegState* state = reinterpret_cast<SegState*>(ws + l.state);
+    uint32_t* preds = reinterpret_cast<uint32_t*>(ws + l.preds);
+    uint32_t* part = reinterpret_cast<uint32_t*>(ws + l.part);
     uint32_t* hist0 = reinterpret_cast<uint32_t*>(ws + l.hist0);
     uint32_t* hist1 = reinterpret_cast<uint32_t*>(ws + l.hist1);
     uint32_t* hist2 = reinterpret_cast<uint32_t*>(ws + l.hist2);
@@ -1005,16 +1234,17 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     }
     if (n_st > 0) {
         const int hgrid = std::min(n_st, kHistGridMax);
-        k_hist<G, 0><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist0, cand, st_cand_cnt);
-        k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0);
+        k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, cand, st_cand_cnt, preds, wt_cnt,
+                                               sel_mask, eq_mask, part);
+        k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist0, preds, part);
+        k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part);
         mark(1);
-        k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask,
-                                             eq_mask);
+        k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask);
         mark(2);
-        k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist1, cand, st_cand_cnt);
-        k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1);
-        k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2, cand, st_cand_cnt);
-        k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2);
+        k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt);
+        k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part);
+        k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt);
+        k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part);
         mark(3);
         k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask,
                                                eq_mask, st_sum);
