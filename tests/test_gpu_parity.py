@@ -147,6 +147,45 @@ def test_bucket_keys_clustered_in_one_place(gu):
     ctx.close()
 
 
+def test_threshold_jumps_between_steps(gu):
+    """The library predicts each step's threshold bucket from the previous step (same context,
+    same layout) to save a pass over the leader; the prediction must never change the result.
+    Gradient scale and lr jump by orders of magnitude from step to step, so predictions miss,
+    hit, and land just inside / outside their window."""
+    w = workloads.scaled(workloads.by_name("resnet50_sized"), 300_007, n_learners=3, steps=1)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV)
+    mem = workloads.zero_memories(w, gu.DEV)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    base = workloads.gradients(w, 0, gu.DEV)
+    scales = [1.0, 1.0, 100.0, 1.04, 1.0, 1e-3, 1.09, 0.92, 1.2, 0.8, 1e4, 1.0]
+    for step, sc in enumerate(scales):
+        grad = [g * sc for g in base]
+        lr = 0.1 if step % 5 else 1.0
+        gu.compare_step(ctx, mem, grad, ref, step, 0.5, lr, k=w.k, what=f"scale {sc}")
+    ctx.close()
+
+
+def test_per_layer_predictions(gu):
+    """Per-tensor mode keeps one prediction per tensor; tensors' thresholds move independently."""
+    w = workloads.per_layer_workload(name="per_layer_pred", n_learners=3, n_tensors=25, lo=8, hi=60_000, rate=50,
+                                     steps=1, seed=78)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, w.n_tensors, gu.DEV)
+    mem = workloads.zero_memories(w, gu.DEV)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    base = workloads.gradients(w, 0, gu.DEV)
+    g = torch.Generator(device="cpu").manual_seed(3)
+    for step in range(6):
+        # every tensor gets its own scale factor each step
+        factors = torch.exp(torch.randn(w.n_tensors, generator=g) * (0.05 if step % 2 else 2.0))
+        scale = torch.ones(w.numel)
+        for t in range(w.n_tensors):
+            scale[w.offsets[t]:w.offsets[t + 1]] = factors[t]
+        scale = scale.to(gu.DEV)
+        grad = [b * scale for b in base]
+        gu.compare_step(ctx, mem, grad, ref, step, 0.3, 0.5, offsets=w.offsets, ks=w.ks, what=f"step {step}")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
@@ -212,6 +251,9 @@ def test_argument_errors(gu):
     assert status(lambda: ctx.scalecom_step(mem, grad, 10, float("nan"), 0.1, 0)) == E
     assert status(lambda: ctx.scalecom_step(mem, grad, 10, 0.5, float("inf"), 0)) == E
     assert status(lambda: ctx.scalecom_step(mem, grad, 10, 0.5, 0.1, -1)) == E
+    small = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV, k_max=5)
+    assert status(lambda: small.scalecom_step(mem, grad, 6, 0.5, 0.1, 0)) == E           # k > k_max of the context
+    small.close()
     assert status(lambda: ctx.scalecom_step(mem * 2, grad * 2, 10, 0.5, 0.1, 0)) == E     # more learners than the context allows
     big = [torch.zeros(numel + 1, device=gu.DEV) for _ in range(n)]
     assert status(lambda: ctx.scalecom_step(big, big, 10, 0.5, 0.1, 0)) == E              # numel > numel_max
