@@ -89,7 +89,7 @@ struct ChunkDesc {        // one per scan chunk: up to kChunk consecutive supert
     int32_t pad;
 };
 
-struct SegState {         // selection state of one segment; zeroed at the start of every step
+struct SegState {         // selection state of one segment; every field is rewritten by k_find<0> each step
     uint32_t prefix;      // key bits fixed so far (level 0: 12 bits, level 1: 24 bits)
     uint32_t k_rem;       // members still to be found inside the current bucket
     uint32_t T;           // threshold key (after level 2)
@@ -97,7 +97,7 @@ struct SegState {         // selection state of one segment; zeroed at the start
     uint32_t done;        // 1: empty index set, nothing to refine
     uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
     uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
-    uint32_t spec_overflow;   // 1: a candidate slice overflowed during the predicted pass
+    uint32_t pad;
 };
 
 constexpr uint32_t kWindow = 5;                  // predicted window: previous bucket +- 2 digits
@@ -358,10 +358,18 @@ __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool o
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-            const StDesc* __restrict__ sts, SegState* __restrict__ state, uint2* __restrict__ cand,
+            const StDesc* __restrict__ sts, uint2* __restrict__ cand,
             uint32_t* __restrict__ st_cand_cnt, const uint32_t* __restrict__ preds, uint32_t* __restrict__ wt_cnt,
-            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part)
+            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part,
+            uint32_t* __restrict__ overflow, uint32_t* __restrict__ next_scratch, size_t next_words)
 {
+    // The counters and histograms of a step live in one of two copies of a scratch zone; this
+    // kernel, the first of a step, clears the copy the NEXT step will use (nothing else touches it
+    // during this step), so no step needs a separate clearing pass.
+    for (size_t i = blockIdx.x * static_cast<size_t>(kBlock) + threadIdx.x; i < next_words;
+         i += static_cast<size_t>(gridDim.x) * kBlock)
+        next_scratch[i] = 0u;
+
     const int st = blockIdx.x;
     const StDesc d = sts[st];
     const uint32_t p = preds[d.seg];                        // 0: none, else predicted bucket + 1
@@ -402,7 +410,7 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     if (threadIdx.x == 0) {
         const uint32_t n = fill;
         st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
-        if (n > kCandSlice) state[d.seg].spec_overflow = 1u;   // every overflowing block stores the same value
+        if (n > kCandSlice) overflow[d.seg] = 1u;           // every overflowing block stores the same value
     }
     if (threadIdx.x <= kWindow) {
         const uint32_t v = acc[threadIdx.x];
@@ -417,20 +425,19 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_hist0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-        const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state, uint32_t* __restrict__ hist,
-        const uint32_t* __restrict__ preds, const uint32_t* __restrict__ part)
+        const StDesc* __restrict__ sts, int n_st, uint32_t* __restrict__ hist, const uint32_t* __restrict__ preds,
+        const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow)
 {
     __shared__ uint32_t lh[kBins0];
+    __shared__ uint32_t tot_s[kPartWords];
     __shared__ int needed;
-    for (int b = threadIdx.x; b < kBins0; b += kBlock) lh[b] = 0u;
-    __syncthreads();
 
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
     const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
     const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
 
     int cur = -1;
-    bool histogram = false, dirty = false;
+    bool histogram = false, dirty = false, lh_ready = false;
     auto flush = [&]() {
         if (!dirty) return;
         __syncthreads();
@@ -449,19 +456,32 @@ k_hist0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
         if (d.seg != cur) {
             if (cur >= 0) flush();
             cur = d.seg;
-            if (threadIdx.x == 0) {
-                const uint32_t p = preds[cur];
-                const uint32_t k = static_cast<uint32_t>(segs[cur].k);
-                needed = k != 0;
-                if (k != 0 && p != 0) {                     // did the prediction hold?
-                    uint32_t tot[1 + kWindow], digit, k_rem;
-                    spec_totals(part, cur, tot);
-                    needed = !spec_resolve(tot, state[cur].spec_overflow != 0, p, k, digit, k_rem);
+            const uint32_t p = preds[cur];
+            const uint32_t k = static_cast<uint32_t>(segs[cur].k);
+            if (k != 0 && p != 0) {                         // did the prediction hold?  (block-uniform branch)
+                if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
+                __syncthreads();
+                for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
+                    const uint32_t v = part[static_cast<size_t>(cur) * kPartSlots * kPartWords + i];
+                    if (v) atomicAdd(&tot_s[i % kPartWords], v);
                 }
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    uint32_t tot[1 + kWindow], digit, k_rem;
+                    for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
+                    needed = !spec_resolve(tot, overflow[cur] != 0, p, k, digit, k_rem);
+                }
+            } else if (threadIdx.x == 0) {
+                needed = k != 0;
             }
             __syncthreads();
             histogram = needed != 0;
             __syncthreads();
+            if (histogram && !lh_ready) {                   // the histogram is only cleared when it is used
+                for (int b = threadIdx.x; b < kBins0; b += kBlock) lh[b] = 0u;
+                __syncthreads();
+                lh_ready = true;
+            }
         }
         if (!histogram) continue;
         dirty = true;
@@ -565,7 +585,7 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
 template <int LEVEL>
 __global__ void __launch_bounds__(kBlock)
 k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uint32_t* __restrict__ hist,
-       uint32_t* __restrict__ preds, const uint32_t* __restrict__ part)
+       uint32_t* __restrict__ preds, const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow)
 {
     constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
     constexpr int BITS = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
@@ -573,7 +593,7 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     constexpr int ACTIVE = NB >= kBlock ? kBlock : NB;     // threads that own bins
     const int seg = blockIdx.x;
     const uint32_t* h = hist + static_cast<size_t>(seg) * NB;
-    __shared__ uint32_t above[kBlock];   // keys in the chunks of higher threads
+    __shared__ uint32_t above[kWaves];   // per-wave totals
 
     SegState s = state[seg];
     if (LEVEL == 0) {
@@ -596,7 +616,7 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
             resolved = 0;
             if (p != 0) {
                 spec_totals(part, seg, tot);
-                if (spec_resolve(tot, s.spec_overflow != 0, p, s.k_rem, digit, k_rem)) {
+                if (spec_resolve(tot, overflow[seg] != 0, p, s.k_rem, digit, k_rem)) {
                     resolved = 1;
                     s.prefix = digit;
                     s.k_rem = k_rem;
@@ -617,16 +637,18 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     uint32_t mine = 0;
     if (t < ACTIVE)
         for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
-    // inclusive suffix sums over threads (Hillis-Steele on the reversed order)
-    above[t] = t < ACTIVE ? mine : 0u;
-    __syncthreads();
-    for (int off = 1; off < kBlock; off <<= 1) {
-        const uint32_t add = (t + off < kBlock) ? above[t + off] : 0u;
-        __syncthreads();
-        above[t] += add;
-        __syncthreads();
+    // inclusive suffix sums over threads: within a wave by shuffles, across the 4 waves through LDS
+    const int lane = t % kLanes, wave = t / kLanes;
+    uint32_t suf = mine;
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t v = __shfl_down(suf, off, kLanes);
+        if (lane + off < kLanes) suf += v;
     }
-    const uint32_t incl = above[t];          // keys in my chunk and all higher chunks
+    if (lane == 0) above[wave] = suf;                       // the wave's total
+    __syncthreads();
+    for (int w = wave + 1; w < kWaves; ++w) suf += above[w];
+    const uint32_t incl = suf;               // keys in my chunk and all higher chunks
     const uint32_t excl = incl - mine;       // keys strictly above my chunk
     if (t < ACTIVE && excl < s.k_rem && s.k_rem <= incl) {
         uint32_t c = excl;
@@ -1016,9 +1038,10 @@ inline int64_t max_chunks(int64_t numel_max, int n_tensors_max)
 }
 
 struct WsLayout {
-    size_t segs, sts, chunks, preds, state, part, hist0, hist1, hist2, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand,
-        sel_mask, eq_mask, tile_slot, vals, total;
-    size_t zero_words;   // state + histograms are contiguous and zeroed every step
+    size_t segs, sts, chunks, preds, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask, eq_mask,
+        tile_slot, vals, total;
+    // per-step counters and histograms: two copies of one zone, used alternately (offsets inside a copy)
+    size_t zone[2], zone_bytes, z_overflow, z_part, z_hist0, z_hist1, z_hist2;
 };
 
 WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
@@ -1039,11 +1062,22 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.chunks = take(nch * sizeof(ChunkDesc));
     l.preds = take(nt * sizeof(uint32_t));
     l.state = take(nt * sizeof(SegState));
-    l.part = take(nt * kPartSlots * kPartWords * sizeof(uint32_t));
-    l.hist0 = take(nt * kBins0 * sizeof(uint32_t));
-    l.hist1 = take(nt * kBins1 * sizeof(uint32_t));
-    l.hist2 = take(nt * kBins2 * sizeof(uint32_t));
-    l.zero_words = (o - l.state) / sizeof(uint32_t);
+    {
+        size_t z = 0;
+        auto ztake = [&](size_t bytes) {
+            const size_t at = z;
+            z = align_up(z + bytes, 256);
+            return at;
+        };
+        l.z_overflow = ztake(nt * sizeof(uint32_t));
+        l.z_part = ztake(nt * kPartSlots * kPartWords * sizeof(uint32_t));
+        l.z_hist0 = ztake(nt * kBins0 * sizeof(uint32_t));
+        l.z_hist1 = ztake(nt * kBins1 * sizeof(uint32_t));
+        l.z_hist2 = ztake(nt * kBins2 * sizeof(uint32_t));
+        l.zone_bytes = z;
+    }
+    l.zone[0] = take(l.zone_bytes);
+    l.zone[1] = take(l.zone_bytes);
     l.wt_cnt = take(ntile * sizeof(uint32_t));
     l.st_sum = take(nst * sizeof(uint2));
     l.st_prefix = take(nst * sizeof(uint2));
@@ -1079,6 +1113,8 @@ struct scalecom_ctx {
     // tables of the layout used last, kept on the device until the layout changes
     std::vector<int64_t> cached_offsets, cached_ks;
     int n_st = 0, n_chunks = 0;
+    int parity = 0;                  // which copy of the scratch zone the next step uses
+    bool scratch_clean = false;      // false: both copies must be cleared before the next step
     char* pinned = nullptr;          // staging for the table upload
     size_t pinned_bytes = 0;
     hipEvent_t upload_done = nullptr;
@@ -1180,6 +1216,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     // predictions of the previous layout's buckets mean nothing for this one
     k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds),
                                           static_cast<size_t>(ctx->n_tensors_max));
+    ctx->scratch_clean = false;
     SC_HIP(ctx, hipEventRecord(ctx->upload_done, ctx->stream));
     ctx->upload_pending = true;
     ctx->n_st = static_cast<int>(n_st);
@@ -1200,10 +1237,14 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     const ChunkDesc* chunks = reinterpret_cast<const ChunkDesc*>(ws + l.chunks);
     SegState* state = reinterpret_cast<SegState*>(ws + l.state);
     uint32_t* preds = reinterpret_cast<uint32_t*>(ws + l.preds);
-    uint32_t* part = reinterpret_cast<uint32_t*>(ws + l.part);
-    uint32_t* hist0 = reinterpret_cast<uint32_t*>(ws + l.hist0);
-    uint32_t* hist1 = reinterpret_cast<uint32_t*>(ws + l.hist1);
-    uint32_t* hist2 = reinterpret_cast<uint32_t*>(ws + l.hist2);
+    char* zone = ws + l.zone[ctx->parity];
+    uint32_t* overflow = reinterpret_cast<uint32_t*>(zone + l.z_overflow);
+    uint32_t* part = reinterpret_cast<uint32_t*>(zone + l.z_part);
+    uint32_t* hist0 = reinterpret_cast<uint32_t*>(zone + l.z_hist0);
+    uint32_t* hist1 = reinterpret_cast<uint32_t*>(zone + l.z_hist1);
+    uint32_t* hist2 = reinterpret_cast<uint32_t*>(zone + l.z_hist2);
+    uint32_t* next_zone = reinterpret_cast<uint32_t*>(ws + l.zone[ctx->parity ^ 1]);
+    const size_t zone_words = l.zone_bytes / sizeof(uint32_t);
     uint32_t* wt_cnt = reinterpret_cast<uint32_t*>(ws + l.wt_cnt);
     uint2* st_sum = reinterpret_cast<uint2*>(ws + l.st_sum);
     uint2* st_prefix = reinterpret_cast<uint2*>(ws + l.st_prefix);
@@ -1226,25 +1267,25 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
         if (timed) (void)hipEventRecord(ev[boundary], s);
     };
     mark(0);
-    // selection state and the three histogram arrays start every step at zero
-    {
-        const size_t words = l.zero_words;
+    if (n_st > 0 && !ctx->scratch_clean) {   // first step, new layout, or a failed step: clear both scratch copies
+        const size_t words = 2 * zone_words;   // the two copies are adjacent
         const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
-        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.state), words);
+        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.zone[0]), words);
     }
     if (n_st > 0) {
         const int hgrid = std::min(n_st, kHistGridMax);
-        k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, cand, st_cand_cnt, preds, wt_cnt,
-                                               sel_mask, eq_mask, part);
-        k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist0, preds, part);
-        k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part);
+        ctx->scratch_clean = false;             // until every kernel of this step has been enqueued
+        k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask,
+                                               eq_mask, part, overflow, next_zone, zone_words);
+        k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, hist0, preds, part, overflow);
+        k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow);
         mark(1);
         k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask);
         mark(2);
         k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt);
-        k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part);
+        k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow);
         k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt);
-        k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part);
+        k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow);
         mark(3);
         k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask,
                                                eq_mask, st_sum);
@@ -1266,6 +1307,10 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
         if (timed) ++ctx->prof_steps;
     }
     SC_HIP(ctx, hipGetLastError());
+    if (n_st > 0) {                             // the copy for the next step was cleared by this step
+        ctx->parity ^= 1;
+        ctx->scratch_clean = true;
+    }
     return SCALECOM_OK;
 }
 
