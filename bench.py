@@ -194,7 +194,7 @@ def main():
             "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
             "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "copy_kernel_GBps": copy_gbps,
-            "phase_ms": dict(zip(["hist0_find", "collect", "refine", "counts_scan_slots", "update", "reduce"], phase_avg)) if phase_avg else None,
+            "phase_ms": dict(zip(["leader_first_look", "leader_second_pass", "refine", "counts_scan_slots", "update", "reduce"], phase_avg)) if phase_avg else None,
         },
     }
     if not args.no_cpu_baseline:

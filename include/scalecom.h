@@ -24,6 +24,9 @@
  *  - The caller owns every buffer, including the workspace; the library allocates no
  *    device memory.  Per context it keeps pinned host staging for its tile tables
  *    (about numel_max / 1000 + 64 * n_tensors_max bytes).
+ *  - The result of a call depends only on its arguments.  The context remembers, per tensor,
+ *    where the previous step's threshold fell and uses it to skip a pass over the leader when
+ *    the guess holds (checked exactly); this changes the time a step takes, never its result.
  *  - All work is enqueued on the HIP stream given to scalecom_init; calls do not wait for
  *    the GPU.  Outputs are valid once that stream has reached the end of the call's work.
  *    A context must not be used from two threads at once.
@@ -126,9 +129,9 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
  * Optional per-phase GPU timing, for benchmarks.  Not part of the paper's method: it only
  * records HIP events on the context's stream between the kernel groups of a step.
  * Phases of one step, in order:
- *   0  leader pass 1: histogram of the top 12 bits of the magnitude keys + bucket search (Eq. 2)
- *   1  leader pass 2: keys above the bucket counted and marked as members, bucket keys copied
- *      to the candidate list
+ *   0  first look at the leader (Eq. 2): single predicted pass, or histogram of the top 12 bits
+ *      of the magnitude keys, + search of the threshold bucket
+ *   1  second leader pass (only when the prediction missed): bucket keys to the candidate list
  *   2  remaining 19 key bits resolved on the candidate list: exact threshold and tie quota
  *   3  per-tile member counts, prefix sums, output slot of every tile, ties resolved
  *   4  all-learner pass: accumulate, low-pass memory update, members' values staged (Eq. 3, 5)

@@ -2,18 +2,21 @@
 // compression path: CLT-k with low-pass-filtered error feedback (arXiv 2104.11125, Alg. 1
 // lines 6, 7, 10; Eq. 2, 3, 5).  See include/scalecom.h for the contract of each entry point.
 //
-// Structure of one step (all on the context's stream, no host synchronisation):
+// Structure of one step (all on the context's stream, no host synchronisation).  The 31-bit
+// magnitude key |x_L| of the leader's x_L = fma(lr, grad_L, mem_L) (recomputed on the fly, never
+// stored) is resolved 12 + 12 + 7 bits at a time (radix select):
 //
-//   init        zero the digit histograms and per-segment selection state
-//   hist<0>     leader only: x_L = fma(lr, grad_L, mem_L) is recomputed on the fly (never
-//               stored) and the top 12 bits of the 31-bit magnitude key |x_L| are histogrammed
-//   find<0>     per segment: walk the histogram from the top to the bucket holding the k-th
-//               largest key  (Eq. 2)
-//   collect     leader only, second and last full pass: keys above the bucket are members for
-//               sure: counted per 256-element wave tile and marked in the membership bitmask;
-//               keys inside the bucket (a fraction of a percent of the vector) are copied, with
-//               their positions, into a small candidate list
-//   hist<1,2>   the remaining 12 + 7 key bits, histogrammed over the candidate list only
+//   predicted   leader, ONE pass, for segments that carry the threshold bucket of the previous
+//               step as a prediction: keys whose top 12 bits lie above a 5-bucket window around
+//               it are members for sure (counted per 256-element wave tile, marked in the
+//               membership bitmask); keys inside the window are copied, with their positions,
+//               to a small candidate list and counted per bucket
+//   hist0       leader, histogram of the top 12 key bits -- only for segments without a
+//               prediction or whose window missed the k-th largest key (exact check on counts)
+//   find<0>     per segment: the bucket holding the k-th largest key  (Eq. 2)
+//   collect     leader, second pass -- only for segments that went through hist0: same job as
+//               `predicted` with the now known bucket as the window
+//   hist<1,2>   the remaining 12 + 7 key bits, histogrammed over the candidate list
 //   find<1,2>   after level 2 the exact threshold key T and the number q of keys equal to T
 //               that still belong to the set are known
 //   tilecount   candidates above / equal to T are added to the per-tile counts and bitmasks
@@ -26,9 +29,11 @@
 //               [learner][slot] staging array and learner 0 writes the index (Eq. 3)
 //   reduce      reduced[t] = x_0[t] + x_1[t] + ... in learner order  (Alg. 1 line 10)
 //
-// The output is ascending by position and deterministic.  Nothing here is a dense
-// contraction, so there is no MFMA; the kernels are bound by HBM traffic (update, collect)
-// and by LDS atomics + HBM (hist<0>).
+// In the steady state (predictions hold) hist0 and collect find nothing to do, and the leader's
+// vector is read exactly once before the all-learner pass.  The prediction only decides how
+// much work is done, never what is selected.  The output is ascending by position and
+// deterministic.  Nothing here is a dense contraction, so there is no MFMA; the kernels are
+// bound by HBM traffic (update, predicted) and by launch latency (the small ones).
 
 #include <hip/hip_runtime.h>
 
@@ -120,27 +125,18 @@ __device__ __forceinline__ uint32_t magnitude_key(float x) { return __float_as_u
 __device__ __forceinline__ float widen(float g) { return g; }
 __device__ __forceinline__ float widen(uint16_t g) { return __uint_as_float(static_cast<uint32_t>(g) << 16); }
 
-#ifndef SC_NT
-#define SC_NT 1
-#endif
+// Streaming accesses carry the nontemporal hint: every byte of mem and grad is touched once per
+// pass, so keeping it in cache only evicts what is reused (measured: +3 to +10 % bandwidth).
 typedef float vf4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t vu2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float4 load4(const float* p)
 {
-#if SC_NT
     const vf4_t v = __builtin_nontemporal_load(reinterpret_cast<const vf4_t*>(p));
     return make_float4(v.x, v.y, v.z, v.w);
-#else
-    return *reinterpret_cast<const float4*>(p);
-#endif
 }
 __device__ __forceinline__ float4 load4(const uint16_t* p)
 {
-#if SC_NT
     const vu2_t v = __builtin_nontemporal_load(reinterpret_cast<const vu2_t*>(p));
-#else
-    const uint2 v = *reinterpret_cast<const uint2*>(p);
-#endif
     float4 r;
     r.x = __uint_as_float(v.x << 16);
     r.y = __uint_as_float(v.x & 0xffff0000u);
@@ -150,13 +146,12 @@ __device__ __forceinline__ float4 load4(const uint16_t* p)
 }
 __device__ __forceinline__ void store4(float* p, const float4& v)
 {
-#if SC_NT
     vf4_t w;
-    w.x = v.x; w.y = v.y; w.z = v.z; w.w = v.w;
+    w.x = v.x;
+    w.y = v.y;
+    w.z = v.z;
+    w.w = v.w;
     __builtin_nontemporal_store(w, reinterpret_cast<vf4_t*>(p));
-#else
-    *reinterpret_cast<float4*>(p) = v;
-#endif
 }
 
 // number of set bits of a wave-wide ballot that belong to lanes below the calling lane
@@ -973,9 +968,6 @@ k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDes
     }
 
     if (total == 0) return;                                 // no member in the block's tiles (block-uniform)
-#ifdef SC_EXP_NOVALS
-    return;
-#endif
     // The block's members occupy consecutive output slots (tiles are consecutive): compact them
     // through LDS and write them with one contiguous store.
     __shared__ float stage_val[kWaves * kWaveTile];
@@ -1014,12 +1006,12 @@ k_reduce(const float* __restrict__ vals, int n_learners, int64_t k_total, float*
     red_out[t] = s;
 }
 
-// Plain streaming copy (16 bytes per lane per access): the yardstick the other kernels'
-// bandwidth and the profiler's byte counters are compared with.
-__global__ void __launch_bounds__(kBlock) k_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16)
+// Plain streaming copy, one 16-byte nontemporal load and store per thread: the yardstick the
+// other kernels' bandwidth and the profiler's byte counters are compared with.
+__global__ void __launch_bounds__(kBlock) k_copy(const vf4_t* __restrict__ src, vf4_t* __restrict__ dst, size_t n16)
 {
-    const size_t stride = static_cast<size_t>(gridDim.x) * kBlock;
-    for (size_t i = blockIdx.x * static_cast<size_t>(kBlock) + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    const size_t i = (static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
+    if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1440,8 +1432,11 @@ scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* s
     DeviceGuard guard;
     SC_HIP(ctx, guard.enter(ctx->device));
     const size_t n16 = bytes / 16;
-    const int grid = static_cast<int>(std::min<size_t>((n16 + kBlock - 1) / kBlock, 256 * 32));
-    k_copy<<<grid, kBlock, 0, ctx->stream>>>(static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
+    const size_t blocks = (n16 + kBlock - 1) / kBlock;
+    const unsigned gx = static_cast<unsigned>(std::min<size_t>(blocks, 1u << 20));
+    const unsigned gy = static_cast<unsigned>((blocks + gx - 1) / gx);
+    if (gy > 65535) return fail(ctx, SCALECOM_EINVAL, "copy too large");
+    k_copy<<<dim3(gx, gy), kBlock, 0, ctx->stream>>>(static_cast<const vf4_t*>(src), static_cast<vf4_t*>(dst), n16);
     SC_HIP(ctx, hipGetLastError());
     return SCALECOM_OK;
 }
