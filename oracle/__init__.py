@@ -45,12 +45,15 @@ def _load():
         lib.oracle_accumulate.argtypes = [vp, vp, i32, i64, f32, vp]
         lib.oracle_topk_sort.argtypes = [vp, i64, i64, vp]
         lib.oracle_topk_select.argtypes = [vp, i64, i64, vp]
+        lib.oracle_chunk_select.argtypes = [vp, i64, i64, vp]
+        lib.oracle_step_chunked.argtypes = [vp, vp, i32, i32, i64, i64, f32, f32, i64, vp, vp]
         lib.oracle_gather.argtypes = [vp, vp, i64, vp]
         lib.oracle_reduce.argtypes = [vp, i32, i64, vp]
         lib.oracle_memory_update.argtypes = [vp, vp, vp, i64, i64, f32]
         lib.oracle_step.argtypes = [vp, vp, i32, i32, i64, i64, f32, f32, i64, vp, vp]
         lib.oracle_step_layers.argtypes = [vp, vp, i32, i32, i32, vp, vp, f32, f32, i64, vp, vp]
         for name in ("oracle_accumulate", "oracle_topk_sort", "oracle_topk_select", "oracle_gather",
+                     "oracle_chunk_select", "oracle_step_chunked",
                      "oracle_reduce", "oracle_memory_update", "oracle_step", "oracle_step_layers"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -103,6 +106,35 @@ def topk_select(x: np.ndarray, k: int) -> np.ndarray:
     if _load().oracle_topk_select(_p(x), x.size, k, _p(idx)):
         raise ValueError("oracle_topk_select: bad arguments")
     return idx
+
+
+def chunk_select(x: np.ndarray, chunk: int) -> np.ndarray:
+    """One position per chunk of ``chunk`` consecutive elements: its largest magnitude."""
+    _check_f32(x, "x")
+    if chunk < 1:
+        raise ValueError("chunk must be >= 1")
+    idx = np.empty(-(-x.size // chunk), dtype=np.int32)
+    if _load().oracle_chunk_select(_p(x), x.size, chunk, _p(idx)):
+        raise ValueError("oracle_chunk_select: bad arguments")
+    return idx
+
+
+def step_chunked(mem, grad, chunk: int, beta: float, lr: float, step: int):
+    """One iteration with the chunk-wise selector.  Returns (idx, reduced); ``mem`` updated in place."""
+    n = len(mem)
+    for m in mem:
+        _check_f32(m, "mem[i]")
+    numel = mem[0].size
+    if chunk < 1:
+        raise ValueError("chunk must be >= 1")
+    k = -(-numel // chunk)
+    idx = np.empty(k, dtype=np.int32)
+    red = np.empty(k, dtype=np.float32)
+    rc = _load().oracle_step_chunked(_ptr_array(mem), _ptr_array(grad), _grad_dtype(grad[0]), n, numel, chunk, beta,
+                                     lr, step, _p(idx), _p(red))
+    if rc:
+        raise ValueError("oracle_step_chunked: bad arguments")
+    return idx, red
 
 
 def gather(acc: np.ndarray, idx: np.ndarray) -> np.ndarray:

@@ -9,6 +9,7 @@
 //
 //   accumulate      x_i = m_i + lr * grad_i             Alg. 1 line 6 (argument of CLT-k), Sec. 2 footnote
 //   top-k index set I^k(x_L), L = step mod n            Eq. 2, leader rule of Alg. 1 line 6
+//   (or one position per chunk of the leader's vector   Sec. 4, App. E: chunk-wise selection)
 //   CLT-k gather    (g_i)_j = (x_i)_j for j in I        Eq. 3
 //   reduction       g = sum_i g_i (the 1/n is left out) Alg. 1 line 10, Eq. 1
 //   memory update   m_i <- (1-b) m_i + b (x_i - g_i)    Eq. 5, Alg. 1 line 7
@@ -111,6 +112,26 @@ int oracle_topk_select(const float* x, int64_t numel, int64_t k, int32_t* idx_ou
     return 0;
 }
 
+// Chunk-wise selection, the selector the paper's own implementation used in place of an exact
+// top-k (Sec. 4 "divides the whole buffer into chunks", App. E "chunk-wise quasi-sorting", demo of
+// Fig. A2: 8 values, two chunks, one position chosen in each): the vector is cut into consecutive
+// chunks of `chunk` elements (the last may be shorter) and each chunk contributes the position
+// of its largest magnitude, the lowest position among equals.  ceil(numel / chunk) positions,
+// ascending.
+int oracle_chunk_select(const float* x, int64_t numel, int64_t chunk, int32_t* idx_out)
+{
+    if (numel < 0 || chunk < 1 || numel > INT32_MAX) return 1;
+    int64_t t = 0;
+    for (int64_t start = 0; start < numel; start += chunk, ++t) {
+        const int64_t stop = std::min(start + chunk, numel);
+        int64_t best = start;
+        for (int64_t j = start + 1; j < stop; ++j)
+            if (magnitude_key(x[j]) > magnitude_key(x[best])) best = j;
+        idx_out[t] = static_cast<int32_t>(best);
+    }
+    return 0;
+}
+
 // Non-zero entries of CLT^k_L(x_i): the learner's own values at the leader's positions (Eq. 3).
 int oracle_gather(const float* acc, const int32_t* idx, int64_t k, float* vals)
 {
@@ -191,6 +212,31 @@ int oracle_step_layers(float* const* mem, const void* const* grad, int grad_dtyp
         for (int64_t t = 0; t < k; ++t) idx_out[out + t] = static_cast<int32_t>(begin + local[t]);
         out += k;
     }
+    return 0;
+}
+
+// One iteration with the chunk-wise selector on the leader instead of the exact top-k; everything
+// else (leader rule, Eq. 3 gather, reduction, Eq. 5 memory update) as in oracle_step_layers.
+int oracle_step_chunked(float* const* mem, const void* const* grad, int grad_dtype, int n_learners, int64_t numel,
+                        int64_t chunk, float beta, float lr, int64_t step, int32_t* idx_out, float* reduced_out)
+{
+    if (n_learners < 1 || numel < 0 || chunk < 1 || step < 0) return 1;
+    if (!(beta > 0.0f && beta <= 1.0f)) return 1;
+    const int leader = static_cast<int>(step % n_learners);
+    const int64_t k = (numel + chunk - 1) / chunk;
+    std::vector<float> acc(static_cast<size_t>(numel));
+    oracle_accumulate(mem[leader], grad[leader], grad_dtype, numel, lr, acc.data());
+    if (oracle_chunk_select(acc.data(), numel, chunk, idx_out)) return 1;
+    std::vector<std::vector<float>> vals(static_cast<size_t>(n_learners));
+    std::vector<const float*> vptr(static_cast<size_t>(n_learners));
+    for (int i = 0; i < n_learners; ++i) {
+        oracle_accumulate(mem[i], grad[i], grad_dtype, numel, lr, acc.data());
+        vals[i].resize(static_cast<size_t>(k));
+        oracle_gather(acc.data(), idx_out, k, vals[i].data());
+        if (oracle_memory_update(mem[i], acc.data(), idx_out, k, numel, beta)) return 1;
+        vptr[i] = vals[i].data();
+    }
+    if (k > 0) oracle_reduce(vptr.data(), n_learners, k, reduced_out);
     return 0;
 }
 

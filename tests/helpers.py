@@ -17,9 +17,10 @@ def load_golden(path):
                 continue
             name, vals = line.split(":", 1)
             nums = [float(v) for v in vals.split()]
-            out[name.strip()] = nums[0] if name.strip() in ("n", "numel", "k", "step", "lr", "beta") else np.array(nums)
-    for key in ("n", "numel", "k", "step"):
-        out[key] = int(out[key])
+            out[name.strip()] = nums[0] if name.strip() in ("n", "numel", "k", "step", "lr", "beta", "chunk") else np.array(nums)
+    for key in ("n", "numel", "k", "step", "chunk"):
+        if key in out:
+            out[key] = int(out[key])
     return out
 
 

@@ -309,3 +309,67 @@ def test_degenerate_sizes():
         oracle.step(m, g, 4, 0.5, 1.0, 0)                              # k > numel
     with pytest.raises(ValueError):
         oracle.step(m, g, 1, 0.0, 1.0, 0)                              # beta outside (0, 1]
+
+
+# ---------------------------------------------------------------- chunk-wise selection (Sec. 4, App. E)
+def test_chunk_selection_hand_worked_example(golden_dir):
+    g = load_golden(os.path.join(golden_dir, "e4_chunks.txt"))
+    mem = [f32(g["mem_0"]), f32(g["mem_1"])]
+    grad = [f32(g["grad_0"]), f32(g["grad_1"])]
+    idx, red = oracle.step_chunked(mem, grad, g["chunk"], g["beta"], g["lr"], g["step"])
+    assert idx.tolist() == g["idx"].astype(int).tolist()
+    assert red.tolist() == g["reduced"].tolist()
+    assert mem[0].tolist() == g["mem_0_out"].tolist()
+    assert mem[1].tolist() == g["mem_1_out"].tolist()
+
+
+def test_chunk_selection_against_brute_force():
+    rng = np.random.default_rng(31)
+    for n in (1, 2, 5, 16, 17, 100, 1000):
+        for kind in ("normal", "ties"):
+            x = f32(rng.standard_normal(n)) if kind == "normal" else f32(rng.choice([-1.0, 0.0, 1.0, -0.0], size=n))
+            for chunk in (1, 2, 3, 4, 7, 16, n, n + 5):
+                want = [max(range(a, min(a + chunk, n)), key=lambda j: (mag_key(x[j]), -j)) for a in range(0, n, chunk)]
+                assert oracle.chunk_select(x, chunk).tolist() == want, (n, kind, chunk)
+
+
+def test_chunk_selection_special_cases_are_top_k():
+    """chunk >= numel is the top-1; chunk = 1 selects everything; and when the k largest entries
+    happen to sit one per chunk, chunk-wise selection IS the top-k of Eq. 2."""
+    rng = np.random.default_rng(32)
+    x = f32(rng.standard_normal(4096) * 1e-3)
+    assert oracle.chunk_select(x, 4096).tolist() == oracle.topk_select(x, 1).tolist()
+    assert oracle.chunk_select(x, 10_000).tolist() == oracle.topk_select(x, 1).tolist()
+    assert oracle.chunk_select(x, 1).tolist() == list(range(4096))
+    y = f32(rng.standard_normal(64 * 50) * 1e-3)
+    peaks = np.arange(64) * 50 + rng.integers(0, 50, size=64)
+    y[peaks] = np.float32(1.0) + f32(rng.random(64))
+    assert oracle.chunk_select(y, 50).tolist() == oracle.topk_select(y, 64).tolist() == sorted(peaks.tolist())
+
+
+def test_chunk_selection_keeps_no_more_energy_than_top_k():
+    rng = np.random.default_rng(33)
+    x = f32(rng.standard_normal(30_000))
+    for chunk in (10, 100, 112):
+        sel = oracle.chunk_select(x, chunk)
+        top = oracle.topk_select(x, sel.size)
+        e = lambda idx: float(np.sum(x[idx].astype(np.float64) ** 2))
+        assert e(sel) <= e(top) and e(sel) >= sel.size / x.size * float(np.sum(x.astype(np.float64) ** 2))
+        assert np.all(sel // chunk == np.arange(sel.size))            # exactly one position in every chunk
+
+
+def test_chunked_step_equals_primitives():
+    """The chunked step is the same Eq. 3 / Alg. 1 line 10 / Eq. 5 pipeline with another index set."""
+    rng = np.random.default_rng(34)
+    n, numel, chunk = 4, 5003, 37
+    mem, grad = _random_problem(rng, n, numel)
+    accs = [oracle.accumulate(mem[i], grad[i], 0.3) for i in range(n)]
+    want_idx = oracle.chunk_select(accs[2], chunk)                    # step 6 -> leader 2
+    want_mem = [m.copy() for m in mem]
+    for i in range(n):
+        oracle.memory_update(want_mem[i], accs[i], want_idx, 0.2)
+    idx, red = oracle.step_chunked(mem, grad, chunk, 0.2, 0.3, 6)
+    assert np.array_equal(idx, want_idx)
+    assert np.array_equal(red, oracle.reduce([a[want_idx] for a in accs]))
+    for i in range(n):
+        assert np.array_equal(mem[i], want_mem[i])
