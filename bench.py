@@ -1,12 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the CLT-k + low-pass error-feedback step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--select exact|chunk]
+                    [--no-cpu-baseline]
 
 A "step" is one call of scalecom_step (scalecom_step_layers for the per-layer workload): the
 whole path -- accumulate, exact top-k on the cyclic leader, gather, sum over learners,
 low-pass memory update -- over one batch of synthetic gradients that already sit in HBM.
 Memories are carried from step to step, the leader rotates with the step index.
+
+`--select chunk` times the chunk-wise selector of the paper's own implementation (one position
+per `rate` consecutive elements, scalecom_step_chunked) instead of the exact top-k.
 
 Prints ONE JSON line.  `value` is gradient elements per second (n_learners * numel / step
 time).  `roofline` is for the dominant kernel (the all-learner pass k_update), timed with HIP
@@ -29,12 +33,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(w):
+def index_set_size(w, select):
+    return w.k if select == "exact" else -(-w.numel // w.rate)
+
+
+def algorithmic_bytes(w, k):
     """Bytes one step must move (stated in the design doc): read every learner's mem and grad,
     write every mem, one extra look at the leader's (mem, grad) to find the threshold, write
     idx + reduced values."""
     gb = 2 if w.grad_dtype == "bf16" else 4
-    n, N, k = w.n_learners, w.numel, w.k
+    n, N = w.n_learners, w.numel
     update = n * N * (4 + gb) + n * N * 4 + k * 8      # the all-learner pass (k_update) and its outputs
     leader = N * (4 + gb)
     return update, update + leader
@@ -52,7 +60,7 @@ def recorded_traffic(workload_name):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(w, budget_s=20.0):
+def cpu_baseline(w, select, budget_s=20.0):
     """The oracle as it stands, single thread, on host copies of the first steps' inputs."""
     import numpy as np
     import torch
@@ -70,7 +78,9 @@ def cpu_baseline(w, budget_s=20.0):
             grad.append(g.view(torch.int16).cpu().numpy().view(np.uint16) if g.dtype == torch.bfloat16
                         else g.cpu().numpy())
         t0 = time.perf_counter()
-        if w.n_tensors == 1:
+        if select == "chunk":
+            oracle.step_chunked(mem, grad, w.rate, w.beta, w.lr, done)
+        elif w.n_tensors == 1:
             oracle.step(mem, grad, w.k, w.beta, w.lr, done)
         else:
             oracle.step_layers(mem, grad, w.offsets, w.ks, w.beta, w.lr, done)
@@ -83,7 +93,7 @@ def cpu_baseline(w, budget_s=20.0):
         "cores": 1,
         "kind": "oracle",
         "sample": f"first {done} step(s) of the full workload ({w.n_learners} learners x {w.numel} elements, "
-                  f"k={w.k}), memory carried; {per_step * 1e3:.0f} ms/step; host has {os.cpu_count()} logical cores",
+                  f"k={index_set_size(w, select)}, select={select}), memory carried; {per_step * 1e3:.0f} ms/step; host has {os.cpu_count()} logical cores",
         "ms_per_step": per_step * 1e3,
     }
 
@@ -94,6 +104,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50_sized")
+    ap.add_argument("--select", choices=["exact", "chunk"], default="exact")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool", type=int, default=8, help="distinct gradient batches kept in HBM and cycled")
     args = ap.parse_args()
@@ -111,20 +122,26 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     w = workloads.by_name(args.workload)
+    if args.select == "chunk" and w.n_tensors != 1:
+        print("bench.py: --select chunk needs a whole-vector workload", file=sys.stderr)
+        sys.exit(2)
+    k = index_set_size(w, args.select)
     gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
-    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, w.n_tensors, dev, k_max=w.k)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, w.n_tensors, dev, k_max=k)
 
     # inputs resident in HBM before the timed region: a pool of gradient batches, zero memories
     gbytes = w.n_learners * w.numel * (2 if w.grad_dtype == "bf16" else 4)
     pool_n = max(1, min(args.pool, args.steps + args.warmup, int(40e9 // gbytes)))
     pool = [workloads.gradients(w, t, dev) for t in range(pool_n)]
     mem = workloads.zero_memories(w, dev)
-    idx = torch.empty(w.k, dtype=torch.int32, device=dev)
-    red = torch.empty(w.k, dtype=torch.float32, device=dev)
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    red = torch.empty(k, dtype=torch.float32, device=dev)
 
     def one_step(t):
         g = pool[t % pool_n]
-        if w.n_tensors == 1:
+        if args.select == "chunk":
+            ctx.scalecom_step_chunked(mem, g, w.rate, w.beta, w.lr, t, idx, red)
+        elif w.n_tensors == 1:
             ctx.scalecom_step(mem, g, w.k, w.beta, w.lr, t, idx, red)
         else:
             ctx.scalecom_step_layers(mem, g, w.offsets, w.ks, w.beta, w.lr, t, idx, red)
@@ -132,20 +149,26 @@ def main():
     for t in range(args.warmup):
         one_step(t)
     torch.cuda.synchronize()
-    ctx.scalecom_timing_begin(args.steps)
+    ctx.scalecom_timing_begin(args.steps)            # HIP events around the dominant kernel only
     t0 = time.perf_counter()
     for t in range(args.warmup, args.warmup + args.steps):
         one_step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    phases = ctx.scalecom_timing_read(args.steps)
+    timed = ctx.scalecom_timing_read(args.steps)
+    # outside the timed region: a few more steps with an event at every phase boundary
+    extra = min(args.steps, 10)
+    ctx.scalecom_timing_begin(extra, all_phases=True)
+    for t in range(args.warmup + args.steps, args.warmup + args.steps + extra):
+        one_step(t)
+    phases = ctx.scalecom_timing_read(extra)
 
     ms_per_step = elapsed / args.steps * 1e3
     elements = w.n_learners * w.numel
-    fused_bytes, step_bytes = algorithmic_bytes(w)
+    fused_bytes, step_bytes = algorithmic_bytes(w, k)
     n_ph = len(phases)
     phase_avg = [sum(p[j] for p in phases) / n_ph for j in range(binding.SCALECOM_N_PHASES)] if n_ph else None
-    fused_ms = phase_avg[4] if phase_avg else None      # phase 4 = the all-learner pass k_update
+    fused_ms = sum(p[4] for p in timed) / len(timed) if timed else None      # phase 4 = the all-learner pass k_update
     achieved = fused_bytes / (fused_ms * 1e-3) / 1e9 if fused_ms else None
 
     # practical ceiling: the library's plain copy kernel over 1 GiB (read + write)
@@ -175,7 +198,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": w.name, "n_learners": w.n_learners, "numel": w.numel, "k": w.k, "grad_dtype": w.grad_dtype,
+            "workload": w.name, "select": args.select, "n_learners": w.n_learners, "numel": w.numel, "k": k,
+            "grad_dtype": w.grad_dtype,
             "n_tensors": w.n_tensors, "beta": w.beta, "lr": w.lr, "gradient_pool": pool_n,
         },
         "roofline": {
@@ -185,7 +209,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS if achieved else None,
-            "traffic": recorded_traffic(w.name),
+            "traffic": recorded_traffic(w.name) if args.select == "exact" else None,
             "algorithmic_bytes_per_launch": fused_bytes,
             "avg_launch_ms": fused_ms,
         },
@@ -194,13 +218,13 @@ def main():
             "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
             "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "copy_kernel_GBps": copy_gbps,
-            "phase_ms": dict(zip(["leader_first_look", "leader_second_pass", "refine", "counts_scan_slots", "update", "reduce"], phase_avg)) if phase_avg else None,
+            "phase_ms_untimed_extra_steps": dict(zip(["leader_first_look", "leader_second_pass", "refine", "counts_scan_slots", "update", "reduce"], phase_avg)) if phase_avg else None,
         },
     }
     if not args.no_cpu_baseline:
         del pool
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, args.select)
     ctx.close()
     print(json.dumps(out))
 

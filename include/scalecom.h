@@ -64,7 +64,7 @@ typedef enum {
  * Bytes of device workspace needed for up to n_learners_max learners with vectors of up to
  * numel_max elements each, split into at most n_tensors_max segments (1 for whole-vector
  * use), with index sets of at most k_max positions in total per step.  Pure host arithmetic
- * (about 0.8 * numel_max + 4 * n_learners_max * k_max + 33 KB * n_tensors_max bytes).
+ * (about 0.8 * numel_max + (4 * n_learners_max + 16) * k_max + 90 KB * n_tensors_max bytes).
  * Returns 0 if an argument is out of range (numel_max < 0 or > 2^31 - 1, n_tensors_max < 1,
  * n_learners_max outside 1 .. SCALECOM_MAX_LEARNERS, k_max < 0 or > numel_max).
  */
@@ -126,6 +126,23 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
                                      int32_t* idx_out, float* reduced_vals_out);
 
 /*
+ * One iteration over whole vectors with the chunk-wise selector of the paper's own implementation
+ * (Sec. 4: the buffer is divided into chunks that are searched independently; App. E, Fig. A2:
+ * one position per chunk) in place of the exact top-k: the leader's x is cut into consecutive
+ * chunks of `chunk` elements (the last may be shorter) and each chunk contributes the position
+ * of its largest |x|, the lowest position among equals.  Everything else -- leader rule, gather,
+ * sum over learners, Eq. 5 -- is as in scalecom_step.  The index set has ceil(numel / chunk)
+ * positions, which must not exceed the context's k_max.
+ *   chunk            >= 1 (the compression rate; the paper uses 25 .. 400)
+ *   idx_out          [device] int32[ceil(numel / chunk)], ascending: entry j lies in chunk j
+ *   reduced_vals_out [device] float[ceil(numel / chunk)]
+ * Other arguments and errors as for scalecom_step.
+ */
+scalecom_status scalecom_step_chunked(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                                      int64_t numel, int64_t chunk, float beta, float lr, int64_t step,
+                                      int32_t* idx_out, float* reduced_vals_out);
+
+/*
  * Optional per-phase GPU timing, for benchmarks.  Not part of the paper's method: it only
  * records HIP events on the context's stream between the kernel groups of a step.
  * Phases of one step, in order:
@@ -137,16 +154,19 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
  *   4  all-learner pass: accumulate, low-pass memory update, members' values staged (Eq. 3, 5)
  *   5  sum of the staged values over learners (Alg. 1 line 10)
  *
- * scalecom_timing_begin: the next max_steps (0 .. 4096) calls of scalecom_step /
- * scalecom_step_layers on this context record their phase boundaries (later calls are not
- * recorded).  scalecom_timing_read: waits for the stream, writes
- * phase_ms[t * SCALECOM_N_PHASES + p] = milliseconds of phase p of recorded step t for at most
- * capacity_steps steps, stores the number of steps written in *n_steps_out, and stops recording.
+ * scalecom_timing_begin: the next max_steps (0 .. 4096) calls of scalecom_step* on this context
+ * record phase boundaries (later calls are not recorded).  With all_phases = 0 only the two
+ * boundaries of phase 4, the dominant kernel, are recorded (an event costs the stream a few
+ * microseconds, so this is what a throughput measurement should use); with all_phases != 0 all
+ * seven.  scalecom_timing_read: waits for the stream, writes
+ * phase_ms[t * SCALECOM_N_PHASES + p] = milliseconds of phase p of recorded step t (0 for phases
+ * that were not recorded) for at most capacity_steps steps, stores the number of steps written in
+ * *n_steps_out, and stops recording.
  *   phase_ms     [host] float[capacity_steps * SCALECOM_N_PHASES]
  *   n_steps_out  [host]
  */
 #define SCALECOM_N_PHASES 6
-scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps);
+scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps, int all_phases);
 scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int capacity_steps, int* n_steps_out);
 
 /*

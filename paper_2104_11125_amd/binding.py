@@ -44,9 +44,11 @@ def lib() -> ctypes.CDLL:
         L.scalecom_init.restype = i32
         L.scalecom_step.argtypes = [vp, vp, vp, i32, i64, i64, f32, f32, i64, vp, vp]
         L.scalecom_step.restype = i32
+        L.scalecom_step_chunked.argtypes = [vp, vp, vp, i32, i64, i64, f32, f32, i64, vp, vp]
+        L.scalecom_step_chunked.restype = i32
         L.scalecom_step_layers.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, f32, i64, vp, vp]
         L.scalecom_step_layers.restype = i32
-        L.scalecom_timing_begin.argtypes = [vp, i32]
+        L.scalecom_timing_begin.argtypes = [vp, i32, i32]
         L.scalecom_timing_begin.restype = i32
         L.scalecom_timing_read.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
         L.scalecom_timing_read.restype = i32
@@ -123,6 +125,23 @@ class ScaleCom:
         self._check(st)
         return idx_out, reduced_vals_out
 
+    def scalecom_step_chunked(self, mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor], chunk: int,
+                              beta: float, lr: float, step: int, idx_out: Optional[torch.Tensor] = None,
+                              reduced_vals_out: Optional[torch.Tensor] = None):
+        """``scalecom_step_chunked`` of the C-ABI: one position per chunk of ``chunk`` elements."""
+        self._check_buffers(mem, grad)
+        numel = mem[0].numel()
+        k = -(-numel // chunk) if chunk >= 1 else 0
+        if idx_out is None:
+            idx_out = torch.empty(k, dtype=torch.int32, device=self.device)
+        if reduced_vals_out is None:
+            reduced_vals_out = torch.empty(k, dtype=torch.float32, device=self.device)
+        st = lib().scalecom_step_chunked(self._ctx, _ptrs(mem), _ptrs(grad), len(mem), numel, chunk, beta, lr, step,
+                                         ctypes.c_void_p(idx_out.data_ptr()),
+                                         ctypes.c_void_p(reduced_vals_out.data_ptr()))
+        self._check(st)
+        return idx_out, reduced_vals_out
+
     def scalecom_step_layers(self, mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor],
                              offsets: Sequence[int], ks: Sequence[int], beta: float, lr: float, step: int,
                              idx_out: Optional[torch.Tensor] = None,
@@ -145,8 +164,8 @@ class ScaleCom:
         self._check(st)
         return idx_out, reduced_vals_out
 
-    def scalecom_timing_begin(self, max_steps: int) -> None:
-        self._check(lib().scalecom_timing_begin(self._ctx, max_steps))
+    def scalecom_timing_begin(self, max_steps: int, all_phases: bool = False) -> None:
+        self._check(lib().scalecom_timing_begin(self._ctx, max_steps, 1 if all_phases else 0))
 
     def scalecom_timing_read(self, capacity_steps: int):
         """Per-step lists of SCALECOM_N_PHASES phase durations in milliseconds."""

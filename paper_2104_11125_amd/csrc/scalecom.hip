@@ -1006,6 +1006,91 @@ k_reduce(const float* __restrict__ vals, int n_learners, int64_t k_total, float*
     red_out[t] = s;
 }
 
+// ------------------------------------------------------------------------------------------
+// chunk-wise selection (the selector of the paper's own implementation: Sec. 4, App. E)
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t wave_max64(uint64_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), off, kLanes);
+        const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), off, kLanes);
+        const uint64_t o = (static_cast<uint64_t>(hi) << 32) | lo;
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// Leader pass of the chunk-wise selector, one wave per wave tile: every element becomes the word
+// (magnitude key << 32 | ~position), so that the largest word of a chunk is its largest
+// magnitude at the lowest position; for each chunk that overlaps the tile the wave reduces its
+// part and merges it into best[chunk] with one 64-bit atomic max (a chunk touches at most
+// chunk/256 + 2 tiles).  Also clears the tile's membership mask.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_chunk_select(const float* __restrict__ mem, const G* __restrict__ grad, float lr, int64_t numel, int64_t chunk,
+               unsigned long long* __restrict__ best, uint64_t* __restrict__ sel_mask, int64_t n_tiles)
+{
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int64_t tile = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kWaves + wave;
+    if (tile >= n_tiles) return;                            // whole wave
+    const int64_t tile_first = tile * kWaveTile;
+    const int64_t p0 = tile_first + lane * kVec;
+    uint32_t key[4];
+    bool ok[4];
+    leader_keys(mem, grad, lr, p0, static_cast<int64_t>(0), numel, key, ok);
+    uint64_t word[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        word[c] = ok[c] ? (static_cast<uint64_t>(key[c]) << 32) | (0xffffffffu - static_cast<uint32_t>(p0 + c)) : 0ull;
+    if (lane == 0) {
+        const uint64_t zero[4] = {0, 0, 0, 0};
+        store_tile_masks(sel_mask, static_cast<size_t>(tile), zero);
+    }
+    const int64_t tile_last = (tile_first + kWaveTile < numel ? tile_first + kWaveTile : numel) - 1;
+    const int64_t j_first = tile_first / chunk, j_last = tile_last / chunk;
+    for (int64_t j = j_first; j <= j_last; ++j) {           // wave-uniform trip count
+        const int64_t lo = j * chunk, hi = lo + chunk;
+        uint64_t m = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (p0 + c >= lo && p0 + c < hi && word[c] > m) m = word[c];
+        m = wave_max64(m);
+        if (lane == 0) atomicMax(&best[j], static_cast<unsigned long long>(m));
+    }
+}
+
+// After the leader pass: position of each chunk's winner to idx_out and to the membership mask;
+// first output slot of every wave tile (chunk j owns slot j); and the other copy of best[] is
+// cleared for the next step.
+__global__ void __launch_bounds__(kBlock)
+k_chunk_marks(const unsigned long long* __restrict__ best, unsigned long long* __restrict__ best_next, int64_t k,
+              int64_t chunk, int64_t n_tiles, uint64_t* __restrict__ sel_mask, uint32_t* __restrict__ tile_slot,
+              int32_t* __restrict__ idx_out)
+{
+    const int64_t t = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
+    if (t < k) {
+        const uint32_t pos = 0xffffffffu - static_cast<uint32_t>(best[t]);
+        idx_out[t] = static_cast<int32_t>(pos);
+        const uint32_t tile = pos / kWaveTile, l = (pos % kWaveTile) / kVec, c = pos % kVec;
+        atomicOr(reinterpret_cast<uint32_t*>(sel_mask) + (static_cast<size_t>(tile) * 4 + c) * 2 + (l >> 5),
+                 1u << (l & 31));
+        best_next[t] = 0ull;
+    }
+    if (t < n_tiles) {
+        // winners before this tile: one per chunk that ends before it, plus the straddling
+        // chunk's winner if it lies before the tile
+        const int64_t first = t * kWaveTile;
+        const int64_t j = first / chunk;
+        uint32_t slot = static_cast<uint32_t>(j);
+        if (j < k && j * chunk < first) {
+            const uint32_t pos = 0xffffffffu - static_cast<uint32_t>(best[j]);
+            if (static_cast<int64_t>(pos) < first) ++slot;
+        }
+        tile_slot[t] = slot;
+    }
+}
+
 // Plain streaming copy, one 16-byte nontemporal load and store per thread: the yardstick the
 // other kernels' bandwidth and the profiler's byte counters are compared with.
 __global__ void __launch_bounds__(kBlock) k_copy(const vf4_t* __restrict__ src, vf4_t* __restrict__ dst, size_t n16)
@@ -1031,7 +1116,7 @@ inline int64_t max_chunks(int64_t numel_max, int n_tensors_max)
 
 struct WsLayout {
     size_t segs, sts, chunks, preds, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask, eq_mask,
-        tile_slot, vals, total;
+        tile_slot, vals, best, total;
     // per-step counters and histograms: two copies of one zone, used alternately (offsets inside a copy)
     size_t zone[2], zone_bytes, z_overflow, z_part, z_hist0, z_hist1, z_hist2;
 };
@@ -1080,6 +1165,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.eq_mask = take(ntile * 4 * sizeof(uint64_t));
     l.tile_slot = take(ntile * sizeof(uint32_t));
     l.vals = take(static_cast<size_t>(n_learners_max) * static_cast<size_t>(k_max) * sizeof(float));
+    l.best = take(2 * static_cast<size_t>(k_max) * sizeof(unsigned long long));   // chunk-wise selector, two copies
     l.total = o;
     return l;
 }
@@ -1107,6 +1193,8 @@ struct scalecom_ctx {
     int n_st = 0, n_chunks = 0;
     int parity = 0;                  // which copy of the scratch zone the next step uses
     bool scratch_clean = false;      // false: both copies must be cleared before the next step
+    int best_parity = 0;             // same scheme for the chunk-wise selector's per-chunk maxima
+    bool best_clean = false;
     char* pinned = nullptr;          // staging for the table upload
     size_t pinned_bytes = 0;
     hipEvent_t upload_done = nullptr;
@@ -1114,6 +1202,7 @@ struct scalecom_ctx {
     // optional per-phase timing: events recorded on the context's stream between kernel groups
     std::vector<hipEvent_t> prof_events;     // (SCALECOM_N_PHASES + 1) per recorded step
     int prof_cap = 0, prof_steps = 0;
+    bool prof_all = false;           // false: only the boundaries of the all-learner pass are recorded
     std::string last_error;
 };
 
@@ -1218,6 +1307,32 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     return SCALECOM_OK;
 }
 
+// The all-learner pass and the sum over learners, shared by the exact and the chunk-wise selector:
+// both leave the membership mask and the first output slot of every wave tile behind.
+template <typename G, typename Mark>
+void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int64_t k_total, float beta, float lr,
+                          int32_t* idx_out, float* red_out, Mark&& mark)
+{
+    char* ws = ctx->ws;
+    const WsLayout& l = ctx->lay;
+    hipStream_t s = ctx->stream;
+    const int n_st = ctx->n_st;
+    const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
+    const uint64_t* sel_mask = reinterpret_cast<const uint64_t*>(ws + l.sel_mask);
+    const uint32_t* tile_slot = reinterpret_cast<const uint32_t*>(ws + l.tile_slot);
+    float* vals = reinterpret_cast<float*>(ws + l.vals);
+    // groups of 4 wave tiles over grid y and z (y is limited to 65535); surplus groups find no supertile
+    const int64_t groups = static_cast<int64_t>(n_st) * kUpdateBlocksPerSuper;
+    const unsigned gz = static_cast<unsigned>((groups + 65534) / 65535);
+    const unsigned gy = static_cast<unsigned>((groups + gz - 1) / gz);
+    k_update<G><<<dim3(n_learners, gy, gz), kBlock, 0, s>>>(lp, lr, beta, 1.0f - beta, sts, n_st, sel_mask, tile_slot, vals,
+                                                           k_total, idx_out);
+    mark(5);
+    if (k_total > 0)
+        k_reduce<<<static_cast<unsigned>((k_total + kBlock - 1) / kBlock), kBlock, 0, s>>>(vals, n_learners, k_total,
+                                                                                           red_out);
+}
+
 template <typename G>
 scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, int64_t k_total,
                             float beta, float lr, int leader, int32_t* idx_out, float* red_out)
@@ -1246,7 +1361,6 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
     uint64_t* eq_mask = reinterpret_cast<uint64_t*>(ws + l.eq_mask);
     uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
-    float* vals = reinterpret_cast<float*>(ws + l.vals);
     hipStream_t s = ctx->stream;
     const int n_st = ctx->n_st;
     const float* memL = lp.mem[leader];
@@ -1255,8 +1369,8 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     // phase boundaries for scalecom_timing_*: one event before the first kernel, one after each phase
     const bool timed = ctx->prof_steps < ctx->prof_cap;
     hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
-    auto mark = [&](int boundary) {
-        if (timed) (void)hipEventRecord(ev[boundary], s);
+    auto mark = [&](int boundary) {   // boundaries 4 and 5 enclose the all-learner pass
+        if (timed && (ctx->prof_all || boundary == 4 || boundary == 5)) (void)hipEventRecord(ev[boundary], s);
     };
     mark(0);
     if (n_st > 0 && !ctx->scratch_clean) {   // first step, new layout, or a failed step: clear both scratch copies
@@ -1285,16 +1399,7 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
         k_slots<<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot,
                                                                 sel_mask, eq_mask, tile_slot);
         mark(4);
-        // groups of 4 wave tiles over grid y and z (y is limited to 65535); surplus groups find no supertile
-        const int64_t groups = static_cast<int64_t>(n_st) * kUpdateBlocksPerSuper;
-        const unsigned gz = static_cast<unsigned>((groups + 65534) / 65535);
-        const unsigned gy = static_cast<unsigned>((groups + gz - 1) / gz);
-        k_update<G><<<dim3(n_learners, gy, gz), kBlock, 0, s>>>(lp, lr, beta, 1.0f - beta, sts, n_st, sel_mask, tile_slot,
-                                                               vals, k_total, idx_out);
-        mark(5);
-        if (k_total > 0)
-            k_reduce<<<static_cast<unsigned>((k_total + kBlock - 1) / kBlock), kBlock, 0, s>>>(vals, n_learners, k_total,
-                                                                                               red_out);
+        launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
         mark(6);
         if (timed) ++ctx->prof_steps;
     }
@@ -1306,9 +1411,57 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     return SCALECOM_OK;
 }
 
+// One step with the chunk-wise selector: leader pass (per-chunk maxima), marks, then the same
+// all-learner pass and reduction as the exact path.
+template <typename G>
+scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int64_t numel, int64_t chunk,
+                               int64_t k_total, float beta, float lr, int leader, int32_t* idx_out, float* red_out)
+{
+    char* ws = ctx->ws;
+    const WsLayout& l = ctx->lay;
+    hipStream_t s = ctx->stream;
+    unsigned long long* best = reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity) * ctx->k_max;
+    unsigned long long* best_next =
+        reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity ^ 1) * ctx->k_max;
+    uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
+    uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
+    const bool timed = ctx->prof_steps < ctx->prof_cap;
+    hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
+    auto mark = [&](int boundary) {   // boundaries 4 and 5 enclose the all-learner pass
+        if (timed && (ctx->prof_all || boundary == 4 || boundary == 5)) (void)hipEventRecord(ev[boundary], s);
+    };
+    auto grid2 = [](int64_t blocks) {   // x up to 2^20 blocks, the rest over y
+        const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
+        return dim3(gx, static_cast<unsigned>((blocks + gx - 1) / gx));
+    };
+    mark(0);
+    if (!ctx->best_clean) {             // first chunked step of this context, or one failed before: clear both copies
+        const size_t words = 4 * static_cast<size_t>(ctx->k_max);   // 2 copies x 2 words per entry
+        const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
+        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.best), words);
+    }
+    ctx->best_clean = false;
+    const int64_t n_tiles = static_cast<int64_t>(ctx->n_st) * kTilesPerSuper;   // flat layout: tile t starts at 256 t
+    k_chunk_select<G><<<grid2((n_tiles + kWaves - 1) / kWaves), kBlock, 0, s>>>(
+        lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, numel, chunk, best, sel_mask, n_tiles);
+    mark(1);
+    mark(2);
+    mark(3);
+    k_chunk_marks<<<grid2((std::max(n_tiles, k_total) + kBlock - 1) / kBlock), kBlock, 0, s>>>(
+        best, best_next, k_total, chunk, n_tiles, sel_mask, tile_slot, idx_out);
+    mark(4);
+    launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
+    mark(6);
+    if (timed) ++ctx->prof_steps;
+    SC_HIP(ctx, hipGetLastError());
+    ctx->best_parity ^= 1;
+    ctx->best_clean = true;
+    return SCALECOM_OK;
+}
+
 scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
                             int n_tensors, const int64_t* offsets, const int64_t* ks, float beta, float lr,
-                            int64_t step, int32_t* idx_out, float* red_out)
+                            int64_t step, int32_t* idx_out, float* red_out, int64_t chunk = 0)
 {
     if (!ctx) return SCALECOM_EINVAL;
     ctx->last_error.clear();
@@ -1348,6 +1501,12 @@ scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* co
     scalecom_status st = ensure_tables(ctx, n_tensors, offsets, ks);
     if (st != SCALECOM_OK) return st;
     const int leader = static_cast<int>(step % n_learners);    // Alg. 1 line 6: CLT-k of learner mod(t, n)
+    if (chunk > 0) {                                            // chunk-wise selector on the whole vector
+        if (ctx->gdt == SCALECOM_GRAD_BF16)
+            return launch_chunked<uint16_t>(ctx, lp, n_learners, offsets[1], chunk, k_total, beta, lr, leader, idx_out,
+                                            red_out);
+        return launch_chunked<float>(ctx, lp, n_learners, offsets[1], chunk, k_total, beta, lr, leader, idx_out, red_out);
+    }
     if (ctx->gdt == SCALECOM_GRAD_BF16)
         return launch_step<uint16_t>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
     return launch_step<float>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
@@ -1415,6 +1574,18 @@ scalecom_status scalecom_step(scalecom_ctx* ctx, float* const* mem, const void* 
     return step_common(ctx, mem, grad, n_learners, 1, offsets, &k, beta, lr, step, idx_out, reduced_vals_out);
 }
 
+scalecom_status scalecom_step_chunked(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                                      int64_t numel, int64_t chunk, float beta, float lr, int64_t step,
+                                      int32_t* idx_out, float* reduced_vals_out)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    if (numel < 0 || numel > ctx->numel_max) return fail(ctx, SCALECOM_EINVAL, "numel out of range");
+    if (chunk < 1) return fail(ctx, SCALECOM_EINVAL, "chunk must be >= 1");
+    const int64_t offsets[2] = {0, numel};
+    const int64_t k = (numel + chunk - 1) / chunk;               // one position per chunk
+    return step_common(ctx, mem, grad, n_learners, 1, offsets, &k, beta, lr, step, idx_out, reduced_vals_out, chunk);
+}
+
 scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
                                      int n_tensors, const int64_t* offsets, const int64_t* ks, float beta, float lr,
                                      int64_t step, int32_t* idx_out, float* reduced_vals_out)
@@ -1441,7 +1612,7 @@ scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* s
     return SCALECOM_OK;
 }
 
-scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps)
+scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps, int all_phases)
 {
     if (!ctx) return SCALECOM_EINVAL;
     if (max_steps < 0 || max_steps > 4096) return fail(ctx, SCALECOM_EINVAL, "max_steps out of range");
@@ -1455,6 +1626,7 @@ scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps)
     }
     ctx->prof_cap = max_steps;
     ctx->prof_steps = 0;
+    ctx->prof_all = all_phases != 0;
     return SCALECOM_OK;
 }
 
@@ -1469,8 +1641,11 @@ scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int cap
     const int n = std::min(ctx->prof_steps, capacity_steps);
     for (int t = 0; t < n; ++t) {
         hipEvent_t* ev = &ctx->prof_events[static_cast<size_t>(t) * (SCALECOM_N_PHASES + 1)];
-        for (int p = 0; p < SCALECOM_N_PHASES; ++p)
-            SC_HIP(ctx, hipEventElapsedTime(&phase_ms[t * SCALECOM_N_PHASES + p], ev[p], ev[p + 1]));
+        for (int p = 0; p < SCALECOM_N_PHASES; ++p) {
+            float* out = &phase_ms[t * SCALECOM_N_PHASES + p];
+            *out = 0.0f;
+            if (ctx->prof_all || p == 4) SC_HIP(ctx, hipEventElapsedTime(out, ev[p], ev[p + 1]));
+        }
     }
     *n_steps_out = n;
     ctx->prof_cap = 0;   // recording stops until the next scalecom_timing_begin

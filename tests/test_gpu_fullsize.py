@@ -47,6 +47,19 @@ def test_resnet50_sized_full(gu):
     ctx.close()
 
 
+def test_resnet50_sized_chunked_full(gu):
+    """The chunk-wise selector at the benchmark's size and rate (one position per 112 elements)."""
+    w = workloads.by_name("resnet50_sized")
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV, k_max=-(-w.numel // w.rate))
+    mem = _random_memories(w, gu.DEV, 915)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    for step in (0, 5):
+        print(f"[fullsize] {w.name} chunked step {step}", flush=True)
+        grad = workloads.gradients(w, step, gu.DEV)
+        gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, chunk=w.rate, what=w.name + " chunked")
+    ctx.close()
+
+
 def test_per_layer_full(gu):
     w = workloads.by_name("per_layer")
     ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, w.n_tensors, gu.DEV, k_max=w.k)

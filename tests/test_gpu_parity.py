@@ -186,6 +186,40 @@ def test_per_layer_predictions(gu):
     ctx.close()
 
 
+# ------------------------------------------------------------------ chunk-wise selector
+@pytest.mark.parametrize("numel,chunk", [(1, 1), (5, 1), (7, 3), (1000, 112), (100_003, 112), (100_003, 400),
+                                         (65_536, 256), (65_536, 64), (40_000, 100), (9_000, 9_000), (9_000, 20_000),
+                                         (8_193, 255), (300_001, 25)])
+def test_chunked_selector(gu, numel, chunk):
+    n = 3
+    g = torch.Generator(device="cpu").manual_seed(numel * 31 + chunk)
+    mem = [(torch.randn(numel, generator=g) * 1e-3).to(gu.DEV) for _ in range(n)]
+    grad = [(torch.randn(numel, generator=g) * 1e-3).to(gu.DEV) for _ in range(n)]
+    ref = [m.cpu().numpy().copy() for m in mem]
+    ctx = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV)
+    for step in range(3):
+        gu.compare_step(ctx, mem, grad, ref, step, 0.3, 0.7, chunk=chunk, what=f"chunk={chunk} numel={numel}")
+    ctx.close()
+
+
+def test_chunked_selector_ties_bf16_and_mixed_calls(gu):
+    """Equal magnitudes inside a chunk go to the lowest position; bf16 gradients; and exact and
+    chunk-wise steps alternate on one context without disturbing each other."""
+    numel, n, chunk = 50_007, 4, 112
+    rng = np.random.default_rng(5)
+    vals = rng.choice(np.array([1.0, -1.0, 0.5, 0.0], np.float32), size=(n, numel))
+    ctx = binding.scalecom_init(numel, n, torch.bfloat16, 1, gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    grad = [torch.from_numpy(v).to(gu.DEV).to(torch.bfloat16) for v in vals]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    for step in range(6):
+        if step % 2:
+            gu.compare_step(ctx, mem, grad, ref, step, 0.5, 1.0, k=numel // 100, what="mixed exact")
+        else:
+            gu.compare_step(ctx, mem, grad, ref, step, 0.5, 1.0, chunk=chunk, what="mixed chunked")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
@@ -251,8 +285,10 @@ def test_argument_errors(gu):
     assert status(lambda: ctx.scalecom_step(mem, grad, 10, float("nan"), 0.1, 0)) == E
     assert status(lambda: ctx.scalecom_step(mem, grad, 10, 0.5, float("inf"), 0)) == E
     assert status(lambda: ctx.scalecom_step(mem, grad, 10, 0.5, 0.1, -1)) == E
+    assert status(lambda: ctx.scalecom_step_chunked(mem, grad, 0, 0.5, 0.1, 0)) == E      # chunk < 1
     small = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV, k_max=5)
     assert status(lambda: small.scalecom_step(mem, grad, 6, 0.5, 0.1, 0)) == E           # k > k_max of the context
+    assert status(lambda: small.scalecom_step_chunked(mem, grad, 100, 0.5, 0.1, 0)) == E  # 10 chunks > k_max
     small.close()
     assert status(lambda: ctx.scalecom_step(mem * 2, grad * 2, 10, 0.5, 0.1, 0)) == E     # more learners than the context allows
     big = [torch.zeros(numel + 1, device=gu.DEV) for _ in range(n)]
