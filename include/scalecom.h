@@ -143,6 +143,34 @@ scalecom_status scalecom_step_chunked(scalecom_ctx* ctx, float* const* mem, cons
                                       int32_t* idx_out, float* reduced_vals_out);
 
 /*
+ * Weight update on the index set (Alg. 1 lines 10 and 12): theta[idx[t]] -= scale * vals[t] for
+ * t < k, one rounding per entry (fma(-scale, vals[t], theta[idx[t]])).  With the outputs of a
+ * step, scale = 1 / n_learners applies the averaged compressed gradient when lr was the step
+ * size, and scale = alpha / n_learners when lr was 1.  Enqueued on the context's stream, so it
+ * may directly follow the step that produced idx and vals.
+ *   theta   [device] float[numel], updated in place at the k positions only
+ *   idx     [device] int32[k], distinct positions in [0, numel) (not checked on the device)
+ *   vals    [device] float[k]
+ *   scale   finite
+ * EINVAL for null pointers (when k > 0), k < 0, numel < 0 or non-finite scale.
+ */
+scalecom_status scalecom_apply_update(scalecom_ctx* ctx, float* theta, int64_t numel, const int32_t* idx,
+                                      const float* vals, int64_t k, float scale);
+
+/*
+ * Per-layer sizes of the index sets from the paper's rate guidance (Sec. 4): a layer whose
+ * FLOPs-per-gradient ratio is >= 196 is compressed 25X, one in [128, 196) 50X, one below 128
+ * 400X; ks_out[s] = ceil(sizes[s] / rate), ready for scalecom_step_layers.  Pure host arithmetic.
+ *   flops_per_gradient [host] double[n_tensors], each > 0
+ *   sizes              [host] int64[n_tensors], each >= 0
+ *   ks_out             [host] int64[n_tensors]
+ *   rates_out          [host] int64[n_tensors] or NULL: the rate chosen per layer
+ * EINVAL for null pointers, n_tensors < 0, a ratio that is not > 0, or a negative size.
+ */
+scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradient, const int64_t* sizes,
+                                  int64_t* ks_out, int64_t* rates_out);
+
+/*
  * Optional per-phase GPU timing, for benchmarks.  Not part of the paper's method: it only
  * records HIP events on the context's stream between the kernel groups of a step.
  * Phases of one step, in order:

@@ -47,6 +47,10 @@ def _load():
         lib.oracle_topk_select.argtypes = [vp, i64, i64, vp]
         lib.oracle_chunk_select.argtypes = [vp, i64, i64, vp]
         lib.oracle_step_chunked.argtypes = [vp, vp, i32, i32, i64, i64, f32, f32, i64, vp, vp]
+        lib.oracle_apply_update.argtypes = [vp, i64, vp, vp, i64, f32]
+        lib.oracle_apply_update.restype = ctypes.c_int
+        lib.oracle_layer_rate.argtypes = [ctypes.c_double]
+        lib.oracle_layer_rate.restype = ctypes.c_int64
         lib.oracle_gather.argtypes = [vp, vp, i64, vp]
         lib.oracle_reduce.argtypes = [vp, i32, i64, vp]
         lib.oracle_memory_update.argtypes = [vp, vp, vp, i64, i64, f32]
@@ -135,6 +139,20 @@ def step_chunked(mem, grad, chunk: int, beta: float, lr: float, step: int):
     if rc:
         raise ValueError("oracle_step_chunked: bad arguments")
     return idx, red
+
+
+def apply_update(theta: np.ndarray, idx: np.ndarray, reduced: np.ndarray, scale: float) -> None:
+    """theta[idx] -= scale * reduced, in place (Alg. 1 lines 10 and 12 on the index set)."""
+    _check_f32(theta, "theta")
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    reduced = np.ascontiguousarray(reduced, dtype=np.float32)
+    if _load().oracle_apply_update(_p(theta), theta.size, _p(idx), _p(reduced), idx.size, scale):
+        raise ValueError("oracle_apply_update: index out of range")
+
+
+def layer_rate(flops_per_gradient: float) -> int:
+    """Compression rate of a layer from its FLOPs/gradient ratio (Sec. 4)."""
+    return int(_load().oracle_layer_rate(float(flops_per_gradient)))
 
 
 def gather(acc: np.ndarray, idx: np.ndarray) -> np.ndarray:

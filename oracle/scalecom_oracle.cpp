@@ -172,6 +172,28 @@ int oracle_memory_update(float* mem, const float* acc, const int32_t* idx, int64
     return 0;
 }
 
+// Weight update of Alg. 1 lines 10 and 12 on the index set: theta[idx[t]] -= scale * reduced[t],
+// with scale = alpha / n when `reduced` is the plain sum of the learners' values (line 10 divides
+// by n, line 12 multiplies by alpha), or 1 / n when the step size was already applied in the
+// accumulate.  One rounding per entry: fmaf(-scale, reduced, theta).
+int oracle_apply_update(float* theta, int64_t numel, const int32_t* idx, const float* reduced, int64_t k, float scale)
+{
+    for (int64_t t = 0; t < k; ++t) {
+        if (idx[t] < 0 || idx[t] >= numel) return 1;
+        theta[idx[t]] = std::fmaf(-scale, reduced[t], theta[idx[t]]);
+    }
+    return 0;
+}
+
+// Compression rate of a layer from its FLOPs-per-gradient ratio (Sec. 4, "conservative engineering
+// guidance"): 25X for a ratio in [196, inf), 50X for [128, 196), 400X for (0, 128).
+int64_t oracle_layer_rate(double flops_per_gradient)
+{
+    if (flops_per_gradient >= 196.0) return 25;
+    if (flops_per_gradient >= 128.0) return 50;
+    return 400;
+}
+
 // One iteration of Alg. 1 lines 6, 7 and 10 for n learners whose vectors are split into
 // n_tensors consecutive segments [offsets[s], offsets[s+1]); the index set of each segment
 // is chosen inside that segment with its own k (per-layer compression, Sec. 4) by the same

@@ -52,6 +52,10 @@ def lib() -> ctypes.CDLL:
         L.scalecom_timing_begin.restype = i32
         L.scalecom_timing_read.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
         L.scalecom_timing_read.restype = i32
+        L.scalecom_apply_update.argtypes = [vp, vp, i64, vp, vp, i64, f32]
+        L.scalecom_apply_update.restype = i32
+        L.scalecom_layer_ks.argtypes = [i32, vp, vp, vp, vp]
+        L.scalecom_layer_ks.restype = i32
         L.scalecom_stream_copy.argtypes = [vp, vp, vp, sz]
         L.scalecom_stream_copy.restype = i32
         L.scalecom_strerror.argtypes = [i32]
@@ -70,6 +74,21 @@ def scalecom_workspace_bytes(numel_max: int, n_tensors_max: int, n_learners_max:
 
 def _ptrs(tensors: Sequence[torch.Tensor]):
     return (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def scalecom_layer_ks(flops_per_gradient: Sequence[float], sizes: Sequence[int]):
+    """``scalecom_layer_ks`` of the C-ABI: (ks, rates) per layer from the paper's rate guidance."""
+    n = len(sizes)
+    if len(flops_per_gradient) != n:
+        raise ValueError("one ratio per layer")
+    c_r = (ctypes.c_double * n)(*[float(v) for v in flops_per_gradient])
+    c_s = (ctypes.c_int64 * n)(*[int(v) for v in sizes])
+    c_k = (ctypes.c_int64 * n)()
+    c_rate = (ctypes.c_int64 * n)()
+    st = lib().scalecom_layer_ks(n, c_r, c_s, c_k, c_rate)
+    if st != SCALECOM_OK:
+        raise ScaleComError(st)
+    return list(c_k), list(c_rate)
 
 
 class ScaleCom:
@@ -173,6 +192,16 @@ class ScaleCom:
         n = ctypes.c_int(0)
         self._check(lib().scalecom_timing_read(self._ctx, buf, capacity_steps, ctypes.byref(n)))
         return [[buf[t * SCALECOM_N_PHASES + p] for p in range(SCALECOM_N_PHASES)] for t in range(n.value)]
+
+    def scalecom_apply_update(self, theta: torch.Tensor, idx: torch.Tensor, vals: torch.Tensor, scale: float) -> None:
+        """``scalecom_apply_update`` of the C-ABI: theta[idx] -= scale * vals, in place."""
+        if theta.dtype != torch.float32 or idx.dtype != torch.int32 or vals.dtype != torch.float32:
+            raise TypeError("theta/vals must be float32 and idx int32")
+        if idx.numel() != vals.numel():
+            raise ValueError("idx and vals must have the same length")
+        self._check(lib().scalecom_apply_update(self._ctx, ctypes.c_void_p(theta.data_ptr()), theta.numel(),
+                                                ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(vals.data_ptr()),
+                                                idx.numel(), scale))
 
     def scalecom_stream_copy(self, dst: torch.Tensor, src: torch.Tensor) -> None:
         nbytes = src.numel() * src.element_size()

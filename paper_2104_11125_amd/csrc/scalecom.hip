@@ -1091,6 +1091,17 @@ k_chunk_marks(const unsigned long long* __restrict__ best, unsigned long long* _
     }
 }
 
+// Weight update on the index set (Alg. 1 lines 10 and 12): theta[idx[t]] -= scale * vals[t].
+__global__ void __launch_bounds__(kBlock)
+k_apply_update(float* __restrict__ theta, const int32_t* __restrict__ idx, const float* __restrict__ vals, int64_t k,
+               float neg_scale)
+{
+    const int64_t t = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
+    if (t >= k) return;
+    const int32_t j = idx[t];
+    theta[j] = fmaf(neg_scale, vals[t], theta[j]);
+}
+
 // Plain streaming copy, one 16-byte nontemporal load and store per thread: the yardstick the
 // other kernels' bandwidth and the profiler's byte counters are compared with.
 __global__ void __launch_bounds__(kBlock) k_copy(const vf4_t* __restrict__ src, vf4_t* __restrict__ dst, size_t n16)
@@ -1592,6 +1603,39 @@ scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const
 {
     return step_common(ctx, mem, grad, n_learners, n_tensors, offsets, ks, beta, lr, step, idx_out,
                        reduced_vals_out);
+}
+
+scalecom_status scalecom_apply_update(scalecom_ctx* ctx, float* theta, int64_t numel, const int32_t* idx,
+                                      const float* vals, int64_t k, float scale)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    ctx->last_error.clear();
+    if (k < 0 || numel < 0 || !std::isfinite(scale)) return fail(ctx, SCALECOM_EINVAL, "bad size or scale");
+    if (k == 0) return SCALECOM_OK;
+    if (!theta || !idx || !vals) return fail(ctx, SCALECOM_EINVAL, "null argument");
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    const int64_t blocks = (k + kBlock - 1) / kBlock;
+    const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
+    const unsigned gy = static_cast<unsigned>((blocks + gx - 1) / gx);
+    k_apply_update<<<dim3(gx, gy), kBlock, 0, ctx->stream>>>(theta, idx, vals, k, -scale);
+    SC_HIP(ctx, hipGetLastError());
+    return SCALECOM_OK;
+}
+
+scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradient, const int64_t* sizes,
+                                  int64_t* ks_out, int64_t* rates_out)
+{
+    if (n_tensors < 0 || (n_tensors > 0 && (!flops_per_gradient || !sizes || !ks_out))) return SCALECOM_EINVAL;
+    for (int s = 0; s < n_tensors; ++s)
+        if (!(flops_per_gradient[s] > 0.0) || sizes[s] < 0) return SCALECOM_EINVAL;
+    for (int s = 0; s < n_tensors; ++s) {
+        // Sec. 4: 25X for a FLOPs/gradient ratio in [196, inf), 50X for [128, 196), 400X below 128
+        const int64_t rate = flops_per_gradient[s] >= 196.0 ? 25 : (flops_per_gradient[s] >= 128.0 ? 50 : 400);
+        ks_out[s] = (sizes[s] + rate - 1) / rate;
+        if (rates_out) rates_out[s] = rate;
+    }
+    return SCALECOM_OK;
 }
 
 scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* src, size_t bytes)

@@ -62,3 +62,17 @@ def test_workloads_match_the_benchmark_table():
     pl = cfg["per_layer"]
     assert pl.n_tensors == 200 and len(pl.offsets) == 201 and all(64 <= b - a <= 4_194_304 for a, b in zip(pl.offsets, pl.offsets[1:]))
     assert all(k == -(-(b - a) // 100) for k, a, b in zip(pl.ks, pl.offsets, pl.offsets[1:]))
+
+
+def test_layer_ks_follows_the_rate_guidance():
+    import oracle
+    ratios = [3000.0, 196.0, 150.0, 128.0, 64.0, 0.5]
+    sizes = [1_000_000, 25, 4097, 50, 400, 0]
+    ks, rates = binding.scalecom_layer_ks(ratios, sizes)
+    assert rates == [25, 25, 50, 50, 400, 400] == [oracle.layer_rate(r) for r in ratios]
+    assert ks == [40_000, 1, 82, 1, 1, 0]
+    L = binding.lib()
+    assert L.scalecom_layer_ks(1, None, None, None, None) == binding.SCALECOM_EINVAL
+    bad = (ctypes.c_double * 1)(0.0); one = (ctypes.c_int64 * 1)(5); out = (ctypes.c_int64 * 1)()
+    assert L.scalecom_layer_ks(1, bad, one, out, None) == binding.SCALECOM_EINVAL
+    assert L.scalecom_apply_update(None, None, 0, None, None, 0, 1.0) == binding.SCALECOM_EINVAL

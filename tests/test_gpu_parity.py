@@ -220,6 +220,29 @@ def test_chunked_selector_ties_bf16_and_mixed_calls(gu):
     ctx.close()
 
 
+def test_apply_update_after_a_step(gu):
+    """Alg. 1 lines 10 and 12: the step's outputs applied to the weights on the same stream."""
+    import oracle
+    w = workloads.scaled(workloads.by_name("resnet50_sized"), 400_003, n_learners=4, steps=1)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV)
+    mem = workloads.zero_memories(w, gu.DEV)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    g = torch.Generator(device="cpu").manual_seed(8)
+    theta = torch.randn(w.numel, generator=g).to(gu.DEV)
+    theta_ref = theta.cpu().numpy().copy()
+    for step in range(3):
+        grad = workloads.gradients(w, step, gu.DEV)
+        idx, red = gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, k=w.k, what="apply")
+        ctx.scalecom_apply_update(theta, idx, red, 1.0 / w.n_learners)
+        oracle.apply_update(theta_ref, idx.cpu().numpy(), red.cpu().numpy(), 1.0 / w.n_learners)
+        torch.cuda.synchronize()
+        gu.assert_same("theta", theta.cpu().numpy(), theta_ref, 1e-6, f"step {step}")
+    ctx.scalecom_apply_update(theta, idx[:0], red[:0], 1.0)          # k = 0: nothing happens
+    with pytest.raises(binding.ScaleComError):
+        ctx.scalecom_apply_update(theta, idx, red, float("nan"))
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and

@@ -373,3 +373,33 @@ def test_chunked_step_equals_primitives():
     assert np.array_equal(red, oracle.reduce([a[want_idx] for a in accs]))
     for i in range(n):
         assert np.array_equal(mem[i], want_mem[i])
+
+
+# ---------------------------------------------------------------- weight update and rate guidance
+def test_apply_update_closed_form_and_full_iteration():
+    """Alg. 1 lines 10 and 12 on the index set: with every learner sending the same gradient g,
+    zero memory and k = numel, the compressed average is g and theta moves by -alpha * g exactly."""
+    rng = np.random.default_rng(41)
+    n, numel, alpha = 4, 257, 0.5
+    g = f32(rng.integers(-8, 9, size=numel) / 8.0)                    # dyadic: every step below is exact
+    theta = f32(rng.integers(-64, 65, size=numel) / 16.0)
+    want = theta - np.float32(alpha) * g
+    mem = [np.zeros(numel, np.float32) for _ in range(n)]
+    idx, red = oracle.step(mem, [g.copy() for _ in range(n)], numel, 1.0, 1.0, 0)
+    oracle.apply_update(theta, idx, red, alpha / n)
+    assert np.array_equal(theta, want)
+    # sparse case against float64, untouched entries stay bit-identical
+    theta = f32(rng.standard_normal(1000)); before = theta.copy()
+    idx = np.array([3, 10, 999], np.int32); red = f32([0.3, -1.7, 2.5])
+    oracle.apply_update(theta, idx, red, 0.125)
+    assert np.allclose(theta[idx], before[idx].astype(np.float64) - 0.125 * red.astype(np.float64), rtol=1e-7)
+    rest = np.setdiff1d(np.arange(1000), idx)
+    assert np.array_equal(theta[rest], before[rest])
+    with pytest.raises(ValueError):
+        oracle.apply_update(theta, np.array([1000], np.int32), f32([1.0]), 1.0)
+
+
+def test_layer_rate_guidance_table():
+    """Sec. 4: 25X for FLOPs/gradient in [196, inf), 50X for [128, 196), 400X for (0, 128)."""
+    for ratio, rate in ((1e6, 25), (196.0, 25), (195.999, 50), (128.0, 50), (127.999, 400), (1.0, 400), (1e-3, 400)):
+        assert oracle.layer_rate(ratio) == rate
