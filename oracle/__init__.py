@@ -51,6 +51,10 @@ def _load():
         lib.oracle_apply_update.restype = ctypes.c_int
         lib.oracle_layer_rate.argtypes = [ctypes.c_double]
         lib.oracle_layer_rate.restype = ctypes.c_int64
+        lib.oracle_hamming_distance.argtypes = [vp, vp, i32, i32, i64, i64, f32, i64]
+        lib.oracle_hamming_distance.restype = ctypes.c_int64
+        lib.oracle_cosine_distance.argtypes = [vp, vp, i64]
+        lib.oracle_cosine_distance.restype = ctypes.c_double
         lib.oracle_gather.argtypes = [vp, vp, i64, vp]
         lib.oracle_reduce.argtypes = [vp, i32, i64, vp]
         lib.oracle_memory_update.argtypes = [vp, vp, vp, i64, i64, f32]
@@ -153,6 +157,23 @@ def apply_update(theta: np.ndarray, idx: np.ndarray, reduced: np.ndarray, scale:
 def layer_rate(flops_per_gradient: float) -> int:
     """Compression rate of a layer from its FLOPs/gradient ratio (Sec. 4)."""
     return int(_load().oracle_layer_rate(float(flops_per_gradient)))
+
+
+def hamming_distance(mem, grad, k: int, lr: float, step: int) -> int:
+    """d of Eq. 6 between the leader's top-k and the top-k of the summed error-feedback gradients."""
+    for m in mem:
+        _check_f32(m, "mem[i]")
+    d = _load().oracle_hamming_distance(_ptr_array(mem), _ptr_array(grad), _grad_dtype(grad[0]), len(mem),
+                                        mem[0].size, k, lr, step)
+    if d < 0:
+        raise ValueError("oracle_hamming_distance: bad arguments")
+    return int(d)
+
+
+def cosine_distance(a: np.ndarray, b: np.ndarray) -> float:
+    _check_f32(a, "a")
+    _check_f32(b, "b")
+    return float(_load().oracle_cosine_distance(_p(a), _p(b), a.size))
 
 
 def gather(acc: np.ndarray, idx: np.ndarray) -> np.ndarray:

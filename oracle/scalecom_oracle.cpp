@@ -29,6 +29,7 @@
 #include <cstdint>
 #include <cstring>
 #include <functional>
+#include <iterator>
 #include <vector>
 
 namespace {
@@ -192,6 +193,42 @@ int64_t oracle_layer_rate(double flops_per_gradient)
     if (flops_per_gradient >= 196.0) return 25;
     if (flops_per_gradient >= 128.0) return 50;
     return 400;
+}
+
+// Similarity diagnostics of Sec. 3.  Hamming distance between the leader's index set and the
+// "true top-k", the top-k of the all-reduced error-feedback gradient y = sum_i x_i (Lemma 1 takes
+// the mean; the positive factor 1/n does not change the set): both sets have k members, the
+// binarised vectors of Eq. 6 differ in 2d places, and d = k - |intersection| is returned
+// (Fig. 3 plots d / k).  Nothing is modified.
+int64_t oracle_hamming_distance(const float* const* mem, const void* const* grad, int grad_dtype, int n_learners,
+                                int64_t numel, int64_t k, float lr, int64_t step)
+{
+    if (n_learners < 1 || numel < 0 || k < 0 || k > numel || step < 0) return -1;
+    const int leader = static_cast<int>(step % n_learners);
+    std::vector<float> acc(static_cast<size_t>(numel)), y(static_cast<size_t>(numel)), xl(static_cast<size_t>(numel));
+    for (int i = 0; i < n_learners; ++i) {
+        oracle_accumulate(mem[i], grad[i], grad_dtype, numel, lr, acc.data());
+        if (i == leader) xl = acc;
+        for (int64_t j = 0; j < numel; ++j) y[j] = i == 0 ? acc[j] : y[j] + acc[j];
+    }
+    std::vector<int32_t> a(static_cast<size_t>(k)), b(static_cast<size_t>(k));
+    if (oracle_topk_select(xl.data(), numel, k, a.data()) || oracle_topk_select(y.data(), numel, k, b.data())) return -1;
+    std::vector<int32_t> both;
+    std::set_intersection(a.begin(), a.end(), b.begin(), b.end(), std::back_inserter(both));
+    return k - static_cast<int64_t>(both.size());
+}
+
+// Cosine distance 1 - a.b / (|a| |b|) of two vectors (footnote of Sec. 2: similarity of two
+// learners' memories), accumulated in binary64.
+double oracle_cosine_distance(const float* a, const float* b, int64_t numel)
+{
+    double ab = 0.0, aa = 0.0, bb = 0.0;
+    for (int64_t j = 0; j < numel; ++j) {
+        ab += static_cast<double>(a[j]) * static_cast<double>(b[j]);
+        aa += static_cast<double>(a[j]) * static_cast<double>(a[j]);
+        bb += static_cast<double>(b[j]) * static_cast<double>(b[j]);
+    }
+    return 1.0 - ab / (std::sqrt(aa) * std::sqrt(bb));
 }
 
 // One iteration of Alg. 1 lines 6, 7 and 10 for n learners whose vectors are split into

@@ -403,3 +403,41 @@ def test_layer_rate_guidance_table():
     """Sec. 4: 25X for FLOPs/gradient in [196, inf), 50X for [128, 196), 400X for (0, 128)."""
     for ratio, rate in ((1e6, 25), (196.0, 25), (195.999, 50), (128.0, 50), (127.999, 400), (1.0, 400), (1e-3, 400)):
         assert oracle.layer_rate(ratio) == rate
+
+
+# ---------------------------------------------------------------- similarity diagnostics (Sec. 2, Sec. 3)
+def test_hamming_distance_extremes_and_brute_force():
+    rng = np.random.default_rng(51)
+    n, numel, k = 4, 3000, 60
+    base = f32(rng.standard_normal(numel))
+    zeros = [np.zeros(numel, np.float32) for _ in range(n)]
+    # identical learners: the sum is n * x, same order of magnitudes, distance 0
+    assert oracle.hamming_distance(zeros, [base.copy() for _ in range(n)], k, 1.0, 2) == 0
+    # the leader alone is large on a support where the others vanish and the rest cancel it
+    lead = np.zeros(numel, np.float32); lead[:k] = 5.0
+    other = np.zeros(numel, np.float32); other[:k] = -5.0; other[k:2 * k] = 3.0
+    assert oracle.hamming_distance(zeros[:2], [lead, other], k, 1.0, 0) == k
+    # brute force on random data, with memory and lr
+    mem, grad = _random_problem(rng, n, numel)
+    for step in range(n):
+        accs = [oracle.accumulate(mem[i], grad[i], 0.3) for i in range(n)]
+        y = accs[0].copy()
+        for i in range(1, n):
+            y = y + accs[i]
+        want = k - len(set(brute_topk(accs[step % n], k).tolist()) & set(brute_topk(y, k).tolist()))
+        assert oracle.hamming_distance(mem, grad, k, 0.3, step) == want
+        assert 0 <= want <= k
+
+
+def test_cosine_distance_closed_forms():
+    rng = np.random.default_rng(52)
+    a = f32(rng.standard_normal(5000))
+    assert oracle.cosine_distance(a, f32(3.0 * a)) == pytest.approx(0.0, abs=1e-7)
+    assert oracle.cosine_distance(a, f32(-a)) == pytest.approx(2.0, abs=1e-7)
+    e1 = np.zeros(8, np.float32); e1[0] = 2.0
+    e2 = np.zeros(8, np.float32); e2[3] = -7.0
+    assert oracle.cosine_distance(e1, e2) == 1.0
+    b = f32(rng.standard_normal(5000))
+    want = 1.0 - float(np.dot(a.astype(np.float64), b.astype(np.float64))) / (
+        float(np.linalg.norm(a.astype(np.float64))) * float(np.linalg.norm(b.astype(np.float64))))
+    assert oracle.cosine_distance(a, b) == pytest.approx(want, rel=1e-12)
