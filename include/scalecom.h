@@ -158,6 +158,36 @@ scalecom_status scalecom_apply_update(scalecom_ctx* ctx, float* theta, int64_t n
                                       const float* vals, int64_t k, float scale);
 
 /*
+ * Similarity diagnostic of Sec. 3 (Eq. 6, Fig. 3): per tensor, the Hamming distance d between the
+ * index set CLT-k would use at `step` (the top-k of the leader's x = fma(lr, grad, mem), Eq. 3)
+ * and the "true top-k", the top-k of the all-reduced error-feedback gradient sum_i x_i (summed
+ * over learners 0..n-1 left to right in fp32; the 1/n of the mean does not change the set).  Both
+ * sets have ks[s] members, the binarised vectors of Eq. 6 differ in 2 d places, and
+ * d_out[s] = ks[s] - |intersection| (the paper plots d / k).  Same tie rule as scalecom_step.
+ * Reads mem and grad, modifies neither, and leaves the bucket predictions of scalecom_step alone.
+ *   mem, grad, n_learners, n_tensors, offsets, ks, lr, step: as for scalecom_step_layers
+ *   scratch       [device] at least scalecom_hamming_scratch_bytes(numel_max, n_tensors_max) bytes
+ *                 (the context's maxima), 256-byte aligned, caller-owned, contents undefined afterwards
+ *   d_out         [device] int32[n_tensors]
+ * Asynchronous on the context's stream.  EINVAL / ENOMEM as for scalecom_step_layers, plus ENOMEM
+ * for a scratch that is too small.
+ */
+size_t scalecom_hamming_scratch_bytes(int64_t numel_max, int n_tensors_max);
+scalecom_status scalecom_hamming_distance(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                                          int n_tensors, const int64_t* offsets, const int64_t* ks, float lr,
+                                          int64_t step, void* scratch, size_t scratch_bytes, int32_t* d_out);
+
+/*
+ * Cosine distance 1 - a.b / (|a| |b|) of two fp32 vectors (Sec. 2 measures the similarity of two
+ * learners' memories with it), accumulated in binary64.
+ *   a, b   [device] float[numel]
+ *   out    [device] double[4], 8-byte aligned: out[0] the distance, out[1..3] = a.b, a.a, b.b
+ * The order of the partial sums is not fixed: results agree to a few ulp of binary64 between
+ * runs.  A zero vector gives NaN.  Asynchronous on the context's stream.
+ */
+scalecom_status scalecom_cosine_distance(scalecom_ctx* ctx, const float* a, const float* b, int64_t numel, double* out);
+
+/*
  * Per-layer sizes of the index sets from the paper's rate guidance (Sec. 4): a layer whose
  * FLOPs-per-gradient ratio is >= 196 is compressed 25X, one in [128, 196) 50X, one below 128
  * 400X; ks_out[s] = ceil(sizes[s] / rate), ready for scalecom_step_layers.  Pure host arithmetic.

@@ -54,6 +54,12 @@ def lib() -> ctypes.CDLL:
         L.scalecom_timing_read.restype = i32
         L.scalecom_apply_update.argtypes = [vp, vp, i64, vp, vp, i64, f32]
         L.scalecom_apply_update.restype = i32
+        L.scalecom_hamming_scratch_bytes.argtypes = [i64, i32]
+        L.scalecom_hamming_scratch_bytes.restype = sz
+        L.scalecom_hamming_distance.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, i64, vp, sz, vp]
+        L.scalecom_hamming_distance.restype = i32
+        L.scalecom_cosine_distance.argtypes = [vp, vp, vp, i64, vp]
+        L.scalecom_cosine_distance.restype = i32
         L.scalecom_layer_ks.argtypes = [i32, vp, vp, vp, vp]
         L.scalecom_layer_ks.restype = i32
         L.scalecom_stream_copy.argtypes = [vp, vp, vp, sz]
@@ -102,6 +108,8 @@ class ScaleCom:
         if grad_dtype not in (torch.float32, torch.bfloat16):
             raise TypeError("grad_dtype must be torch.float32 or torch.bfloat16")
         self.grad_dtype = grad_dtype
+        self.numel_max, self.n_tensors_max = numel_max, n_tensors_max
+        self._diag_scratch = None
         k_max = numel_max if k_max is None else k_max
         nbytes = scalecom_workspace_bytes(numel_max, n_tensors_max, n_learners_max, k_max)
         if nbytes == 0:
@@ -202,6 +210,43 @@ class ScaleCom:
         self._check(lib().scalecom_apply_update(self._ctx, ctypes.c_void_p(theta.data_ptr()), theta.numel(),
                                                 ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(vals.data_ptr()),
                                                 idx.numel(), scale))
+
+    def scalecom_hamming_distance(self, mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor],
+                                  offsets: Sequence[int], ks: Sequence[int], lr: float, step: int,
+                                  d_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """``scalecom_hamming_distance`` of the C-ABI; the scratch buffer is allocated on first use and kept."""
+        self._check_buffers(mem, grad)
+        n_tensors = len(ks)
+        if len(offsets) != n_tensors + 1:
+            raise ValueError("offsets must have len(ks) + 1 entries")
+        c_off = (ctypes.c_int64 * (n_tensors + 1))(*[int(o) for o in offsets])
+        c_ks = (ctypes.c_int64 * n_tensors)(*[int(v) for v in ks])
+        if self._diag_scratch is None:
+            nbytes = lib().scalecom_hamming_scratch_bytes(self.numel_max, self.n_tensors_max)
+            self._diag_scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        if d_out is None:
+            d_out = torch.empty(n_tensors, dtype=torch.int32, device=self.device)
+        elif d_out.dtype != torch.int32 or d_out.numel() < n_tensors:
+            raise TypeError("d_out must be int32 with one entry per tensor")
+        st = lib().scalecom_hamming_distance(self._ctx, _ptrs(mem), _ptrs(grad), len(mem), n_tensors, c_off, c_ks, lr,
+                                             step, ctypes.c_void_p(self._diag_scratch.data_ptr()),
+                                             self._diag_scratch.numel(), ctypes.c_void_p(d_out.data_ptr()))
+        self._check(st)
+        return d_out
+
+    def scalecom_cosine_distance(self, a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """``scalecom_cosine_distance`` of the C-ABI; returns the 4 doubles (distance, a.b, a.a, b.b)."""
+        if a.dtype != torch.float32 or b.dtype != torch.float32 or a.numel() != b.numel():
+            raise TypeError("a and b must be float32 vectors of one length")
+        if not (a.is_contiguous() and b.is_contiguous() and a.device == self.device and b.device == self.device):
+            raise ValueError("a and b must be contiguous tensors on the context's device")
+        if out is None:
+            out = torch.empty(4, dtype=torch.float64, device=self.device)
+        elif out.dtype != torch.float64 or out.numel() < 4:
+            raise TypeError("out must hold 4 float64 values")
+        self._check(lib().scalecom_cosine_distance(self._ctx, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()),
+                                                   a.numel(), ctypes.c_void_p(out.data_ptr())))
+        return out
 
     def scalecom_stream_copy(self, dst: torch.Tensor, src: torch.Tensor) -> None:
         nbytes = src.numel() * src.element_size()

@@ -154,6 +154,11 @@ __device__ __forceinline__ void store4(float* p, const float4& v)
     __builtin_nontemporal_store(w, reinterpret_cast<vf4_t*>(p));
 }
 
+// Stand-in gradient type for selecting on a plain vector: every element reads as +0, so that
+// x = fma(lr, 0, v) has v's magnitude bits for any finite lr (non-finite v included).  Never
+// dereferenced.
+struct NoGrad {};
+
 // number of set bits of a wave-wide ballot that belong to lanes below the calling lane
 __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
 {
@@ -181,6 +186,11 @@ __device__ __forceinline__ float4 load_guarded(const T* base, int64_t p0, int64_
         v[c] = (p >= begin && p < end) ? widen(base[p]) : 0.0f;
     }
     return make_float4(v[0], v[1], v[2], v[3]);
+}
+
+__device__ __forceinline__ float4 load_guarded(const NoGrad*, int64_t, int64_t, int64_t, bool)
+{
+    return make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
 
 __device__ __forceinline__ void store_guarded(float* base, int64_t p0, int64_t begin, int64_t end, bool full,
@@ -1102,6 +1112,82 @@ k_apply_update(float* __restrict__ theta, const int32_t* __restrict__ idx, const
     theta[j] = fmaf(neg_scale, vals[t], theta[j]);
 }
 
+// Similarity diagnostics (Sec. 3) --------------------------------------------------------------
+// y[p] = sum over learners 0..n-1, left to right, of x_i[p] = fma(lr, grad_i[p], mem_i[p]): the
+// all-reduced error-feedback gradient whose top-k is the "true top-k" (times n, which does not
+// change the order of magnitudes).
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_sum_x(const LearnerPtrs lp, int n_learners, float lr, int64_t begin, int64_t end, float* __restrict__ y)
+{
+    const int64_t p = begin + (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
+    if (p >= end) return;
+    float acc = fmaf(lr, widen(static_cast<const G*>(lp.grad[0])[p]), lp.mem[0][p]);
+    for (int i = 1; i < n_learners; ++i) acc += fmaf(lr, widen(static_cast<const G*>(lp.grad[i])[p]), lp.mem[i][p]);
+    y[p] = acc;
+}
+
+__global__ void __launch_bounds__(kBlock) k_set_ks(const SegDesc* __restrict__ segs, int n_tensors, int32_t* __restrict__ d)
+{
+    const int s = blockIdx.x * kBlock + threadIdx.x;
+    if (s < n_tensors) d[s] = segs[s].k;
+}
+
+// d[seg] -= |A and B| over the membership masks of two selections: with d preset to k, what is
+// left is the number of positions of one index set that the other one lacks (Eq. 6: the binarised
+// vectors differ in 2d places).  One wave per supertile.
+__global__ void __launch_bounds__(kBlock)
+k_mask_overlap(const StDesc* __restrict__ sts, int n_st, const uint64_t* __restrict__ mask_a,
+               const uint64_t* __restrict__ mask_b, int32_t* __restrict__ d)
+{
+    const int st = blockIdx.x * kWaves + threadIdx.x / kLanes;
+    if (st >= n_st) return;
+    const int lane = threadIdx.x % kLanes;
+    const size_t w0 = static_cast<size_t>(st) * kTilesPerSuper * 4;   // 4 words per wave tile
+    uint32_t both = 0;
+    for (int w = lane; w < kTilesPerSuper * 4; w += kLanes) both += __popcll(mask_a[w0 + w] & mask_b[w0 + w]);
+    both = wave_sum(both);
+    if (lane == 0 && both) atomicSub(&d[sts[st].seg], static_cast<int32_t>(both));
+}
+
+// Partial sums of a.b, a.a and b.b in binary64, added into acc[1..3].
+__global__ void __launch_bounds__(kBlock)
+k_dots(const float* __restrict__ a, const float* __restrict__ b, int64_t numel, double* __restrict__ acc)
+{
+    double ab = 0.0, aa = 0.0, bb = 0.0;
+    for (int64_t j = blockIdx.x * static_cast<int64_t>(kBlock) + threadIdx.x; j < numel;
+         j += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const double x = a[j], y = b[j];
+        ab += x * y;
+        aa += x * x;
+        bb += y * y;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        ab += __shfl_xor(ab, off, kLanes);
+        aa += __shfl_xor(aa, off, kLanes);
+        bb += __shfl_xor(bb, off, kLanes);
+    }
+    __shared__ double part[3][kWaves];
+    if (threadIdx.x % kLanes == 0) {
+        part[0][threadIdx.x / kLanes] = ab;
+        part[1][threadIdx.x / kLanes] = aa;
+        part[2][threadIdx.x / kLanes] = bb;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double t = 0.0;
+        for (int w = 0; w < kWaves; ++w) t += part[threadIdx.x][w];
+        atomicAdd(&acc[1 + threadIdx.x], t);
+    }
+}
+
+// acc[0] = 1 - a.b / (|a| |b|)
+__global__ void k_cosine_final(double* __restrict__ acc)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) acc[0] = 1.0 - acc[1] / (sqrt(acc[2]) * sqrt(acc[3]));
+}
+
 // Plain streaming copy, one 16-byte nontemporal load and store per thread: the yardstick the
 // other kernels' bandwidth and the profiler's byte counters are compared with.
 __global__ void __launch_bounds__(kBlock) k_copy(const vf4_t* __restrict__ src, vf4_t* __restrict__ dst, size_t n16)
@@ -1344,9 +1430,13 @@ void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learne
                                                                                            red_out);
 }
 
-template <typename G>
-scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, int64_t k_total,
-                            float beta, float lr, int leader, int32_t* idx_out, float* red_out)
+// The exact selection on one vector x = fma(lr, grad, mem) (Eq. 2): every kernel from the first
+// look at the vector to the output slot of every wave tile.  Leaves the membership mask, the
+// tile slots and the threshold behind.  `preds` holds one bucket prediction per segment (read and
+// rewritten).  Uses one copy of the scratch zone and leaves the other one cleared.
+template <typename G, typename Mark>
+void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float lr, int n_tensors, uint32_t* preds,
+                   Mark&& mark)
 {
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
@@ -1354,7 +1444,6 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
     const ChunkDesc* chunks = reinterpret_cast<const ChunkDesc*>(ws + l.chunks);
     SegState* state = reinterpret_cast<SegState*>(ws + l.state);
-    uint32_t* preds = reinterpret_cast<uint32_t*>(ws + l.preds);
     char* zone = ws + l.zone[ctx->parity];
     uint32_t* overflow = reinterpret_cast<uint32_t*>(zone + l.z_overflow);
     uint32_t* part = reinterpret_cast<uint32_t*>(zone + l.z_part);
@@ -1374,51 +1463,58 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
     hipStream_t s = ctx->stream;
     const int n_st = ctx->n_st;
-    const float* memL = lp.mem[leader];
-    const G* gradL = static_cast<const G*>(lp.grad[leader]);
 
+    if (!ctx->scratch_clean) {   // first step, new layout, or a failed step: clear both scratch copies
+        const size_t words = 2 * zone_words;   // the two copies are adjacent
+        const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
+        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.zone[0]), words);
+    }
+    const int hgrid = std::min(n_st, kHistGridMax);
+    ctx->scratch_clean = false;             // until every kernel of this selection has been enqueued
+    k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
+                                           part, overflow, next_zone, zone_words);
+    k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, hist0, preds, part, overflow);
+    k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow);
+    mark(1);
+    k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask);
+    mark(2);
+    k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt);
+    k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow);
+    k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt);
+    k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow);
+    mark(3);
+    k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask,
+                                           st_sum);
+    k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
+    k_slots<<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot, sel_mask,
+                                                            eq_mask, tile_slot);
+    if (hipPeekAtLastError() == hipSuccess) {   // the copy for the next selection was cleared by this one
+        ctx->parity ^= 1;
+        ctx->scratch_clean = true;
+    }
+}
+
+template <typename G>
+scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, int64_t k_total,
+                            float beta, float lr, int leader, int32_t* idx_out, float* red_out)
+{
+    hipStream_t s = ctx->stream;
     // phase boundaries for scalecom_timing_*: one event before the first kernel, one after each phase
     const bool timed = ctx->prof_steps < ctx->prof_cap;
     hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
     auto mark = [&](int boundary) {   // boundaries 4 and 5 enclose the all-learner pass
         if (timed && (ctx->prof_all || boundary == 4 || boundary == 5)) (void)hipEventRecord(ev[boundary], s);
     };
-    mark(0);
-    if (n_st > 0 && !ctx->scratch_clean) {   // first step, new layout, or a failed step: clear both scratch copies
-        const size_t words = 2 * zone_words;   // the two copies are adjacent
-        const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
-        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.zone[0]), words);
-    }
-    if (n_st > 0) {
-        const int hgrid = std::min(n_st, kHistGridMax);
-        ctx->scratch_clean = false;             // until every kernel of this step has been enqueued
-        k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask,
-                                               eq_mask, part, overflow, next_zone, zone_words);
-        k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, hist0, preds, part, overflow);
-        k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow);
-        mark(1);
-        k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask);
-        mark(2);
-        k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt);
-        k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow);
-        k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt);
-        k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow);
-        mark(3);
-        k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask,
-                                               eq_mask, st_sum);
-        k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
-        k_slots<<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot,
-                                                                sel_mask, eq_mask, tile_slot);
+    if (ctx->n_st > 0) {
+        mark(0);
+        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors,
+                         reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds), mark);
         mark(4);
         launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
         mark(6);
         if (timed) ++ctx->prof_steps;
     }
     SC_HIP(ctx, hipGetLastError());
-    if (n_st > 0) {                             // the copy for the next step was cleared by this step
-        ctx->parity ^= 1;
-        ctx->scratch_clean = true;
-    }
     return SCALECOM_OK;
 }
 
@@ -1470,20 +1566,13 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     return SCALECOM_OK;
 }
 
-scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
-                            int n_tensors, const int64_t* offsets, const int64_t* ks, float beta, float lr,
-                            int64_t step, int32_t* idx_out, float* red_out, int64_t chunk = 0)
+// Argument checks shared by the step and the diagnostics: the layout (segments and set sizes) ...
+scalecom_status check_layout(scalecom_ctx* ctx, int n_tensors, const int64_t* offsets, const int64_t* ks, int64_t& k_total)
 {
-    if (!ctx) return SCALECOM_EINVAL;
-    ctx->last_error.clear();
-    if (!mem || !grad || !offsets || !ks) return fail(ctx, SCALECOM_EINVAL, "null argument");
-    if (n_learners < 1 || n_learners > ctx->n_learners_max) return fail(ctx, SCALECOM_EINVAL, "n_learners out of range");
+    if (!offsets || !ks) return fail(ctx, SCALECOM_EINVAL, "null argument");
     if (n_tensors < 1 || n_tensors > ctx->n_tensors_max) return fail(ctx, SCALECOM_EINVAL, "n_tensors out of range");
-    if (!(beta > 0.0f && beta <= 1.0f)) return fail(ctx, SCALECOM_EINVAL, "beta must satisfy 0 < beta <= 1");
-    if (!std::isfinite(lr)) return fail(ctx, SCALECOM_EINVAL, "lr must be finite");
-    if (step < 0) return fail(ctx, SCALECOM_EINVAL, "step must be >= 0");
     if (offsets[0] < 0 || offsets[n_tensors] > ctx->numel_max) return fail(ctx, SCALECOM_EINVAL, "offsets out of range");
-    int64_t k_total = 0;
+    k_total = 0;
     for (int s = 0; s < n_tensors; ++s) {
         const int64_t len = offsets[s + 1] - offsets[s];
         if (len < 0) return fail(ctx, SCALECOM_EINVAL, "offsets must be non-decreasing");
@@ -1491,10 +1580,16 @@ scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* co
         k_total += ks[s];
     }
     if (k_total > ctx->k_max) return fail(ctx, SCALECOM_EINVAL, "k exceeds the context's k_max");
-    if (offsets[n_tensors] == offsets[0]) return SCALECOM_OK;   // nothing to do
-    if (k_total > 0 && (!idx_out || !red_out)) return fail(ctx, SCALECOM_EINVAL, "null output");
+    return SCALECOM_OK;
+}
+
+// ... and the learners' buffers, gathered into the kernel argument.
+scalecom_status check_learners(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                               LearnerPtrs& lp)
+{
+    if (!mem || !grad) return fail(ctx, SCALECOM_EINVAL, "null argument");
+    if (n_learners < 1 || n_learners > ctx->n_learners_max) return fail(ctx, SCALECOM_EINVAL, "n_learners out of range");
     const uintptr_t galign = ctx->gdt == SCALECOM_GRAD_BF16 ? 8 : 16;
-    LearnerPtrs lp;
     for (int i = 0; i < n_learners; ++i) {
         if (!mem[i] || !grad[i]) return fail(ctx, SCALECOM_EINVAL, "null learner buffer");
         if (reinterpret_cast<uintptr_t>(mem[i]) % 16 || reinterpret_cast<uintptr_t>(grad[i]) % galign)
@@ -1506,10 +1601,32 @@ scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* co
         lp.mem[i] = nullptr;
         lp.grad[i] = nullptr;
     }
+    return SCALECOM_OK;
+}
+
+scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                            int n_tensors, const int64_t* offsets, const int64_t* ks, float beta, float lr,
+                            int64_t step, int32_t* idx_out, float* red_out, int64_t chunk = 0)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    ctx->last_error.clear();
+    if (!mem || !grad || !offsets || !ks) return fail(ctx, SCALECOM_EINVAL, "null argument");
+    if (n_learners < 1 || n_learners > ctx->n_learners_max) return fail(ctx, SCALECOM_EINVAL, "n_learners out of range");
+    if (!(beta > 0.0f && beta <= 1.0f)) return fail(ctx, SCALECOM_EINVAL, "beta must satisfy 0 < beta <= 1");
+    if (!std::isfinite(lr)) return fail(ctx, SCALECOM_EINVAL, "lr must be finite");
+    if (step < 0) return fail(ctx, SCALECOM_EINVAL, "step must be >= 0");
+    int64_t k_total = 0;
+    scalecom_status st = check_layout(ctx, n_tensors, offsets, ks, k_total);
+    if (st != SCALECOM_OK) return st;
+    if (offsets[n_tensors] == offsets[0]) return SCALECOM_OK;   // nothing to do
+    if (k_total > 0 && (!idx_out || !red_out)) return fail(ctx, SCALECOM_EINVAL, "null output");
+    LearnerPtrs lp;
+    st = check_learners(ctx, mem, grad, n_learners, lp);
+    if (st != SCALECOM_OK) return st;
 
     DeviceGuard guard;
     SC_HIP(ctx, guard.enter(ctx->device));
-    scalecom_status st = ensure_tables(ctx, n_tensors, offsets, ks);
+    st = ensure_tables(ctx, n_tensors, offsets, ks);
     if (st != SCALECOM_OK) return st;
     const int leader = static_cast<int>(step % n_learners);    // Alg. 1 line 6: CLT-k of learner mod(t, n)
     if (chunk > 0) {                                            // chunk-wise selector on the whole vector
@@ -1521,6 +1638,57 @@ scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* co
     if (ctx->gdt == SCALECOM_GRAD_BF16)
         return launch_step<uint16_t>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
     return launch_step<float>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
+}
+
+// Scratch of scalecom_hamming_distance: the summed vector, a copy of the leader's membership
+// mask, and bucket predictions of its own (so the step's predictions stay untouched).
+struct DiagLayout {
+    size_t y, mask, preds, total;
+};
+
+DiagLayout diag_layout(int64_t numel_max, int n_tensors_max)
+{
+    DiagLayout d{};
+    const size_t ntile = static_cast<size_t>(max_supertiles(numel_max, n_tensors_max)) * kTilesPerSuper;
+    d.y = 0;
+    d.mask = align_up(static_cast<size_t>(numel_max) * sizeof(float), 256);
+    d.preds = d.mask + align_up(ntile * 4 * sizeof(uint64_t), 256);
+    d.total = d.preds + align_up(static_cast<size_t>(n_tensors_max) * sizeof(uint32_t), 256);
+    return d;
+}
+
+template <typename G>
+scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, int64_t begin,
+                               int64_t end, float lr, int leader, char* scratch, int32_t* d_out)
+{
+    const WsLayout& l = ctx->lay;
+    hipStream_t s = ctx->stream;
+    const DiagLayout dl = diag_layout(ctx->numel_max, ctx->n_tensors_max);
+    float* y = reinterpret_cast<float*>(scratch + dl.y);
+    uint64_t* mask_a = reinterpret_cast<uint64_t*>(scratch + dl.mask);
+    uint32_t* preds = reinterpret_cast<uint32_t*>(scratch + dl.preds);
+    const SegDesc* segs = reinterpret_cast<const SegDesc*>(ctx->ws + l.segs);
+    const StDesc* sts = reinterpret_cast<const StDesc*>(ctx->ws + l.sts);
+    const uint64_t* sel_mask = reinterpret_cast<const uint64_t*>(ctx->ws + l.sel_mask);
+    const size_t mask_bytes = static_cast<size_t>(ctx->n_st) * kTilesPerSuper * 4 * sizeof(uint64_t);
+    auto no_mark = [](int) {};
+
+    k_set_ks<<<(n_tensors + kBlock - 1) / kBlock, kBlock, 0, s>>>(segs, n_tensors, d_out);
+    if (ctx->n_st > 0) {
+        // the leader's index set (Eq. 3)
+        k_init<<<1, kBlock, 0, s>>>(preds, static_cast<size_t>(n_tensors));
+        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, no_mark);
+        SC_HIP(ctx, hipMemcpyAsync(mask_a, sel_mask, mask_bytes, hipMemcpyDeviceToDevice, s));
+        // the top-k of the summed error-feedback gradients
+        const int64_t blocks = (end - begin + kBlock - 1) / kBlock;
+        const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
+        k_sum_x<G><<<dim3(gx, static_cast<unsigned>((blocks + gx - 1) / gx)), kBlock, 0, s>>>(lp, n_learners, lr, begin, end, y);
+        k_init<<<1, kBlock, 0, s>>>(preds, static_cast<size_t>(n_tensors));
+        launch_select<NoGrad>(ctx, y, static_cast<const NoGrad*>(nullptr), 0.0f, n_tensors, preds, no_mark);
+        k_mask_overlap<<<(ctx->n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(sts, ctx->n_st, mask_a, sel_mask, d_out);
+    }
+    SC_HIP(ctx, hipGetLastError());
+    return SCALECOM_OK;
 }
 
 }  // namespace
@@ -1619,6 +1787,61 @@ scalecom_status scalecom_apply_update(scalecom_ctx* ctx, float* theta, int64_t n
     const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
     const unsigned gy = static_cast<unsigned>((blocks + gx - 1) / gx);
     k_apply_update<<<dim3(gx, gy), kBlock, 0, ctx->stream>>>(theta, idx, vals, k, -scale);
+    SC_HIP(ctx, hipGetLastError());
+    return SCALECOM_OK;
+}
+
+size_t scalecom_hamming_scratch_bytes(int64_t numel_max, int n_tensors_max)
+{
+    if (numel_max < 0 || numel_max > INT32_MAX || n_tensors_max < 1) return 0;
+    return diag_layout(numel_max, n_tensors_max).total;
+}
+
+scalecom_status scalecom_hamming_distance(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
+                                          int n_tensors, const int64_t* offsets, const int64_t* ks, float lr,
+                                          int64_t step, void* scratch, size_t scratch_bytes, int32_t* d_out)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    ctx->last_error.clear();
+    if (!std::isfinite(lr)) return fail(ctx, SCALECOM_EINVAL, "lr must be finite");
+    if (step < 0) return fail(ctx, SCALECOM_EINVAL, "step must be >= 0");
+    int64_t k_total = 0;
+    scalecom_status st = check_layout(ctx, n_tensors, offsets, ks, k_total);
+    if (st != SCALECOM_OK) return st;
+    LearnerPtrs lp;
+    st = check_learners(ctx, mem, grad, n_learners, lp);
+    if (st != SCALECOM_OK) return st;
+    if (!d_out) return fail(ctx, SCALECOM_EINVAL, "null output");
+    if (!scratch || reinterpret_cast<uintptr_t>(scratch) % 256) return fail(ctx, SCALECOM_EINVAL, "scratch must be 256-byte aligned");
+    if (scratch_bytes < diag_layout(ctx->numel_max, ctx->n_tensors_max).total)
+        return fail(ctx, SCALECOM_ENOMEM, "scratch smaller than scalecom_hamming_scratch_bytes");
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    st = ensure_tables(ctx, n_tensors, offsets, ks);
+    if (st != SCALECOM_OK) return st;
+    const int leader = static_cast<int>(step % n_learners);
+    if (ctx->gdt == SCALECOM_GRAD_BF16)
+        return launch_hamming<uint16_t>(ctx, lp, n_learners, n_tensors, offsets[0], offsets[n_tensors], lr, leader,
+                                        static_cast<char*>(scratch), d_out);
+    return launch_hamming<float>(ctx, lp, n_learners, n_tensors, offsets[0], offsets[n_tensors], lr, leader,
+                                 static_cast<char*>(scratch), d_out);
+}
+
+scalecom_status scalecom_cosine_distance(scalecom_ctx* ctx, const float* a, const float* b, int64_t numel, double* out)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    ctx->last_error.clear();
+    if (!a || !b || !out) return fail(ctx, SCALECOM_EINVAL, "null argument");
+    if (numel < 0) return fail(ctx, SCALECOM_EINVAL, "numel out of range");
+    if (reinterpret_cast<uintptr_t>(out) % 8) return fail(ctx, SCALECOM_EINVAL, "out is not aligned");
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(out), 8);
+    if (numel > 0) {
+        const int grid = static_cast<int>(std::min<int64_t>((numel + kBlock - 1) / kBlock, 2048));
+        k_dots<<<grid, kBlock, 0, ctx->stream>>>(a, b, numel, out);
+    }
+    k_cosine_final<<<1, kLanes, 0, ctx->stream>>>(out);
     SC_HIP(ctx, hipGetLastError());
     return SCALECOM_OK;
 }

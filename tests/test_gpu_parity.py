@@ -243,6 +243,98 @@ def test_apply_update_after_a_step(gu):
     ctx.close()
 
 
+# ------------------------------------------------------------------ similarity diagnostics (Sec. 3)
+def _oracle_d(gu, mem, grad, offsets, ks, lr, step):
+    import oracle
+    mem_h = [m.cpu().numpy() for m in mem]
+    grad_h = [gu.to_host(g) for g in grad]
+    out = []
+    for s, k in enumerate(ks):
+        a, b = offsets[s], offsets[s + 1]
+        if b == a:
+            out.append(0)
+            continue
+        out.append(oracle.hamming_distance([np.ascontiguousarray(m[a:b]) for m in mem_h],
+                                           [np.ascontiguousarray(g[a:b]) for g in grad_h], int(k), lr, step))
+    return np.array(out, np.int32)
+
+
+@pytest.mark.parametrize("recipe,numel", [("resnet50_sized", 300_001), ("large_bf16", 150_002)])
+def test_hamming_distance_between_steps(gu, recipe, numel):
+    """d between the leader's set and the true top-k, asked for between ordinary steps: exact,
+    leaves the memories alone and does not disturb the steps that follow."""
+    w = workloads.scaled(workloads.by_name(recipe), numel, n_learners=4, steps=4)
+    gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, 1, gu.DEV)
+    mem = workloads.zero_memories(w, gu.DEV)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    for step in range(4):
+        grad = workloads.gradients(w, step, gu.DEV)
+        d = ctx.scalecom_hamming_distance(mem, grad, [0, w.numel], [w.k], w.lr, step)
+        torch.cuda.synchronize()
+        want = _oracle_d(gu, mem, grad, [0, w.numel], [w.k], w.lr, step)
+        print(f"[hamming] {recipe} step {step}: d/k = {int(want[0])}/{w.k}", flush=True)
+        assert np.array_equal(d.cpu().numpy(), want)
+        for i in range(w.n_learners):
+            gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], None, f"untouched, learner {i}")
+        gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, k=w.k, what="after hamming")
+    ctx.close()
+
+
+def test_hamming_distance_per_layer_and_extremes(gu):
+    n = 3
+    sizes = [0, 1, 7, 8192, 8193, 300, 2, 0, 40_000]
+    ks = [0, 1, 3, 100, 8193, 0, 1, 0, 400]
+    offsets = np.concatenate([[4], 4 + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1] + 3
+    g = torch.Generator(device="cpu").manual_seed(15)
+    mem = [torch.randn(numel, generator=g).to(gu.DEV) for _ in range(n)]
+    shared = torch.randn(numel, generator=g)
+    grad = [(shared + 0.5 * torch.randn(numel, generator=g)).to(gu.DEV) for _ in range(n)]
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(ks), gu.DEV)
+    for step in range(n):
+        d = ctx.scalecom_hamming_distance(mem, grad, offsets, ks, 0.7, step)
+        torch.cuda.synchronize()
+        assert np.array_equal(d.cpu().numpy(), _oracle_d(gu, mem, grad, offsets, ks, 0.7, step))
+    # identical learners: distance 0; a leader whose large entries the others cancel: distance k
+    k = 50
+    same = [grad[0].clone() for _ in range(n)]
+    zeros = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    d = ctx.scalecom_hamming_distance(zeros, same, [0, numel], [k], 1.0, 1)
+    assert d.cpu().tolist() == [0]
+    lead = torch.zeros(numel); lead[:k] = 5.0
+    other = torch.zeros(numel); other[:k] = -5.0; other[k:2 * k] = 3.0
+    d = ctx.scalecom_hamming_distance(zeros[:2], [lead.to(gu.DEV), other.to(gu.DEV)], [0, numel], [k], 1.0, 0)
+    assert d.cpu().tolist() == [k]
+    # non-finite sums rank above every finite value on both sides
+    bad = [gr.clone() for gr in grad]
+    bad[1][1000] = float("inf"); bad[2][1000] = float("-inf"); bad[0][2000] = float("inf"); bad[2][3000] = float("nan")
+    d = ctx.scalecom_hamming_distance(mem, bad, [0, numel], [k], 0.7, 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(d.cpu().numpy(), _oracle_d(gu, mem, bad, [0, numel], [k], 0.7, 2))
+    with pytest.raises(binding.ScaleComError):
+        ctx.scalecom_hamming_distance(mem, grad, [0, numel], [numel + 1], 0.7, 0)
+    ctx.close()
+
+
+def test_cosine_distance(gu):
+    import oracle
+    ctx = binding.scalecom_init(16, 1, torch.float32, 1, gu.DEV)
+    g = torch.Generator(device="cpu").manual_seed(16)
+    for numel in (1, 255, 1_000_003):
+        a = torch.randn(numel, generator=g)
+        b = (0.3 * a + torch.randn(numel, generator=g))
+        out = ctx.scalecom_cosine_distance(a.to(gu.DEV), b.to(gu.DEV)).cpu().numpy()
+        want = oracle.cosine_distance(a.numpy(), b.numpy())
+        assert abs(out[0] - want) <= 1e-12 * max(1.0, abs(want)), (numel, out[0], want)
+        a64, b64 = a.numpy().astype(np.float64), b.numpy().astype(np.float64)
+        np.testing.assert_allclose(out[1:], [a64 @ b64, a64 @ a64, b64 @ b64], rtol=1e-12)
+    a = torch.randn(4096, generator=g).to(gu.DEV)
+    assert abs(float(ctx.scalecom_cosine_distance(a, a * 2)[0])) < 1e-12
+    assert abs(float(ctx.scalecom_cosine_distance(a, -a)[0]) - 2.0) < 1e-12
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
