@@ -190,15 +190,19 @@ scalecom_status scalecom_cosine_distance(scalecom_ctx* ctx, const float* a, cons
 /*
  * Per-layer sizes of the index sets from the paper's rate guidance (Sec. 4): a layer whose
  * FLOPs-per-gradient ratio is >= 196 is compressed 25X, one in [128, 196) 50X, one below 128
- * 400X; ks_out[s] = ceil(sizes[s] / rate), ready for scalecom_step_layers.  Pure host arithmetic.
+ * 400X; ks_out[s] = ceil(sizes[s] / rate), ready for scalecom_step_layers.  A layer marked as
+ * uncompressed (App. E keeps the first convolution out of compression, Sec. 4 every layer during
+ * the warm-up epochs) gets rate 1, k = its size: scalecom_step_layers then sums all of its
+ * elements over the learners and leaves (1 - beta) * mem behind.  Pure host arithmetic.
  *   flops_per_gradient [host] double[n_tensors], each > 0
  *   sizes              [host] int64[n_tensors], each >= 0
+ *   uncompressed       [host] uint8[n_tensors] (non-zero: not compressed) or NULL: none
  *   ks_out             [host] int64[n_tensors]
  *   rates_out          [host] int64[n_tensors] or NULL: the rate chosen per layer
  * EINVAL for null pointers, n_tensors < 0, a ratio that is not > 0, or a negative size.
  */
 scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradient, const int64_t* sizes,
-                                  int64_t* ks_out, int64_t* rates_out);
+                                  const uint8_t* uncompressed, int64_t* ks_out, int64_t* rates_out);
 
 /*
  * Optional per-phase GPU timing, for benchmarks.  Not part of the paper's method: it only

@@ -60,7 +60,7 @@ def lib() -> ctypes.CDLL:
         L.scalecom_hamming_distance.restype = i32
         L.scalecom_cosine_distance.argtypes = [vp, vp, vp, i64, vp]
         L.scalecom_cosine_distance.restype = i32
-        L.scalecom_layer_ks.argtypes = [i32, vp, vp, vp, vp]
+        L.scalecom_layer_ks.argtypes = [i32, vp, vp, vp, vp, vp]
         L.scalecom_layer_ks.restype = i32
         L.scalecom_stream_copy.argtypes = [vp, vp, vp, sz]
         L.scalecom_stream_copy.restype = i32
@@ -82,16 +82,18 @@ def _ptrs(tensors: Sequence[torch.Tensor]):
     return (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
 
 
-def scalecom_layer_ks(flops_per_gradient: Sequence[float], sizes: Sequence[int]):
+def scalecom_layer_ks(flops_per_gradient: Sequence[float], sizes: Sequence[int],
+                      uncompressed: Optional[Sequence[bool]] = None):
     """``scalecom_layer_ks`` of the C-ABI: (ks, rates) per layer from the paper's rate guidance."""
     n = len(sizes)
-    if len(flops_per_gradient) != n:
-        raise ValueError("one ratio per layer")
+    if len(flops_per_gradient) != n or (uncompressed is not None and len(uncompressed) != n):
+        raise ValueError("one ratio (and one flag) per layer")
+    c_u = (ctypes.c_uint8 * n)(*[1 if v else 0 for v in uncompressed]) if uncompressed is not None else None
     c_r = (ctypes.c_double * n)(*[float(v) for v in flops_per_gradient])
     c_s = (ctypes.c_int64 * n)(*[int(v) for v in sizes])
     c_k = (ctypes.c_int64 * n)()
     c_rate = (ctypes.c_int64 * n)()
-    st = lib().scalecom_layer_ks(n, c_r, c_s, c_k, c_rate)
+    st = lib().scalecom_layer_ks(n, c_r, c_s, c_u, c_k, c_rate)
     if st != SCALECOM_OK:
         raise ScaleComError(st)
     return list(c_k), list(c_rate)

@@ -1847,14 +1847,17 @@ scalecom_status scalecom_cosine_distance(scalecom_ctx* ctx, const float* a, cons
 }
 
 scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradient, const int64_t* sizes,
-                                  int64_t* ks_out, int64_t* rates_out)
+                                  const uint8_t* uncompressed, int64_t* ks_out, int64_t* rates_out)
 {
     if (n_tensors < 0 || (n_tensors > 0 && (!flops_per_gradient || !sizes || !ks_out))) return SCALECOM_EINVAL;
     for (int s = 0; s < n_tensors; ++s)
         if (!(flops_per_gradient[s] > 0.0) || sizes[s] < 0) return SCALECOM_EINVAL;
     for (int s = 0; s < n_tensors; ++s) {
-        // Sec. 4: 25X for a FLOPs/gradient ratio in [196, inf), 50X for [128, 196), 400X below 128
-        const int64_t rate = flops_per_gradient[s] >= 196.0 ? 25 : (flops_per_gradient[s] >= 128.0 ? 50 : 400);
+        // Sec. 4: 25X for a FLOPs/gradient ratio in [196, inf), 50X for [128, 196), 400X below 128;
+        // a layer kept out of compression (App. E: the first convolution; every layer during the
+        // warm-up epochs) sends all of its elements
+        int64_t rate = flops_per_gradient[s] >= 196.0 ? 25 : (flops_per_gradient[s] >= 128.0 ? 50 : 400);
+        if (uncompressed && uncompressed[s]) rate = 1;
         ks_out[s] = (sizes[s] + rate - 1) / rate;
         if (rates_out) rates_out[s] = rate;
     }

@@ -71,8 +71,11 @@ def test_layer_ks_follows_the_rate_guidance():
     ks, rates = binding.scalecom_layer_ks(ratios, sizes)
     assert rates == [25, 25, 50, 50, 400, 400] == [oracle.layer_rate(r) for r in ratios]
     assert ks == [40_000, 1, 82, 1, 1, 0]
+    # layers kept out of compression send everything (App. E: first convolution; warm-up epochs)
+    ks, rates = binding.scalecom_layer_ks(ratios, sizes, [True, False, False, True, False, True])
+    assert rates == [1, 25, 50, 1, 400, 1] and ks == [1_000_000, 1, 82, 50, 1, 0]
     L = binding.lib()
-    assert L.scalecom_layer_ks(1, None, None, None, None) == binding.SCALECOM_EINVAL
+    assert L.scalecom_layer_ks(1, None, None, None, None, None) == binding.SCALECOM_EINVAL
     bad = (ctypes.c_double * 1)(0.0); one = (ctypes.c_int64 * 1)(5); out = (ctypes.c_int64 * 1)()
-    assert L.scalecom_layer_ks(1, bad, one, out, None) == binding.SCALECOM_EINVAL
+    assert L.scalecom_layer_ks(1, bad, one, None, out, None) == binding.SCALECOM_EINVAL
     assert L.scalecom_apply_update(None, None, 0, None, None, 0, 1.0) == binding.SCALECOM_EINVAL
