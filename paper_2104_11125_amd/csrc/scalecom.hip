@@ -158,6 +158,7 @@ __device__ __forceinline__ void store4(float* p, const float4& v)
 // x = fma(lr, 0, v) has v's magnitude bits for any finite lr (non-finite v included).  Never
 // dereferenced.
 struct NoGrad {};
+__device__ __forceinline__ float4 load4(const NoGrad*) { return make_float4(0.0f, 0.0f, 0.0f, 0.0f); }
 
 // number of set bits of a wave-wide ballot that belong to lanes below the calling lane
 __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
@@ -306,50 +307,79 @@ __device__ __forceinline__ void store_tile_masks(uint64_t* mask, size_t tile, co
     dst[1] = make_ulonglong2(b[2], b[3]);
 }
 
+struct CollectStage {       // LDS staging of one supertile's outputs of the collecting passes
+    uint64_t mask[kTilesPerSuper][4];
+    uint32_t cnt[kTilesPerSuper];
+    uint2 cand[kCandSlice];
+};
+
 // The per-tile work of the "collect" pass, given the tile's keys: keys whose top digit lies above
-// `hi` are members for sure (count to wt_cnt, ballots to the membership mask); keys with a top
-// digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice
+// `hi` are members for sure (their count and ballots are staged for the tile); keys with a top
+// digit in [lo, hi] are appended, with their positions, to the supertile's staged candidate slice
 // (slots handed out through the block's LDS counter `fill`) and, if `wc` is given, counted per
 // digit there.  Called by all lanes of a wave; n_above is the same in every lane.
-__device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], int64_t p0, uint32_t lo,
-                                             uint32_t hi, size_t tile, int lane, uint32_t* __restrict__ wt_cnt,
-                                             uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
-                                             uint2* __restrict__ slice, uint32_t* fill, uint32_t* wc, uint32_t& n_above)
+template <bool ALL_OK>
+__device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
+                                             uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* wc,
+                                             uint32_t& n_above, CollectStage& stg)
 {
-    uint32_t mine = 0;
+    // top digit > hi  <=>  key >= (hi + 1) << 19;  lo <= top digit <= hi  <=>  key - (lo << 19) < span
+    const uint32_t lo_key = lo << (kBits1 + kBits2);
+    const uint32_t above_key = (hi + 1u) << (kBits1 + kBits2);   // 2^31 for the last digit: no key reaches it
+    const uint32_t span = above_key - lo_key;
     n_above = 0;
+    uint32_t n_in = 0;
     bool in[4];
-    uint64_t above[4];
+    uint64_t above[4], inside[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        const uint32_t digit = key[c] >> (kBits1 + kBits2);
-        above[c] = __ballot(ok[c] && digit > hi);
+        above[c] = __builtin_amdgcn_ballot_w64((ALL_OK || ok[c]) && key[c] >= above_key);
         n_above += __popcll(above[c]);
-        in[c] = ok[c] && digit >= lo && digit <= hi;
-        mine += in[c] ? 1u : 0u;
+        in[c] = (ALL_OK || ok[c]) && key[c] - lo_key < span;
+        inside[c] = __builtin_amdgcn_ballot_w64(in[c]);
+        n_in += __popcll(inside[c]);
     }
     if (lane == 0) {
-        wt_cnt[tile] = n_above;
-        store_tile_masks(sel_mask, tile, above);
-        const uint64_t zero[4] = {0, 0, 0, 0};
-        store_tile_masks(eq_mask, tile, zero);
+        stg.cnt[wt] = n_above;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) stg.mask[wt][c] = above[c];
     }
-    const uint32_t n_in = wave_sum(mine);
     if (n_in == 0) return;                                 // wave-uniform
     uint32_t base = 0;
     if (lane == 0) base = atomicAdd(fill, n_in);
-    base = __shfl(base, 0, kLanes);
+    base = __builtin_amdgcn_readfirstlane(base);
     uint32_t rank = base;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) rank += lanes_below(__ballot(in[c]));
+    for (int c = 0; c < 4; ++c) rank += lanes_below(inside[c]);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         if (in[c]) {
-            if (rank < kCandSlice) slice[rank] = make_uint2(key[c], static_cast<uint32_t>(p0 + c));
+            if (rank < kCandSlice) stg.cand[rank] = make_uint2(key[c], p0 + c);
             if (wc) atomicAdd(&wc[(key[c] >> (kBits1 + kBits2)) - lo], 1u);
             ++rank;
         }
     }
+}
+
+// After the block's barrier: the staged masks, counts and candidates of the supertile go out with
+// full-width stores (lane-0 stores of 32 bytes per tile cost the collecting passes 8 % of their time).
+__device__ __forceinline__ void collect_flush(const CollectStage& stg, size_t tile0, uint32_t n_cand,
+                                              uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask,
+                                              uint64_t* __restrict__ eq_mask, uint2* __restrict__ slice)
+{
+    static_assert(kTilesPerSuper * 4 * sizeof(uint64_t) == kLanes * sizeof(ulonglong2), "one 16-byte store per lane");
+    static_assert(kBlock >= 2 * kLanes + kTilesPerSuper, "threads for the three flushes");
+    const int t = threadIdx.x;
+    if (t < kLanes) {
+        const ulonglong2* src = reinterpret_cast<const ulonglong2*>(&stg.mask[0][0]);
+        reinterpret_cast<ulonglong2*>(sel_mask + tile0 * 4)[t] = src[t];
+    } else if (t < 2 * kLanes) {
+        reinterpret_cast<ulonglong2*>(eq_mask + tile0 * 4)[t - kLanes] = make_ulonglong2(0ull, 0ull);
+    } else if (t < 2 * kLanes + kTilesPerSuper) {
+        wt_cnt[tile0 + (t - 2 * kLanes)] = stg.cnt[t - 2 * kLanes];
+    }
+    const uint32_t n = n_cand < kCandSlice ? n_cand : kCandSlice;
+    for (uint32_t e = threadIdx.x; e < n; e += kBlock) slice[e] = stg.cand[e];
 }
 
 // First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
@@ -360,6 +390,52 @@ __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool o
 // that the k-th largest key fell inside the window, the threshold bucket is known exactly and
 // no other full pass over the leader is needed.  The prediction only decides how much work is
 // done, never what is selected.  One block per supertile.
+// The 8 tiles a wave owns in a supertile of the predicted pass.  INSIDE: the whole supertile
+// lies in the segment, so loads are unguarded and every position counts; otherwise both are
+// checked per element.  Positions stay below 2^31 + 8192 and are kept in 32 bits.
+template <typename G, bool INSIDE>
+__device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
+                                                    const StDesc& d, uint32_t lo, uint32_t hi, int wave, int lane,
+                                                    uint32_t* fill, uint32_t* wc, CollectStage& stg)
+{
+    constexpr int kIters = kTilesPerSuper / kWaves;
+    constexpr uint32_t kStride = kWaves * kWaveTile;
+    const int64_t begin = d.begin, end = d.end;
+    // the next tile's loads are issued before this tile is processed (measured: neither a deeper
+    // prefetch nor full unrolling changes the kernel's time)
+    float4 m_cur, g_cur, m_nxt, g_nxt;
+    uint32_t p_cur = static_cast<uint32_t>(d.a0) + wave * kWaveTile + lane * kVec;
+    auto fetch = [&](uint32_t p0, float4& m, float4& g) {
+        if (INSIDE) {
+            m = load4(mem + p0);
+            g = load4(grad + p0);
+        } else {
+            leader_load(mem, grad, p0, begin, end, m, g);
+        }
+    };
+    fetch(p_cur, m_cur, g_cur);
+    uint32_t above_acc = 0;
+#pragma unroll 1
+    for (int it = 0; it < kIters; ++it) {
+        const int wt = it * kWaves + wave;
+        if (it + 1 < kIters) fetch(p_cur + kStride, m_nxt, g_nxt);
+        const float4 x = accumulate4(m_cur, g_cur, lr);
+        const uint32_t key[4] = {magnitude_key(x.x), magnitude_key(x.y), magnitude_key(x.z), magnitude_key(x.w)};
+        bool ok[4] = {true, true, true, true};
+        if (!INSIDE) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) ok[c] = static_cast<int64_t>(p_cur) + c >= begin && static_cast<int64_t>(p_cur) + c < end;
+        }
+        uint32_t n_above;
+        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, n_above, stg);
+        above_acc += n_above;
+        m_cur = m_nxt;
+        g_cur = g_nxt;
+        p_cur += kStride;
+    }
+    return above_acc;
+}
+
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
@@ -380,38 +456,23 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const uint32_t p = preds[d.seg];                        // 0: none, else predicted bucket + 1
     if (p == 0 || segs[d.seg].k == 0) return;
     const uint32_t lo = window_lo(p), hi = window_hi(p);
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
-    const int64_t begin = d.begin, end = d.end;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
     __shared__ uint32_t fill;
     __shared__ uint32_t acc[kPartWords];                    // [0] above the window, [1 + d] per window digit
+    __shared__ CollectStage stg;
     if (threadIdx.x == 0) fill = 0u;
     if (threadIdx.x < kPartWords) acc[threadIdx.x] = 0u;
     __syncthreads();
 
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-    // software pipeline: the next tile's loads are in flight while this tile is processed
-    float4 m_cur, g_cur, m_nxt, g_nxt;
-    int64_t p_cur = static_cast<int64_t>(d.a0) + wave * kWaveTile + lane * kVec;
-    leader_load(mem, grad, p_cur, begin, end, m_cur, g_cur);
-    uint32_t above_acc = 0;
-#pragma unroll 1
-    for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-        const int wt = it * kWaves + wave;
-        const int64_t p_nxt = p_cur + kWaves * kWaveTile;
-        if (it + 1 < kTilesPerSuper / kWaves) leader_load(mem, grad, p_nxt, begin, end, m_nxt, g_nxt);
-        uint32_t key[4];
-        bool ok[4];
-        keys_from(m_cur, g_cur, lr, p_cur, begin, end, key, ok);
-        uint32_t n_above;
-        collect_tile(key, ok, p_cur, lo, hi, static_cast<size_t>(st) * kTilesPerSuper + wt, lane, wt_cnt, sel_mask, eq_mask,
-                     slice, &fill, acc + 1, n_above);
-        above_acc += n_above;
-        m_cur = m_nxt;
-        g_cur = g_nxt;
-        p_cur = p_nxt;
-    }
+    uint32_t above_acc;
+    if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
+        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg);
+    else
+        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg);
     if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
     __syncthreads();
+    collect_flush(stg, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
     if (threadIdx.x == 0) {
         const uint32_t n = fill;
         st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
@@ -701,6 +762,7 @@ k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, c
     const uint32_t bucket = ss.prefix;
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
     __shared__ uint32_t fill;
+    __shared__ CollectStage stg;
     if (threadIdx.x == 0) fill = 0u;
     __syncthreads();
 
@@ -711,10 +773,10 @@ k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, c
         bool ok[4] = {false, false, false, false};
         if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
         uint32_t n_above;
-        collect_tile(key, ok, p0, bucket, bucket, static_cast<size_t>(st) * kTilesPerSuper + wt, lane, wt_cnt, sel_mask,
-                     eq_mask, slice, &fill, nullptr, n_above);
+        collect_tile<false>(key, ok, static_cast<uint32_t>(p0), bucket, bucket, wt, lane, &fill, nullptr, n_above, stg);
     }
     __syncthreads();
+    collect_flush(stg, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
     if (threadIdx.x == 0) {
         const uint32_t n = fill;
         st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
@@ -908,6 +970,72 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
 // zeroed on the index set (Eq. 5), and for members the learner's own value x_i (Eq. 3) into
 // vals[learner][slot].  Membership and slots come from the leader's bitmask and prefix
 // counts, so no learner's block reads another learner's data.
+// INSIDE: all 1024 positions of the block belong to the segment, so the two streaming loads and
+// the store need no guards and are issued back to back; otherwise every access is guarded.
+template <typename G, bool INSIDE>
+__device__ __forceinline__ void update_block(float* __restrict__ mem, const G* __restrict__ grad, float lr, float beta,
+                                             float one_minus_beta, const StDesc& d, int wave, int lane, uint32_t rel0,
+                                             const uint64_t S[4], uint32_t before, uint32_t total, uint32_t slot0,
+                                             float* __restrict__ my_vals, int32_t* __restrict__ idx_out,
+                                             float* stage_val, int32_t* stage_pos)
+{
+    // position of this lane's 4 elements; below 2^31 + 8192, so 32 bits hold it
+    const uint32_t p0 = static_cast<uint32_t>(d.a0) + rel0;
+    const int64_t begin = d.begin, end = d.end;
+    const bool full = INSIDE || (static_cast<int64_t>(p0) >= begin && static_cast<int64_t>(p0) + 3 < end);
+    const bool any_ok = INSIDE || (static_cast<int64_t>(p0) + 3 >= begin && static_cast<int64_t>(p0) < end);
+    float4 m = make_float4(0, 0, 0, 0), x = m;
+    if (INSIDE) {
+        m = load4(mem + p0);
+        const float4 g = load4(grad + p0);
+        x = accumulate4(m, g, lr);
+    } else if (any_ok) {
+        m = load_guarded(mem, p0, begin, end, full);
+        const float4 g = load_guarded(grad, p0, begin, end, full);
+        x = accumulate4(m, g, lr);
+    }
+    bool sel[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sel[c] = (S[c] >> lane) & 1ull;
+
+    if (any_ok) {
+        // Eq. 5: residual is x off the index set, 0 on it
+        float4 out;
+        out.x = fmaf(beta, sel[0] ? 0.0f : x.x, one_minus_beta * m.x);
+        out.y = fmaf(beta, sel[1] ? 0.0f : x.y, one_minus_beta * m.y);
+        out.z = fmaf(beta, sel[2] ? 0.0f : x.z, one_minus_beta * m.z);
+        out.w = fmaf(beta, sel[3] ? 0.0f : x.w, one_minus_beta * m.w);
+        if (INSIDE)
+            store4(mem + p0, out);
+        else
+            store_guarded(mem, p0, begin, end, full, out);
+    }
+
+    if (total == 0) return;                                 // no member in the block's tiles (block-uniform)
+    // The block's members occupy consecutive output slots (tiles are consecutive): compact them
+    // through LDS and write them with one contiguous store.
+    uint32_t rank = before;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) rank += lanes_below(S[c]);
+    const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (sel[c]) {
+            stage_val[rank] = xs[c];
+            if (idx_out) stage_pos[rank] = static_cast<int32_t>(p0 + c);
+            ++rank;
+        }
+    }
+    __syncthreads();
+    const uint32_t slot_end = static_cast<uint32_t>(d.slot_end);
+    for (uint32_t j = threadIdx.x; j < total; j += kBlock) {
+        if (slot0 + j < slot_end) {                         // the bound only matters if the counts were corrupted
+            my_vals[slot0 + j] = stage_val[j];
+            if (idx_out) idx_out[slot0 + j] = stage_pos[j];
+        }
+    }
+}
+
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDesc* __restrict__ sts, int n_st,
@@ -920,14 +1048,12 @@ k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDes
     const int group = blockIdx.y + blockIdx.z * gridDim.y;
     const int st = group / kUpdateBlocksPerSuper;
     if (st >= n_st) return;                                 // padding of the 3-d grid (whole block)
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    // the wave's index is the same in all of its lanes: say so, and everything derived from it
+    // (mask words, counts) stays in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+    const int lane = threadIdx.x % kLanes;
     const int wt0 = (group % kUpdateBlocksPerSuper) * kWaves;   // the block's first wave tile
-    const int wt = wt0 + wave;
     const StDesc d = sts[st];
-    const int64_t begin = d.begin, end = d.end;
-    const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
-    const bool full = p0 >= begin && p0 + 3 < end;
-    const bool any_ok = p0 + 3 >= begin && p0 < end;
 
     // membership of the block's 4 tiles (128 bytes) and the block's first output slot: small,
     // cache-resident, issued together with the streaming loads so that nothing waits on a
@@ -938,15 +1064,6 @@ k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDes
 #pragma unroll
     for (int j = 0; j < 2 * kWaves; ++j) w[j] = mw[j];
     const uint32_t slot0 = tile_slot[tile0];
-
-    float* mem = lp.mem[learner];
-    const G* grad = static_cast<const G*>(lp.grad[learner]);
-    float4 m = make_float4(0, 0, 0, 0), x = m;
-    if (any_ok) {
-        m = load_guarded(mem, p0, begin, end, full);
-        const float4 g = load_guarded(grad, p0, begin, end, full);
-        x = accumulate4(m, g, lr);
-    }
 
     // my tile's ballots, and how many members the block's earlier tiles and the whole block hold
     uint64_t S[4] = {0, 0, 0, 0};
@@ -963,46 +1080,21 @@ k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDes
             S[3] = w[2 * t + 1].y;
         }
     }
-    bool sel[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) sel[c] = (S[c] >> lane) & 1ull;
 
-    if (any_ok) {
-        // Eq. 5: residual is x off the index set, 0 on it
-        float4 out;
-        out.x = fmaf(beta, sel[0] ? 0.0f : x.x, one_minus_beta * m.x);
-        out.y = fmaf(beta, sel[1] ? 0.0f : x.y, one_minus_beta * m.y);
-        out.z = fmaf(beta, sel[2] ? 0.0f : x.z, one_minus_beta * m.z);
-        out.w = fmaf(beta, sel[3] ? 0.0f : x.w, one_minus_beta * m.w);
-        store_guarded(mem, p0, begin, end, full, out);
-    }
-
-    if (total == 0) return;                                 // no member in the block's tiles (block-uniform)
-    // The block's members occupy consecutive output slots (tiles are consecutive): compact them
-    // through LDS and write them with one contiguous store.
+    float* mem = lp.mem[learner];
+    const G* grad = static_cast<const G*>(lp.grad[learner]);
+    float* my_vals = vals + static_cast<size_t>(learner) * static_cast<size_t>(k_total);
+    int32_t* my_idx = learner == 0 ? idx_out : nullptr;    // one learner's blocks write the positions
+    const uint32_t rel0 = static_cast<uint32_t>((wt0 + wave) * kWaveTile + lane * kVec);
+    const int64_t blk0 = static_cast<int64_t>(d.a0) + wt0 * kWaveTile;
     __shared__ float stage_val[kWaves * kWaveTile];
     __shared__ int32_t stage_pos[kWaves * kWaveTile];
-    uint32_t rank = before;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) rank += lanes_below(S[c]);
-    const float xs[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        if (sel[c]) {
-            stage_val[rank] = xs[c];
-            if (learner == 0) stage_pos[rank] = static_cast<int32_t>(p0 + c);
-            ++rank;
-        }
-    }
-    __syncthreads();
-    const uint32_t slot_end = static_cast<uint32_t>(d.slot_end);
-    float* my_vals = vals + static_cast<size_t>(learner) * static_cast<size_t>(k_total);
-    for (uint32_t j = threadIdx.x; j < total; j += kBlock) {
-        if (slot0 + j < slot_end) {                         // the bound only matters if the counts were corrupted
-            my_vals[slot0 + j] = stage_val[j];
-            if (learner == 0) idx_out[slot0 + j] = stage_pos[j];
-        }
-    }
+    if (blk0 >= d.begin && blk0 + kWaves * kWaveTile <= d.end)
+        update_block<G, true>(mem, grad, lr, beta, one_minus_beta, d, wave, lane, rel0, S, before, total, slot0, my_vals, my_idx,
+                              stage_val, stage_pos);
+    else
+        update_block<G, false>(mem, grad, lr, beta, one_minus_beta, d, wave, lane, rel0, S, before, total, slot0, my_vals,
+                               my_idx, stage_val, stage_pos);
 }
 
 // Sum of the learners' values at the index set, learner 0 first (Alg. 1 line 10 without 1/n).
