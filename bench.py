@@ -149,7 +149,10 @@ def main():
     for t in range(args.warmup):
         one_step(t)
     torch.cuda.synchronize()
-    ctx.scalecom_timing_begin(args.steps)            # HIP events around the dominant kernel only
+    # HIP events around the dominant kernel only, on every 4th step: an event pair costs the
+    # stream about 10 us, which the timed region should not carry on every step
+    sample_every = 4 if args.steps >= 8 else 1
+    ctx.scalecom_timing_begin(args.steps, every=sample_every)
     t0 = time.perf_counter()
     for t in range(args.warmup, args.warmup + args.steps):
         one_step(t)
@@ -212,6 +215,7 @@ def main():
             "traffic": recorded_traffic(w.name) if args.select == "exact" else None,
             "algorithmic_bytes_per_launch": fused_bytes,
             "avg_launch_ms": fused_ms,
+            "launches_timed": len(timed),
         },
         "step_roofline": {
             "algorithmic_bytes_per_step": step_bytes,

@@ -216,11 +216,12 @@ scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradien
  *   4  all-learner pass: accumulate, low-pass memory update, members' values staged (Eq. 3, 5)
  *   5  sum of the staged values over learners (Alg. 1 line 10)
  *
- * scalecom_timing_begin: the next max_steps (0 .. 4096) calls of scalecom_step* on this context
- * record phase boundaries (later calls are not recorded).  With all_phases = 0 only the two
- * boundaries of phase 4, the dominant kernel, are recorded (an event costs the stream a few
- * microseconds, so this is what a throughput measurement should use); with all_phases != 0 all
- * seven.  scalecom_timing_read: waits for the stream, writes
+ * scalecom_timing_begin: of the following calls of scalecom_step* on this context, every
+ * `every`-th (the first, the (every + 1)-th, ...; every >= 1) records phase boundaries, until
+ * max_steps (0 .. 4096) calls have been recorded.  With all_phases = 0 only the two boundaries of
+ * phase 4, the dominant kernel, are recorded; with all_phases != 0 all seven.  An event costs the
+ * stream a few microseconds, so a throughput measurement should record two boundaries on a
+ * sample of its steps.  scalecom_timing_read: waits for the stream, writes
  * phase_ms[t * SCALECOM_N_PHASES + p] = milliseconds of phase p of recorded step t (0 for phases
  * that were not recorded) for at most capacity_steps steps, stores the number of steps written in
  * *n_steps_out, and stops recording.
@@ -228,7 +229,7 @@ scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradien
  *   n_steps_out  [host]
  */
 #define SCALECOM_N_PHASES 6
-scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps, int all_phases);
+scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps, int all_phases, int every);
 scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int capacity_steps, int* n_steps_out);
 
 /*

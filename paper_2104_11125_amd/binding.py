@@ -48,7 +48,7 @@ def lib() -> ctypes.CDLL:
         L.scalecom_step_chunked.restype = i32
         L.scalecom_step_layers.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, f32, i64, vp, vp]
         L.scalecom_step_layers.restype = i32
-        L.scalecom_timing_begin.argtypes = [vp, i32, i32]
+        L.scalecom_timing_begin.argtypes = [vp, i32, i32, i32]
         L.scalecom_timing_begin.restype = i32
         L.scalecom_timing_read.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
         L.scalecom_timing_read.restype = i32
@@ -193,8 +193,8 @@ class ScaleCom:
         self._check(st)
         return idx_out, reduced_vals_out
 
-    def scalecom_timing_begin(self, max_steps: int, all_phases: bool = False) -> None:
-        self._check(lib().scalecom_timing_begin(self._ctx, max_steps, 1 if all_phases else 0))
+    def scalecom_timing_begin(self, max_steps: int, all_phases: bool = False, every: int = 1) -> None:
+        self._check(lib().scalecom_timing_begin(self._ctx, max_steps, 1 if all_phases else 0, every))
 
     def scalecom_timing_read(self, capacity_steps: int):
         """Per-step lists of SCALECOM_N_PHASES phase durations in milliseconds."""

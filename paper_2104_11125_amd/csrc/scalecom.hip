@@ -1391,6 +1391,7 @@ struct scalecom_ctx {
     // optional per-phase timing: events recorded on the context's stream between kernel groups
     std::vector<hipEvent_t> prof_events;     // (SCALECOM_N_PHASES + 1) per recorded step
     int prof_cap = 0, prof_steps = 0;
+    int prof_every = 1, prof_seen = 0;   // of the calls since timing began, every prof_every-th is recorded
     bool prof_all = false;           // false: only the boundaries of the all-learner pass are recorded
     std::string last_error;
 };
@@ -1496,6 +1497,13 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     return SCALECOM_OK;
 }
 
+// Is the step that is being enqueued one whose phase boundaries are recorded?  (Counts the call.)
+bool timed_step(scalecom_ctx* ctx)
+{
+    if (ctx->prof_steps >= ctx->prof_cap) return false;
+    return ctx->prof_seen++ % ctx->prof_every == 0;
+}
+
 // The all-learner pass and the sum over learners, shared by the exact and the chunk-wise selector:
 // both leave the membership mask and the first output slot of every wave tile behind.
 template <typename G, typename Mark>
@@ -1592,7 +1600,7 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
 {
     hipStream_t s = ctx->stream;
     // phase boundaries for scalecom_timing_*: one event before the first kernel, one after each phase
-    const bool timed = ctx->prof_steps < ctx->prof_cap;
+    const bool timed = timed_step(ctx);
     hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
     auto mark = [&](int boundary) {   // boundaries 4 and 5 enclose the all-learner pass
         if (timed && (ctx->prof_all || boundary == 4 || boundary == 5)) (void)hipEventRecord(ev[boundary], s);
@@ -1624,7 +1632,7 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity ^ 1) * ctx->k_max;
     uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
     uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
-    const bool timed = ctx->prof_steps < ctx->prof_cap;
+    const bool timed = timed_step(ctx);
     hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
     auto mark = [&](int boundary) {   // boundaries 4 and 5 enclose the all-learner pass
         if (timed && (ctx->prof_all || boundary == 4 || boundary == 5)) (void)hipEventRecord(ev[boundary], s);
@@ -1974,20 +1982,24 @@ scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* s
     return SCALECOM_OK;
 }
 
-scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps, int all_phases)
+scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps, int all_phases, int every)
 {
     if (!ctx) return SCALECOM_EINVAL;
     if (max_steps < 0 || max_steps > 4096) return fail(ctx, SCALECOM_EINVAL, "max_steps out of range");
+    if (every < 1) return fail(ctx, SCALECOM_EINVAL, "every must be >= 1");
     DeviceGuard guard;
     SC_HIP(ctx, guard.enter(ctx->device));
     const size_t need = static_cast<size_t>(max_steps) * (SCALECOM_N_PHASES + 1);
     while (ctx->prof_events.size() < need) {
         hipEvent_t e;
-        SC_HIP(ctx, hipEventCreate(&e));
+        // timing only: no system-scope fence (cache write-back) when the event is reached
+        SC_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
         ctx->prof_events.push_back(e);
     }
     ctx->prof_cap = max_steps;
     ctx->prof_steps = 0;
+    ctx->prof_every = every;
+    ctx->prof_seen = 0;
     ctx->prof_all = all_phases != 0;
     return SCALECOM_OK;
 }
