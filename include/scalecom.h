@@ -210,16 +210,16 @@ scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradien
  * Phases of one step, in order:
  *   0  first look at the leader (Eq. 2): single predicted pass, or histogram of the top 12 bits
  *      of the magnitude keys, + search of the threshold bucket
- *   1  second leader pass (only when the prediction missed): bucket keys to the candidate list
- *   2  remaining 19 key bits resolved on the candidate list: exact threshold and tie quota
- *   3  per-tile member counts, prefix sums, output slot of every tile, ties resolved
- *   4  all-learner pass: accumulate, low-pass memory update, members' values staged (Eq. 3, 5)
- *   5  sum of the staged values over learners (Alg. 1 line 10)
+ *   1  remaining 19 key bits resolved (on the candidate list; a second pass over the leader makes
+ *      that list when the prediction missed): exact threshold and tie quota
+ *   2  per-tile member counts, prefix sums, output slot of every tile, ties resolved
+ *   3  all-learner pass: accumulate, low-pass memory update, members' values staged (Eq. 3, 5)
+ *   4  sum of the staged values over learners (Alg. 1 line 10)
  *
  * scalecom_timing_begin: of the following calls of scalecom_step* on this context, every
  * `every`-th (the first, the (every + 1)-th, ...; every >= 1) records phase boundaries, until
  * max_steps (0 .. 4096) calls have been recorded.  With all_phases = 0 only the two boundaries of
- * phase 4, the dominant kernel, are recorded; with all_phases != 0 all seven.  An event costs the
+ * phase 3, the dominant kernel, are recorded; with all_phases != 0 all six.  An event costs the
  * stream a few microseconds, so a throughput measurement should record two boundaries on a
  * sample of its steps.  scalecom_timing_read: waits for the stream, writes
  * phase_ms[t * SCALECOM_N_PHASES + p] = milliseconds of phase p of recorded step t (0 for phases
@@ -228,7 +228,7 @@ scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradien
  *   phase_ms     [host] float[capacity_steps * SCALECOM_N_PHASES]
  *   n_steps_out  [host]
  */
-#define SCALECOM_N_PHASES 6
+#define SCALECOM_N_PHASES 5
 scalecom_status scalecom_timing_begin(scalecom_ctx* ctx, int max_steps, int all_phases, int every);
 scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int capacity_steps, int* n_steps_out);
 

@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 SCALECOM_OK, SCALECOM_EINVAL, SCALECOM_ENOMEM, SCALECOM_EHIP, SCALECOM_EUNSUPPORTED = range(5)
 SCALECOM_GRAD_F32, SCALECOM_GRAD_BF16 = 0, 1
 SCALECOM_MAX_LEARNERS = 64
-SCALECOM_N_PHASES = 6
+SCALECOM_N_PHASES = 5
 
 _lib = None
 

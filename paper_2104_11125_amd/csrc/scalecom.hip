@@ -66,6 +66,7 @@ constexpr int kChunk = 1024;                     // supertiles per chunk of the 
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
 constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
 constexpr int kHistGridMax = 2048;
+constexpr int kFoldLastSearchMaxSt = 32768;      // up to this many supertiles k_tilecount searches the last level itself
 constexpr int kCandSlice = 512;                  // candidate slots per supertile (1/16 of its positions)
 constexpr uint32_t kModeFull = 0, kModeCand = 1;
 
@@ -255,18 +256,6 @@ __device__ __forceinline__ void leader_keys(const float* mem, const G* grad, flo
 __device__ __forceinline__ uint32_t window_lo(uint32_t p) { return p >= 3 ? p - 3 : 0u; }
 __device__ __forceinline__ uint32_t window_hi(uint32_t p) { return p + 1 < static_cast<uint32_t>(kBins0) ? p + 1 : kBins0 - 1u; }
 
-// Totals of the predicted pass for one segment: tot[0] keys above the window, tot[1 + d] keys with
-// the window's d-th digit.
-__device__ __forceinline__ void spec_totals(const uint32_t* __restrict__ part, int seg, uint32_t tot[1 + kWindow])
-{
-    const uint32_t* base = part + static_cast<size_t>(seg) * kPartSlots * kPartWords;
-#pragma unroll
-    for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = 0;
-    for (int sl = 0; sl < kPartSlots; ++sl)
-#pragma unroll
-        for (uint32_t j = 0; j <= kWindow; ++j) tot[j] += base[sl * kPartWords + j];
-}
-
 // Did the predicted single pass see the k-th largest key inside its window?  If so: the key's
 // top digit and how many members remain to be found inside that digit's bucket.  Exact: uses
 // only counts gathered over the whole segment.
@@ -307,21 +296,21 @@ __device__ __forceinline__ void store_tile_masks(uint64_t* mask, size_t tile, co
     dst[1] = make_ulonglong2(b[2], b[3]);
 }
 
-struct CollectStage {       // LDS staging of one supertile's outputs of the collecting passes
+struct CollectStage {       // LDS staging of one supertile's masks and tile counts in the collecting passes
     uint64_t mask[kTilesPerSuper][4];
     uint32_t cnt[kTilesPerSuper];
-    uint2 cand[kCandSlice];
 };
 
 // The per-tile work of the "collect" pass, given the tile's keys: keys whose top digit lies above
 // `hi` are members for sure (their count and ballots are staged for the tile); keys with a top
-// digit in [lo, hi] are appended, with their positions, to the supertile's staged candidate slice
-// (slots handed out through the block's LDS counter `fill`) and, if `wc` is given, counted per
-// digit there.  Called by all lanes of a wave; n_above is the same in every lane.
+// digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice `cand_dst`
+// (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if `wc` is given, counted per
+// digit there, and, if `lh1` is given (then lo == hi), per second digit there.  Called by all lanes
+// of a wave; n_above is the same in every lane.
 template <bool ALL_OK>
 __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
                                              uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* wc,
-                                             uint32_t& n_above, CollectStage& stg)
+                                             uint32_t* lh1, uint32_t& n_above, CollectStage& stg, uint2* cand_dst)
 {
     // top digit > hi  <=>  key >= (hi + 1) << 19;  lo <= top digit <= hi  <=>  key - (lo << 19) < span
     const uint32_t lo_key = lo << (kBits1 + kBits2);
@@ -354,18 +343,20 @@ __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool o
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         if (in[c]) {
-            if (rank < kCandSlice) stg.cand[rank] = make_uint2(key[c], p0 + c);
+            if (rank < kCandSlice) cand_dst[rank] = make_uint2(key[c], p0 + c);
             if (wc) atomicAdd(&wc[(key[c] >> (kBits1 + kBits2)) - lo], 1u);
+            if (lh1) atomicAdd(&lh1[(key[c] >> kBits2) & (kBins1 - 1)], 1u);   // counted whether or not it is listed
             ++rank;
         }
     }
 }
 
-// After the block's barrier: the staged masks, counts and candidates of the supertile go out with
-// full-width stores (lane-0 stores of 32 bytes per tile cost the collecting passes 8 % of their time).
-__device__ __forceinline__ void collect_flush(const CollectStage& stg, size_t tile0, uint32_t n_cand,
-                                              uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask,
-                                              uint64_t* __restrict__ eq_mask, uint2* __restrict__ slice)
+// After the block's barrier: the staged masks and counts of the supertile, and its candidates if
+// they were staged too, go out with full-width stores (lane-0 stores of 32 bytes per tile cost the collecting passes 8 % of their time).
+__device__ __forceinline__ void collect_flush(const CollectStage& stg, const uint2* cand_stage, size_t tile0,
+                                              uint32_t n_cand, uint32_t* __restrict__ wt_cnt,
+                                              uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
+                                              uint2* __restrict__ slice)
 {
     static_assert(kTilesPerSuper * 4 * sizeof(uint64_t) == kLanes * sizeof(ulonglong2), "one 16-byte store per lane");
     static_assert(kBlock >= 2 * kLanes + kTilesPerSuper, "threads for the three flushes");
@@ -378,8 +369,9 @@ __device__ __forceinline__ void collect_flush(const CollectStage& stg, size_t ti
     } else if (t < 2 * kLanes + kTilesPerSuper) {
         wt_cnt[tile0 + (t - 2 * kLanes)] = stg.cnt[t - 2 * kLanes];
     }
+    if (!cand_stage) return;                                // the candidates went to the slice directly
     const uint32_t n = n_cand < kCandSlice ? n_cand : kCandSlice;
-    for (uint32_t e = threadIdx.x; e < n; e += kBlock) slice[e] = stg.cand[e];
+    for (uint32_t e = threadIdx.x; e < n; e += kBlock) slice[e] = cand_stage[e];
 }
 
 // First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
@@ -396,7 +388,7 @@ __device__ __forceinline__ void collect_flush(const CollectStage& stg, size_t ti
 template <typename G, bool INSIDE>
 __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                                                     const StDesc& d, uint32_t lo, uint32_t hi, int wave, int lane,
-                                                    uint32_t* fill, uint32_t* wc, CollectStage& stg)
+                                                    uint32_t* fill, uint32_t* wc, CollectStage& stg, uint2* cand_stage)
 {
     constexpr int kIters = kTilesPerSuper / kWaves;
     constexpr uint32_t kStride = kWaves * kWaveTile;
@@ -427,7 +419,7 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
             for (int c = 0; c < 4; ++c) ok[c] = static_cast<int64_t>(p_cur) + c >= begin && static_cast<int64_t>(p_cur) + c < end;
         }
         uint32_t n_above;
-        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, n_above, stg);
+        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, n_above, stg, cand_stage);
         above_acc += n_above;
         m_cur = m_nxt;
         g_cur = g_nxt;
@@ -460,6 +452,7 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     __shared__ uint32_t fill;
     __shared__ uint32_t acc[kPartWords];                    // [0] above the window, [1 + d] per window digit
     __shared__ CollectStage stg;
+    __shared__ uint2 cand_stage[kCandSlice];
     if (threadIdx.x == 0) fill = 0u;
     if (threadIdx.x < kPartWords) acc[threadIdx.x] = 0u;
     __syncthreads();
@@ -467,12 +460,12 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
     uint32_t above_acc;
     if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
-        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg);
+        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg, cand_stage);
     else
-        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg);
+        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg, cand_stage);
     if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
     __syncthreads();
-    collect_flush(stg, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
+    collect_flush(stg, cand_stage, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
     if (threadIdx.x == 0) {
         const uint32_t n = fill;
         st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
@@ -502,80 +495,95 @@ k_hist0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
     const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
 
-    int cur = -1;
-    bool histogram = false, dirty = false, lh_ready = false;
-    auto flush = [&]() {
-        if (!dirty) return;
-        __syncthreads();
-        for (int b = threadIdx.x; b < kBins0; b += kBlock) {
-            const uint32_t v = lh[b];
-            if (v) {
-                atomicAdd(&hist[static_cast<size_t>(cur) * kBins0 + b], v);
-                lh[b] = 0u;
+    bool lh_ready = false;
+    // walk the block's supertiles segment by segment: a segment that needs no histogram (the
+    // steady state) costs one look at its counters, not one per supertile
+    int st = st_lo;
+    while (st < st_hi) {
+        const int cur = sts[st].seg;
+        const SegDesc sd = segs[cur];
+        const int seg_hi = sd.st_first + sd.st_count < st_hi ? sd.st_first + sd.st_count : st_hi;
+        const uint32_t p = preds[cur];
+        const uint32_t k = static_cast<uint32_t>(sd.k);
+        if (k != 0 && p != 0) {                             // did the prediction hold?  (block-uniform branch)
+            if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
+            __syncthreads();
+            for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
+                const uint32_t v = part[static_cast<size_t>(cur) * kPartSlots * kPartWords + i];
+                if (v) atomicAdd(&tot_s[i % kPartWords], v);
             }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                uint32_t tot[1 + kWindow], digit, k_rem;
+                for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
+                needed = !spec_resolve(tot, overflow[cur] != 0, p, k, digit, k_rem);
+            }
+        } else if (threadIdx.x == 0) {
+            needed = k != 0;
         }
         __syncthreads();
-        dirty = false;
-    };
-    for (int st = st_lo; st < st_hi; ++st) {
-        const StDesc d = sts[st];
-        if (d.seg != cur) {
-            if (cur >= 0) flush();
-            cur = d.seg;
-            const uint32_t p = preds[cur];
-            const uint32_t k = static_cast<uint32_t>(segs[cur].k);
-            if (k != 0 && p != 0) {                         // did the prediction hold?  (block-uniform branch)
-                if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
-                __syncthreads();
-                for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
-                    const uint32_t v = part[static_cast<size_t>(cur) * kPartSlots * kPartWords + i];
-                    if (v) atomicAdd(&tot_s[i % kPartWords], v);
-                }
-                __syncthreads();
-                if (threadIdx.x == 0) {
-                    uint32_t tot[1 + kWindow], digit, k_rem;
-                    for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
-                    needed = !spec_resolve(tot, overflow[cur] != 0, p, k, digit, k_rem);
-                }
-            } else if (threadIdx.x == 0) {
-                needed = k != 0;
-            }
-            __syncthreads();
-            histogram = needed != 0;
-            __syncthreads();
-            if (histogram && !lh_ready) {                   // the histogram is only cleared when it is used
+        const bool histogram = needed != 0;
+        __syncthreads();
+        if (histogram) {
+            if (!lh_ready) {                                // the histogram is only cleared when it is used
                 for (int b = threadIdx.x; b < kBins0; b += kBlock) lh[b] = 0u;
                 __syncthreads();
                 lh_ready = true;
             }
-        }
-        if (!histogram) continue;
-        dirty = true;
-        const int64_t begin = d.begin, end = d.end;
+            const int64_t begin = sd.begin, end = sd.end;
+            for (int s2 = st; s2 < seg_hi; ++s2) {
+                const int64_t a0 = sts[s2].a0;
 #pragma unroll 2
-        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-            const int64_t p0 = static_cast<int64_t>(d.a0) + (it * kWaves + wave) * kWaveTile + lane * kVec;
-            if (p0 >= end) continue;
-            uint32_t key[4];
-            bool ok[4];
-            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+                for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+                    const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+                    if (p0 >= end) continue;
+                    uint32_t key[4];
+                    bool ok[4];
+                    leader_keys(mem, grad, lr, p0, begin, end, key, ok);
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
+                    for (int c = 0; c < 4; ++c)
+                        if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
+                }
+            }
+            __syncthreads();                                // flush the segment's counts
+            for (int b = threadIdx.x; b < kBins0; b += kBlock) {
+                const uint32_t v = lh[b];
+                if (v) {
+                    atomicAdd(&hist[static_cast<size_t>(cur) * kBins0 + b], v);
+                    lh[b] = 0u;
+                }
+            }
+            __syncthreads();
         }
+        st = seg_hi;
     }
-    if (cur >= 0) flush();
 }
+
+// What the level-1 pass writes when it also has to collect (see k_hist).
+struct CollectOut {
+    SegState* state;
+    uint32_t* wt_cnt;
+    uint64_t* sel_mask;
+    uint64_t* eq_mask;
+    uint2* cand;
+    uint32_t* st_cand_cnt;
+};
 
 // Histogram of the next digit of the leader's magnitude keys, per segment.  LEVEL 1: bits 18..7
 // of keys whose top 12 bits equal the chosen bucket; LEVEL 2: last 7 bits of keys matching 24
 // bits.  Candidate mode reads the keys from the candidate list, full mode recomputes them from
 // the leader's vector.
+// LEVEL 1 is also the second full pass over the leader's vector for segments in candidate mode
+// whose list the predicted pass did not fill (no prediction, or one that missed): per wave tile,
+// keys above the level-0 bucket are members for sure, keys inside the bucket go to the
+// supertile's slice of the candidate list and are counted here directly.  A slice that overflows
+// (bucket keys clustered in one place) sends the whole segment back to full-pass mode for the
+// kernels that follow; this kernel's counts are complete either way.
 template <typename G, int LEVEL>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8)))   // 2048 blocks = 8 waves on every SIMD
 k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const StDesc* __restrict__ sts, int n_st,
        const SegState* __restrict__ state, uint32_t* __restrict__ hist, const uint2* __restrict__ cand,
-       const uint32_t* __restrict__ st_cand_cnt)
+       const uint32_t* __restrict__ st_cand_cnt, CollectOut out)
 {
     static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_hist0");
     constexpr int NB = LEVEL == 1 ? kBins1 : kBins2;
@@ -597,7 +605,7 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
 
     int cur = -1;
     uint32_t prefix = 0;
-    bool skip = false, from_list = false;
+    bool skip = false, from_list = false, collect = false;
     for (int st = st_lo; st < st_hi; ++st) {
         const StDesc d = sts[st];
         if (d.seg != cur) {
@@ -613,11 +621,43 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
                 __syncthreads();
             }
             cur = d.seg;
-            prefix = state[cur].prefix;
-            skip = state[cur].done != 0;
-            from_list = state[cur].mode == kModeCand;
+            const SegState ss = state[cur];
+            prefix = ss.prefix;
+            skip = ss.done != 0;
+            from_list = ss.mode == kModeCand;
+            collect = LEVEL == 1 && from_list && ss.collected == 0;
         }
         if (skip) continue;
+        if constexpr (LEVEL == 1) {
+            if (collect) {   // block-uniform: no list yet, this pass makes it
+                __shared__ uint32_t fill;
+                __shared__ CollectStage stg;
+                if (threadIdx.x == 0) fill = 0u;
+                __syncthreads();
+                const int64_t begin = d.begin, end = d.end;
+                uint2* slice = out.cand + static_cast<size_t>(st) * kCandSlice;   // written directly: LDS is the histogram's
+                for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+                    const int wt = it * kWaves + wave;
+                    const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
+                    uint32_t key[4] = {0, 0, 0, 0};
+                    bool ok[4] = {false, false, false, false};
+                    if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+                    uint32_t n_above;
+                    collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, nullptr, lh, n_above,
+                                        stg, slice);
+                }
+                __syncthreads();
+                collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask, out.eq_mask,
+                              slice);
+                if (threadIdx.x == 0) {
+                    const uint32_t n = fill;
+                    out.st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
+                    if (n > kCandSlice) out.state[cur].mode = kModeFull;   // every overflowing block stores the same value
+                }
+                __syncthreads();   // the staging area is reused for the block's next supertile
+                continue;
+            }
+        }
         if (from_list) {   // keys of this supertile that were copied to the candidate list
             const uint32_t cnt = st_cand_cnt[st];
             const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
@@ -676,12 +716,22 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
         }
         // a prediction that held: the single pass already produced everything level 0 gives
         __shared__ int resolved;
+        __shared__ uint32_t tot_s[kPartWords];
+        const uint32_t p = preds[seg];
+        if (p != 0) {                                       // block-uniform: sum the slotted copies of the counters
+            if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
+            __syncthreads();
+            for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
+                const uint32_t v = part[static_cast<size_t>(seg) * kPartSlots * kPartWords + i];
+                if (v) atomicAdd(&tot_s[i % kPartWords], v);
+            }
+            __syncthreads();
+        }
         if (threadIdx.x == 0) {
             uint32_t tot[1 + kWindow], digit, k_rem;
-            const uint32_t p = preds[seg];
             resolved = 0;
             if (p != 0) {
-                spec_totals(part, seg, tot);
+                for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
                 if (spec_resolve(tot, overflow[seg] != 0, p, s.k_rem, digit, k_rem)) {
                     resolved = 1;
                     s.prefix = digit;
@@ -742,46 +792,40 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     }
 }
 
-// Second full pass over the leader's vector, for segments in candidate mode whose list was not
-// already filled during the histogram pass.  Per wave tile: keys above the level-0 bucket are
-// members for sure; keys inside the bucket go to this supertile's slice of the candidate list.
-// A slice that overflows (bucket keys clustered in one place) sends the whole segment back to
-// full-pass mode.
-template <typename G>
-__global__ void __launch_bounds__(kBlock)
-k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const StDesc* __restrict__ sts,
-          SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt, uint2* __restrict__ cand,
-          uint32_t* __restrict__ st_cand_cnt, uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask)
+// The last search of the threshold (7 key bits, 128 counters), done by every block that needs the
+// result instead of by a kernel of its own (k_find<2>, which is launched instead when there are so
+// many blocks that their added barriers cost more than the launch): from the top of the histogram, the bin that holds the
+// k_rem-th largest key of the current 24-bit bucket.  All threads of the block call it; `bcast`
+// is three words of LDS.  Returns the threshold key T and sets q, the number of keys equal to T that
+// are members.  The histogram is 512 bytes, so re-reading it in every block is cheap (the 16 KB
+// histograms of the earlier levels are not: those searches stay kernels).
+__device__ __forceinline__ uint32_t find_threshold(const uint32_t* __restrict__ h, uint32_t prefix24, uint32_t k_rem,
+                                                   uint32_t* bcast, uint32_t& q)
 {
-    const int st = blockIdx.x;
-    const StDesc d = sts[st];
-    const SegState ss = state[d.seg];
-    if (ss.done || ss.mode != kModeCand || ss.collected) return;
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
-    const int64_t begin = d.begin, end = d.end;
-    const uint32_t bucket = ss.prefix;
-    uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-    __shared__ uint32_t fill;
-    __shared__ CollectStage stg;
-    if (threadIdx.x == 0) fill = 0u;
-    __syncthreads();
-
-    for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-        const int wt = it * kWaves + wave;
-        const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
-        uint32_t key[4] = {0, 0, 0, 0};
-        bool ok[4] = {false, false, false, false};
-        if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-        uint32_t n_above;
-        collect_tile<false>(key, ok, static_cast<uint32_t>(p0), bucket, bucket, wt, lane, &fill, nullptr, n_above, stg);
+    static_assert(kBins2 == 2 * kLanes, "two waves hold the last level's counters");
+    const int t = threadIdx.x, lane = t % kLanes;
+    const uint32_t mine = t < kBins2 ? h[t] : 0u;
+    uint32_t suf = mine;                                    // inclusive suffix sum inside the wave
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t v = __shfl_down(suf, off, kLanes);
+        if (lane + off < kLanes) suf += v;
+    }
+    if (t == kLanes) bcast[0] = suf;                        // total of bins 64..127
+    if (t == kBins2) {                                      // if the counts were corrupted: nothing is a member
+        bcast[1] = 0xffffffffu;
+        bcast[2] = 0u;
     }
     __syncthreads();
-    collect_flush(stg, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
-    if (threadIdx.x == 0) {
-        const uint32_t n = fill;
-        st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
-        if (n > kCandSlice) state[d.seg].mode = kModeFull;   // every overflowing block stores the same value
+    if (t < kLanes) suf += bcast[0];
+    const uint32_t excl = suf - mine;                       // keys in higher bins
+    if (t < kBins2 && excl < k_rem && k_rem <= suf) {       // exactly one bin qualifies
+        bcast[1] = (prefix24 << kBits2) | static_cast<uint32_t>(t);
+        bcast[2] = k_rem - excl;
     }
+    __syncthreads();
+    q = bcast[2];
+    return bcast[1];
 }
 
 // Per wave tile of the leader's vector: number of keys above the threshold (low half of the
@@ -791,17 +835,25 @@ k_collect(const float* __restrict__ mem, const G* __restrict__ grad, float lr, c
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-            const StDesc* __restrict__ sts, const SegState* __restrict__ state, uint32_t* __restrict__ wt_cnt,
-            const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt, uint64_t* __restrict__ sel_mask,
-            uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
+            const StDesc* __restrict__ sts, SegState* __restrict__ state, const uint32_t* __restrict__ hist2,
+            uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt,
+            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
 {
     const int st = blockIdx.x;
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
     const StDesc d = sts[st];
     const SegState ss = state[d.seg];
-    const uint32_t T = ss.T;
     const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper;
     __shared__ uint32_t cnt[kTilesPerSuper];
+    __shared__ uint32_t bcast[3];
+    uint32_t T = ss.T, q = ss.q;                            // an empty index set keeps T above every key
+    if (!ss.done && hist2) {                                // block-uniform; without hist2 a kernel has searched already
+        T = find_threshold(hist2 + static_cast<size_t>(d.seg) * kBins2, ss.prefix, ss.k_rem, bcast, q);
+        if (st == segs[d.seg].st_first && threadIdx.x == 0) {   // for the tie quota of the slot pass
+            state[d.seg].T = T;
+            state[d.seg].q = q;
+        }
+    }
 
     if (!ss.done && ss.mode == kModeCand) {
         if (threadIdx.x < kTilesPerSuper) cnt[threadIdx.x] = wt_cnt[tile0 + threadIdx.x];
@@ -1524,7 +1576,7 @@ void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learne
     const unsigned gy = static_cast<unsigned>((groups + gz - 1) / gz);
     k_update<G><<<dim3(n_learners, gy, gz), kBlock, 0, s>>>(lp, lr, beta, 1.0f - beta, sts, n_st, sel_mask, tile_slot, vals,
                                                            k_total, idx_out);
-    mark(5);
+    mark(4);
     if (k_total > 0)
         k_reduce<<<static_cast<unsigned>((k_total + kBlock - 1) / kBlock), kBlock, 0, s>>>(vals, n_learners, k_total,
                                                                                            red_out);
@@ -1576,14 +1628,15 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, hist0, preds, part, overflow);
     k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow);
     mark(1);
-    k_collect<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask);
-    mark(2);
-    k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt);
+    const CollectOut cout{state, wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt};
+    k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt, cout);
     k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow);
-    k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt);
-    k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow);
-    mark(3);
-    k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask,
+    k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt, cout);
+    // the last search: inside k_tilecount's blocks, or a kernel of its own when those are very many
+    const bool fold_last = n_st <= kFoldLastSearchMaxSt;
+    if (!fold_last) k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow);
+    mark(2);
+    k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, fold_last ? hist2 : nullptr, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask,
                                            st_sum);
     k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
     k_slots<<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot, sel_mask,
@@ -1602,16 +1655,16 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     // phase boundaries for scalecom_timing_*: one event before the first kernel, one after each phase
     const bool timed = timed_step(ctx);
     hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
-    auto mark = [&](int boundary) {   // boundaries 4 and 5 enclose the all-learner pass
-        if (timed && (ctx->prof_all || boundary == 4 || boundary == 5)) (void)hipEventRecord(ev[boundary], s);
+    auto mark = [&](int boundary) {   // boundaries 3 and 4 enclose the all-learner pass
+        if (timed && (ctx->prof_all || boundary == 3 || boundary == 4)) (void)hipEventRecord(ev[boundary], s);
     };
     if (ctx->n_st > 0) {
         mark(0);
         launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors,
                          reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds), mark);
-        mark(4);
+        mark(3);
         launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
-        mark(6);
+        mark(5);
         if (timed) ++ctx->prof_steps;
     }
     SC_HIP(ctx, hipGetLastError());
@@ -1634,8 +1687,8 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
     const bool timed = timed_step(ctx);
     hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
-    auto mark = [&](int boundary) {   // boundaries 4 and 5 enclose the all-learner pass
-        if (timed && (ctx->prof_all || boundary == 4 || boundary == 5)) (void)hipEventRecord(ev[boundary], s);
+    auto mark = [&](int boundary) {   // boundaries 3 and 4 enclose the all-learner pass
+        if (timed && (ctx->prof_all || boundary == 3 || boundary == 4)) (void)hipEventRecord(ev[boundary], s);
     };
     auto grid2 = [](int64_t blocks) {   // x up to 2^20 blocks, the rest over y
         const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
@@ -1653,12 +1706,11 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, numel, chunk, best, sel_mask, n_tiles);
     mark(1);
     mark(2);
-    mark(3);
     k_chunk_marks<<<grid2((std::max(n_tiles, k_total) + kBlock - 1) / kBlock), kBlock, 0, s>>>(
         best, best_next, k_total, chunk, n_tiles, sel_mask, tile_slot, idx_out);
-    mark(4);
+    mark(3);
     launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
-    mark(6);
+    mark(5);
     if (timed) ++ctx->prof_steps;
     SC_HIP(ctx, hipGetLastError());
     ctx->best_parity ^= 1;
@@ -2018,7 +2070,7 @@ scalecom_status scalecom_timing_read(scalecom_ctx* ctx, float* phase_ms, int cap
         for (int p = 0; p < SCALECOM_N_PHASES; ++p) {
             float* out = &phase_ms[t * SCALECOM_N_PHASES + p];
             *out = 0.0f;
-            if (ctx->prof_all || p == 4) SC_HIP(ctx, hipEventElapsedTime(out, ev[p], ev[p + 1]));
+            if (ctx->prof_all || p == 3) SC_HIP(ctx, hipEventElapsedTime(out, ev[p], ev[p + 1]));
         }
     }
     *n_steps_out = n;
