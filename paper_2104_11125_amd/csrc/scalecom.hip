@@ -1163,16 +1163,22 @@ k_reduce(const float* __restrict__ vals, int n_learners, int64_t k_total, float*
 // ------------------------------------------------------------------------------------------
 // chunk-wise selection (the selector of the paper's own implementation: Sec. 4, App. E)
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t wave_max64(uint64_t v)
+// Largest value of v over the 64 lanes, in a scalar register.  Data-parallel-primitive moves inside
+// the vector ALU (shift right by 1, 2, 4, 8 lanes inside each row of 16, then row 0's and rows
+// 0-1's last lane broadcast to the following rows) instead of cross-lane reads through the LDS
+// crossbar; lanes without a source take the identity 0.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), off, kLanes);
-        const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), off, kLanes);
-        const uint64_t o = (static_cast<uint64_t>(hi) << 32) | lo;
-        v = o > v ? o : v;
-    }
-    return v;
+    constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+    constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+    auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
+    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr1, 0xf, 0xf, false)));
+    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr2, 0xf, 0xf, false)));
+    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr4, 0xf, 0xf, false)));
+    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr8, 0xf, 0xf, false)));
+    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowBcast15, 0xa, 0xf, false)));
+    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowBcast31, 0xc, 0xf, false)));
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), kLanes - 1));
 }
 
 // Leader pass of the chunk-wise selector, one wave per wave tile: every element becomes the word
@@ -1185,32 +1191,49 @@ __global__ void __launch_bounds__(kBlock)
 k_chunk_select(const float* __restrict__ mem, const G* __restrict__ grad, float lr, int64_t numel, int64_t chunk,
                unsigned long long* __restrict__ best, uint64_t* __restrict__ sel_mask, int64_t n_tiles)
 {
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
     const int64_t tile = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kWaves + wave;
     if (tile >= n_tiles) return;                            // whole wave
-    const int64_t tile_first = tile * kWaveTile;
-    const int64_t p0 = tile_first + lane * kVec;
-    uint32_t key[4];
-    bool ok[4];
-    leader_keys(mem, grad, lr, p0, static_cast<int64_t>(0), numel, key, ok);
-    uint64_t word[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-        word[c] = ok[c] ? (static_cast<uint64_t>(key[c]) << 32) | (0xffffffffu - static_cast<uint32_t>(p0 + c)) : 0ull;
+    // positions and chunk size are below 2^31: 32-bit arithmetic throughout
+    const uint32_t n = static_cast<uint32_t>(numel), ch = static_cast<uint32_t>(chunk);
+    const uint32_t tile_first = static_cast<uint32_t>(tile) * kWaveTile;
+    const uint32_t p0 = tile_first + lane * kVec;
+    float4 m, g;
+    if (tile_first + kWaveTile <= n) {                      // wave-uniform: the whole tile exists
+        m = load4(mem + p0);
+        g = load4(grad + p0);
+    } else {
+        leader_load(mem, grad, p0, static_cast<int64_t>(0), numel, m, g);
+    }
+    const float4 x = accumulate4(m, g, lr);
+    const uint32_t key[4] = {magnitude_key(x.x), magnitude_key(x.y), magnitude_key(x.z), magnitude_key(x.w)};
     if (lane == 0) {
         const uint64_t zero[4] = {0, 0, 0, 0};
         store_tile_masks(sel_mask, static_cast<size_t>(tile), zero);
     }
-    const int64_t tile_last = (tile_first + kWaveTile < numel ? tile_first + kWaveTile : numel) - 1;
-    const int64_t j_first = tile_first / chunk, j_last = tile_last / chunk;
-    for (int64_t j = j_first; j <= j_last; ++j) {           // wave-uniform trip count
-        const int64_t lo = j * chunk, hi = lo + chunk;
-        uint64_t m = 0;
+    const uint32_t tile_last = (tile_first + kWaveTile < n ? tile_first + kWaveTile : n) - 1;
+    const uint32_t j_first = tile_first / ch, j_last = tile_last / ch;
+    uint32_t lo = j_first * ch;                             // at most tile_first: no overflow
+    for (uint32_t j = j_first; j <= j_last; ++j, lo += ch) { // wave-uniform trip count
+        // positions of chunk j: lo <= p < lo + chunk, i.e. p - lo < chunk (unsigned; lo + chunk may pass 2^32),
+        // and p < numel.  The largest word (key << 32 | ~position) in two 32-bit steps: the largest key,
+        // then the largest ~position among the elements that have it.  ~position is never 0, so a
+        // result of 0 means that no element of the chunk lies in this tile.
+        bool in[4];
+        uint32_t k_here = 0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (p0 + c >= lo && p0 + c < hi && word[c] > m) m = word[c];
-        m = wave_max64(m);
-        if (lane == 0) atomicMax(&best[j], static_cast<unsigned long long>(m));
+        for (int c = 0; c < 4; ++c) {
+            in[c] = p0 + c - lo < ch && p0 + c < n;
+            if (in[c] && key[c] > k_here) k_here = key[c];
+        }
+        const uint32_t k_max = wave_max_u32(k_here);
+        uint32_t inv_here = 0;                              // element c = 0 has the largest ~position of the lane
+#pragma unroll
+        for (int c = 3; c >= 0; --c)
+            if (in[c] && key[c] == k_max) inv_here = 0xffffffffu - (p0 + c);
+        const uint32_t inv_max = wave_max_u32(inv_here);
+        if (lane == 0)
+            atomicMax(&best[j], (static_cast<unsigned long long>(k_max) << 32) | inv_max);
     }
 }
 
