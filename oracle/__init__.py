@@ -60,8 +60,9 @@ def _load():
         lib.oracle_memory_update.argtypes = [vp, vp, vp, i64, i64, f32]
         lib.oracle_step.argtypes = [vp, vp, i32, i32, i64, i64, f32, f32, i64, vp, vp]
         lib.oracle_step_layers.argtypes = [vp, vp, i32, i32, i32, vp, vp, f32, f32, i64, vp, vp]
+        lib.oracle_step_layers_chunked.argtypes = [vp, vp, i32, i32, i32, vp, vp, f32, f32, i64, vp, vp]
         for name in ("oracle_accumulate", "oracle_topk_sort", "oracle_topk_select", "oracle_gather",
-                     "oracle_chunk_select", "oracle_step_chunked",
+                     "oracle_chunk_select", "oracle_step_chunked", "oracle_step_layers_chunked",
                      "oracle_reduce", "oracle_memory_update", "oracle_step", "oracle_step_layers"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -234,4 +235,24 @@ def step_layers(mem, grad, offsets, ks, beta: float, lr: float, step: int):
                                     beta, lr, step, _p(idx), _p(red))
     if rc:
         raise ValueError("oracle_step_layers: bad arguments")
+    return idx, red
+
+
+def step_layers_chunked(mem, grad, offsets, chunks, beta: float, lr: float, step: int):
+    """One iteration with the chunk-wise selector and a chunk size per segment."""
+    n = len(mem)
+    for m in mem:
+        _check_f32(m, "mem[i]")
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    chunks = np.ascontiguousarray(chunks, dtype=np.int64)
+    if chunks.size and chunks.min() < 1:
+        raise ValueError("chunk sizes must be >= 1")
+    lens = np.diff(offsets)
+    total = int((-(-lens // chunks)).sum())
+    idx = np.empty(total, dtype=np.int32)
+    red = np.empty(total, dtype=np.float32)
+    rc = _load().oracle_step_layers_chunked(_ptr_array(mem), _ptr_array(grad), _grad_dtype(grad[0]), n, chunks.size,
+                                            _p(offsets), _p(chunks), beta, lr, step, _p(idx), _p(red))
+    if rc:
+        raise ValueError("oracle_step_layers_chunked: bad arguments")
     return idx, red

@@ -299,6 +299,40 @@ int oracle_step_chunked(float* const* mem, const void* const* grad, int grad_dty
     return 0;
 }
 
+// The same with a separate chunk size per segment (the paper compresses layer by layer, each at
+// its own rate, Sec. 4): segment s contributes one position per chunk of chunks[s] consecutive
+// elements counted from the segment's start, ceil(len_s / chunks[s]) positions, in the order of the
+// chunks; segments follow each other in idx_out as in oracle_step_layers.  A segment of length 0
+// contributes nothing.
+int oracle_step_layers_chunked(float* const* mem, const void* const* grad, int grad_dtype, int n_learners,
+                               int n_tensors, const int64_t* offsets, const int64_t* chunks, float beta, float lr,
+                               int64_t step, int32_t* idx_out, float* reduced_out)
+{
+    if (n_learners < 1 || n_tensors < 0 || step < 0) return 1;
+    if (!(beta > 0.0f && beta <= 1.0f)) return 1;
+    const size_t gsz = grad_dtype == GRAD_BF16 ? 2 : 4;
+    std::vector<float*> m(static_cast<size_t>(n_learners));
+    std::vector<const void*> g(static_cast<size_t>(n_learners));
+    int64_t out = 0;
+    for (int s = 0; s < n_tensors; ++s) {
+        const int64_t begin = offsets[s], len = offsets[s + 1] - offsets[s];
+        if (len < 0 || chunks[s] < 1) return 1;
+        if (len == 0) continue;
+        const int64_t k = (len + chunks[s] - 1) / chunks[s];
+        for (int i = 0; i < n_learners; ++i) {
+            m[i] = mem[i] + begin;
+            g[i] = static_cast<const char*>(grad[i]) + gsz * begin;
+        }
+        // the segment on its own is the whole-vector case; its positions are then shifted by begin
+        if (oracle_step_chunked(m.data(), g.data(), grad_dtype, n_learners, len, chunks[s], beta, lr, step,
+                                idx_out + out, reduced_out + out))
+            return 1;
+        for (int64_t t = 0; t < k; ++t) idx_out[out + t] += static_cast<int32_t>(begin);
+        out += k;
+    }
+    return 0;
+}
+
 // Whole-vector form: one segment covering everything.
 int oracle_step(float* const* mem, const void* const* grad, int grad_dtype, int n_learners, int64_t numel,
                 int64_t k, float beta, float lr, int64_t step, int32_t* idx_out, float* reduced_out)

@@ -375,6 +375,45 @@ def test_chunked_step_equals_primitives():
         assert np.array_equal(mem[i], want_mem[i])
 
 
+def test_chunked_layers_step_is_the_chunked_step_per_segment():
+    """Per-layer chunk sizes: every segment on its own is the whole-vector case (positions shifted
+    by the segment's start); elements outside all segments keep their bits; brute force on the
+    leader's segment decides the positions."""
+    rng = np.random.default_rng(35)
+    n = 3
+    sizes = [0, 5, 1, 40, 0, 1000, 333]
+    chunks = [7, 2, 9, 40, 1, 112, 400]
+    offsets = np.concatenate([[2], 2 + np.cumsum(sizes)])
+    numel = int(offsets[-1]) + 4
+    mem, grad = _random_problem(rng, n, numel)
+    before = [m.copy() for m in mem]
+    step, lr, beta = 4, 0.3, 0.2                                       # leader 1
+    x_leader = oracle.accumulate(mem[1], grad[1], lr)
+    want_idx = []
+    for a, b, ch in zip(offsets[:-1], offsets[1:], chunks):
+        for c0 in range(int(a), int(b), ch):
+            want_idx.append(max(range(c0, min(c0 + ch, int(b))), key=lambda j: (mag_key(x_leader[j]), -j)))
+    ref_mem = [m.copy() for m in mem]
+    ref_idx, ref_red = [], []
+    for a, b, ch in zip(offsets[:-1], offsets[1:], chunks):
+        if b == a:
+            continue
+        sub_m = [np.ascontiguousarray(m[a:b]) for m in ref_mem]
+        sub_g = [np.ascontiguousarray(g[a:b]) for g in grad]
+        i2, r2 = oracle.step_chunked(sub_m, sub_g, ch, beta, lr, step)
+        for m, sm in zip(ref_mem, sub_m):
+            m[a:b] = sm
+        ref_idx += (i2 + a).tolist(); ref_red += r2.tolist()
+    idx, red = oracle.step_layers_chunked(mem, grad, offsets, chunks, beta, lr, step)
+    assert idx.tolist() == want_idx == ref_idx
+    assert red.tolist() == ref_red
+    for i in range(n):
+        assert np.array_equal(mem[i], ref_mem[i])
+        assert np.array_equal(mem[i][:2], before[i][:2]) and np.array_equal(mem[i][-4:], before[i][-4:])
+    with pytest.raises(ValueError):
+        oracle.step_layers_chunked(mem, grad, offsets, [0] * len(chunks), beta, lr, step)
+
+
 # ---------------------------------------------------------------- weight update and rate guidance
 def test_apply_update_closed_form_and_full_iteration():
     """Alg. 1 lines 10 and 12 on the index set: with every learner sending the same gradient g,
