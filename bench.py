@@ -10,7 +10,8 @@ low-pass memory update -- over one batch of synthetic gradients that already sit
 Memories are carried from step to step, the leader rotates with the step index.
 
 `--select chunk` times the chunk-wise selector of the paper's own implementation (one position
-per `rate` consecutive elements, scalecom_step_chunked) instead of the exact top-k.
+per `rate` consecutive elements: scalecom_step_chunked, or scalecom_step_layers_chunked for the
+per-layer workload) instead of the exact top-k.
 
 Prints ONE JSON line.  `value` is gradient elements per second (n_learners * numel / step
 time).  `roofline` is for the dominant kernel (the all-learner pass k_update), timed with HIP
@@ -33,8 +34,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
+def chunk_sizes(w):
+    """Chunk-wise selector: the workload's compression rate as the chunk size of every tensor."""
+    return [w.rate] * w.n_tensors
+
+
 def index_set_size(w, select):
-    return w.k if select == "exact" else -(-w.numel // w.rate)
+    if select == "exact":
+        return w.k
+    if w.n_tensors == 1:
+        return -(-w.numel // w.rate)
+    return sum(-(-(b - a) // w.rate) for a, b in zip(w.offsets[:-1], w.offsets[1:]))
 
 
 def algorithmic_bytes(w, k):
@@ -78,7 +88,9 @@ def cpu_baseline(w, select, budget_s=20.0):
             grad.append(g.view(torch.int16).cpu().numpy().view(np.uint16) if g.dtype == torch.bfloat16
                         else g.cpu().numpy())
         t0 = time.perf_counter()
-        if select == "chunk":
+        if select == "chunk" and w.n_tensors > 1:
+            oracle.step_layers_chunked(mem, grad, w.offsets, chunk_sizes(w), w.beta, w.lr, done)
+        elif select == "chunk":
             oracle.step_chunked(mem, grad, w.rate, w.beta, w.lr, done)
         elif w.n_tensors == 1:
             oracle.step(mem, grad, w.k, w.beta, w.lr, done)
@@ -122,9 +134,6 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     w = workloads.by_name(args.workload)
-    if args.select == "chunk" and w.n_tensors != 1:
-        print("bench.py: --select chunk needs a whole-vector workload", file=sys.stderr)
-        sys.exit(2)
     k = index_set_size(w, args.select)
     gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
     ctx = binding.scalecom_init(w.numel, w.n_learners, gd, w.n_tensors, dev, k_max=k)
@@ -139,7 +148,9 @@ def main():
 
     def one_step(t):
         g = pool[t % pool_n]
-        if args.select == "chunk":
+        if args.select == "chunk" and w.n_tensors > 1:
+            ctx.scalecom_step_layers_chunked(mem, g, w.offsets, chunk_sizes(w), w.beta, w.lr, t, idx, red)
+        elif args.select == "chunk":
             ctx.scalecom_step_chunked(mem, g, w.rate, w.beta, w.lr, t, idx, red)
         elif w.n_tensors == 1:
             ctx.scalecom_step(mem, g, w.k, w.beta, w.lr, t, idx, red)

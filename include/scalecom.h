@@ -143,6 +143,23 @@ scalecom_status scalecom_step_chunked(scalecom_ctx* ctx, float* const* mem, cons
                                       int32_t* idx_out, float* reduced_vals_out);
 
 /*
+ * The chunk-wise selector with a chunk size per tensor: the paper compresses layer by layer, each
+ * at its own rate (Sec. 4), with the selector of scalecom_step_chunked.  Segment s is cut into
+ * chunks of chunks[s] elements counted from offsets[s] (its last chunk may be shorter) and
+ * contributes one position per chunk, ceil(length_s / chunks[s]) positions; an empty segment
+ * contributes none.  Segments follow each other in the outputs as in scalecom_step_layers.
+ *   chunks           [host] int64[n_tensors], each >= 1 (scalecom_layer_ks' rates_out can be passed)
+ *   idx_out          [device] int32[sum of ceil(length_s / chunks[s])], ascending
+ *   reduced_vals_out [device] float[same], paired with idx_out
+ * The number of positions must not exceed the context's k_max.  Other arguments and errors as for
+ * scalecom_step_layers.
+ */
+scalecom_status scalecom_step_layers_chunked(scalecom_ctx* ctx, float* const* mem, const void* const* grad,
+                                             int n_learners, int n_tensors, const int64_t* offsets,
+                                             const int64_t* chunks, float beta, float lr, int64_t step,
+                                             int32_t* idx_out, float* reduced_vals_out);
+
+/*
  * Weight update on the index set (Alg. 1 lines 10 and 12): theta[idx[t]] -= scale * vals[t] for
  * t < k, one rounding per entry (fma(-scale, vals[t], theta[idx[t]])).  With the outputs of a
  * step, scale = 1 / n_learners applies the averaged compressed gradient when lr was the step

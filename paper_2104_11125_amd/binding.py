@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L.scalecom_step_chunked.restype = i32
         L.scalecom_step_layers.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, f32, i64, vp, vp]
         L.scalecom_step_layers.restype = i32
+        L.scalecom_step_layers_chunked.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, f32, i64, vp, vp]
+        L.scalecom_step_layers_chunked.restype = i32
         L.scalecom_timing_begin.argtypes = [vp, i32, i32, i32]
         L.scalecom_timing_begin.restype = i32
         L.scalecom_timing_read.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
@@ -190,6 +192,29 @@ class ScaleCom:
         st = lib().scalecom_step_layers(self._ctx, _ptrs(mem), _ptrs(grad), len(mem), n_tensors, c_off, c_ks, beta,
                                         lr, step, ctypes.c_void_p(idx_out.data_ptr()),
                                         ctypes.c_void_p(reduced_vals_out.data_ptr()))
+        self._check(st)
+        return idx_out, reduced_vals_out
+
+    def scalecom_step_layers_chunked(self, mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor],
+                                     offsets: Sequence[int], chunks: Sequence[int], beta: float, lr: float, step: int,
+                                     idx_out: Optional[torch.Tensor] = None,
+                                     reduced_vals_out: Optional[torch.Tensor] = None):
+        """``scalecom_step_layers_chunked`` of the C-ABI: one position per chunk, a chunk size per tensor."""
+        self._check_buffers(mem, grad)
+        n_tensors = len(chunks)
+        if len(offsets) != n_tensors + 1:
+            raise ValueError("offsets must have len(chunks) + 1 entries")
+        c_off = (ctypes.c_int64 * (n_tensors + 1))(*[int(o) for o in offsets])
+        c_ch = (ctypes.c_int64 * n_tensors)(*[int(v) for v in chunks])
+        total = sum(-(-(int(b) - int(a)) // int(c)) for a, b, c in zip(offsets[:-1], offsets[1:], chunks)
+                    if int(c) >= 1 and int(b) >= int(a))
+        if idx_out is None:
+            idx_out = torch.empty(total, dtype=torch.int32, device=self.device)
+        if reduced_vals_out is None:
+            reduced_vals_out = torch.empty(total, dtype=torch.float32, device=self.device)
+        st = lib().scalecom_step_layers_chunked(self._ctx, _ptrs(mem), _ptrs(grad), len(mem), n_tensors, c_off, c_ch,
+                                                beta, lr, step, ctypes.c_void_p(idx_out.data_ptr()),
+                                                ctypes.c_void_p(reduced_vals_out.data_ptr()))
         self._check(st)
         return idx_out, reduced_vals_out
 

@@ -78,6 +78,8 @@ struct SegDesc {          // one per tensor (segment of the flat vector)
     int32_t st_count;     // number of supertiles
     int32_t chunk_first;  // first scan chunk
     int32_t chunk_count;
+    int32_t sel_chunk;    // chunk-wise selector: elements per chunk of this segment (0 in exact mode)
+    int32_t pad;
 };
 
 struct StDesc {           // one per supertile; carries what the streaming kernels need of its segment
@@ -1183,47 +1185,57 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 
 // Leader pass of the chunk-wise selector, one wave per wave tile: every element becomes the word
 // (magnitude key << 32 | ~position), so that the largest word of a chunk is its largest
-// magnitude at the lowest position; for each chunk that overlaps the tile the wave reduces its
-// part and merges it into best[chunk] with one 64-bit atomic max (a chunk touches at most
-// chunk/256 + 2 tiles).  Also clears the tile's membership mask.
+// magnitude at the lowest position; for each chunk of the tile's segment that overlaps the tile
+// the wave reduces its part and merges it into best[out_base + chunk] with one 64-bit atomic max
+// (a chunk touches at most chunk/256 + 2 tiles).  Chunks are counted from the segment's first
+// element.  Also clears the tile's membership mask.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
-k_chunk_select(const float* __restrict__ mem, const G* __restrict__ grad, float lr, int64_t numel, int64_t chunk,
-               unsigned long long* __restrict__ best, uint64_t* __restrict__ sel_mask, int64_t n_tiles)
+k_chunk_select(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+               const StDesc* __restrict__ sts, int n_st, unsigned long long* __restrict__ best,
+               uint64_t* __restrict__ sel_mask)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
-    const int64_t tile = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kWaves + wave;
-    if (tile >= n_tiles) return;                            // whole wave
-    // positions and chunk size are below 2^31: 32-bit arithmetic throughout
-    const uint32_t n = static_cast<uint32_t>(numel), ch = static_cast<uint32_t>(chunk);
-    const uint32_t tile_first = static_cast<uint32_t>(tile) * kWaveTile;
+    const int64_t group = static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x;   // 4 wave tiles
+    const int st = static_cast<int>(group / kUpdateBlocksPerSuper);
+    if (st >= n_st) return;                                 // whole block
+    const int wt = static_cast<int>(group % kUpdateBlocksPerSuper) * kWaves + wave;
+    const StDesc d = sts[st];
+    const SegDesc sd = segs[d.seg];
+    const size_t tile = static_cast<size_t>(st) * kTilesPerSuper + wt;
+    if (lane == 0) {
+        const uint64_t zero[4] = {0, 0, 0, 0};
+        store_tile_masks(sel_mask, tile, zero);
+    }
+    // positions and chunk sizes are below 2^31 + 8192: 32-bit arithmetic throughout
+    const uint32_t begin = static_cast<uint32_t>(sd.begin), end = static_cast<uint32_t>(sd.end);
+    const uint32_t ch = static_cast<uint32_t>(sd.sel_chunk);
+    const uint32_t tile_first = static_cast<uint32_t>(d.a0) + static_cast<uint32_t>(wt) * kWaveTile;
+    const uint32_t v_lo = tile_first > begin ? tile_first : begin;             // the tile's part of the segment
+    const uint32_t v_hi = tile_first + kWaveTile < end ? tile_first + kWaveTile : end;
+    if (v_lo >= v_hi) return;                               // whole wave: the tile lies outside the segment
     const uint32_t p0 = tile_first + lane * kVec;
     float4 m, g;
-    if (tile_first + kWaveTile <= n) {                      // wave-uniform: the whole tile exists
+    if (tile_first >= begin && tile_first + kWaveTile <= end) {   // wave-uniform: the whole tile belongs to the segment
         m = load4(mem + p0);
         g = load4(grad + p0);
     } else {
-        leader_load(mem, grad, p0, static_cast<int64_t>(0), numel, m, g);
+        leader_load(mem, grad, p0, static_cast<int64_t>(begin), static_cast<int64_t>(end), m, g);
     }
     const float4 x = accumulate4(m, g, lr);
     const uint32_t key[4] = {magnitude_key(x.x), magnitude_key(x.y), magnitude_key(x.z), magnitude_key(x.w)};
-    if (lane == 0) {
-        const uint64_t zero[4] = {0, 0, 0, 0};
-        store_tile_masks(sel_mask, static_cast<size_t>(tile), zero);
-    }
-    const uint32_t tile_last = (tile_first + kWaveTile < n ? tile_first + kWaveTile : n) - 1;
-    const uint32_t j_first = tile_first / ch, j_last = tile_last / ch;
-    uint32_t lo = j_first * ch;                             // at most tile_first: no overflow
+    const uint32_t j_first = (v_lo - begin) / ch, j_last = (v_hi - 1 - begin) / ch;
+    uint32_t lo = begin + j_first * ch;                     // at most v_lo: no overflow
     for (uint32_t j = j_first; j <= j_last; ++j, lo += ch) { // wave-uniform trip count
         // positions of chunk j: lo <= p < lo + chunk, i.e. p - lo < chunk (unsigned; lo + chunk may pass 2^32),
-        // and p < numel.  The largest word (key << 32 | ~position) in two 32-bit steps: the largest key,
+        // and p < end.  The largest word (key << 32 | ~position) in two 32-bit steps: the largest key,
         // then the largest ~position among the elements that have it.  ~position is never 0, so a
         // result of 0 means that no element of the chunk lies in this tile.
         bool in[4];
         uint32_t k_here = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            in[c] = p0 + c - lo < ch && p0 + c < n;
+            in[c] = p0 + c - lo < ch && p0 + c < end;
             if (in[c] && key[c] > k_here) k_here = key[c];
         }
         const uint32_t k_max = wave_max_u32(k_here);
@@ -1233,36 +1245,55 @@ k_chunk_select(const float* __restrict__ mem, const G* __restrict__ grad, float 
             if (in[c] && key[c] == k_max) inv_here = 0xffffffffu - (p0 + c);
         const uint32_t inv_max = wave_max_u32(inv_here);
         if (lane == 0)
-            atomicMax(&best[j], (static_cast<unsigned long long>(k_max) << 32) | inv_max);
+            atomicMax(&best[static_cast<uint32_t>(sd.out_base) + j], (static_cast<unsigned long long>(k_max) << 32) | inv_max);
     }
 }
 
 // After the leader pass: position of each chunk's winner to idx_out and to the membership mask;
-// first output slot of every wave tile (chunk j owns slot j); and the other copy of best[] is
-// cleared for the next step.
+// first output slot of every wave tile (chunk j of a segment owns slot out_base + j); and the
+// other copy of best[] is cleared for the next step.
 __global__ void __launch_bounds__(kBlock)
-k_chunk_marks(const unsigned long long* __restrict__ best, unsigned long long* __restrict__ best_next, int64_t k,
-              int64_t chunk, int64_t n_tiles, uint64_t* __restrict__ sel_mask, uint32_t* __restrict__ tile_slot,
+k_chunk_marks(const SegDesc* __restrict__ segs, int n_tensors, const StDesc* __restrict__ sts,
+              const unsigned long long* __restrict__ best, unsigned long long* __restrict__ best_next, int64_t k_total,
+              int64_t n_tiles, uint64_t* __restrict__ sel_mask, uint32_t* __restrict__ tile_slot,
               int32_t* __restrict__ idx_out)
 {
     const int64_t t = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
-    if (t < k) {
+    if (t < k_total) {
+        // the segment that owns output slot t: the last one whose first slot is <= t (a segment without
+        // slots shares its first slot with its successor, so it is never the last such one while t < k_total)
+        int lo = 0, hi = n_tensors - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) / 2;
+            if (segs[mid].out_base <= t) lo = mid; else hi = mid - 1;
+        }
+        const SegDesc sd = segs[lo];
         const uint32_t pos = 0xffffffffu - static_cast<uint32_t>(best[t]);
         idx_out[t] = static_cast<int32_t>(pos);
-        const uint32_t tile = pos / kWaveTile, l = (pos % kWaveTile) / kVec, c = pos % kVec;
-        atomicOr(reinterpret_cast<uint32_t*>(sel_mask) + (static_cast<size_t>(tile) * 4 + c) * 2 + (l >> 5),
-                 1u << (l & 31));
+        const uint32_t rel = pos - (static_cast<uint32_t>(sd.begin) & ~static_cast<uint32_t>(kVec - 1));
+        const size_t tile = static_cast<size_t>(sd.st_first) * kTilesPerSuper + rel / kWaveTile;
+        const uint32_t l = (rel % kWaveTile) / kVec, c = rel % kVec;
+        atomicOr(reinterpret_cast<uint32_t*>(sel_mask) + (tile * 4 + c) * 2 + (l >> 5), 1u << (l & 31));
         best_next[t] = 0ull;
     }
     if (t < n_tiles) {
-        // winners before this tile: one per chunk that ends before it, plus the straddling
-        // chunk's winner if it lies before the tile
-        const int64_t first = t * kWaveTile;
-        const int64_t j = first / chunk;
-        uint32_t slot = static_cast<uint32_t>(j);
-        if (j < k && j * chunk < first) {
-            const uint32_t pos = 0xffffffffu - static_cast<uint32_t>(best[j]);
-            if (static_cast<int64_t>(pos) < first) ++slot;
+        // winners of the segment before this tile: one per chunk that ends before it, plus the
+        // straddling chunk's winner if it lies before the tile
+        const StDesc d = sts[t / kTilesPerSuper];
+        const SegDesc sd = segs[d.seg];
+        const uint32_t begin = static_cast<uint32_t>(sd.begin), end = static_cast<uint32_t>(sd.end);
+        const uint32_t ch = static_cast<uint32_t>(sd.sel_chunk);
+        const uint32_t first = static_cast<uint32_t>(d.a0) + static_cast<uint32_t>(t % kTilesPerSuper) * kWaveTile;
+        uint32_t slot = static_cast<uint32_t>(sd.out_base);
+        if (first >= end) {
+            slot += static_cast<uint32_t>(sd.k);            // past the segment: its mask is empty
+        } else if (first > begin) {
+            const uint32_t j = (first - begin) / ch;
+            slot += j;
+            if (begin + j * ch < first) {
+                const uint32_t pos = 0xffffffffu - static_cast<uint32_t>(best[static_cast<uint32_t>(sd.out_base) + j]);
+                if (pos < first) ++slot;
+            }
         }
         tile_slot[t] = slot;
     }
@@ -1453,7 +1484,7 @@ struct scalecom_ctx {
     scalecom_grad_dtype gdt = SCALECOM_GRAD_F32;
     WsLayout lay{};
     // tables of the layout used last, kept on the device until the layout changes
-    std::vector<int64_t> cached_offsets, cached_ks;
+    std::vector<int64_t> cached_offsets, cached_ks, cached_chunks;
     int n_st = 0, n_chunks = 0;
     int parity = 0;                  // which copy of the scratch zone the next step uses
     bool scratch_clean = false;      // false: both copies must be cleared before the next step
@@ -1513,11 +1544,16 @@ size_t pinned_bytes_for(int64_t numel_max, int n_tensors_max)
 }
 
 // Rebuild and upload the segment, supertile and chunk tables if the layout differs from the cached one.
-scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* offsets, const int64_t* ks)
+scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* offsets, const int64_t* ks,
+                              const int64_t* sel_chunks = nullptr)
 {
+    // chunk sizes of the chunk-wise selector (0: exact selection) are part of the layout: two
+    // chunk sizes can give the same number of chunks
+    std::vector<int64_t> ch(static_cast<size_t>(n_tensors), 0);
+    if (sel_chunks) ch.assign(sel_chunks, sel_chunks + n_tensors);
     const bool same = ctx->cached_ks.size() == static_cast<size_t>(n_tensors) &&
                       std::memcmp(ctx->cached_offsets.data(), offsets, sizeof(int64_t) * (n_tensors + 1)) == 0 &&
-                      std::memcmp(ctx->cached_ks.data(), ks, sizeof(int64_t) * n_tensors) == 0;
+                      std::memcmp(ctx->cached_ks.data(), ks, sizeof(int64_t) * n_tensors) == 0 && ctx->cached_chunks == ch;
     if (same) return SCALECOM_OK;
 
     if (ctx->upload_pending) {   // staging memory may still be read by an earlier copy
@@ -1540,7 +1576,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
         if (n_st + count > st_cap || n_ch + n_chunks > ch_cap) return fail(ctx, SCALECOM_ENOMEM, "tile table overflow");
         segs[s] = SegDesc{static_cast<int32_t>(b),    static_cast<int32_t>(e),     static_cast<int32_t>(ks[s]),
                           static_cast<int32_t>(out),  static_cast<int32_t>(n_st),  static_cast<int32_t>(count),
-                          static_cast<int32_t>(n_ch), static_cast<int32_t>(n_chunks)};
+                          static_cast<int32_t>(n_ch), static_cast<int32_t>(n_chunks), static_cast<int32_t>(ch[s]), 0};
         for (int64_t j = 0; j < count; ++j)
             sts[n_st + j] = StDesc{s, static_cast<int32_t>(a_first + j * kSuper), static_cast<int32_t>(b),
                                    static_cast<int32_t>(e), static_cast<int32_t>(out + ks[s]), {0, 0, 0}};
@@ -1569,6 +1605,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     ctx->n_chunks = static_cast<int>(n_ch);
     ctx->cached_offsets.assign(offsets, offsets + n_tensors + 1);
     ctx->cached_ks.assign(ks, ks + n_tensors);
+    ctx->cached_chunks = ch;
     return SCALECOM_OK;
 }
 
@@ -1697,8 +1734,8 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
 // One step with the chunk-wise selector: leader pass (per-chunk maxima), marks, then the same
 // all-learner pass and reduction as the exact path.
 template <typename G>
-scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int64_t numel, int64_t chunk,
-                               int64_t k_total, float beta, float lr, int leader, int32_t* idx_out, float* red_out)
+scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int n_tensors, int64_t k_total,
+                               float beta, float lr, int leader, int32_t* idx_out, float* red_out)
 {
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
@@ -1708,6 +1745,8 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity ^ 1) * ctx->k_max;
     uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
     uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
+    const SegDesc* segs = reinterpret_cast<const SegDesc*>(ws + l.segs);
+    const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
     const bool timed = timed_step(ctx);
     hipEvent_t* ev = timed ? &ctx->prof_events[static_cast<size_t>(ctx->prof_steps) * (SCALECOM_N_PHASES + 1)] : nullptr;
     auto mark = [&](int boundary) {   // boundaries 3 and 4 enclose the all-learner pass
@@ -1724,13 +1763,13 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.best), words);
     }
     ctx->best_clean = false;
-    const int64_t n_tiles = static_cast<int64_t>(ctx->n_st) * kTilesPerSuper;   // flat layout: tile t starts at 256 t
-    k_chunk_select<G><<<grid2((n_tiles + kWaves - 1) / kWaves), kBlock, 0, s>>>(
-        lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, numel, chunk, best, sel_mask, n_tiles);
+    const int64_t n_tiles = static_cast<int64_t>(ctx->n_st) * kTilesPerSuper;
+    k_chunk_select<G><<<grid2(n_tiles / kWaves), kBlock, 0, s>>>(lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr,
+                                                                 segs, sts, ctx->n_st, best, sel_mask);
     mark(1);
     mark(2);
     k_chunk_marks<<<grid2((std::max(n_tiles, k_total) + kBlock - 1) / kBlock), kBlock, 0, s>>>(
-        best, best_next, k_total, chunk, n_tiles, sel_mask, tile_slot, idx_out);
+        segs, n_tensors, sts, best, best_next, k_total, n_tiles, sel_mask, tile_slot, idx_out);
     mark(3);
     launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
     mark(5);
@@ -1781,7 +1820,7 @@ scalecom_status check_learners(scalecom_ctx* ctx, float* const* mem, const void*
 
 scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
                             int n_tensors, const int64_t* offsets, const int64_t* ks, float beta, float lr,
-                            int64_t step, int32_t* idx_out, float* red_out, int64_t chunk = 0)
+                            int64_t step, int32_t* idx_out, float* red_out, const int64_t* chunks = nullptr)
 {
     if (!ctx) return SCALECOM_EINVAL;
     ctx->last_error.clear();
@@ -1801,14 +1840,13 @@ scalecom_status step_common(scalecom_ctx* ctx, float* const* mem, const void* co
 
     DeviceGuard guard;
     SC_HIP(ctx, guard.enter(ctx->device));
-    st = ensure_tables(ctx, n_tensors, offsets, ks);
+    st = ensure_tables(ctx, n_tensors, offsets, ks, chunks);
     if (st != SCALECOM_OK) return st;
     const int leader = static_cast<int>(step % n_learners);    // Alg. 1 line 6: CLT-k of learner mod(t, n)
-    if (chunk > 0) {                                            // chunk-wise selector on the whole vector
+    if (chunks) {                                               // chunk-wise selector
         if (ctx->gdt == SCALECOM_GRAD_BF16)
-            return launch_chunked<uint16_t>(ctx, lp, n_learners, offsets[1], chunk, k_total, beta, lr, leader, idx_out,
-                                            red_out);
-        return launch_chunked<float>(ctx, lp, n_learners, offsets[1], chunk, k_total, beta, lr, leader, idx_out, red_out);
+            return launch_chunked<uint16_t>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
+        return launch_chunked<float>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
     }
     if (ctx->gdt == SCALECOM_GRAD_BF16)
         return launch_step<uint16_t>(ctx, lp, n_learners, n_tensors, k_total, beta, lr, leader, idx_out, red_out);
@@ -1937,7 +1975,26 @@ scalecom_status scalecom_step_chunked(scalecom_ctx* ctx, float* const* mem, cons
     if (chunk < 1) return fail(ctx, SCALECOM_EINVAL, "chunk must be >= 1");
     const int64_t offsets[2] = {0, numel};
     const int64_t k = (numel + chunk - 1) / chunk;               // one position per chunk
-    return step_common(ctx, mem, grad, n_learners, 1, offsets, &k, beta, lr, step, idx_out, reduced_vals_out, chunk);
+    return step_common(ctx, mem, grad, n_learners, 1, offsets, &k, beta, lr, step, idx_out, reduced_vals_out, &chunk);
+}
+
+scalecom_status scalecom_step_layers_chunked(scalecom_ctx* ctx, float* const* mem, const void* const* grad,
+                                             int n_learners, int n_tensors, const int64_t* offsets,
+                                             const int64_t* chunks, float beta, float lr, int64_t step,
+                                             int32_t* idx_out, float* reduced_vals_out)
+{
+    if (!ctx) return SCALECOM_EINVAL;
+    if (!offsets || !chunks) return fail(ctx, SCALECOM_EINVAL, "null argument");
+    if (n_tensors < 1 || n_tensors > ctx->n_tensors_max) return fail(ctx, SCALECOM_EINVAL, "n_tensors out of range");
+    std::vector<int64_t> ks(static_cast<size_t>(n_tensors));
+    for (int s = 0; s < n_tensors; ++s) {
+        if (chunks[s] < 1) return fail(ctx, SCALECOM_EINVAL, "chunk must be >= 1");
+        const int64_t len = offsets[s + 1] - offsets[s];
+        if (len < 0) return fail(ctx, SCALECOM_EINVAL, "offsets must be non-decreasing");
+        ks[s] = (len + chunks[s] - 1) / chunks[s];               // one position per chunk
+    }
+    return step_common(ctx, mem, grad, n_learners, n_tensors, offsets, ks.data(), beta, lr, step, idx_out,
+                       reduced_vals_out, chunks);
 }
 
 scalecom_status scalecom_step_layers(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,

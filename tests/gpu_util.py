@@ -48,10 +48,14 @@ def assert_same(kind, got: np.ndarray, want: np.ndarray, rtol=None, what=""):
     raise AssertionError(f"{kind} {what}: within rtol={rtol} but not bit-exact (the arithmetic is meant to be pinned)")
 
 
-def compare_step(ctx, mem_dev, grad_dev, mem_ref, step, beta, lr, k=None, offsets=None, ks=None, what="", chunk=None):
+def compare_step(ctx, mem_dev, grad_dev, mem_ref, step, beta, lr, k=None, offsets=None, ks=None, what="", chunk=None,
+                 chunks=None):
     """Run one step on both sides; mem_dev / mem_ref are updated in place."""
     grad_host = [to_host(g) for g in grad_dev]
-    if chunk is not None:
+    if chunks is not None:
+        idx, red = ctx.scalecom_step_layers_chunked(mem_dev, grad_dev, offsets, chunks, beta, lr, step)
+        want_idx, want_red = oracle.step_layers_chunked(mem_ref, grad_host, offsets, chunks, beta, lr, step)
+    elif chunk is not None:
         idx, red = ctx.scalecom_step_chunked(mem_dev, grad_dev, chunk, beta, lr, step)
         want_idx, want_red = oracle.step_chunked(mem_ref, grad_host, chunk, beta, lr, step)
     elif offsets is None:

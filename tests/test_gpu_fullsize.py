@@ -72,6 +72,21 @@ def test_per_layer_full(gu):
     ctx.close()
 
 
+def test_per_layer_chunked_full(gu):
+    """The chunk-wise selector with a chunk size per tensor, 200 tensors at the benchmark's size."""
+    w = workloads.by_name("per_layer")
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, w.n_tensors, gu.DEV, k_max=w.k)
+    mem = _random_memories(w, gu.DEV, 925)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    chunks = [w.rate] * w.n_tensors
+    for step in (1, 6):
+        print(f"[fullsize] {w.name} chunked step {step}", flush=True)
+        grad = workloads.gradients(w, step, gu.DEV)
+        gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, offsets=w.offsets, chunks=chunks,
+                        what=w.name + " chunked")
+    ctx.close()
+
+
 def _streamed_parity(gu, w, step, seed):
     """One full-size step checked learner by learner with the oracle's primitives."""
     dev = gu.DEV

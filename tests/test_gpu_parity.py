@@ -220,6 +220,38 @@ def test_chunked_selector_ties_bf16_and_mixed_calls(gu):
     ctx.close()
 
 
+def test_chunked_selector_per_layer(gu):
+    """A chunk size per tensor: odd layouts (empty segments, chunk larger than the tensor, chunk 1,
+    segments that start and end inside a wave tile), rates from the paper's guidance, and steps
+    of the other kinds in between on the same context."""
+    n = 3
+    sizes = [0, 5, 1, 40, 0, 1000, 333, 8192, 8193, 70_001, 2, 20_000]
+    chunks = [7, 2, 9, 40, 1, 112, 400, 25, 50, 400, 5, 1]
+    offsets = np.concatenate([[3], 3 + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1] + 5
+    g = torch.Generator(device="cpu").manual_seed(21)
+    mem = [(torch.randn(numel, generator=g) * 1e-3).to(gu.DEV) for _ in range(n)]
+    grad = [(torch.randn(numel, generator=g) * 1e-3).to(gu.DEV) for _ in range(n)]
+    ref = [m.cpu().numpy().copy() for m in mem]
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes), gu.DEV)
+    ks = [-(-sz // 100) for sz in sizes]
+    for step in range(6):
+        if step == 3:      # an exact per-layer step in between
+            gu.compare_step(ctx, mem, grad, ref, step, 0.3, 0.7, offsets=offsets, ks=ks, what="exact between chunked")
+        else:
+            gu.compare_step(ctx, mem, grad, ref, step, 0.3, 0.7, offsets=offsets, chunks=chunks, what="chunked layers")
+    # same number of chunks, other chunk sizes: the cached layout must not be reused
+    chunks2 = [c + 1 if sz and -(-sz // c) == -(-sz // (c + 1)) else c for sz, c in zip(sizes, chunks)]
+    assert chunks2 != chunks
+    gu.compare_step(ctx, mem, grad, ref, 6, 0.3, 0.7, offsets=offsets, chunks=chunks2, what="chunk sizes changed")
+    # the paper's rate guidance feeds it directly
+    _, rates = binding.scalecom_layer_ks([300.0, 150.0, 64.0] * 4, sizes)
+    gu.compare_step(ctx, mem, grad, ref, 7, 0.3, 0.7, offsets=offsets, chunks=rates, what="rates of the guidance")
+    with pytest.raises(binding.ScaleComError):
+        ctx.scalecom_step_layers_chunked(mem, grad, offsets, [0] * len(sizes), 0.3, 0.7, 0)
+    ctx.close()
+
+
 def test_apply_update_after_a_step(gu):
     """Alg. 1 lines 10 and 12: the step's outputs applied to the weights on the same stream."""
     import oracle
