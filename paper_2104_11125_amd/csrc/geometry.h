@@ -1,0 +1,78 @@
+// Geometry of the work (wave tiles, supertiles, scan chunks, radix digits) and the descriptor
+// tables the host uploads.  Part of scalecom.hip's single translation unit.
+#pragma once
+
+#include <cstdint>
+
+#include "scalecom.h"
+
+namespace {
+
+constexpr int kLanes = 64;                       // wavefront width on CDNA
+constexpr int kVec = 4;                          // elements per lane per access (16 B of fp32)
+constexpr int kWaveTile = kLanes * kVec;         // 256 consecutive positions handled by one wave
+constexpr int kTilesPerSuper = 32;               // wave tiles per supertile
+constexpr int kSuper = kWaveTile * kTilesPerSuper;   // 8192 positions
+constexpr int kBlock = 256;                      // threads per block in the streaming kernels
+constexpr int kWaves = kBlock / kLanes;          // 4
+constexpr int kUpdateBlocksPerSuper = kTilesPerSuper / kWaves;   // update: one wave tile per wave
+constexpr int kChunk = 1024;                     // supertiles per chunk of the prefix scan
+
+constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
+constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
+constexpr int kHistGridMax = 2048;
+constexpr int kFoldLastSearchMaxSt = 32768;      // up to this many supertiles k_tilecount searches the last level itself
+constexpr int kCandSlice = 512;                  // candidate slots per supertile (1/16 of its positions)
+constexpr uint32_t kModeFull = 0, kModeCand = 1;
+
+struct SegDesc {          // one per tensor (segment of the flat vector)
+    int32_t begin, end;   // positions [begin, end)
+    int32_t k;            // size of this segment's index set
+    int32_t out_base;     // first output slot of this segment
+    int32_t st_first;     // first supertile
+    int32_t st_count;     // number of supertiles
+    int32_t chunk_first;  // first scan chunk
+    int32_t chunk_count;
+    int32_t sel_chunk;    // chunk-wise selector: elements per chunk of this segment (0 in exact mode)
+    int32_t pad;
+};
+
+struct StDesc {           // one per supertile; carries what the streaming kernels need of its segment
+    int32_t seg;
+    int32_t a0;           // first position, a multiple of 4 (may lie up to 3 before begin)
+    int32_t begin, end;   // the segment's positions [begin, end)
+    int32_t slot_end;     // one past the segment's last output slot
+    int32_t pad[3];
+};
+
+struct ChunkDesc {        // one per scan chunk: up to kChunk consecutive supertiles of one segment
+    int32_t seg;
+    int32_t st_begin;
+    int32_t st_count;
+    int32_t pad;
+};
+
+struct SegState {         // selection state of one segment; every field is rewritten by k_find<0> each step
+    uint32_t prefix;      // key bits fixed so far (level 0: 12 bits, level 1: 24 bits)
+    uint32_t k_rem;       // members still to be found inside the current bucket
+    uint32_t T;           // threshold key (after level 2)
+    uint32_t q;           // number of keys == T that are members (the lowest positions)
+    uint32_t done;        // 1: empty index set, nothing to refine
+    uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
+    uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
+    uint32_t pad;
+};
+
+constexpr uint32_t kWindow = 5;                  // predicted window: previous bucket +- 2 digits
+// Counts of the predicted pass, per segment: [0] keys above the window, [1 + d] keys with the
+// d-th digit of the window.  Blocks add into one of kPartSlots copies (same-address atomics from
+// thousands of blocks would serialise); readers sum the copies.
+constexpr int kPartSlots = 64;
+constexpr int kPartWords = 8;
+
+struct LearnerPtrs {
+    float* mem[SCALECOM_MAX_LEARNERS];
+    const void* grad[SCALECOM_MAX_LEARNERS];
+};
+
+}  // namespace

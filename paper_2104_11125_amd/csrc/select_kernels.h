@@ -1,0 +1,742 @@
+// Exact top-k selection on the leader's vector x_L = fma(lr, grad_L, mem_L) (Eq. 2, Alg. 1 line 6):
+// radix select over the 31-bit magnitude key, 12 + 12 + 7 bits.  Kernels in the order a step runs
+// them: k_predicted, k_hist0, k_find<0>, k_hist<1>, k_find<1>, k_hist<2>, (k_find<2>,) k_tilecount,
+// k_scan, k_slots.  Part of scalecom.hip's single translation unit.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "device_helpers.h"
+#include "geometry.h"
+
+namespace {
+
+__global__ void __launch_bounds__(kBlock) k_init(uint32_t* zero_from, size_t n_words)
+{
+    for (size_t i = blockIdx.x * static_cast<size_t>(kBlock) + threadIdx.x; i < n_words;
+         i += static_cast<size_t>(gridDim.x) * kBlock)
+        zero_from[i] = 0u;
+}
+
+struct CollectStage {       // LDS staging of one supertile's masks and tile counts in the collecting passes
+    uint64_t mask[kTilesPerSuper][4];
+    uint32_t cnt[kTilesPerSuper];
+};
+
+// The per-tile work of the "collect" pass, given the tile's keys: keys whose top digit lies above
+// `hi` are members for sure (their count and ballots are staged for the tile); keys with a top
+// digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice `cand_dst`
+// (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if `wc` is given, counted per
+// digit there, and, if `lh1` is given (then lo == hi), per second digit there.  Called by all lanes
+// of a wave; n_above is the same in every lane.
+template <bool ALL_OK>
+__device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
+                                             uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* wc,
+                                             uint32_t* lh1, uint32_t& n_above, CollectStage& stg, uint2* cand_dst)
+{
+    // top digit > hi  <=>  key >= (hi + 1) << 19;  lo <= top digit <= hi  <=>  key - (lo << 19) < span
+    const uint32_t lo_key = lo << (kBits1 + kBits2);
+    const uint32_t above_key = (hi + 1u) << (kBits1 + kBits2);   // 2^31 for the last digit: no key reaches it
+    const uint32_t span = above_key - lo_key;
+    n_above = 0;
+    uint32_t n_in = 0;
+    bool in[4];
+    uint64_t above[4], inside[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        above[c] = __builtin_amdgcn_ballot_w64((ALL_OK || ok[c]) && key[c] >= above_key);
+        n_above += __popcll(above[c]);
+        in[c] = (ALL_OK || ok[c]) && key[c] - lo_key < span;
+        inside[c] = __builtin_amdgcn_ballot_w64(in[c]);
+        n_in += __popcll(inside[c]);
+    }
+    if (lane == 0) {
+        stg.cnt[wt] = n_above;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) stg.mask[wt][c] = above[c];
+    }
+    if (n_in == 0) return;                                 // wave-uniform
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(fill, n_in);
+    base = __builtin_amdgcn_readfirstlane(base);
+    uint32_t rank = base;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) rank += lanes_below(inside[c]);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (in[c]) {
+            if (rank < kCandSlice) cand_dst[rank] = make_uint2(key[c], p0 + c);
+            if (wc) atomicAdd(&wc[(key[c] >> (kBits1 + kBits2)) - lo], 1u);
+            if (lh1) atomicAdd(&lh1[(key[c] >> kBits2) & (kBins1 - 1)], 1u);   // counted whether or not it is listed
+            ++rank;
+        }
+    }
+}
+
+// After the block's barrier: the staged masks and counts of the supertile, and its candidates if
+// they were staged too, go out with full-width stores (lane-0 stores of 32 bytes per tile cost the collecting passes 8 % of their time).
+__device__ __forceinline__ void collect_flush(const CollectStage& stg, const uint2* cand_stage, size_t tile0,
+                                              uint32_t n_cand, uint32_t* __restrict__ wt_cnt,
+                                              uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
+                                              uint2* __restrict__ slice)
+{
+    static_assert(kTilesPerSuper * 4 * sizeof(uint64_t) == kLanes * sizeof(ulonglong2), "one 16-byte store per lane");
+    static_assert(kBlock >= 2 * kLanes + kTilesPerSuper, "threads for the three flushes");
+    const int t = threadIdx.x;
+    if (t < kLanes) {
+        const ulonglong2* src = reinterpret_cast<const ulonglong2*>(&stg.mask[0][0]);
+        reinterpret_cast<ulonglong2*>(sel_mask + tile0 * 4)[t] = src[t];
+    } else if (t < 2 * kLanes) {
+        reinterpret_cast<ulonglong2*>(eq_mask + tile0 * 4)[t - kLanes] = make_ulonglong2(0ull, 0ull);
+    } else if (t < 2 * kLanes + kTilesPerSuper) {
+        wt_cnt[tile0 + (t - 2 * kLanes)] = stg.cnt[t - 2 * kLanes];
+    }
+    if (!cand_stage) return;                                // the candidates went to the slice directly
+    const uint32_t n = n_cand < kCandSlice ? n_cand : kCandSlice;
+    for (uint32_t e = threadIdx.x; e < n; e += kBlock) slice[e] = cand_stage[e];
+}
+
+// First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
+// that carry a prediction of their threshold bucket (the bucket found in the previous step).
+// ONE pass, no histogram: keys whose top digit lies above a 5-digit window around the
+// prediction are members for sure (counted per tile, marked in the mask), keys inside the
+// window go to the candidate list and are counted per digit.  If the counts show afterwards
+// that the k-th largest key fell inside the window, the threshold bucket is known exactly and
+// no other full pass over the leader is needed.  The prediction only decides how much work is
+// done, never what is selected.  One block per supertile.
+// The 8 tiles a wave owns in a supertile of the predicted pass.  INSIDE: the whole supertile
+// lies in the segment, so loads are unguarded and every position counts; otherwise both are
+// checked per element.  Positions stay below 2^31 + 8192 and are kept in 32 bits.
+template <typename G, bool INSIDE>
+__device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
+                                                    const StDesc& d, uint32_t lo, uint32_t hi, int wave, int lane,
+                                                    uint32_t* fill, uint32_t* wc, CollectStage& stg, uint2* cand_stage)
+{
+    constexpr int kIters = kTilesPerSuper / kWaves;
+    constexpr uint32_t kStride = kWaves * kWaveTile;
+    const int64_t begin = d.begin, end = d.end;
+    // the next tile's loads are issued before this tile is processed (measured: neither a deeper
+    // prefetch nor full unrolling changes the kernel's time)
+    float4 m_cur, g_cur, m_nxt, g_nxt;
+    uint32_t p_cur = static_cast<uint32_t>(d.a0) + wave * kWaveTile + lane * kVec;
+    auto fetch = [&](uint32_t p0, float4& m, float4& g) {
+        if (INSIDE) {
+            m = load4(mem + p0);
+            g = load4(grad + p0);
+        } else {
+            leader_load(mem, grad, p0, begin, end, m, g);
+        }
+    };
+    fetch(p_cur, m_cur, g_cur);
+    uint32_t above_acc = 0;
+#pragma unroll 1
+    for (int it = 0; it < kIters; ++it) {
+        const int wt = it * kWaves + wave;
+        if (it + 1 < kIters) fetch(p_cur + kStride, m_nxt, g_nxt);
+        const float4 x = accumulate4(m_cur, g_cur, lr);
+        const uint32_t key[4] = {magnitude_key(x.x), magnitude_key(x.y), magnitude_key(x.z), magnitude_key(x.w)};
+        bool ok[4] = {true, true, true, true};
+        if (!INSIDE) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) ok[c] = static_cast<int64_t>(p_cur) + c >= begin && static_cast<int64_t>(p_cur) + c < end;
+        }
+        uint32_t n_above;
+        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, n_above, stg, cand_stage);
+        above_acc += n_above;
+        m_cur = m_nxt;
+        g_cur = g_nxt;
+        p_cur += kStride;
+    }
+    return above_acc;
+}
+
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+            const StDesc* __restrict__ sts, uint2* __restrict__ cand,
+            uint32_t* __restrict__ st_cand_cnt, const uint32_t* __restrict__ preds, uint32_t* __restrict__ wt_cnt,
+            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part,
+            uint32_t* __restrict__ overflow, uint32_t* __restrict__ next_scratch, size_t next_words)
+{
+    // The counters and histograms of a step live in one of two copies of a scratch zone; this
+    // kernel, the first of a step, clears the copy the NEXT step will use (nothing else touches it
+    // during this step), so no step needs a separate clearing pass.
+    for (size_t i = blockIdx.x * static_cast<size_t>(kBlock) + threadIdx.x; i < next_words;
+         i += static_cast<size_t>(gridDim.x) * kBlock)
+        next_scratch[i] = 0u;
+
+    const int st = blockIdx.x;
+    const StDesc d = sts[st];
+    const uint32_t p = preds[d.seg];                        // 0: none, else predicted bucket + 1
+    if (p == 0 || segs[d.seg].k == 0) return;
+    const uint32_t lo = window_lo(p), hi = window_hi(p);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
+    __shared__ uint32_t fill;
+    __shared__ uint32_t acc[kPartWords];                    // [0] above the window, [1 + d] per window digit
+    __shared__ CollectStage stg;
+    __shared__ uint2 cand_stage[kCandSlice];
+    if (threadIdx.x == 0) fill = 0u;
+    if (threadIdx.x < kPartWords) acc[threadIdx.x] = 0u;
+    __syncthreads();
+
+    uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+    uint32_t above_acc;
+    if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
+        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg, cand_stage);
+    else
+        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg, cand_stage);
+    if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
+    __syncthreads();
+    collect_flush(stg, cand_stage, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
+    if (threadIdx.x == 0) {
+        const uint32_t n = fill;
+        st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
+        if (n > kCandSlice) overflow[d.seg] = 1u;           // every overflowing block stores the same value
+    }
+    if (threadIdx.x <= kWindow) {
+        const uint32_t v = acc[threadIdx.x];
+        if (v)
+            atomicAdd(&part[(static_cast<size_t>(d.seg) * kPartSlots + st % kPartSlots) * kPartWords + threadIdx.x], v);
+    }
+}
+
+// Histogram of the top 12 key bits of the leader's vector, for the segments that need it: those
+// without a prediction, and those whose prediction failed (the k-th largest key was not inside
+// the window k_predicted collected).
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_hist0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+        const StDesc* __restrict__ sts, int n_st, uint32_t* __restrict__ hist, const uint32_t* __restrict__ preds,
+        const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow)
+{
+    __shared__ uint32_t lh[kBins0];
+    __shared__ uint32_t tot_s[kPartWords];
+    __shared__ int needed;
+
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
+    const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
+
+    bool lh_ready = false;
+    // walk the block's supertiles segment by segment: a segment that needs no histogram (the
+    // steady state) costs one look at its counters, not one per supertile
+    int st = st_lo;
+    while (st < st_hi) {
+        const int cur = sts[st].seg;
+        const SegDesc sd = segs[cur];
+        const int seg_hi = sd.st_first + sd.st_count < st_hi ? sd.st_first + sd.st_count : st_hi;
+        const uint32_t p = preds[cur];
+        const uint32_t k = static_cast<uint32_t>(sd.k);
+        if (k != 0 && p != 0) {                             // did the prediction hold?  (block-uniform branch)
+            if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
+            __syncthreads();
+            for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
+                const uint32_t v = part[static_cast<size_t>(cur) * kPartSlots * kPartWords + i];
+                if (v) atomicAdd(&tot_s[i % kPartWords], v);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                uint32_t tot[1 + kWindow], digit, k_rem;
+                for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
+                needed = !spec_resolve(tot, overflow[cur] != 0, p, k, digit, k_rem);
+            }
+        } else if (threadIdx.x == 0) {
+            needed = k != 0;
+        }
+        __syncthreads();
+        const bool histogram = needed != 0;
+        __syncthreads();
+        if (histogram) {
+            if (!lh_ready) {                                // the histogram is only cleared when it is used
+                for (int b = threadIdx.x; b < kBins0; b += kBlock) lh[b] = 0u;
+                __syncthreads();
+                lh_ready = true;
+            }
+            const int64_t begin = sd.begin, end = sd.end;
+            for (int s2 = st; s2 < seg_hi; ++s2) {
+                const int64_t a0 = sts[s2].a0;
+#pragma unroll 2
+                for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+                    const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+                    if (p0 >= end) continue;
+                    uint32_t key[4];
+                    bool ok[4];
+                    leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
+                }
+            }
+            __syncthreads();                                // flush the segment's counts
+            for (int b = threadIdx.x; b < kBins0; b += kBlock) {
+                const uint32_t v = lh[b];
+                if (v) {
+                    atomicAdd(&hist[static_cast<size_t>(cur) * kBins0 + b], v);
+                    lh[b] = 0u;
+                }
+            }
+            __syncthreads();
+        }
+        st = seg_hi;
+    }
+}
+
+// What the level-1 pass writes when it also has to collect (see k_hist).
+struct CollectOut {
+    SegState* state;
+    uint32_t* wt_cnt;
+    uint64_t* sel_mask;
+    uint64_t* eq_mask;
+    uint2* cand;
+    uint32_t* st_cand_cnt;
+};
+
+// Histogram of the next digit of the leader's magnitude keys, per segment.  LEVEL 1: bits 18..7
+// of keys whose top 12 bits equal the chosen bucket; LEVEL 2: last 7 bits of keys matching 24
+// bits.  Candidate mode reads the keys from the candidate list, full mode recomputes them from
+// the leader's vector.
+// LEVEL 1 is also the second full pass over the leader's vector for segments in candidate mode
+// whose list the predicted pass did not fill (no prediction, or one that missed): per wave tile,
+// keys above the level-0 bucket are members for sure, keys inside the bucket go to the
+// supertile's slice of the candidate list and are counted here directly.  A slice that overflows
+// (bucket keys clustered in one place) sends the whole segment back to full-pass mode for the
+// kernels that follow; this kernel's counts are complete either way.
+template <typename G, int LEVEL>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8)))   // 2048 blocks = 8 waves on every SIMD
+k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const StDesc* __restrict__ sts, int n_st,
+       const SegState* __restrict__ state, uint32_t* __restrict__ hist, const uint2* __restrict__ cand,
+       const uint32_t* __restrict__ st_cand_cnt, CollectOut out)
+{
+    static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_hist0");
+    constexpr int NB = LEVEL == 1 ? kBins1 : kBins2;
+    __shared__ uint32_t lh[NB];
+    for (int b = threadIdx.x; b < NB; b += kBlock) lh[b] = 0u;
+    __syncthreads();
+
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
+    const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
+
+    auto count = [&](uint32_t key, uint32_t prefix) {
+        if (LEVEL == 1) {
+            if ((key >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
+        } else {
+            if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
+        }
+    };
+
+    int cur = -1;
+    uint32_t prefix = 0;
+    bool skip = false, from_list = false, collect = false;
+    for (int st = st_lo; st < st_hi; ++st) {
+        const StDesc d = sts[st];
+        if (d.seg != cur) {
+            if (cur >= 0) {   // flush the finished segment's counts
+                __syncthreads();
+                for (int b = threadIdx.x; b < NB; b += kBlock) {
+                    const uint32_t v = lh[b];
+                    if (v) {
+                        atomicAdd(&hist[static_cast<size_t>(cur) * NB + b], v);
+                        lh[b] = 0u;
+                    }
+                }
+                __syncthreads();
+            }
+            cur = d.seg;
+            const SegState ss = state[cur];
+            prefix = ss.prefix;
+            skip = ss.done != 0;
+            from_list = ss.mode == kModeCand;
+            collect = LEVEL == 1 && from_list && ss.collected == 0;
+        }
+        if (skip) continue;
+        if constexpr (LEVEL == 1) {
+            if (collect) {   // block-uniform: no list yet, this pass makes it
+                __shared__ uint32_t fill;
+                __shared__ CollectStage stg;
+                if (threadIdx.x == 0) fill = 0u;
+                __syncthreads();
+                const int64_t begin = d.begin, end = d.end;
+                uint2* slice = out.cand + static_cast<size_t>(st) * kCandSlice;   // written directly: LDS is the histogram's
+                for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+                    const int wt = it * kWaves + wave;
+                    const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
+                    uint32_t key[4] = {0, 0, 0, 0};
+                    bool ok[4] = {false, false, false, false};
+                    if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+                    uint32_t n_above;
+                    collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, nullptr, lh, n_above,
+                                        stg, slice);
+                }
+                __syncthreads();
+                collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask, out.eq_mask,
+                              slice);
+                if (threadIdx.x == 0) {
+                    const uint32_t n = fill;
+                    out.st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
+                    if (n > kCandSlice) out.state[cur].mode = kModeFull;   // every overflowing block stores the same value
+                }
+                __syncthreads();   // the staging area is reused for the block's next supertile
+                continue;
+            }
+        }
+        if (from_list) {   // keys of this supertile that were copied to the candidate list
+            const uint32_t cnt = st_cand_cnt[st];
+            const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+            for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) count(slice[e].x, prefix);
+            continue;
+        }
+        const int64_t begin = d.begin, end = d.end;
+#pragma unroll 2
+        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+            const int64_t p0 = static_cast<int64_t>(d.a0) + (it * kWaves + wave) * kWaveTile + lane * kVec;
+            if (p0 >= end) continue;
+            uint32_t key[4];
+            bool ok[4];
+            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (ok[c]) count(key[c], prefix);
+        }
+    }
+    if (cur >= 0) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < NB; b += kBlock) {
+            const uint32_t v = lh[b];
+            if (v) atomicAdd(&hist[static_cast<size_t>(cur) * NB + b], v);
+        }
+    }
+}
+
+// One block per segment: locate, from the top of the histogram, the bucket that holds the
+// k_rem-th largest key of the current bucket, and narrow the state to it.
+template <int LEVEL>
+__global__ void __launch_bounds__(kBlock)
+k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uint32_t* __restrict__ hist,
+       uint32_t* __restrict__ preds, const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow)
+{
+    constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
+    constexpr int BITS = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
+    constexpr int CH = NB >= kBlock ? NB / kBlock : 1;     // bins per thread
+    constexpr int ACTIVE = NB >= kBlock ? kBlock : NB;     // threads that own bins
+    const int seg = blockIdx.x;
+    const uint32_t* h = hist + static_cast<size_t>(seg) * NB;
+    __shared__ uint32_t above[kWaves];   // per-wave totals
+
+    SegState s = state[seg];
+    if (LEVEL == 0) {
+        s.prefix = 0;
+        s.k_rem = static_cast<uint32_t>(segs[seg].k);
+        s.done = s.k_rem == 0 ? 1u : 0u;
+        s.T = 0xffffffffu;     // above every key: nothing is a member
+        s.q = 0;
+        s.mode = kModeFull;
+        s.collected = 0;
+        if (s.done) {
+            if (threadIdx.x == 0) state[seg] = s;
+            return;
+        }
+        // a prediction that held: the single pass already produced everything level 0 gives
+        __shared__ int resolved;
+        __shared__ uint32_t tot_s[kPartWords];
+        const uint32_t p = preds[seg];
+        if (p != 0) {                                       // block-uniform: sum the slotted copies of the counters
+            if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
+            __syncthreads();
+            for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
+                const uint32_t v = part[static_cast<size_t>(seg) * kPartSlots * kPartWords + i];
+                if (v) atomicAdd(&tot_s[i % kPartWords], v);
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            uint32_t tot[1 + kWindow], digit, k_rem;
+            resolved = 0;
+            if (p != 0) {
+                for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
+                if (spec_resolve(tot, overflow[seg] != 0, p, s.k_rem, digit, k_rem)) {
+                    resolved = 1;
+                    s.prefix = digit;
+                    s.k_rem = k_rem;
+                    s.mode = kModeCand;
+                    s.collected = 1;
+                    state[seg] = s;
+                    preds[seg] = digit + 1;
+                }
+            }
+        }
+        __syncthreads();
+        if (resolved) return;
+    } else if (s.done) {
+        return;
+    }
+
+    const int t = threadIdx.x;
+    uint32_t mine = 0;
+    if (t < ACTIVE)
+        for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
+    // inclusive suffix sums over threads: within a wave by shuffles, across the 4 waves through LDS
+    const int lane = t % kLanes, wave = t / kLanes;
+    uint32_t suf = mine;
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t v = __shfl_down(suf, off, kLanes);
+        if (lane + off < kLanes) suf += v;
+    }
+    if (lane == 0) above[wave] = suf;                       // the wave's total
+    __syncthreads();
+    for (int w = wave + 1; w < kWaves; ++w) suf += above[w];
+    const uint32_t incl = suf;               // keys in my chunk and all higher chunks
+    const uint32_t excl = incl - mine;       // keys strictly above my chunk
+    if (t < ACTIVE && excl < s.k_rem && s.k_rem <= incl) {
+        uint32_t c = excl;
+        for (int b = CH - 1; b >= 0; --b) {
+            const uint32_t n = h[t * CH + b];
+            if (c + n >= s.k_rem) {
+                const uint32_t digit = static_cast<uint32_t>(t * CH + b);
+                s.prefix = (s.prefix << BITS) | digit;
+                s.k_rem -= c;
+                if (LEVEL == 0) {
+                    // the bucket's keys go to the candidate list if its slots can hold them
+                    const uint64_t slots = static_cast<uint64_t>(segs[seg].st_count) * kCandSlice;
+                    s.mode = n <= slots ? kModeCand : kModeFull;
+                    preds[seg] = digit + 1;                 // prediction for the next step
+                }
+                if (LEVEL == 2) {
+                    s.T = s.prefix;
+                    s.q = s.k_rem;
+                }
+                state[seg] = s;
+                break;
+            }
+            c += n;
+        }
+    }
+}
+
+// The last search of the threshold (7 key bits, 128 counters), done by every block that needs the
+// result instead of by a kernel of its own (k_find<2>, which is launched instead when there are so
+// many blocks that their added barriers cost more than the launch): from the top of the histogram, the bin that holds the
+// k_rem-th largest key of the current 24-bit bucket.  All threads of the block call it; `bcast`
+// is three words of LDS.  Returns the threshold key T and sets q, the number of keys equal to T that
+// are members.  The histogram is 512 bytes, so re-reading it in every block is cheap (the 16 KB
+// histograms of the earlier levels are not: those searches stay kernels).
+__device__ __forceinline__ uint32_t find_threshold(const uint32_t* __restrict__ h, uint32_t prefix24, uint32_t k_rem,
+                                                   uint32_t* bcast, uint32_t& q)
+{
+    static_assert(kBins2 == 2 * kLanes, "two waves hold the last level's counters");
+    const int t = threadIdx.x, lane = t % kLanes;
+    const uint32_t mine = t < kBins2 ? h[t] : 0u;
+    uint32_t suf = mine;                                    // inclusive suffix sum inside the wave
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t v = __shfl_down(suf, off, kLanes);
+        if (lane + off < kLanes) suf += v;
+    }
+    if (t == kLanes) bcast[0] = suf;                        // total of bins 64..127
+    if (t == kBins2) {                                      // if the counts were corrupted: nothing is a member
+        bcast[1] = 0xffffffffu;
+        bcast[2] = 0u;
+    }
+    __syncthreads();
+    if (t < kLanes) suf += bcast[0];
+    const uint32_t excl = suf - mine;                       // keys in higher bins
+    if (t < kBins2 && excl < k_rem && k_rem <= suf) {       // exactly one bin qualifies
+        bcast[1] = (prefix24 << kBits2) | static_cast<uint32_t>(t);
+        bcast[2] = k_rem - excl;
+    }
+    __syncthreads();
+    q = bcast[2];
+    return bcast[1];
+}
+
+// Per wave tile of the leader's vector: number of keys above the threshold (low half of the
+// packed counter) and equal to it (high half), and the two bitmasks that go with them.
+// Full-pass mode recomputes every key; candidate mode adds the listed keys to what k_collect
+// started.  Also leaves the supertile's totals for the prefix scan.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+            const StDesc* __restrict__ sts, SegState* __restrict__ state, const uint32_t* __restrict__ hist2,
+            uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt,
+            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
+{
+    const int st = blockIdx.x;
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const StDesc d = sts[st];
+    const SegState ss = state[d.seg];
+    const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper;
+    __shared__ uint32_t cnt[kTilesPerSuper];
+    __shared__ uint32_t bcast[3];
+    uint32_t T = ss.T, q = ss.q;                            // an empty index set keeps T above every key
+    if (!ss.done && hist2) {                                // block-uniform; without hist2 a kernel has searched already
+        T = find_threshold(hist2 + static_cast<size_t>(d.seg) * kBins2, ss.prefix, ss.k_rem, bcast, q);
+        if (st == segs[d.seg].st_first && threadIdx.x == 0) {   // for the tie quota of the slot pass
+            state[d.seg].T = T;
+            state[d.seg].q = q;
+        }
+    }
+
+    if (!ss.done && ss.mode == kModeCand) {
+        if (threadIdx.x < kTilesPerSuper) cnt[threadIdx.x] = wt_cnt[tile0 + threadIdx.x];
+        __syncthreads();
+        const uint32_t n = st_cand_cnt[st];
+        const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+        uint32_t* sel32 = reinterpret_cast<uint32_t*>(sel_mask);
+        uint32_t* eq32 = reinterpret_cast<uint32_t*>(eq_mask);
+        for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
+            const uint2 ce = slice[e];
+            if (ce.x >= T) {
+                const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
+                const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
+                const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
+                if (ce.x > T) {
+                    atomicAdd(&cnt[wt], 1u);
+                    atomicOr(&sel32[word], 1u << (l & 31));
+                } else {
+                    atomicAdd(&cnt[wt], 0x10000u);
+                    atomicOr(&eq32[word], 1u << (l & 31));
+                }
+            }
+        }
+        __syncthreads();
+    } else {
+        const int64_t begin = d.begin, end = d.end;
+        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+            const int wt = it * kWaves + wave;
+            const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
+            uint32_t key[4] = {0, 0, 0, 0};
+            bool ok[4] = {false, false, false, false};
+            if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+            uint64_t gt[4], eq[4];
+            uint32_t n_gt = 0, n_eq = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                gt[c] = __ballot(ok[c] && key[c] > T);
+                eq[c] = __ballot(ok[c] && key[c] == T);
+                n_gt += __popcll(gt[c]);
+                n_eq += __popcll(eq[c]);
+            }
+            if (lane == 0) {
+                cnt[wt] = n_gt | (n_eq << 16);             // at most 256 each
+                store_tile_masks(sel_mask, tile0 + wt, gt);
+                store_tile_masks(eq_mask, tile0 + wt, eq);
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < kLanes) {
+        const uint32_t v = threadIdx.x < kTilesPerSuper ? cnt[threadIdx.x] : 0u;
+        if (threadIdx.x < kTilesPerSuper) wt_cnt[tile0 + threadIdx.x] = v;
+        const uint32_t s2 = wave_sum(v);                   // at most 8192 each: no carry between halves
+        if (threadIdx.x == 0) st_sum[st] = make_uint2(s2 & 0xffffu, s2 >> 16);
+    }
+}
+
+// Prefix scan, level 1: one block per chunk of up to 1024 supertiles of one segment; exclusive
+// prefix of (above, equal) inside the chunk and the chunk's totals.
+__global__ void __launch_bounds__(kChunk)
+k_scan(const ChunkDesc* __restrict__ chunks, const uint2* __restrict__ st_sum, uint2* __restrict__ st_prefix,
+       uint2* __restrict__ chunk_tot)
+{
+    const ChunkDesc cd = chunks[blockIdx.x];
+    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    __shared__ uint2 wtot[kChunk / kLanes];
+    const int i = threadIdx.x;
+    const uint2 v = i < cd.st_count ? st_sum[cd.st_begin + i] : make_uint2(0, 0);
+    uint2 inc = v;
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t ax = __shfl_up(inc.x, off, kLanes), ay = __shfl_up(inc.y, off, kLanes);
+        if (lane >= off) {
+            inc.x += ax;
+            inc.y += ay;
+        }
+    }
+    if (lane == kLanes - 1) wtot[wave] = inc;
+    __syncthreads();
+    uint2 before = make_uint2(0, 0), total = make_uint2(0, 0);
+    for (int w = 0; w < kChunk / kLanes; ++w) {
+        const uint2 t = wtot[w];
+        if (w < wave) {
+            before.x += t.x;
+            before.y += t.y;
+        }
+        total.x += t.x;
+        total.y += t.y;
+    }
+    if (i < cd.st_count) st_prefix[cd.st_begin + i] = make_uint2(before.x + inc.x - v.x, before.y + inc.y - v.y);
+    if (i == 0) chunk_tot[blockIdx.x] = total;
+}
+
+// Prefix scan, level 2, one wave per supertile: first output slot of each of its 32 wave tiles
+// = members in earlier chunks + earlier supertiles of the chunk + earlier tiles of the
+// supertile.  Keys equal to the threshold become members here, in position order, until the
+// segment's quota q is used up (Eq. 2 with ties resolved towards the lowest positions).
+__global__ void __launch_bounds__(kBlock)
+k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state,
+        const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_prefix, const uint2* __restrict__ chunk_tot,
+        uint64_t* __restrict__ sel_mask, const uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ tile_slot)
+{
+    const int st = blockIdx.x * kWaves + threadIdx.x / kLanes;
+    const int lane = threadIdx.x % kLanes;
+    if (st >= n_st) return;                                 // whole wave
+    const StDesc d = sts[st];
+    const SegDesc sd = segs[d.seg];
+    const uint32_t q = state[d.seg].q;
+
+    // totals of the segment's earlier chunks
+    const int my_chunk = (st - sd.st_first) / kChunk;
+    uint32_t cx = 0, cy = 0;
+    for (int c = lane; c < my_chunk; c += kLanes) {
+        const uint2 t = chunk_tot[sd.chunk_first + c];
+        cx += t.x;
+        cy += t.y;
+    }
+    cx = wave_sum(cx);
+    cy = wave_sum(cy);
+    const uint2 sp = st_prefix[st];
+
+    const size_t tile = static_cast<size_t>(st) * kTilesPerSuper + lane;   // lanes 0..31 own one tile each
+    const uint32_t packed = lane < kTilesPerSuper ? wt_cnt[tile] : 0u;
+    uint32_t inc = packed;
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t a = __shfl_up(inc, off, kLanes);
+        if (lane >= off) inc += a;
+    }
+    const uint32_t excl = inc - packed;                     // halves stay below 8192: no carry
+    const uint32_t gt_before = cx + sp.x + (excl & 0xffffu);
+    const uint32_t eq_before = cy + sp.y + (excl >> 16);
+    if (lane >= kTilesPerSuper) return;
+    tile_slot[tile] = static_cast<uint32_t>(sd.out_base) + gt_before + (eq_before < q ? eq_before : q);
+
+    const uint32_t own_eq = packed >> 16;
+    uint32_t take = q > eq_before ? q - eq_before : 0u;     // ties of this tile that are members
+    if (take > own_eq) take = own_eq;
+    if (take == 0) return;
+    uint64_t s4[4], e4[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        s4[c] = sel_mask[tile * 4 + c];
+        e4[c] = eq_mask[tile * 4 + c];
+    }
+    if (take == own_eq) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) s4[c] |= e4[c];
+    } else {                                                // the one tile where the quota runs out
+        for (int l = 0; l < kLanes && take > 0; ++l) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (take > 0 && ((e4[c] >> l) & 1ull)) {
+                    s4[c] |= 1ull << l;
+                    --take;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sel_mask[tile * 4 + c] = s4[c];
+}
+
+}  // namespace
