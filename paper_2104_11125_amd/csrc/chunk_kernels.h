@@ -89,7 +89,8 @@ k_chunk_select(const float* __restrict__ mem, const G* __restrict__ grad, float 
             if (in[c] && key[c] == k_max) inv_here = 0xffffffffu - (p0 + c);
         const uint32_t inv_max = wave_max_u32(inv_here);
         if (lane == 0)
-            atomicMax(&best[static_cast<uint32_t>(sd.out_base) + j], (static_cast<unsigned long long>(k_max) << 32) | inv_max);
+            atomicMax(&best[static_cast<uint32_t>(sd.out_base) + j],
+                      (static_cast<unsigned long long>(k_max) << 32) | inv_max);
     }
 }
 

@@ -144,7 +144,10 @@ __device__ __forceinline__ void leader_keys(const float* mem, const G* grad, flo
 
 // first and last top digit of the window collected around a predicted bucket (p = bucket + 1)
 __device__ __forceinline__ uint32_t window_lo(uint32_t p) { return p >= 3 ? p - 3 : 0u; }
-__device__ __forceinline__ uint32_t window_hi(uint32_t p) { return p + 1 < static_cast<uint32_t>(kBins0) ? p + 1 : kBins0 - 1u; }
+__device__ __forceinline__ uint32_t window_hi(uint32_t p)
+{
+    return p + 1 < static_cast<uint32_t>(kBins0) ? p + 1 : kBins0 - 1u;
+}
 
 // Did the predicted single pass see the k-th largest key inside its window?  If so: the key's
 // top digit and how many members remain to be found inside that digit's bucket.  Exact: uses

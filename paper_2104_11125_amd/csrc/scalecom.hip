@@ -354,16 +354,16 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, hist0, preds, part, overflow);
     k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow);
     mark(1);
-    const CollectOut cout{state, wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt};
-    k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt, cout);
+    const CollectOut collect_out{state, wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt};
+    k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt, collect_out);
     k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow);
-    k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt, cout);
+    k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt, collect_out);
     // the last search: inside k_tilecount's blocks, or a kernel of its own when those are very many
     const bool fold_last = n_st <= kFoldLastSearchMaxSt;
     if (!fold_last) k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow);
     mark(2);
-    k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, fold_last ? hist2 : nullptr, wt_cnt, cand, st_cand_cnt, sel_mask, eq_mask,
-                                           st_sum);
+    k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, fold_last ? hist2 : nullptr, wt_cnt, cand,
+                                           st_cand_cnt, sel_mask, eq_mask, st_sum);
     k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
     k_slots<<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot, sel_mask,
                                                             eq_mask, tile_slot);
@@ -406,7 +406,8 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
     hipStream_t s = ctx->stream;
-    unsigned long long* best = reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity) * ctx->k_max;
+    unsigned long long* best =
+        reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity) * ctx->k_max;
     unsigned long long* best_next =
         reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity ^ 1) * ctx->k_max;
     uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
@@ -561,7 +562,8 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         // the top-k of the summed error-feedback gradients
         const int64_t blocks = (end - begin + kBlock - 1) / kBlock;
         const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
-        k_sum_x<G><<<dim3(gx, static_cast<unsigned>((blocks + gx - 1) / gx)), kBlock, 0, s>>>(lp, n_learners, lr, begin, end, y);
+        const dim3 grid(gx, static_cast<unsigned>((blocks + gx - 1) / gx));
+        k_sum_x<G><<<grid, kBlock, 0, s>>>(lp, n_learners, lr, begin, end, y);
         k_init<<<1, kBlock, 0, s>>>(preds, static_cast<size_t>(n_tensors));
         launch_select<NoGrad>(ctx, y, static_cast<const NoGrad*>(nullptr), 0.0f, n_tensors, preds, no_mark);
         k_mask_overlap<<<(ctx->n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(sts, ctx->n_st, mask_a, sel_mask, d_out);
@@ -710,7 +712,8 @@ scalecom_status scalecom_hamming_distance(scalecom_ctx* ctx, float* const* mem, 
     st = check_learners(ctx, mem, grad, n_learners, lp);
     if (st != SCALECOM_OK) return st;
     if (!d_out) return fail(ctx, SCALECOM_EINVAL, "null output");
-    if (!scratch || reinterpret_cast<uintptr_t>(scratch) % 256) return fail(ctx, SCALECOM_EINVAL, "scratch must be 256-byte aligned");
+    if (!scratch || reinterpret_cast<uintptr_t>(scratch) % 256)
+        return fail(ctx, SCALECOM_EINVAL, "scratch must be 256-byte aligned");
     if (scratch_bytes < diag_layout(ctx->numel_max, ctx->n_tensors_max).total)
         return fail(ctx, SCALECOM_ENOMEM, "scratch smaller than scalecom_hamming_scratch_bytes");
     DeviceGuard guard;

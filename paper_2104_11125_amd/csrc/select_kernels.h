@@ -25,10 +25,10 @@ struct CollectStage {       // LDS staging of one supertile's masks and tile cou
 
 // The per-tile work of the "collect" pass, given the tile's keys: keys whose top digit lies above
 // `hi` are members for sure (their count and ballots are staged for the tile); keys with a top
-// digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice `cand_dst`
-// (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if `wc` is given, counted per
-// digit there, and, if `lh1` is given (then lo == hi), per second digit there.  Called by all lanes
-// of a wave; n_above is the same in every lane.
+// digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice
+// `cand_dst` (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if
+// `wc` is given, counted per digit there, and, if `lh1` is given (then lo == hi), per second digit
+// there.  Called by all lanes of a wave; n_above is the same in every lane.
 template <bool ALL_OK>
 __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
                                              uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* wc,
@@ -74,7 +74,8 @@ __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool o
 }
 
 // After the block's barrier: the staged masks and counts of the supertile, and its candidates if
-// they were staged too, go out with full-width stores (lane-0 stores of 32 bytes per tile cost the collecting passes 8 % of their time).
+// they were staged too, go out with full-width stores (lane-0 stores of 32 bytes per tile cost the
+// collecting passes 8 % of their time).
 __device__ __forceinline__ void collect_flush(const CollectStage& stg, const uint2* cand_stage, size_t tile0,
                                               uint32_t n_cand, uint32_t* __restrict__ wt_cnt,
                                               uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
@@ -96,14 +97,6 @@ __device__ __forceinline__ void collect_flush(const CollectStage& stg, const uin
     for (uint32_t e = threadIdx.x; e < n; e += kBlock) slice[e] = cand_stage[e];
 }
 
-// First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
-// that carry a prediction of their threshold bucket (the bucket found in the previous step).
-// ONE pass, no histogram: keys whose top digit lies above a 5-digit window around the
-// prediction are members for sure (counted per tile, marked in the mask), keys inside the
-// window go to the candidate list and are counted per digit.  If the counts show afterwards
-// that the k-th largest key fell inside the window, the threshold bucket is known exactly and
-// no other full pass over the leader is needed.  The prediction only decides how much work is
-// done, never what is selected.  One block per supertile.
 // The 8 tiles a wave owns in a supertile of the predicted pass.  INSIDE: the whole supertile
 // lies in the segment, so loads are unguarded and every position counts; otherwise both are
 // checked per element.  Positions stay below 2^31 + 8192 and are kept in 32 bits.
@@ -138,7 +131,10 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
         bool ok[4] = {true, true, true, true};
         if (!INSIDE) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) ok[c] = static_cast<int64_t>(p_cur) + c >= begin && static_cast<int64_t>(p_cur) + c < end;
+            for (int c = 0; c < 4; ++c) {
+                const int64_t pos = static_cast<int64_t>(p_cur) + c;
+                ok[c] = pos >= begin && pos < end;
+            }
         }
         uint32_t n_above;
         collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, n_above, stg, cand_stage);
@@ -150,6 +146,14 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
     return above_acc;
 }
 
+// First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
+// that carry a prediction of their threshold bucket (the bucket found in the previous step).
+// ONE pass, no histogram: keys whose top digit lies above a 5-digit window around the
+// prediction are members for sure (counted per tile, marked in the mask), keys inside the
+// window go to the candidate list and are counted per digit.  If the counts show afterwards
+// that the k-th largest key fell inside the window, the threshold bucket is known exactly and
+// no other full pass over the leader is needed.  The prediction only decides how much work is
+// done, never what is selected.  One block per supertile.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
@@ -302,10 +306,11 @@ struct CollectOut {
 // (bucket keys clustered in one place) sends the whole segment back to full-pass mode for the
 // kernels that follow; this kernel's counts are complete either way.
 template <typename G, int LEVEL>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8)))   // 2048 blocks = 8 waves on every SIMD
+// (register use is capped so that 8 waves fit a SIMD: the grid of 2048 blocks is one wave per slot)
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8)))
 k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const StDesc* __restrict__ sts, int n_st,
-       const SegState* __restrict__ state, uint32_t* __restrict__ hist, const uint2* __restrict__ cand,
-       const uint32_t* __restrict__ st_cand_cnt, CollectOut out)
+       const SegState* state, uint32_t* __restrict__ hist, const uint2* cand, const uint32_t* st_cand_cnt,
+       CollectOut out)   // state, cand and st_cand_cnt are also reachable, for writing, through `out`
 {
     static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_hist0");
     constexpr int NB = LEVEL == 1 ? kBins1 : kBins2;
@@ -365,12 +370,12 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
                     bool ok[4] = {false, false, false, false};
                     if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
                     uint32_t n_above;
-                    collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, nullptr, lh, n_above,
-                                        stg, slice);
+                    collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, nullptr, lh,
+                                        n_above, stg, slice);
                 }
                 __syncthreads();
-                collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask, out.eq_mask,
-                              slice);
+                collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask,
+                              out.eq_mask, slice);
                 if (threadIdx.x == 0) {
                     const uint32_t n = fill;
                     out.st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;

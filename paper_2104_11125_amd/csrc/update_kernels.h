@@ -134,8 +134,8 @@ k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDes
     __shared__ float stage_val[kWaves * kWaveTile];
     __shared__ int32_t stage_pos[kWaves * kWaveTile];
     if (blk0 >= d.begin && blk0 + kWaves * kWaveTile <= d.end)
-        update_block<G, true>(mem, grad, lr, beta, one_minus_beta, d, wave, lane, rel0, S, before, total, slot0, my_vals, my_idx,
-                              stage_val, stage_pos);
+        update_block<G, true>(mem, grad, lr, beta, one_minus_beta, d, wave, lane, rel0, S, before, total, slot0, my_vals,
+                              my_idx, stage_val, stage_pos);
     else
         update_block<G, false>(mem, grad, lr, beta, one_minus_beta, d, wave, lane, rel0, S, before, total, slot0, my_vals,
                                my_idx, stage_val, stage_pos);
