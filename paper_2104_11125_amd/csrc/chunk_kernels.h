@@ -9,24 +9,6 @@
 
 namespace {
 
-// Largest value of v over the 64 lanes, in a scalar register.  Data-parallel-primitive moves inside
-// the vector ALU (shift right by 1, 2, 4, 8 lanes inside each row of 16, then row 0's and rows
-// 0-1's last lane broadcast to the following rows) instead of cross-lane reads through the LDS
-// crossbar; lanes without a source take the identity 0.
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
-{
-    constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
-    constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
-    auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
-    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr1, 0xf, 0xf, false)));
-    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr2, 0xf, 0xf, false)));
-    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr4, 0xf, 0xf, false)));
-    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowShr8, 0xf, 0xf, false)));
-    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowBcast15, 0xa, 0xf, false)));
-    v = mx(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kRowBcast31, 0xc, 0xf, false)));
-    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), kLanes - 1));
-}
-
 // Leader pass of the chunk-wise selector, one wave per wave tile: every element becomes the word
 // (magnitude key << 32 | ~position), so that the largest word of a chunk is its largest
 // magnitude at the lowest position; for each chunk of the tile's segment that overlaps the tile

@@ -58,11 +58,39 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
                                      __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ballot), 0u));
 }
 
+// Reductions over the 64 lanes of a wave, result in a scalar register: data-parallel-primitive
+// moves inside the vector ALU (shift right by 1, 2, 4, 8 lanes inside each row of 16, then the
+// last lane of row 0 and of rows 0-1 broadcast to the rows that follow) instead of cross-lane reads
+// through the LDS crossbar; lanes without a source take the identity 0.  All 64 lanes must be
+// active at the call.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t x)   // x of the lane CTRL names, 0 where there is none
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, ROW_MASK, 0xf, false));
+}
+
+template <typename Op>
+__device__ __forceinline__ uint32_t wave_reduce_u32(uint32_t v, Op op)
+{
+    constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+    constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+    v = op(v, dpp_move<kRowShr1, 0xf>(v));
+    v = op(v, dpp_move<kRowShr2, 0xf>(v));
+    v = op(v, dpp_move<kRowShr4, 0xf>(v));
+    v = op(v, dpp_move<kRowShr8, 0xf>(v));                  // lane 15 of every row holds the row's result
+    v = op(v, dpp_move<kRowBcast15, 0xa>(v));               // into rows 1 and 3
+    v = op(v, dpp_move<kRowBcast31, 0xc>(v));               // into rows 2 and 3
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), kLanes - 1));
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kLanes);
-    return v;
+    return wave_reduce_u32(v, [](uint32_t a, uint32_t b) { return a + b; });
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    return wave_reduce_u32(v, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
 }
 
 // 4 consecutive values starting at position p0 (a multiple of 4) of one learner's array;

@@ -17,6 +17,8 @@ constexpr int kBlock = 256;                      // threads per block in the str
 constexpr int kWaves = kBlock / kLanes;          // 4
 constexpr int kUpdateBlocksPerSuper = kTilesPerSuper / kWaves;   // update: one wave tile per wave
 constexpr int kChunk = 1024;                     // supertiles per chunk of the prefix scan
+constexpr int kOwnScanMaxSt = 10240;             // up to this many supertiles k_slots scans the supertile totals itself
+constexpr int kSlotsOwnScanBlock = 1024;         // threads of its blocks then (16 waves = 16 supertiles)
 
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
 constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;

@@ -364,9 +364,15 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     mark(2);
     k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, fold_last ? hist2 : nullptr, wt_cnt, cand,
                                            st_cand_cnt, sel_mask, eq_mask, st_sum);
-    k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
-    k_slots<<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot, sel_mask,
-                                                            eq_mask, tile_slot);
+    if (n_st <= kOwnScanMaxSt) {   // few supertiles: the slot kernel adds up the totals before each block itself
+        constexpr int per_block = kSlotsOwnScanBlock / kLanes;
+        k_slots<true><<<(n_st + per_block - 1) / per_block, kSlotsOwnScanBlock, 0, s>>>(
+            segs, sts, n_st, state, wt_cnt, st_sum, st_prefix, chunk_tot, sel_mask, eq_mask, tile_slot);
+    } else {
+        k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
+        k_slots<false><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_sum, st_prefix,
+                                                                       chunk_tot, sel_mask, eq_mask, tile_slot);
+    }
     if (hipPeekAtLastError() == hipSuccess) {   // the copy for the next selection was cleared by this one
         ctx->parity ^= 1;
         ctx->scratch_clean = true;

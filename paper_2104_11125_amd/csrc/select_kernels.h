@@ -675,32 +675,78 @@ k_scan(const ChunkDesc* __restrict__ chunks, const uint2* __restrict__ st_sum, u
 }
 
 // Prefix scan, level 2, one wave per supertile: first output slot of each of its 32 wave tiles
-// = members in earlier chunks + earlier supertiles of the chunk + earlier tiles of the
-// supertile.  Keys equal to the threshold become members here, in position order, until the
-// segment's quota q is used up (Eq. 2 with ties resolved towards the lowest positions).
-__global__ void __launch_bounds__(kBlock)
+// = members in the segment's earlier supertiles + earlier tiles of the supertile.  Keys equal to
+// the threshold become members here, in position order, until the segment's quota q is used up
+// (Eq. 2 with ties resolved towards the lowest positions).
+// OWN_SCAN (up to kOwnScanMaxSt supertiles): blocks of 16 waves add up the supertile totals before
+// their first supertile themselves, which saves the k_scan launch; each block reads at most n_st
+// totals, n_st^2 / 32 in all.  Otherwise the prefixes come from k_scan (per chunk of 1024
+// supertiles) and the chunk totals.
+template <bool OWN_SCAN>
+__global__ void __launch_bounds__(OWN_SCAN ? kSlotsOwnScanBlock : kBlock)
 k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state,
-        const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_prefix, const uint2* __restrict__ chunk_tot,
-        uint64_t* __restrict__ sel_mask, const uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ tile_slot)
+        const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_sum, const uint2* __restrict__ st_prefix,
+        const uint2* __restrict__ chunk_tot, uint64_t* __restrict__ sel_mask, const uint64_t* __restrict__ eq_mask,
+        uint32_t* __restrict__ tile_slot)
 {
-    const int st = blockIdx.x * kWaves + threadIdx.x / kLanes;
+    constexpr int kThreads = OWN_SCAN ? kSlotsOwnScanBlock : kBlock;
+    constexpr int kWavesHere = kThreads / kLanes;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
     const int lane = threadIdx.x % kLanes;
-    if (st >= n_st) return;                                 // whole wave
+    const int st0 = blockIdx.x * kWavesHere;                // the block's first supertile (exists: the grid is exact)
+    const int st = st0 + wave;
+    uint32_t px = 0, py = 0;                                // members / ties in the segment's earlier supertiles
+    if (OWN_SCAN) {
+        // all threads: totals of the supertiles between the start of the first supertile's segment and st0
+        __shared__ uint32_t part_x[kWavesHere], part_y[kWavesHere];
+        const int seg0 = sts[st0].seg;
+        const int seg0_first = segs[seg0].st_first;
+        uint32_t bx = 0, by = 0;
+        for (int j = seg0_first + static_cast<int>(threadIdx.x); j < st0; j += kThreads) {
+            const uint2 t = st_sum[j];
+            bx += t.x;
+            by += t.y;
+        }
+        bx = wave_sum(bx);
+        by = wave_sum(by);
+        if (lane == 0) {
+            part_x[wave] = bx;
+            part_y[wave] = by;
+        }
+        __syncthreads();
+        if (st >= n_st) return;                             // whole wave
+        const StDesc d0 = sts[st];
+        const int first = segs[d0.seg].st_first;
+        if (d0.seg == seg0) {                               // wave-uniform
+            for (int w = 0; w < kWavesHere; ++w) {
+                px += part_x[w];
+                py += part_y[w];
+            }
+        }
+        // the block's own supertiles before mine that belong to my segment (at most 15)
+        const int j = (first > st0 ? first : st0) + lane;
+        const uint2 t = j < st ? st_sum[j] : make_uint2(0, 0);
+        px += wave_sum(t.x);
+        py += wave_sum(t.y);
+    } else if (st >= n_st) {
+        return;                                             // whole wave
+    }
     const StDesc d = sts[st];
     const SegDesc sd = segs[d.seg];
     const uint32_t q = state[d.seg].q;
-
-    // totals of the segment's earlier chunks
-    const int my_chunk = (st - sd.st_first) / kChunk;
-    uint32_t cx = 0, cy = 0;
-    for (int c = lane; c < my_chunk; c += kLanes) {
-        const uint2 t = chunk_tot[sd.chunk_first + c];
-        cx += t.x;
-        cy += t.y;
+    if (!OWN_SCAN) {
+        // totals of the segment's earlier chunks, then the prefix inside my chunk
+        const int my_chunk = (st - sd.st_first) / kChunk;
+        uint32_t cx = 0, cy = 0;
+        for (int c = lane; c < my_chunk; c += kLanes) {
+            const uint2 t = chunk_tot[sd.chunk_first + c];
+            cx += t.x;
+            cy += t.y;
+        }
+        const uint2 sp = st_prefix[st];
+        px = wave_sum(cx) + sp.x;
+        py = wave_sum(cy) + sp.y;
     }
-    cx = wave_sum(cx);
-    cy = wave_sum(cy);
-    const uint2 sp = st_prefix[st];
 
     const size_t tile = static_cast<size_t>(st) * kTilesPerSuper + lane;   // lanes 0..31 own one tile each
     const uint32_t packed = lane < kTilesPerSuper ? wt_cnt[tile] : 0u;
@@ -711,8 +757,8 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
         if (lane >= off) inc += a;
     }
     const uint32_t excl = inc - packed;                     // halves stay below 8192: no carry
-    const uint32_t gt_before = cx + sp.x + (excl & 0xffffu);
-    const uint32_t eq_before = cy + sp.y + (excl >> 16);
+    const uint32_t gt_before = px + (excl & 0xffffu);
+    const uint32_t eq_before = py + (excl >> 16);
     if (lane >= kTilesPerSuper) return;
     tile_slot[tile] = static_cast<uint32_t>(sd.out_base) + gt_before + (eq_before < q ? eq_before : q);
 
