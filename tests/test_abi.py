@@ -24,6 +24,31 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary's header compiles as C99 on its own (no C++ or torch types in the signatures)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    assert gcc, "gcc is part of the image"
+    src = tmp_path / "abi.c"
+    src.write_text('#include "scalecom.h"\nint main(void) { return (int)scalecom_workspace_bytes(0, 1, 1, 0); }\n')
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                          "-c", str(src), "-o", str(tmp_path / "abi.o")], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+
+
+def test_hamming_scratch_bytes_is_host_arithmetic():
+    L = binding.lib()
+    small = L.scalecom_hamming_scratch_bytes(1_000_000, 1)
+    large = L.scalecom_hamming_scratch_bytes(100_000_000, 200)
+    assert 4 * 1_000_000 < small < 5 * 1_000_000          # the summed vector + one bit per position + predictions
+    assert small < large < 5 * 100_000_000
+    assert L.scalecom_hamming_scratch_bytes(-1, 1) == 0 and L.scalecom_hamming_scratch_bytes(10, 0) == 0
+    assert L.scalecom_hamming_distance(None, None, None, 1, 1, None, None, 0.1, 0, None, 0, None) == binding.SCALECOM_EINVAL
+    assert L.scalecom_cosine_distance(None, None, None, 0, None) == binding.SCALECOM_EINVAL
+    assert L.scalecom_step_layers_chunked(None, None, None, 1, 1, None, None, 0.5, 0.1, 0, None, None) == binding.SCALECOM_EINVAL
+
+
 def test_workspace_bytes_is_host_arithmetic():
     small = binding.scalecom_workspace_bytes(1_048_576, 1, 4, 10_485)
     large = binding.scalecom_workspace_bytes(1_000_000_000, 1, 8, 2_500_000)
