@@ -233,6 +233,11 @@ def main():
             "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
             "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "copy_kernel_GBps": copy_gbps,
+            "frac_of_copy_kernel": step_bytes / (ms_per_step * 1e-3) / 1e9 / copy_gbps,
+            # the extra steps after the timed region, each bracketed by HIP events at every phase boundary
+            # (the events themselves add a few microseconds per boundary)
+            "event_timed_extra_steps_ms": [sum(p) for p in phases] if n_ph else None,
+            "event_timed_extra_steps_median_ms": sorted(sum(p) for p in phases)[n_ph // 2] if n_ph else None,
             "phase_ms_untimed_extra_steps": dict(zip(["leader_first_look", "refine", "counts_scan_slots", "update", "reduce"], phase_avg)) if phase_avg else None,
         },
     }
