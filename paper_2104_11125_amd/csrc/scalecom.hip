@@ -156,6 +156,7 @@ struct scalecom_ctx {
     bool scratch_clean = false;      // false: both copies must be cleared before the next step
     int best_parity = 0;             // same scheme for the chunk-wise selector's per-chunk maxima
     bool best_clean = false;
+    int64_t best_used[2] = {0, 0};   // entries of each copy that its last use may have left non-zero
     char* pinned = nullptr;          // staging for the table upload
     size_t pinned_bytes = 0;
     hipEvent_t upload_done = nullptr;
@@ -434,6 +435,7 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         const size_t words = 4 * static_cast<size_t>(ctx->k_max);   // 2 copies x 2 words per entry
         const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
         k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.best), words);
+        ctx->best_used[0] = ctx->best_used[1] = 0;
     }
     ctx->best_clean = false;
     const int64_t n_tiles = static_cast<int64_t>(ctx->n_st) * kTilesPerSuper;
@@ -441,13 +443,17 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
                                                                  segs, sts, ctx->n_st, best, sel_mask);
     mark(1);
     mark(2);
-    k_chunk_marks<<<grid2((std::max(n_tiles, k_total) + kBlock - 1) / kBlock), kBlock, 0, s>>>(
-        segs, n_tensors, sts, best, best_next, k_total, n_tiles, sel_mask, tile_slot, idx_out);
+    // the other copy still holds what its last use wrote (possibly more entries than this call has)
+    const int64_t clear_next = ctx->best_used[ctx->best_parity ^ 1];
+    k_chunk_marks<<<grid2((std::max({n_tiles, k_total, clear_next}) + kBlock - 1) / kBlock), kBlock, 0, s>>>(
+        segs, n_tensors, sts, best, best_next, clear_next, k_total, n_tiles, sel_mask, tile_slot, idx_out);
     mark(3);
     launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
     mark(5);
     if (timed) ++ctx->prof_steps;
     SC_HIP(ctx, hipGetLastError());
+    ctx->best_used[ctx->best_parity] = k_total;
+    ctx->best_used[ctx->best_parity ^ 1] = 0;
     ctx->best_parity ^= 1;
     ctx->best_clean = true;
     return SCALECOM_OK;

@@ -247,6 +247,10 @@ def test_chunked_selector_per_layer(gu):
     # the paper's rate guidance feeds it directly
     _, rates = binding.scalecom_layer_ks([300.0, 150.0, 64.0] * 4, sizes)
     gu.compare_step(ctx, mem, grad, ref, 7, 0.3, 0.7, offsets=offsets, chunks=rates, what="rates of the guidance")
+    # many positions, then few, then more again: the per-chunk maxima of a longer earlier call must not survive
+    for step, ch in ((8, 1), (9, 400), (10, 7), (11, 3)):
+        gu.compare_step(ctx, mem, grad, ref, step, 0.3, 0.7, offsets=offsets, chunks=[ch] * len(sizes),
+                        what=f"all chunks {ch}")
     with pytest.raises(binding.ScaleComError):
         ctx.scalecom_step_layers_chunked(mem, grad, offsets, [0] * len(sizes), 0.3, 0.7, 0)
     ctx.close()
@@ -364,6 +368,66 @@ def test_cosine_distance(gu):
     a = torch.randn(4096, generator=g).to(gu.DEV)
     assert abs(float(ctx.scalecom_cosine_distance(a, a * 2)[0])) < 1e-12
     assert abs(float(ctx.scalecom_cosine_distance(a, -a)[0]) - 2.0) < 1e-12
+    ctx.close()
+
+
+# ------------------------------------------------------------------ randomized layouts and values
+@pytest.mark.parametrize("seed", range(16))
+def test_randomized_layouts_values_and_modes(gu, seed):
+    """Seeded random problems: learner count, tensor layout (gaps, empty tensors, unaligned starts),
+    set sizes from 0 to everything, value distributions with heavy ties, both gradient types, and
+    exact, chunk-wise and diagnostic calls mixed on one context.  Every output is compared."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 10))
+    n_tensors = int(rng.integers(1, 13))
+    sizes = [int(v) for v in rng.choice([0, 1, 3, 255, 256, 257, 1000, 8191, 8192, 8193, 30_000, 70_000], size=n_tensors)]
+    gaps = [int(v) for v in rng.integers(0, 7, size=n_tensors + 1)]
+    offsets, pos = [], gaps[0]
+    for sz, gap in zip(sizes, gaps[1:]):
+        offsets.append(pos)
+        pos += sz
+    offsets.append(pos)                                        # tensors are back to back; a gap only in front
+    numel = pos + gaps[-1]
+    bf16 = bool(seed % 2)
+    kind = ["normal", "rounded", "few_levels", "sparse"][seed % 4]
+    def draw(scale):
+        x = rng.standard_normal(numel).astype(np.float32) * np.float32(scale)
+        if kind == "rounded":
+            x = np.round(x * 8) / 8 * np.float32(scale)        # many exact ties
+        elif kind == "few_levels":
+            x = rng.choice(np.array([-2, -1, -0.0, 0.0, 1, 2], np.float32), size=numel) * np.float32(scale)
+        elif kind == "sparse":
+            x = np.where(rng.random(numel) < 0.9, np.float32(0), x)
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    mem = [draw(1e-3).to(gu.DEV) for _ in range(n)]
+    grad = [draw(1e-2).to(gu.DEV) for _ in range(n)]
+    if bf16:
+        grad = [g.to(torch.bfloat16) for g in grad]
+    ref = [m.cpu().numpy().copy() for m in mem]
+    ctx = binding.scalecom_init(max(numel, 1), n, torch.bfloat16 if bf16 else torch.float32, n_tensors, gu.DEV)
+    what = f"seed {seed}: n={n} sizes={sizes} kind={kind} bf16={bf16}"
+    print("[random]", what, flush=True)
+    for step in range(5):
+        beta = float(rng.choice([1.0, 0.5, 0.1]))
+        lr = float(rng.choice([1.0, 0.3, 0.0]))
+        mode = int(rng.integers(0, 4))
+        if mode == 0:                                          # per-tensor exact sets, sizes from 0 to everything
+            ks = [int(rng.choice([0, 1, sz // 100, sz // 2, sz])) if sz else 0 for sz in sizes]
+            gu.compare_step(ctx, mem, grad, ref, step, beta, lr, offsets=offsets, ks=ks, what=what + f" ks={ks}")
+        elif mode == 1:                                        # per-tensor chunk sizes
+            chunks = [int(rng.choice([1, 2, 7, 100, 112, 400, 100_000])) for _ in sizes]
+            gu.compare_step(ctx, mem, grad, ref, step, beta, lr, offsets=offsets, chunks=chunks,
+                            what=what + f" chunks={chunks}")
+        elif mode == 2 and numel > 0:                          # the whole vector as one tensor
+            k = int(rng.choice([0, 1, numel // 100, numel]))
+            gu.compare_step(ctx, mem, grad, ref, step, beta, lr, k=k, what=what + f" flat k={k}")
+        else:                                                  # diagnostic between steps: nothing changes
+            ks = [sz // 50 for sz in sizes]
+            d = ctx.scalecom_hamming_distance(mem, grad, offsets, ks, lr, step)
+            torch.cuda.synchronize()
+            assert np.array_equal(d.cpu().numpy(), _oracle_d(gu, mem, grad, offsets, ks, lr, step)), what
+            for i in range(n):
+                gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], None, what + " untouched")
     ctx.close()
 
 
