@@ -372,7 +372,7 @@ def test_cosine_distance(gu):
 
 
 # ------------------------------------------------------------------ randomized layouts and values
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(32))
 def test_randomized_layouts_values_and_modes(gu, seed):
     """Seeded random problems: learner count, tensor layout (gaps, empty tensors, unaligned starts),
     set sizes from 0 to everything, value distributions with heavy ties, both gradient types, and
@@ -428,6 +428,46 @@ def test_randomized_layouts_values_and_modes(gu, seed):
             assert np.array_equal(d.cpu().numpy(), _oracle_d(gu, mem, grad, offsets, ks, lr, step)), what
             for i in range(n):
                 gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], None, what + " untouched")
+    ctx.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_randomized_prediction_walk(gu, seed):
+    """One layout kept for many steps while the gradients' scale drifts, jumps and collapses into
+    ties: the predicted single pass hits, misses and overflows, and every step stays exact."""
+    rng = np.random.default_rng(2000 + seed)
+    n = int(rng.integers(2, 6))
+    n_tensors = [1, 1, 3, 8][seed % 4]
+    sizes = [int(v) for v in rng.choice([300, 9_000, 40_000, 120_000], size=n_tensors)]
+    offsets = np.concatenate([[seed % 4], (seed % 4) + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1] + 2
+    ks = [max(1, sz // int(rng.choice([25, 100, 400]))) for sz in sizes]
+    bf16 = seed % 3 == 0
+    ctx = binding.scalecom_init(numel, n, torch.bfloat16 if bf16 else torch.float32, n_tensors, gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    shared = rng.standard_normal(numel).astype(np.float32)
+    scale = 1e-3
+    for step in range(10):
+        move = rng.choice(["drift", "drift", "drift", "jump_up", "jump_down", "ties", "same"])
+        if move == "drift":
+            scale *= float(rng.uniform(0.8, 1.25))
+        elif move == "jump_up":
+            scale *= 64.0
+        elif move == "jump_down":
+            scale /= 64.0
+        grads = []
+        for i in range(n):
+            g = (shared + 0.5 * rng.standard_normal(numel).astype(np.float32)) * np.float32(scale)
+            if move == "ties":
+                g = np.sign(g) * np.float32(scale)             # two magnitudes only: the bucket overflows every list
+            t = torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).to(gu.DEV)
+            grads.append(t.to(torch.bfloat16) if bf16 else t)
+        what = f"seed {seed} step {step} {move} sizes={sizes} ks={ks} bf16={bf16}"
+        if n_tensors == 1 and offsets[0] == 0:
+            gu.compare_step(ctx, mem, grads, ref, step, 0.3, 1.0, k=ks[0], what=what)
+        else:
+            gu.compare_step(ctx, mem, grads, ref, step, 0.3, 1.0, offsets=offsets, ks=ks, what=what)
     ctx.close()
 
 
