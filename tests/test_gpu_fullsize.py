@@ -87,6 +87,30 @@ def test_per_layer_chunked_full(gu):
     ctx.close()
 
 
+def test_large_multi_tensor_layout(gu):
+    """More than 10240 supertiles split over several tensors: the two-level prefix scan (per-chunk
+    prefixes and chunk totals of several segments) instead of the slot kernel's own scan, with
+    tensors that start and end inside wave tiles."""
+    n = 2
+    sizes = [30_000_001, 1, 45_000_000, 19_999_999, 7]
+    offsets = np.concatenate([[5], 5 + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1] + 3
+    ks = [sz // 200 for sz in sizes[:-1]] + [7]
+    w = workloads.scaled(workloads.by_name("resnet50_sized"), numel, n_learners=n, steps=2)
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes), gu.DEV, k_max=sum(ks))
+    mem = _random_memories(w, gu.DEV, 930)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    for step in (0, 1):
+        print(f"[fullsize] multi-tensor {numel} elements step {step}", flush=True)
+        grad = workloads.gradients(w, step, gu.DEV)
+        gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, offsets=offsets, ks=ks, what="large multi-tensor")
+    # and the chunk-wise selector on the same layout
+    grad = workloads.gradients(w, 2, gu.DEV)
+    gu.compare_step(ctx, mem, grad, ref, 2, w.beta, w.lr, offsets=offsets, chunks=[200, 1, 400, 200, 1],
+                    what="large multi-tensor chunked")
+    ctx.close()
+
+
 def _streamed_parity(gu, w, step, seed):
     """One full-size step checked learner by learner with the oracle's primitives."""
     dev = gu.DEV
