@@ -88,11 +88,11 @@ def test_per_layer_chunked_full(gu):
 
 
 def test_large_multi_tensor_layout(gu):
-    """More than 10240 supertiles split over several tensors: the two-level prefix scan (per-chunk
-    prefixes and chunk totals of several segments) instead of the slot kernel's own scan, with
-    tensors that start and end inside wave tiles."""
+    """More than 12288 supertiles split over several tensors: the two-level prefix scan (per-chunk
+    prefixes and chunk totals of several segments) instead of the slot kernel's own scan, and the
+    last threshold search as a kernel of its own, with tensors that start and end inside wave tiles."""
     n = 2
-    sizes = [30_000_001, 1, 45_000_000, 19_999_999, 7]
+    sizes = [30_000_001, 1, 55_000_000, 24_999_999, 7]
     offsets = np.concatenate([[5], 5 + np.cumsum(sizes)]).tolist()
     numel = offsets[-1] + 3
     ks = [sz // 200 for sz in sizes[:-1]] + [7]
