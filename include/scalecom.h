@@ -166,7 +166,8 @@ scalecom_status scalecom_step_layers_chunked(scalecom_ctx* ctx, float* const* me
  * size, and scale = alpha / n_learners when lr was 1.  Enqueued on the context's stream, so it
  * may directly follow the step that produced idx and vals.
  *   theta   [device] float[numel], updated in place at the k positions only
- *   idx     [device] int32[k], distinct positions in [0, numel) (not checked on the device)
+ *   idx     [device] int32[k], distinct positions in [0, numel); an entry outside that range is
+ *           skipped (no memory is touched for it)
  *   vals    [device] float[k]
  *   scale   finite
  * EINVAL for null pointers (when k > 0), k < 0, numel < 0 or non-finite scale.

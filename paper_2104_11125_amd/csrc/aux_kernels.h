@@ -11,12 +11,13 @@ namespace {
 
 // Weight update on the index set (Alg. 1 lines 10 and 12): theta[idx[t]] -= scale * vals[t].
 __global__ void __launch_bounds__(kBlock)
-k_apply_update(float* __restrict__ theta, const int32_t* __restrict__ idx, const float* __restrict__ vals, int64_t k,
-               float neg_scale)
+k_apply_update(float* __restrict__ theta, int64_t numel, const int32_t* __restrict__ idx, const float* __restrict__ vals,
+               int64_t k, float neg_scale)
 {
     const int64_t t = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
     if (t >= k) return;
     const int32_t j = idx[t];
+    if (j < 0 || j >= numel) return;                        // a position outside theta is skipped, never touched
     theta[j] = fmaf(neg_scale, vals[t], theta[j]);
 }
 

@@ -98,10 +98,12 @@ k_chunk_marks(const SegDesc* __restrict__ segs, int n_tensors, const StDesc* __r
         const SegDesc sd = segs[lo];
         const uint32_t pos = 0xffffffffu - static_cast<uint32_t>(best[t]);
         idx_out[t] = static_cast<int32_t>(pos);
-        const uint32_t rel = pos - (static_cast<uint32_t>(sd.begin) & ~static_cast<uint32_t>(kVec - 1));
-        const size_t tile = static_cast<size_t>(sd.st_first) * kTilesPerSuper + rel / kWaveTile;
-        const uint32_t l = (rel % kWaveTile) / kVec, c = rel % kVec;
-        atomicOr(reinterpret_cast<uint32_t*>(sel_mask) + (tile * 4 + c) * 2 + (l >> 5), 1u << (l & 31));
+        if (pos >= static_cast<uint32_t>(sd.begin) && pos < static_cast<uint32_t>(sd.end)) {   // always, unless best[] was corrupted
+            const uint32_t rel = pos - (static_cast<uint32_t>(sd.begin) & ~static_cast<uint32_t>(kVec - 1));
+            const size_t tile = static_cast<size_t>(sd.st_first) * kTilesPerSuper + rel / kWaveTile;
+            const uint32_t l = (rel % kWaveTile) / kVec, c = rel % kVec;
+            atomicOr(reinterpret_cast<uint32_t*>(sel_mask) + (tile * 4 + c) * 2 + (l >> 5), 1u << (l & 31));
+        }
     }
     if (t < n_tiles) {
         // winners of the segment before this tile: one per chunk that ends before it, plus the

@@ -698,7 +698,7 @@ scalecom_status scalecom_apply_update(scalecom_ctx* ctx, float* theta, int64_t n
     const int64_t blocks = (k + kBlock - 1) / kBlock;
     const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
     const unsigned gy = static_cast<unsigned>((blocks + gx - 1) / gx);
-    k_apply_update<<<dim3(gx, gy), kBlock, 0, ctx->stream>>>(theta, idx, vals, k, -scale);
+    k_apply_update<<<dim3(gx, gy), kBlock, 0, ctx->stream>>>(theta, numel, idx, vals, k, -scale);
     SC_HIP(ctx, hipGetLastError());
     return SCALECOM_OK;
 }

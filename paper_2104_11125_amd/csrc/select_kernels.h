@@ -386,7 +386,8 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
             }
         }
         if (from_list) {   // keys of this supertile that were copied to the candidate list
-            const uint32_t cnt = st_cand_cnt[st];
+            const uint32_t listed = st_cand_cnt[st];
+            const uint32_t cnt = listed < kCandSlice ? listed : kCandSlice;   // never read past the slice
             const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
             for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) count(slice[e].x, prefix);
             continue;
@@ -585,14 +586,15 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     if (!ss.done && ss.mode == kModeCand) {
         if (threadIdx.x < kTilesPerSuper) cnt[threadIdx.x] = wt_cnt[tile0 + threadIdx.x];
         __syncthreads();
-        const uint32_t n = st_cand_cnt[st];
+        const uint32_t n_listed = st_cand_cnt[st];
+        const uint32_t n = n_listed < kCandSlice ? n_listed : kCandSlice;   // never read past the slice
         const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
         uint32_t* sel32 = reinterpret_cast<uint32_t*>(sel_mask);
         uint32_t* eq32 = reinterpret_cast<uint32_t*>(eq_mask);
         for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
             const uint2 ce = slice[e];
-            if (ce.x >= T) {
-                const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
+            const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
+            if (ce.x >= T && rel < kSuper) {                // a listed position always lies in its supertile
                 const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
                 const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
                 if (ce.x > T) {

@@ -274,6 +274,12 @@ def test_apply_update_after_a_step(gu):
         torch.cuda.synchronize()
         gu.assert_same("theta", theta.cpu().numpy(), theta_ref, 1e-6, f"step {step}")
     ctx.scalecom_apply_update(theta, idx[:0], red[:0], 1.0)          # k = 0: nothing happens
+    bad = torch.tensor([-1, w.numel, 2 ** 31 - 1, 5], dtype=torch.int32, device=gu.DEV)   # outside theta: skipped
+    before = theta.clone()
+    ctx.scalecom_apply_update(theta, bad, torch.ones(4, device=gu.DEV), 1.0)
+    torch.cuda.synchronize()
+    before[5] -= 1.0
+    assert torch.equal(theta, before)
     with pytest.raises(binding.ScaleComError):
         ctx.scalecom_apply_update(theta, idx, red, float("nan"))
     ctx.close()
