@@ -334,7 +334,18 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
     uint32_t prefix = 0;
     bool skip = false, from_list = false, collect = false;
     for (int st = st_lo; st < st_hi; ++st) {
+        // The supertile's listed keys are requested together with its descriptor (one round trip instead of
+        // three) when the block's previous supertile was counted from its list, or there was none yet.
+        const bool early = cur < 0 || from_list;            // block-uniform
+        const uint2* my_slice = cand + static_cast<size_t>(st) * kCandSlice;
         const StDesc d = sts[st];
+        uint32_t listed = 0;
+        uint2 ce[2] = {make_uint2(0, 0), make_uint2(0, 0)};
+        if (early) {
+            listed = st_cand_cnt[st];
+            ce[0] = my_slice[threadIdx.x];
+            ce[1] = my_slice[kBlock + threadIdx.x];
+        }
         if (d.seg != cur) {
             if (cur >= 0) {   // flush the finished segment's counts
                 __syncthreads();
@@ -386,10 +397,16 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
             }
         }
         if (from_list) {   // keys of this supertile that were copied to the candidate list
-            const uint32_t listed = st_cand_cnt[st];
-            const uint32_t cnt = listed < kCandSlice ? listed : kCandSlice;   // never read past the slice
-            const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-            for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) count(slice[e].x, prefix);
+            static_assert(kCandSlice == 2 * kBlock, "two slice entries per thread");
+            if (!early) {
+                listed = st_cand_cnt[st];
+                ce[0] = my_slice[threadIdx.x];
+                ce[1] = my_slice[kBlock + threadIdx.x];
+            }
+            const uint32_t cnt = listed < kCandSlice ? listed : kCandSlice;   // never use what lies past the count
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                if (j * kBlock + threadIdx.x < cnt) count(ce[j].x, prefix);
             continue;
         }
         const int64_t begin = d.begin, end = d.end;
@@ -429,10 +446,27 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     const uint32_t* h = hist + static_cast<size_t>(seg) * NB;
     __shared__ uint32_t above[kWaves];   // per-wave totals
 
-    SegState s = state[seg];
+    // Everything the block may need is requested before the first value is looked at: each dependent
+    // round trip to memory costs these one-block-per-segment kernels close to a microsecond.
+    static_assert(kPartSlots * kPartWords == 2 * kBlock, "two counter words per thread");
+    SegState s{};
+    uint32_t p = 0, ov = 0, w0 = 0, w1 = 0;
+    if (LEVEL == 0) {                                       // level 0 writes every field of the state itself
+        const uint32_t* my_part = part + static_cast<size_t>(seg) * kPartSlots * kPartWords;
+        s.k_rem = static_cast<uint32_t>(segs[seg].k);
+        p = preds[seg];
+        ov = overflow[seg];
+        w0 = my_part[threadIdx.x];
+        w1 = my_part[kBlock + threadIdx.x];
+    } else {
+        s = state[seg];
+    }
+    const int t = threadIdx.x;
+    uint32_t mine = 0;                                      // the counts of my CH bins
+    if (LEVEL != 0 && t < ACTIVE)                           // (level 0 only needs them when no prediction held)
+        for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
     if (LEVEL == 0) {
         s.prefix = 0;
-        s.k_rem = static_cast<uint32_t>(segs[seg].k);
         s.done = s.k_rem == 0 ? 1u : 0u;
         s.T = 0xffffffffu;     // above every key: nothing is a member
         s.q = 0;
@@ -445,14 +479,11 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
         // a prediction that held: the single pass already produced everything level 0 gives
         __shared__ int resolved;
         __shared__ uint32_t tot_s[kPartWords];
-        const uint32_t p = preds[seg];
         if (p != 0) {                                       // block-uniform: sum the slotted copies of the counters
             if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
             __syncthreads();
-            for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
-                const uint32_t v = part[static_cast<size_t>(seg) * kPartSlots * kPartWords + i];
-                if (v) atomicAdd(&tot_s[i % kPartWords], v);
-            }
+            if (w0) atomicAdd(&tot_s[threadIdx.x % kPartWords], w0);
+            if (w1) atomicAdd(&tot_s[(kBlock + threadIdx.x) % kPartWords], w1);
             __syncthreads();
         }
         if (threadIdx.x == 0) {
@@ -460,7 +491,7 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
             resolved = 0;
             if (p != 0) {
                 for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
-                if (spec_resolve(tot, overflow[seg] != 0, p, s.k_rem, digit, k_rem)) {
+                if (spec_resolve(tot, ov != 0, p, s.k_rem, digit, k_rem)) {
                     resolved = 1;
                     s.prefix = digit;
                     s.k_rem = k_rem;
@@ -477,9 +508,7 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
         return;
     }
 
-    const int t = threadIdx.x;
-    uint32_t mine = 0;
-    if (t < ACTIVE)
+    if (LEVEL == 0 && t < ACTIVE)
         for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
     // inclusive suffix sums over threads: within a wave by shuffles, across the 4 waves through LDS
     const int lane = t % kLanes, wave = t / kLanes;
@@ -527,12 +556,11 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
 // is three words of LDS.  Returns the threshold key T and sets q, the number of keys equal to T that
 // are members.  The histogram is 512 bytes, so re-reading it in every block is cheap (the 16 KB
 // histograms of the earlier levels are not: those searches stay kernels).
-__device__ __forceinline__ uint32_t find_threshold(const uint32_t* __restrict__ h, uint32_t prefix24, uint32_t k_rem,
-                                                   uint32_t* bcast, uint32_t& q)
+__device__ __forceinline__ uint32_t find_threshold(uint32_t mine, uint32_t prefix24, uint32_t k_rem, uint32_t* bcast,
+                                                   uint32_t& q)
 {
     static_assert(kBins2 == 2 * kLanes, "two waves hold the last level's counters");
     const int t = threadIdx.x, lane = t % kLanes;
-    const uint32_t mine = t < kBins2 ? h[t] : 0u;
     uint32_t suf = mine;                                    // inclusive suffix sum inside the wave
 #pragma unroll
     for (int off = 1; off < kLanes; off <<= 1) {
@@ -569,32 +597,42 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
 {
     const int st = blockIdx.x;
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
-    const StDesc d = sts[st];
-    const SegState ss = state[d.seg];
     const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper;
+    // Everything the block index alone addresses is requested before the first dependent load returns: the
+    // supertile's descriptor, its candidate count and whole slice (used up to the count, in candidate mode only)
+    // and the tiles' running counts.
+    static_assert(kCandSlice == 2 * kBlock, "two slice entries per thread");
+    const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+    const StDesc d = sts[st];
+    const uint32_t n_listed = st_cand_cnt[st];
+    const uint2 ce_pre[2] = {slice[threadIdx.x], slice[kBlock + threadIdx.x]};
+    const uint32_t cnt_pre = threadIdx.x < kTilesPerSuper ? wt_cnt[tile0 + threadIdx.x] : 0u;
+    // second round trip: what the segment number addresses
+    const SegState ss = state[d.seg];
+    const uint32_t h2 = (hist2 && threadIdx.x < kBins2) ? hist2[static_cast<size_t>(d.seg) * kBins2 + threadIdx.x] : 0u;
+    const int st_first = segs[d.seg].st_first;
     __shared__ uint32_t cnt[kTilesPerSuper];
     __shared__ uint32_t bcast[3];
     uint32_t T = ss.T, q = ss.q;                            // an empty index set keeps T above every key
     if (!ss.done && hist2) {                                // block-uniform; without hist2 a kernel has searched already
-        T = find_threshold(hist2 + static_cast<size_t>(d.seg) * kBins2, ss.prefix, ss.k_rem, bcast, q);
-        if (st == segs[d.seg].st_first && threadIdx.x == 0) {   // for the tie quota of the slot pass
+        T = find_threshold(h2, ss.prefix, ss.k_rem, bcast, q);
+        if (st == st_first && threadIdx.x == 0) {           // for the tie quota of the slot pass
             state[d.seg].T = T;
             state[d.seg].q = q;
         }
     }
 
     if (!ss.done && ss.mode == kModeCand) {
-        if (threadIdx.x < kTilesPerSuper) cnt[threadIdx.x] = wt_cnt[tile0 + threadIdx.x];
+        if (threadIdx.x < kTilesPerSuper) cnt[threadIdx.x] = cnt_pre;
         __syncthreads();
-        const uint32_t n_listed = st_cand_cnt[st];
-        const uint32_t n = n_listed < kCandSlice ? n_listed : kCandSlice;   // never read past the slice
-        const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+        const uint32_t n = n_listed < kCandSlice ? n_listed : kCandSlice;   // never use what lies past the count
         uint32_t* sel32 = reinterpret_cast<uint32_t*>(sel_mask);
         uint32_t* eq32 = reinterpret_cast<uint32_t*>(eq_mask);
-        for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
-            const uint2 ce = slice[e];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint2 ce = ce_pre[j];
             const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
-            if (ce.x >= T && rel < kSuper) {                // a listed position always lies in its supertile
+            if (j * kBlock + threadIdx.x < n && ce.x >= T && rel < kSuper) {   // a listed position lies in its supertile
                 const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
                 const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
                 if (ce.x > T) {
@@ -698,11 +736,23 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
     const int st0 = blockIdx.x * kWavesHere;                // the block's first supertile (exists: the grid is exact)
     const int st = st0 + wave;
     uint32_t px = 0, py = 0;                                // members / ties in the segment's earlier supertiles
+    // Requests are grouped by what addresses them, so that each group costs one round trip: first what the
+    // supertile numbers address, then what the segment numbers address, then the totals to add up.
+    const bool live = st < n_st;                            // whole wave
+    const int st_c = live ? st : st0;
+    const StDesc d = sts[st_c];
+    const size_t tile = static_cast<size_t>(st_c) * kTilesPerSuper + lane;  // lanes 0..31 own one tile each
+    const uint32_t packed = lane < kTilesPerSuper ? wt_cnt[tile] : 0u;
+    const int seg0 = OWN_SCAN ? sts[st0].seg : 0;
+    const SegDesc sd = segs[d.seg];
+    const uint32_t q = state[d.seg].q;
     if (OWN_SCAN) {
         // all threads: totals of the supertiles between the start of the first supertile's segment and st0
         __shared__ uint32_t part_x[kWavesHere], part_y[kWavesHere];
-        const int seg0 = sts[st0].seg;
         const int seg0_first = segs[seg0].st_first;
+        // the block's own supertiles before mine that belong to my segment (at most 15)
+        const int j_own = (sd.st_first > st0 ? sd.st_first : st0) + lane;
+        const uint2 t_own = (live && j_own < st) ? st_sum[j_own] : make_uint2(0, 0);
         uint32_t bx = 0, by = 0;
         for (int j = seg0_first + static_cast<int>(threadIdx.x); j < st0; j += kThreads) {
             const uint2 t = st_sum[j];
@@ -716,27 +766,17 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
             part_y[wave] = by;
         }
         __syncthreads();
-        if (st >= n_st) return;                             // whole wave
-        const StDesc d0 = sts[st];
-        const int first = segs[d0.seg].st_first;
-        if (d0.seg == seg0) {                               // wave-uniform
+        if (!live) return;                                  // whole wave
+        if (d.seg == seg0) {                                // wave-uniform
             for (int w = 0; w < kWavesHere; ++w) {
                 px += part_x[w];
                 py += part_y[w];
             }
         }
-        // the block's own supertiles before mine that belong to my segment (at most 15)
-        const int j = (first > st0 ? first : st0) + lane;
-        const uint2 t = j < st ? st_sum[j] : make_uint2(0, 0);
-        px += wave_sum(t.x);
-        py += wave_sum(t.y);
-    } else if (st >= n_st) {
-        return;                                             // whole wave
-    }
-    const StDesc d = sts[st];
-    const SegDesc sd = segs[d.seg];
-    const uint32_t q = state[d.seg].q;
-    if (!OWN_SCAN) {
+        px += wave_sum(t_own.x);
+        py += wave_sum(t_own.y);
+    } else {
+        if (!live) return;                                  // whole wave
         // totals of the segment's earlier chunks, then the prefix inside my chunk
         const int my_chunk = (st - sd.st_first) / kChunk;
         uint32_t cx = 0, cy = 0;
@@ -750,8 +790,6 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
         py = wave_sum(cy) + sp.y;
     }
 
-    const size_t tile = static_cast<size_t>(st) * kTilesPerSuper + lane;   // lanes 0..31 own one tile each
-    const uint32_t packed = lane < kTilesPerSuper ? wt_cnt[tile] : 0u;
     uint32_t inc = packed;
 #pragma unroll
     for (int off = 1; off < kLanes; off <<= 1) {
