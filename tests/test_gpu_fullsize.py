@@ -111,27 +111,32 @@ def test_large_multi_tensor_layout(gu):
     ctx.close()
 
 
-def _streamed_parity(gu, w, step, seed):
-    """One full-size step checked learner by learner with the oracle's primitives."""
+def _streamed_parity(gu, w, step, seed, chunk=None):
+    """One full-size step checked learner by learner with the oracle's primitives (chunk: the
+    chunk-wise selector with that many elements per chunk instead of the exact top-k)."""
     dev = gu.DEV
     gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
-    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, 1, dev, k_max=w.k)
+    k_max = w.k if chunk is None else -(-w.numel // chunk)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, 1, dev, k_max=k_max)
     mem = _random_memories(w, dev, seed)
     shared = workloads.shared_component(w, step, dev)
     grad = [workloads.learner_gradient(w, step, i, dev, shared=shared) for i in range(w.n_learners)]
     del shared
     before = [m.clone() for m in mem]                    # the GPU step overwrites mem in place
     t0 = time.time()
-    idx, red = ctx.scalecom_step(mem, grad, w.k, w.beta, w.lr, step)
+    if chunk is None:
+        idx, red = ctx.scalecom_step(mem, grad, w.k, w.beta, w.lr, step)
+    else:
+        idx, red = ctx.scalecom_step_chunked(mem, grad, chunk, w.beta, w.lr, step)
     torch.cuda.synchronize()
     idx_h, red_h = idx.cpu().numpy(), red.cpu().numpy()
     print(f"[fullsize] {w.name}: GPU step done in {time.time() - t0:.2f}s, checking on the host", flush=True)
 
     leader = step % w.n_learners
     acc = oracle.accumulate(before[leader].cpu().numpy(), gu.to_host(grad[leader]), w.lr)
-    want_idx = oracle.topk_select(acc, w.k)
+    want_idx = oracle.topk_select(acc, w.k) if chunk is None else oracle.chunk_select(acc, chunk)
     del acc
-    print(f"[fullsize] {w.name}: oracle top-k done at {time.time() - t0:.0f}s", flush=True)
+    print(f"[fullsize] {w.name}: oracle selection done at {time.time() - t0:.0f}s", flush=True)
     gu.assert_same("idx", idx_h, want_idx, None, w.name)
     vals = []
     for i in range(w.n_learners):
@@ -153,3 +158,19 @@ def test_transformer_base_sized_full(gu):
 
 def test_large_bf16_full(gu):
     _streamed_parity(gu, workloads.by_name("large_bf16"), step=2, seed=940)
+
+
+def _maximum_size_workload():
+    # the longest vector the library takes: positions up to 2^31 - 2, the last wave tile ragged
+    return workloads.scaled(workloads.by_name("transformer_base_sized"), 2**31 - 1, n_learners=2, steps=2)
+
+
+def test_maximum_size_full(gu):
+    """2^31 - 1 elements per learner: every position-dependent quantity of the kernels (element
+    offsets, candidate positions, output indices) beyond 2^30, the exact selector."""
+    _streamed_parity(gu, _maximum_size_workload(), step=1, seed=950)
+
+
+def test_maximum_size_chunked_full(gu):
+    """The same length with the chunk-wise selector, the last chunk shorter than the others."""
+    _streamed_parity(gu, _maximum_size_workload(), step=0, seed=960, chunk=400)
