@@ -63,9 +63,10 @@ struct SegState {         // selection state of one segment; every field is rewr
     uint32_t done;        // 1: empty index set, nothing to refine
     uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
     uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
+    uint32_t l1_done;     // 1: level 1 was searched already, on the counts the predicted pass gathered for its bucket
     // One state per 128-byte line: the per-segment blocks of k_find run on different XCDs, and four
     // states in one line made each of those kernels three times slower with 200 segments.
-    uint32_t pad[25];
+    uint32_t pad[24];
 };
 static_assert(sizeof(SegState) == 128, "one selection state per cache line");
 

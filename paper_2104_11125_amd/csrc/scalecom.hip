@@ -79,7 +79,7 @@ struct WsLayout {
     size_t segs, sts, chunks, preds, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask, eq_mask,
         tile_slot, vals, best, total;
     // per-step counters and histograms: two copies of one zone, used alternately (offsets inside a copy)
-    size_t zone[2], zone_bytes, z_overflow, z_part, z_hist0, z_hist1, z_hist2;
+    size_t zone[2], zone_bytes, z_overflow, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
 };
 
 WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
@@ -111,6 +111,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
         l.z_part = ztake(nt * kPartSlots * kPartWords * sizeof(uint32_t));
         l.z_hist0 = ztake(nt * kBins0 * sizeof(uint32_t));
         l.z_hist1 = ztake(nt * kBins1 * sizeof(uint32_t));
+        l.z_hist1_spec = ztake(nt * kBins1 * sizeof(uint32_t));
         l.z_hist2 = ztake(nt * kBins2 * sizeof(uint32_t));
         l.zone_bytes = z;
     }
@@ -328,6 +329,7 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     uint32_t* part = reinterpret_cast<uint32_t*>(zone + l.z_part);
     uint32_t* hist0 = reinterpret_cast<uint32_t*>(zone + l.z_hist0);
     uint32_t* hist1 = reinterpret_cast<uint32_t*>(zone + l.z_hist1);
+    uint32_t* hist1_spec = reinterpret_cast<uint32_t*>(zone + l.z_hist1_spec);
     uint32_t* hist2 = reinterpret_cast<uint32_t*>(zone + l.z_hist2);
     uint32_t* next_zone = reinterpret_cast<uint32_t*>(ws + l.zone[ctx->parity ^ 1]);
     const size_t zone_words = l.zone_bytes / sizeof(uint32_t);
@@ -351,17 +353,17 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     const int hgrid = std::min(n_st, kHistGridMax);
     ctx->scratch_clean = false;             // until every kernel of this selection has been enqueued
     k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
-                                           part, overflow, next_zone, zone_words);
+                                           part, overflow, hist1_spec, next_zone, zone_words);
     k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, hist0, preds, part, overflow);
-    k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow);
+    k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow, hist1_spec);
     mark(1);
     const CollectOut collect_out{state, wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt};
     k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt, collect_out);
-    k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow);
+    k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow, nullptr);
     k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt, collect_out);
     // the last search: inside k_tilecount's blocks, or a kernel of its own when those are very many
     const bool fold_last = n_st <= kFoldLastSearchMaxSt;
-    if (!fold_last) k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow);
+    if (!fold_last) k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow, nullptr);
     mark(2);
     k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, fold_last ? hist2 : nullptr, wt_cnt, cand,
                                            st_cand_cnt, sel_mask, eq_mask, st_sum);

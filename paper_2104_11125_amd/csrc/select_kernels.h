@@ -160,7 +160,8 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
             const StDesc* __restrict__ sts, uint2* __restrict__ cand,
             uint32_t* __restrict__ st_cand_cnt, const uint32_t* __restrict__ preds, uint32_t* __restrict__ wt_cnt,
             uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part,
-            uint32_t* __restrict__ overflow, uint32_t* __restrict__ next_scratch, size_t next_words)
+            uint32_t* __restrict__ overflow, uint32_t* __restrict__ hist1_spec, uint32_t* __restrict__ next_scratch,
+            size_t next_words)
 {
     // The counters and histograms of a step live in one of two copies of a scratch zone; this
     // kernel, the first of a step, clears the copy the NEXT step will use (nothing else touches it
@@ -196,6 +197,17 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
         const uint32_t n = fill;
         st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
         if (n > kCandSlice) overflow[d.seg] = 1u;           // every overflowing block stores the same value
+    }
+    // Most steps find the threshold in the predicted bucket itself (the middle of the window): the
+    // second digits of that bucket's keys are counted here, where the atomics drain behind the
+    // streaming loads of the other blocks, so that such a step needs no level-1 pass over the list.
+    // Used only if the whole segment was listed (no overflow) and the bucket is the predicted one.
+    if (fill <= kCandSlice) {
+        uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1;
+        for (uint32_t e = threadIdx.x; e < fill; e += kBlock) {
+            const uint32_t key = cand_stage[e].x;
+            if ((key >> (kBits1 + kBits2)) == p - 1u) atomicAdd(&h1[(key >> kBits2) & (kBins1 - 1)], 1u);
+        }
     }
     if (threadIdx.x <= kWindow) {
         const uint32_t v = acc[threadIdx.x];
@@ -361,7 +373,7 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
             cur = d.seg;
             const SegState ss = state[cur];
             prefix = ss.prefix;
-            skip = ss.done != 0;
+            skip = ss.done != 0 || (LEVEL == 1 && ss.l1_done != 0);
             from_list = ss.mode == kModeCand;
             collect = LEVEL == 1 && from_list && ss.collected == 0;
         }
@@ -433,15 +445,64 @@ k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, cons
 
 // One block per segment: locate, from the top of the histogram, the bucket that holds the
 // k_rem-th largest key of the current bucket, and narrow the state to it.
+// One digit of the radix search, by all threads of a block: the bin of h[0 .. NB) that holds the
+// k_rem-th largest key counted there, from the top.  The one thread that owns that bin returns true
+// with the bin, its count and the number of keys above it; `above` is kWaves words of LDS.
+template <int NB>
+__device__ __forceinline__ bool search_digit(const uint32_t* __restrict__ h, uint32_t k_rem, uint32_t* above,
+                                             uint32_t& digit, uint32_t& n_digit, uint32_t& n_above)
+{
+    constexpr int CH = NB >= kBlock ? NB / kBlock : 1;     // bins per thread
+    constexpr int ACTIVE = NB >= kBlock ? kBlock : NB;     // threads that own bins
+    const int t = threadIdx.x, lane = t % kLanes, wave = t / kLanes;
+    uint32_t bins[CH];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int b = 0; b < CH; ++b) {
+        bins[b] = t < ACTIVE ? h[t * CH + b] : 0u;
+        mine += bins[b];
+    }
+    // inclusive suffix sums over threads: within a wave by shuffles, across the 4 waves through LDS
+    uint32_t suf = mine;
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t v = __shfl_down(suf, off, kLanes);
+        if (lane + off < kLanes) suf += v;
+    }
+    if (lane == 0) above[wave] = suf;                       // the wave's total
+    __syncthreads();
+    for (int w = wave + 1; w < kWaves; ++w) suf += above[w];
+    const uint32_t incl = suf;               // keys in my bins and all higher ones
+    const uint32_t excl = incl - mine;       // keys strictly above my bins
+    bool found = false;
+    if (t < ACTIVE && excl < k_rem && k_rem <= incl) {
+        uint32_t c = excl;
+#pragma unroll
+        for (int b = CH - 1; b >= 0; --b) {
+            if (!found && c + bins[b] >= k_rem) {
+                digit = static_cast<uint32_t>(t * CH + b);
+                n_digit = bins[b];
+                n_above = c;
+                found = true;
+            }
+            c += bins[b];
+        }
+    }
+    return found;
+}
+
+// Search of one radix level, one block per segment.  Level 0 first checks whether the predicted
+// pass saw the k-th largest key inside its window; if so the bucket is known without a histogram,
+// and if it is the predicted bucket itself, level 1 is searched right away on the counts that pass
+// gathered for it (hist_spec), so the level-1 kernels of this step find nothing to do.
 template <int LEVEL>
 __global__ void __launch_bounds__(kBlock)
 k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uint32_t* __restrict__ hist,
-       uint32_t* __restrict__ preds, const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow)
+       uint32_t* __restrict__ preds, const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow,
+       const uint32_t* __restrict__ hist_spec)
 {
     constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
     constexpr int BITS = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
-    constexpr int CH = NB >= kBlock ? NB / kBlock : 1;     // bins per thread
-    constexpr int ACTIVE = NB >= kBlock ? kBlock : NB;     // threads that own bins
     const int seg = blockIdx.x;
     const uint32_t* h = hist + static_cast<size_t>(seg) * NB;
     __shared__ uint32_t above[kWaves];   // per-wave totals
@@ -461,10 +522,6 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
     } else {
         s = state[seg];
     }
-    const int t = threadIdx.x;
-    uint32_t mine = 0;                                      // the counts of my CH bins
-    if (LEVEL != 0 && t < ACTIVE)                           // (level 0 only needs them when no prediction held)
-        for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
     if (LEVEL == 0) {
         s.prefix = 0;
         s.done = s.k_rem == 0 ? 1u : 0u;
@@ -472,13 +529,15 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
         s.q = 0;
         s.mode = kModeFull;
         s.collected = 0;
+        s.l1_done = 0;
         if (s.done) {
             if (threadIdx.x == 0) state[seg] = s;
             return;
         }
         // a prediction that held: the single pass already produced everything level 0 gives
-        __shared__ int resolved;
+        __shared__ uint32_t resolved[3];                    // flag, digit, k_rem
         __shared__ uint32_t tot_s[kPartWords];
+        __shared__ uint32_t found1;
         if (p != 0) {                                       // block-uniform: sum the slotted copies of the counters
             if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
             __syncthreads();
@@ -487,65 +546,63 @@ k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uin
             __syncthreads();
         }
         if (threadIdx.x == 0) {
-            uint32_t tot[1 + kWindow], digit, k_rem;
-            resolved = 0;
+            uint32_t tot[1 + kWindow], digit = 0, k_rem = 0;
+            resolved[0] = 0u;
+            found1 = 0u;
             if (p != 0) {
                 for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
                 if (spec_resolve(tot, ov != 0, p, s.k_rem, digit, k_rem)) {
-                    resolved = 1;
-                    s.prefix = digit;
-                    s.k_rem = k_rem;
-                    s.mode = kModeCand;
-                    s.collected = 1;
-                    state[seg] = s;
-                    preds[seg] = digit + 1;
+                    resolved[0] = 1u;
+                    resolved[1] = digit;
+                    resolved[2] = k_rem;
                 }
             }
         }
         __syncthreads();
-        if (resolved) return;
-    } else if (s.done) {
+        if (resolved[0]) {                                  // block-uniform
+            s.prefix = resolved[1];
+            s.k_rem = resolved[2];
+            s.mode = kModeCand;
+            s.collected = 1;
+            if (s.prefix == p - 1u) {                       // the predicted bucket: its second digits are counted
+                uint32_t digit, n_digit, n_above;
+                if (search_digit<kBins1>(hist_spec + static_cast<size_t>(seg) * kBins1, s.k_rem, above, digit, n_digit,
+                                         n_above)) {
+                    SegState s1 = s;
+                    s1.prefix = (s.prefix << kBits1) | digit;
+                    s1.k_rem = s.k_rem - n_above;
+                    s1.l1_done = 1;
+                    state[seg] = s1;
+                    found1 = 1u;
+                }
+                __syncthreads();
+            }
+            // (no thread finds the bin only if the counts were corrupted: then level 1 runs from the list)
+            if (threadIdx.x == 0) {
+                if (!found1) state[seg] = s;
+                preds[seg] = s.prefix + 1u;
+            }
+            return;
+        }
+    } else if (s.done || (LEVEL == 1 && s.l1_done)) {
         return;
     }
 
-    if (LEVEL == 0 && t < ACTIVE)
-        for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
-    // inclusive suffix sums over threads: within a wave by shuffles, across the 4 waves through LDS
-    const int lane = t % kLanes, wave = t / kLanes;
-    uint32_t suf = mine;
-#pragma unroll
-    for (int off = 1; off < kLanes; off <<= 1) {
-        const uint32_t v = __shfl_down(suf, off, kLanes);
-        if (lane + off < kLanes) suf += v;
-    }
-    if (lane == 0) above[wave] = suf;                       // the wave's total
-    __syncthreads();
-    for (int w = wave + 1; w < kWaves; ++w) suf += above[w];
-    const uint32_t incl = suf;               // keys in my chunk and all higher chunks
-    const uint32_t excl = incl - mine;       // keys strictly above my chunk
-    if (t < ACTIVE && excl < s.k_rem && s.k_rem <= incl) {
-        uint32_t c = excl;
-        for (int b = CH - 1; b >= 0; --b) {
-            const uint32_t n = h[t * CH + b];
-            if (c + n >= s.k_rem) {
-                const uint32_t digit = static_cast<uint32_t>(t * CH + b);
-                s.prefix = (s.prefix << BITS) | digit;
-                s.k_rem -= c;
-                if (LEVEL == 0) {
-                    // the bucket's keys go to the candidate list if its slots can hold them
-                    const uint64_t slots = static_cast<uint64_t>(segs[seg].st_count) * kCandSlice;
-                    s.mode = n <= slots ? kModeCand : kModeFull;
-                    preds[seg] = digit + 1;                 // prediction for the next step
-                }
-                if (LEVEL == 2) {
-                    s.T = s.prefix;
-                    s.q = s.k_rem;
-                }
-                state[seg] = s;
-                break;
-            }
-            c += n;
+    uint32_t digit, n_digit, n_above;
+    if (search_digit<NB>(h, s.k_rem, above, digit, n_digit, n_above)) {
+        s.prefix = (s.prefix << BITS) | digit;
+        s.k_rem -= n_above;
+        if (LEVEL == 0) {
+            // the bucket's keys go to the candidate list if its slots can hold them
+            const uint64_t slots = static_cast<uint64_t>(segs[seg].st_count) * kCandSlice;
+            s.mode = n_digit <= slots ? kModeCand : kModeFull;
+            preds[seg] = digit + 1;                         // prediction for the next step
         }
+        if (LEVEL == 2) {
+            s.T = s.prefix;
+            s.q = s.k_rem;
+        }
+        state[seg] = s;
     }
 }
 
