@@ -2,6 +2,8 @@
 // tables the host uploads.  Part of scalecom.hip's single translation unit.
 #pragma once
 
+#include <hip/hip_runtime.h>
+
 #include <cstdint>
 
 #include "scalecom.h"
@@ -23,6 +25,10 @@ constexpr int kSlotsOwnScanBlock = 1024;         // threads of its blocks then (
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
 constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
 constexpr int kHistGridMax = 2048;
+// The histogram kernels split the supertiles evenly over their blocks: block b of g owns the
+// supertiles [hist_block_lo(b), hist_block_lo(b + 1)); g <= n_st, so no block is empty.
+__host__ __device__ inline int hist_block_lo(int64_t b, int n_st, int g) { return static_cast<int>(b * n_st / g); }
+inline int hist_grid(int n_st) { return n_st < kHistGridMax ? n_st : kHistGridMax; }
 constexpr int kFoldLastSearchMaxSt = 12288;      // up to this many supertiles k_tilecount searches the last level itself
                                                  // (measured: +45 us over 122 K blocks against one launch of 4.5 us)
 constexpr int kCandSlice = 512;                  // candidate slots per supertile (1/16 of its positions)
@@ -45,7 +51,8 @@ struct StDesc {           // one per supertile; carries what the streaming kerne
     int32_t a0;           // first position, a multiple of 4 (may lie up to 3 before begin)
     int32_t begin, end;   // the segment's positions [begin, end)
     int32_t slot_end;     // one past the segment's last output slot
-    int32_t pad[3];
+    int32_t seg_st_end;   // one past the segment's last supertile
+    int32_t pad[2];
 };
 
 struct ChunkDesc {        // one per scan chunk: up to kChunk consecutive supertiles of one segment
@@ -55,7 +62,7 @@ struct ChunkDesc {        // one per scan chunk: up to kChunk consecutive supert
     int32_t pad;
 };
 
-struct SegState {         // selection state of one segment; every field is rewritten by k_find<0> each step
+struct SegState {         // selection state of one segment after a level; every field is rewritten by k_level0 each step
     uint32_t prefix;      // key bits fixed so far (level 0: 12 bits, level 1: 24 bits)
     uint32_t k_rem;       // members still to be found inside the current bucket
     uint32_t T;           // threshold key (after level 2)
@@ -64,11 +71,21 @@ struct SegState {         // selection state of one segment; every field is rewr
     uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
     uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
     uint32_t l1_done;     // 1: level 1 was searched already, on the counts the predicted pass gathered for its bucket
-    // One state per 128-byte line: the per-segment blocks of k_find run on different XCDs, and four
-    // states in one line made each of those kernels three times slower with 200 segments.
-    uint32_t pad[24];
+    uint32_t pending;     // 1: the last histogram was counted but not searched yet (the next kernel's blocks do that)
 };
-static_assert(sizeof(SegState) == 128, "one selection state per cache line");
+static_assert(sizeof(SegState) == 36, "nine words, no padding to carry along in copies");
+// One state per 128-byte line: blocks that work on different segments run on different XCDs, and
+// four states in one line made the per-segment searches three times slower with 200 segments.
+// (The stride is kept out of the struct so that copies of a state stay in registers.)
+constexpr size_t kStateStride = 128;
+__host__ __device__ inline SegState& state_at(SegState* base, size_t seg)
+{
+    return *reinterpret_cast<SegState*>(reinterpret_cast<char*>(base) + seg * kStateStride);
+}
+__host__ __device__ inline const SegState& state_at(const SegState* base, size_t seg)
+{
+    return *reinterpret_cast<const SegState*>(reinterpret_cast<const char*>(base) + seg * kStateStride);
+}
 
 constexpr uint32_t kWindow = 5;                  // predicted window: previous bucket +- 2 digits
 // Counts of the predicted pass, per segment: [0] keys above the window, [1 + d] keys with the

@@ -79,7 +79,7 @@ struct WsLayout {
     size_t segs, sts, chunks, preds, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask, eq_mask,
         tile_slot, vals, best, total;
     // per-step counters and histograms: two copies of one zone, used alternately (offsets inside a copy)
-    size_t zone[2], zone_bytes, z_overflow, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
+    size_t zone[2], zone_bytes, z_overflow, z_p_used, z_full_flag, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
 };
 
 WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
@@ -99,7 +99,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.sts = take(nst * sizeof(StDesc));
     l.chunks = take(nch * sizeof(ChunkDesc));
     l.preds = take(nt * sizeof(uint32_t));
-    l.state = take(nt * sizeof(SegState));
+    l.state = take(3 * nt * kStateStride);               // after level 0, after level 1, after level 2
     {
         size_t z = 0;
         auto ztake = [&](size_t bytes) {
@@ -108,6 +108,8 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
             return at;
         };
         l.z_overflow = ztake(nt * sizeof(uint32_t));
+        l.z_p_used = ztake(nt * sizeof(uint32_t));
+        l.z_full_flag = ztake(nt * sizeof(uint32_t));
         l.z_part = ztake(nt * kPartSlots * kPartWords * sizeof(uint32_t));
         l.z_hist0 = ztake(nt * kBins0 * sizeof(uint32_t));
         l.z_hist1 = ztake(nt * kBins1 * sizeof(uint32_t));
@@ -247,7 +249,8 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
                           static_cast<int32_t>(n_ch), static_cast<int32_t>(n_chunks), static_cast<int32_t>(ch[s]), 0};
         for (int64_t j = 0; j < count; ++j)
             sts[n_st + j] = StDesc{s, static_cast<int32_t>(a_first + j * kSuper), static_cast<int32_t>(b),
-                                   static_cast<int32_t>(e), static_cast<int32_t>(out + ks[s]), {0, 0, 0}};
+                                   static_cast<int32_t>(e), static_cast<int32_t>(out + ks[s]),
+                                   static_cast<int32_t>(n_st + count), {0, 0}};
         for (int64_t c = 0; c < n_chunks; ++c)
             chunks[n_ch + c] = ChunkDesc{s, static_cast<int32_t>(n_st + c * kChunk),
                                          static_cast<int32_t>(std::min<int64_t>(kChunk, count - c * kChunk)), 0};
@@ -323,9 +326,14 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     const SegDesc* segs = reinterpret_cast<const SegDesc*>(ws + l.segs);
     const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
     const ChunkDesc* chunks = reinterpret_cast<const ChunkDesc*>(ws + l.chunks);
-    SegState* state = reinterpret_cast<SegState*>(ws + l.state);
+    // each level's kernel reads the state the previous one left and writes its own copy
+    SegState* state0 = reinterpret_cast<SegState*>(ws + l.state);
+    SegState* state1 = &state_at(state0, static_cast<size_t>(ctx->n_tensors_max));
+    SegState* state = &state_at(state1, static_cast<size_t>(ctx->n_tensors_max));   // what the kernels after the search read
     char* zone = ws + l.zone[ctx->parity];
     uint32_t* overflow = reinterpret_cast<uint32_t*>(zone + l.z_overflow);
+    uint32_t* p_used = reinterpret_cast<uint32_t*>(zone + l.z_p_used);
+    uint32_t* full_flag = reinterpret_cast<uint32_t*>(zone + l.z_full_flag);
     uint32_t* part = reinterpret_cast<uint32_t*>(zone + l.z_part);
     uint32_t* hist0 = reinterpret_cast<uint32_t*>(zone + l.z_hist0);
     uint32_t* hist1 = reinterpret_cast<uint32_t*>(zone + l.z_hist1);
@@ -350,20 +358,21 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
         const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
         k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.zone[0]), words);
     }
-    const int hgrid = std::min(n_st, kHistGridMax);
+    const int hgrid = hist_grid(n_st);      // the segments' block counts in the tables are those of this grid
     ctx->scratch_clean = false;             // until every kernel of this selection has been enqueued
     k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
-                                           part, overflow, hist1_spec, next_zone, zone_words);
-    k_hist0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, hist0, preds, part, overflow);
-    k_find<0><<<n_tensors, kBlock, 0, s>>>(segs, state, hist0, preds, part, overflow, hist1_spec);
+                                           part, overflow, p_used, hist1_spec, next_zone, zone_words);
+    k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state0, hist0, preds, p_used, part, overflow,
+                                         hist1_spec);
     mark(1);
-    const CollectOut collect_out{state, wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt};
-    k_hist<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist1, cand, st_cand_cnt, collect_out);
-    k_find<1><<<n_tensors, kBlock, 0, s>>>(segs, state, hist1, preds, part, overflow, nullptr);
-    k_hist<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, sts, n_st, state, hist2, cand, st_cand_cnt, collect_out);
+    const CollectOut collect_out{wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt, full_flag};
+    k_level<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state0, state1, hist0, hist1, preds,
+                                           collect_out);
+    k_level<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state1, state, hist1, hist2, preds,
+                                           collect_out);
     // the last search: inside k_tilecount's blocks, or a kernel of its own when those are very many
     const bool fold_last = n_st <= kFoldLastSearchMaxSt;
-    if (!fold_last) k_find<2><<<n_tensors, kBlock, 0, s>>>(segs, state, hist2, preds, part, overflow, nullptr);
+    if (!fold_last) k_find2<<<n_tensors, kBlock, 0, s>>>(state, hist2);
     mark(2);
     k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, fold_last ? hist2 : nullptr, wt_cnt, cand,
                                            st_cand_cnt, sel_mask, eq_mask, st_sum);

@@ -1,7 +1,7 @@
 // Exact top-k selection on the leader's vector x_L = fma(lr, grad_L, mem_L) (Eq. 2, Alg. 1 line 6):
 // radix select over the 31-bit magnitude key, 12 + 12 + 7 bits.  Kernels in the order a step runs
-// them: k_predicted, k_hist0, k_find<0>, k_hist<1>, k_find<1>, k_hist<2>, (k_find<2>,) k_tilecount,
-// k_scan, k_slots.  Part of scalecom.hip's single translation unit.
+// them: k_predicted, k_level0, k_level<1>, k_level<2>, (k_find2,) k_tilecount, (k_scan,) k_slots.
+// Part of scalecom.hip's single translation unit.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -28,11 +28,14 @@ struct CollectStage {       // LDS staging of one supertile's masks and tile cou
 // digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice
 // `cand_dst` (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if
 // `wc` is given, counted per digit there, and, if `lh1` is given (then lo == hi), per second digit
-// there.  Called by all lanes of a wave; n_above is the same in every lane.
+// there, and, if `h1_spec` is given, those with top digit `center` per second digit there (in
+// memory: the atomics return nothing and drain behind the streaming loads).  Called by all lanes
+// of a wave; n_above is the same in every lane.
 template <bool ALL_OK>
 __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
                                              uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* wc,
-                                             uint32_t* lh1, uint32_t& n_above, CollectStage& stg, uint2* cand_dst)
+                                             uint32_t* lh1, uint32_t* h1_spec, uint32_t center, uint32_t& n_above,
+                                             CollectStage& stg, uint2* cand_dst)
 {
     // top digit > hi  <=>  key >= (hi + 1) << 19;  lo <= top digit <= hi  <=>  key - (lo << 19) < span
     const uint32_t lo_key = lo << (kBits1 + kBits2);
@@ -68,6 +71,8 @@ __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool o
             if (rank < kCandSlice) cand_dst[rank] = make_uint2(key[c], p0 + c);
             if (wc) atomicAdd(&wc[(key[c] >> (kBits1 + kBits2)) - lo], 1u);
             if (lh1) atomicAdd(&lh1[(key[c] >> kBits2) & (kBins1 - 1)], 1u);   // counted whether or not it is listed
+            if (h1_spec && (key[c] >> (kBits1 + kBits2)) == center)
+                atomicAdd(&h1_spec[(key[c] >> kBits2) & (kBins1 - 1)], 1u);
             ++rank;
         }
     }
@@ -103,7 +108,8 @@ __device__ __forceinline__ void collect_flush(const CollectStage& stg, const uin
 template <typename G, bool INSIDE>
 __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                                                     const StDesc& d, uint32_t lo, uint32_t hi, int wave, int lane,
-                                                    uint32_t* fill, uint32_t* wc, CollectStage& stg, uint2* cand_stage)
+                                                    uint32_t* fill, uint32_t* wc, uint32_t* h1_spec, uint32_t center,
+                                                    CollectStage& stg, uint2* cand_stage)
 {
     constexpr int kIters = kTilesPerSuper / kWaves;
     constexpr uint32_t kStride = kWaves * kWaveTile;
@@ -137,7 +143,8 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
             }
         }
         uint32_t n_above;
-        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, n_above, stg, cand_stage);
+        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, h1_spec, center, n_above, stg,
+                             cand_stage);
         above_acc += n_above;
         m_cur = m_nxt;
         g_cur = g_nxt;
@@ -150,18 +157,19 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
 // that carry a prediction of their threshold bucket (the bucket found in the previous step).
 // ONE pass, no histogram: keys whose top digit lies above a 5-digit window around the
 // prediction are members for sure (counted per tile, marked in the mask), keys inside the
-// window go to the candidate list and are counted per digit.  If the counts show afterwards
-// that the k-th largest key fell inside the window, the threshold bucket is known exactly and
-// no other full pass over the leader is needed.  The prediction only decides how much work is
-// done, never what is selected.  One block per supertile.
+// window go to the candidate list and are counted per digit; those of the predicted bucket
+// itself, where the threshold lies in most steps, are also counted per second digit.  If the
+// counts show afterwards that the k-th largest key fell inside the window, the threshold bucket
+// is known exactly and no other full pass over the leader is needed.  The prediction only decides
+// how much work is done, never what is selected.  One block per supertile.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
             const StDesc* __restrict__ sts, uint2* __restrict__ cand,
             uint32_t* __restrict__ st_cand_cnt, const uint32_t* __restrict__ preds, uint32_t* __restrict__ wt_cnt,
             uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part,
-            uint32_t* __restrict__ overflow, uint32_t* __restrict__ hist1_spec, uint32_t* __restrict__ next_scratch,
-            size_t next_words)
+            uint32_t* __restrict__ overflow, uint32_t* __restrict__ p_used, uint32_t* __restrict__ hist1_spec,
+            uint32_t* __restrict__ next_scratch, size_t next_words)
 {
     // The counters and histograms of a step live in one of two copies of a scratch zone; this
     // kernel, the first of a step, clears the copy the NEXT step will use (nothing else touches it
@@ -173,7 +181,10 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const int st = blockIdx.x;
     const StDesc d = sts[st];
     const uint32_t p = preds[d.seg];                        // 0: none, else predicted bucket + 1
-    if (p == 0 || segs[d.seg].k == 0) return;
+    const SegDesc sd = segs[d.seg];
+    if (p == 0 || sd.k == 0) return;
+    // the prediction this step works with, for the kernel that checks it (preds is rewritten there)
+    if (st == sd.st_first && threadIdx.x == 0) p_used[d.seg] = p;
     const uint32_t lo = window_lo(p), hi = window_hi(p);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
     __shared__ uint32_t fill;
@@ -185,11 +196,14 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     __syncthreads();
 
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
+    uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1;
     uint32_t above_acc;
     if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
-        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg, cand_stage);
+        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, p - 1u, stg,
+                                             cand_stage);
     else
-        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, stg, cand_stage);
+        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, p - 1u, stg,
+                                              cand_stage);
     if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
     __syncthreads();
     collect_flush(stg, cand_stage, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
@@ -198,17 +212,6 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
         st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
         if (n > kCandSlice) overflow[d.seg] = 1u;           // every overflowing block stores the same value
     }
-    // Most steps find the threshold in the predicted bucket itself (the middle of the window): the
-    // second digits of that bucket's keys are counted here, where the atomics drain behind the
-    // streaming loads of the other blocks, so that such a step needs no level-1 pass over the list.
-    // Used only if the whole segment was listed (no overflow) and the bucket is the predicted one.
-    if (fill <= kCandSlice) {
-        uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1;
-        for (uint32_t e = threadIdx.x; e < fill; e += kBlock) {
-            const uint32_t key = cand_stage[e].x;
-            if ((key >> (kBits1 + kBits2)) == p - 1u) atomicAdd(&h1[(key >> kBits2) & (kBins1 - 1)], 1u);
-        }
-    }
     if (threadIdx.x <= kWindow) {
         const uint32_t v = acc[threadIdx.x];
         if (v)
@@ -216,235 +219,6 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     }
 }
 
-// Histogram of the top 12 key bits of the leader's vector, for the segments that need it: those
-// without a prediction, and those whose prediction failed (the k-th largest key was not inside
-// the window k_predicted collected).
-template <typename G>
-__global__ void __launch_bounds__(kBlock)
-k_hist0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-        const StDesc* __restrict__ sts, int n_st, uint32_t* __restrict__ hist, const uint32_t* __restrict__ preds,
-        const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow)
-{
-    __shared__ uint32_t lh[kBins0];
-    __shared__ uint32_t tot_s[kPartWords];
-    __shared__ int needed;
-
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
-    const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
-    const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
-
-    bool lh_ready = false;
-    // walk the block's supertiles segment by segment: a segment that needs no histogram (the
-    // steady state) costs one look at its counters, not one per supertile
-    int st = st_lo;
-    while (st < st_hi) {
-        const int cur = sts[st].seg;
-        const SegDesc sd = segs[cur];
-        const int seg_hi = sd.st_first + sd.st_count < st_hi ? sd.st_first + sd.st_count : st_hi;
-        const uint32_t p = preds[cur];
-        const uint32_t k = static_cast<uint32_t>(sd.k);
-        if (k != 0 && p != 0) {                             // did the prediction hold?  (block-uniform branch)
-            if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
-            __syncthreads();
-            for (int i = threadIdx.x; i < kPartSlots * kPartWords; i += kBlock) {
-                const uint32_t v = part[static_cast<size_t>(cur) * kPartSlots * kPartWords + i];
-                if (v) atomicAdd(&tot_s[i % kPartWords], v);
-            }
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                uint32_t tot[1 + kWindow], digit, k_rem;
-                for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
-                needed = !spec_resolve(tot, overflow[cur] != 0, p, k, digit, k_rem);
-            }
-        } else if (threadIdx.x == 0) {
-            needed = k != 0;
-        }
-        __syncthreads();
-        const bool histogram = needed != 0;
-        __syncthreads();
-        if (histogram) {
-            if (!lh_ready) {                                // the histogram is only cleared when it is used
-                for (int b = threadIdx.x; b < kBins0; b += kBlock) lh[b] = 0u;
-                __syncthreads();
-                lh_ready = true;
-            }
-            const int64_t begin = sd.begin, end = sd.end;
-            for (int s2 = st; s2 < seg_hi; ++s2) {
-                const int64_t a0 = sts[s2].a0;
-#pragma unroll 2
-                for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-                    const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
-                    if (p0 >= end) continue;
-                    uint32_t key[4];
-                    bool ok[4];
-                    leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
-                }
-            }
-            __syncthreads();                                // flush the segment's counts
-            for (int b = threadIdx.x; b < kBins0; b += kBlock) {
-                const uint32_t v = lh[b];
-                if (v) {
-                    atomicAdd(&hist[static_cast<size_t>(cur) * kBins0 + b], v);
-                    lh[b] = 0u;
-                }
-            }
-            __syncthreads();
-        }
-        st = seg_hi;
-    }
-}
-
-// What the level-1 pass writes when it also has to collect (see k_hist).
-struct CollectOut {
-    SegState* state;
-    uint32_t* wt_cnt;
-    uint64_t* sel_mask;
-    uint64_t* eq_mask;
-    uint2* cand;
-    uint32_t* st_cand_cnt;
-};
-
-// Histogram of the next digit of the leader's magnitude keys, per segment.  LEVEL 1: bits 18..7
-// of keys whose top 12 bits equal the chosen bucket; LEVEL 2: last 7 bits of keys matching 24
-// bits.  Candidate mode reads the keys from the candidate list, full mode recomputes them from
-// the leader's vector.
-// LEVEL 1 is also the second full pass over the leader's vector for segments in candidate mode
-// whose list the predicted pass did not fill (no prediction, or one that missed): per wave tile,
-// keys above the level-0 bucket are members for sure, keys inside the bucket go to the
-// supertile's slice of the candidate list and are counted here directly.  A slice that overflows
-// (bucket keys clustered in one place) sends the whole segment back to full-pass mode for the
-// kernels that follow; this kernel's counts are complete either way.
-template <typename G, int LEVEL>
-// (register use is capped so that 8 waves fit a SIMD: the grid of 2048 blocks is one wave per slot)
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8)))
-k_hist(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const StDesc* __restrict__ sts, int n_st,
-       const SegState* state, uint32_t* __restrict__ hist, const uint2* cand, const uint32_t* st_cand_cnt,
-       CollectOut out)   // state, cand and st_cand_cnt are also reachable, for writing, through `out`
-{
-    static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_hist0");
-    constexpr int NB = LEVEL == 1 ? kBins1 : kBins2;
-    __shared__ uint32_t lh[NB];
-    for (int b = threadIdx.x; b < NB; b += kBlock) lh[b] = 0u;
-    __syncthreads();
-
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
-    const int st_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * n_st / gridDim.x);
-    const int st_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * n_st / gridDim.x);
-
-    auto count = [&](uint32_t key, uint32_t prefix) {
-        if (LEVEL == 1) {
-            if ((key >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
-        } else {
-            if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
-        }
-    };
-
-    int cur = -1;
-    uint32_t prefix = 0;
-    bool skip = false, from_list = false, collect = false;
-    for (int st = st_lo; st < st_hi; ++st) {
-        // The supertile's listed keys are requested together with its descriptor (one round trip instead of
-        // three) when the block's previous supertile was counted from its list, or there was none yet.
-        const bool early = cur < 0 || from_list;            // block-uniform
-        const uint2* my_slice = cand + static_cast<size_t>(st) * kCandSlice;
-        const StDesc d = sts[st];
-        uint32_t listed = 0;
-        uint2 ce[2] = {make_uint2(0, 0), make_uint2(0, 0)};
-        if (early) {
-            listed = st_cand_cnt[st];
-            ce[0] = my_slice[threadIdx.x];
-            ce[1] = my_slice[kBlock + threadIdx.x];
-        }
-        if (d.seg != cur) {
-            if (cur >= 0) {   // flush the finished segment's counts
-                __syncthreads();
-                for (int b = threadIdx.x; b < NB; b += kBlock) {
-                    const uint32_t v = lh[b];
-                    if (v) {
-                        atomicAdd(&hist[static_cast<size_t>(cur) * NB + b], v);
-                        lh[b] = 0u;
-                    }
-                }
-                __syncthreads();
-            }
-            cur = d.seg;
-            const SegState ss = state[cur];
-            prefix = ss.prefix;
-            skip = ss.done != 0 || (LEVEL == 1 && ss.l1_done != 0);
-            from_list = ss.mode == kModeCand;
-            collect = LEVEL == 1 && from_list && ss.collected == 0;
-        }
-        if (skip) continue;
-        if constexpr (LEVEL == 1) {
-            if (collect) {   // block-uniform: no list yet, this pass makes it
-                __shared__ uint32_t fill;
-                __shared__ CollectStage stg;
-                if (threadIdx.x == 0) fill = 0u;
-                __syncthreads();
-                const int64_t begin = d.begin, end = d.end;
-                uint2* slice = out.cand + static_cast<size_t>(st) * kCandSlice;   // written directly: LDS is the histogram's
-                for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-                    const int wt = it * kWaves + wave;
-                    const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
-                    uint32_t key[4] = {0, 0, 0, 0};
-                    bool ok[4] = {false, false, false, false};
-                    if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-                    uint32_t n_above;
-                    collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, nullptr, lh,
-                                        n_above, stg, slice);
-                }
-                __syncthreads();
-                collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask,
-                              out.eq_mask, slice);
-                if (threadIdx.x == 0) {
-                    const uint32_t n = fill;
-                    out.st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
-                    if (n > kCandSlice) out.state[cur].mode = kModeFull;   // every overflowing block stores the same value
-                }
-                __syncthreads();   // the staging area is reused for the block's next supertile
-                continue;
-            }
-        }
-        if (from_list) {   // keys of this supertile that were copied to the candidate list
-            static_assert(kCandSlice == 2 * kBlock, "two slice entries per thread");
-            if (!early) {
-                listed = st_cand_cnt[st];
-                ce[0] = my_slice[threadIdx.x];
-                ce[1] = my_slice[kBlock + threadIdx.x];
-            }
-            const uint32_t cnt = listed < kCandSlice ? listed : kCandSlice;   // never use what lies past the count
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                if (j * kBlock + threadIdx.x < cnt) count(ce[j].x, prefix);
-            continue;
-        }
-        const int64_t begin = d.begin, end = d.end;
-#pragma unroll 2
-        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-            const int64_t p0 = static_cast<int64_t>(d.a0) + (it * kWaves + wave) * kWaveTile + lane * kVec;
-            if (p0 >= end) continue;
-            uint32_t key[4];
-            bool ok[4];
-            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (ok[c]) count(key[c], prefix);
-        }
-    }
-    if (cur >= 0) {
-        __syncthreads();
-        for (int b = threadIdx.x; b < NB; b += kBlock) {
-            const uint32_t v = lh[b];
-            if (v) atomicAdd(&hist[static_cast<size_t>(cur) * NB + b], v);
-        }
-    }
-}
-
-// One block per segment: locate, from the top of the histogram, the bucket that holds the
-// k_rem-th largest key of the current bucket, and narrow the state to it.
 // One digit of the radix search, by all threads of a block: the bin of h[0 .. NB) that holds the
 // k_rem-th largest key counted there, from the top.  The one thread that owns that bin returns true
 // with the bin, its count and the number of keys above it; `above` is kWaves words of LDS.
@@ -455,12 +229,10 @@ __device__ __forceinline__ bool search_digit(const uint32_t* __restrict__ h, uin
     constexpr int CH = NB >= kBlock ? NB / kBlock : 1;     // bins per thread
     constexpr int ACTIVE = NB >= kBlock ? kBlock : NB;     // threads that own bins
     const int t = threadIdx.x, lane = t % kLanes, wave = t / kLanes;
-    uint32_t bins[CH];
     uint32_t mine = 0;
+    if (t < ACTIVE) {
 #pragma unroll
-    for (int b = 0; b < CH; ++b) {
-        bins[b] = t < ACTIVE ? h[t * CH + b] : 0u;
-        mine += bins[b];
+        for (int b = 0; b < CH; ++b) mine += h[t * CH + b];
     }
     // inclusive suffix sums over threads: within a wave by shuffles, across the 4 waves through LDS
     uint32_t suf = mine;
@@ -475,139 +247,363 @@ __device__ __forceinline__ bool search_digit(const uint32_t* __restrict__ h, uin
     const uint32_t incl = suf;               // keys in my bins and all higher ones
     const uint32_t excl = incl - mine;       // keys strictly above my bins
     bool found = false;
-    if (t < ACTIVE && excl < k_rem && k_rem <= incl) {
+    if (t < ACTIVE && excl < k_rem && k_rem <= incl) {      // one thread: its bins are read again, not kept
         uint32_t c = excl;
-#pragma unroll
-        for (int b = CH - 1; b >= 0; --b) {
-            if (!found && c + bins[b] >= k_rem) {
+        for (int b = CH - 1; b >= 0 && !found; --b) {
+            const uint32_t n = h[t * CH + b];
+            if (c + n >= k_rem) {
                 digit = static_cast<uint32_t>(t * CH + b);
-                n_digit = bins[b];
+                n_digit = n;
                 n_above = c;
                 found = true;
             }
-            c += bins[b];
+            c += n;
         }
     }
     return found;
 }
 
-// Search of one radix level, one block per segment.  Level 0 first checks whether the predicted
-// pass saw the k-th largest key inside its window; if so the bucket is known without a histogram,
-// and if it is the predicted bucket itself, level 1 is searched right away on the counts that pass
-// gathered for it (hist_spec), so the level-1 kernels of this step find nothing to do.
-template <int LEVEL>
+// Level 0 of the search, for every segment: did the predicted pass see the k-th largest key inside
+// its window?  Then the segment's bucket is known without a histogram, and if it is the predicted
+// bucket itself, level 1 is searched right away on the counts that pass gathered for it.
+// Otherwise (no prediction, or one that failed) the blocks that hold the segment's supertiles count
+// the top 12 key bits of the leader's vector, and the search of that histogram is left to the
+// blocks of the next kernel (state.pending).  The block that holds the segment's first supertile
+// writes the state either way; no block reads what another block of the same kernel wrote.
+template <typename G>
 __global__ void __launch_bounds__(kBlock)
-k_find(const SegDesc* __restrict__ segs, SegState* __restrict__ state, const uint32_t* __restrict__ hist,
-       uint32_t* __restrict__ preds, const uint32_t* __restrict__ part, const uint32_t* __restrict__ overflow,
-       const uint32_t* __restrict__ hist_spec)
+k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+         const StDesc* __restrict__ sts, int n_st, SegState* __restrict__ state, uint32_t* __restrict__ hist,
+         uint32_t* __restrict__ preds, const uint32_t* __restrict__ p_used, const uint32_t* __restrict__ part,
+         const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec)
 {
-    constexpr int NB = LEVEL == 0 ? kBins0 : (LEVEL == 1 ? kBins1 : kBins2);
-    constexpr int BITS = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
-    const int seg = blockIdx.x;
-    const uint32_t* h = hist + static_cast<size_t>(seg) * NB;
-    __shared__ uint32_t above[kWaves];   // per-wave totals
-
-    // Everything the block may need is requested before the first value is looked at: each dependent
-    // round trip to memory costs these one-block-per-segment kernels close to a microsecond.
+    __shared__ uint32_t lh[kBins0];
+    __shared__ uint32_t tot_s[kPartWords];
+    __shared__ uint32_t res[3];                             // outcome flag, digit(s), members left
+    __shared__ uint32_t above[kWaves];
+    __shared__ uint32_t flag;
     static_assert(kPartSlots * kPartWords == 2 * kBlock, "two counter words per thread");
-    SegState s{};
-    uint32_t p = 0, ov = 0, w0 = 0, w1 = 0;
-    if (LEVEL == 0) {                                       // level 0 writes every field of the state itself
-        const uint32_t* my_part = part + static_cast<size_t>(seg) * kPartSlots * kPartWords;
-        s.k_rem = static_cast<uint32_t>(segs[seg].k);
-        p = preds[seg];
-        ov = overflow[seg];
-        w0 = my_part[threadIdx.x];
-        w1 = my_part[kBlock + threadIdx.x];
-    } else {
-        s = state[seg];
-    }
-    if (LEVEL == 0) {
-        s.prefix = 0;
-        s.done = s.k_rem == 0 ? 1u : 0u;
-        s.T = 0xffffffffu;     // above every key: nothing is a member
-        s.q = 0;
+
+    const int t = threadIdx.x, wave = t / kLanes, lane = t % kLanes;
+    const int st_lo = hist_block_lo(blockIdx.x, n_st, gridDim.x);
+    const int st_hi = hist_block_lo(static_cast<int64_t>(blockIdx.x) + 1, n_st, gridDim.x);
+
+    bool lh_ready = false;
+    // walk the block's supertiles segment by segment: a segment that needs no histogram (the
+    // steady state) costs one look at its counters, not one per supertile
+    int st = st_lo;
+    while (st < st_hi) {
+        const StDesc d0 = sts[st];
+        const int cur = d0.seg;
+        const int seg_hi = d0.seg_st_end < st_hi ? d0.seg_st_end : st_hi;
+        // everything the segment number addresses is requested at once
+        const uint32_t* my_part = part + static_cast<size_t>(cur) * kPartSlots * kPartWords;
+        const SegDesc sd = segs[cur];
+        const uint32_t p = p_used[cur];
+        const uint32_t ov = overflow[cur];
+        const uint32_t w0 = my_part[t], w1 = my_part[kBlock + t];
+        const bool owner = st == sd.st_first;               // this block writes the state if no histogram is needed
+        const uint32_t k = static_cast<uint32_t>(sd.k);
+        SegState s{};                                       // every field is written each step
+        s.k_rem = k;
+        s.T = 0xffffffffu;                                  // above every key: nothing is a member
         s.mode = kModeFull;
-        s.collected = 0;
-        s.l1_done = 0;
-        if (s.done) {
-            if (threadIdx.x == 0) state[seg] = s;
-            return;
+        if (k == 0) {                                       // block-uniform: an empty index set
+            if (owner && t == 0) {
+                s.done = 1;
+                state_at(state, cur) = s;
+            }
+            st = seg_hi;
+            continue;
         }
-        // a prediction that held: the single pass already produced everything level 0 gives
-        __shared__ uint32_t resolved[3];                    // flag, digit, k_rem
-        __shared__ uint32_t tot_s[kPartWords];
-        __shared__ uint32_t found1;
+        if (t == 0) {
+            res[0] = 0u;
+            flag = 0u;
+        }
         if (p != 0) {                                       // block-uniform: sum the slotted copies of the counters
-            if (threadIdx.x < kPartWords) tot_s[threadIdx.x] = 0u;
+            if (t < kPartWords) tot_s[t] = 0u;
             __syncthreads();
-            if (w0) atomicAdd(&tot_s[threadIdx.x % kPartWords], w0);
-            if (w1) atomicAdd(&tot_s[(kBlock + threadIdx.x) % kPartWords], w1);
+            if (w0) atomicAdd(&tot_s[t % kPartWords], w0);
+            if (w1) atomicAdd(&tot_s[(kBlock + t) % kPartWords], w1);
             __syncthreads();
-        }
-        if (threadIdx.x == 0) {
-            uint32_t tot[1 + kWindow], digit = 0, k_rem = 0;
-            resolved[0] = 0u;
-            found1 = 0u;
-            if (p != 0) {
+            if (t == 0) {
+                uint32_t tot[1 + kWindow], digit = 0, k_rem = 0;
                 for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
-                if (spec_resolve(tot, ov != 0, p, s.k_rem, digit, k_rem)) {
-                    resolved[0] = 1u;
-                    resolved[1] = digit;
-                    resolved[2] = k_rem;
+                if (spec_resolve(tot, ov != 0, p, k, digit, k_rem)) {
+                    res[0] = 1u;
+                    res[1] = digit;
+                    res[2] = k_rem;
                 }
             }
         }
         __syncthreads();
-        if (resolved[0]) {                                  // block-uniform
-            s.prefix = resolved[1];
-            s.k_rem = resolved[2];
-            s.mode = kModeCand;
-            s.collected = 1;
-            if (s.prefix == p - 1u) {                       // the predicted bucket: its second digits are counted
-                uint32_t digit, n_digit, n_above;
-                if (search_digit<kBins1>(hist_spec + static_cast<size_t>(seg) * kBins1, s.k_rem, above, digit, n_digit,
-                                         n_above)) {
-                    SegState s1 = s;
-                    s1.prefix = (s.prefix << kBits1) | digit;
-                    s1.k_rem = s.k_rem - n_above;
-                    s1.l1_done = 1;
-                    state[seg] = s1;
-                    found1 = 1u;
+        if (res[0]) {                                       // block-uniform: the prediction held
+            if (owner) {
+                s.prefix = res[1];
+                s.k_rem = res[2];
+                s.mode = kModeCand;
+                s.collected = 1;
+                if (s.prefix == p - 1u) {                   // the predicted bucket: its second digits are counted
+                    uint32_t digit, n_digit, n_above;
+                    if (search_digit<kBins1>(hist1_spec + static_cast<size_t>(cur) * kBins1, s.k_rem, above, digit,
+                                                    n_digit, n_above)) {
+                        res[1] = (s.prefix << kBits1) | digit;
+                        res[2] = s.k_rem - n_above;
+                        flag = 1u;
+                    }
+                    __syncthreads();
                 }
-                __syncthreads();
+                if (t == 0) {
+                    preds[cur] = s.prefix + 1u;             // prediction for the next step
+                    if (flag) {   // (no thread finds the bin only if the counts were corrupted: then level 1 runs from the list)
+                        s.prefix = res[1];
+                        s.k_rem = res[2];
+                        s.l1_done = 1;
+                    }
+                    state_at(state, cur) = s;
+                }
             }
-            // (no thread finds the bin only if the counts were corrupted: then level 1 runs from the list)
-            if (threadIdx.x == 0) {
-                if (!found1) state[seg] = s;
-                preds[seg] = s.prefix + 1u;
-            }
-            return;
+            __syncthreads();                                // the LDS words are reused for the block's next segment
+            st = seg_hi;
+            continue;
         }
-    } else if (s.done || (LEVEL == 1 && s.l1_done)) {
-        return;
-    }
 
+        // no prediction, or one that failed: count the top digits of my part of the segment
+        if (!lh_ready) {                                    // the histogram is only cleared when it is used
+            for (int b = t; b < kBins0; b += kBlock) lh[b] = 0u;
+            __syncthreads();
+            lh_ready = true;
+        }
+        const int64_t begin = sd.begin, end = sd.end;
+        for (int s2 = st; s2 < seg_hi; ++s2) {
+            const int64_t a0 = s2 == st ? d0.a0 : sts[s2].a0;
+#pragma unroll 2
+            for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+                const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+                if (p0 >= end) continue;
+                uint32_t key[4];
+                bool ok[4];
+                leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
+            }
+        }
+        __syncthreads();
+        uint32_t* h = hist + static_cast<size_t>(cur) * kBins0;
+        for (int b = t; b < kBins0; b += kBlock) {
+            const uint32_t v = lh[b];
+            if (v) {
+                atomicAdd(&h[b], v);
+                lh[b] = 0u;
+            }
+        }
+        if (owner && t == 0) {
+            s.pending = 1;                                  // the next kernel's blocks search the histogram
+            state_at(state, cur) = s;
+        }
+        __syncthreads();                                    // the LDS words are reused for the block's next segment
+        st = seg_hi;
+    }
+}
+
+// What the level-1 pass writes when it also has to collect (see k_level).
+struct CollectOut {
+    uint32_t* wt_cnt;
+    uint64_t* sel_mask;
+    uint64_t* eq_mask;
+    uint2* cand;
+    uint32_t* st_cand_cnt;
+    uint32_t* full_flag;     // per segment: a slice overflowed, the kernels that follow work in full mode
+};
+
+// Levels 1 and 2 of the search, per segment: first the search of the previous level's histogram
+// if it is still pending (every block that holds supertiles of the segment does it for itself:
+// the histogram is complete since the previous kernel ended, and re-reading its 16 KB costs less
+// than a launch), then the histogram of the next digit of the leader's magnitude keys.
+// LEVEL 1: bits 18..7 of keys whose top 12 bits equal the chosen bucket; a segment whose level 1
+// was searched by k_level0 already (the steady state) is skipped.  LEVEL 2: last 7 bits of keys
+// matching 24 bits; the search follows in k_tilecount or k_find2.  Candidate mode reads the keys
+// from the candidate list, full mode recomputes them from the leader's vector.  The state comes
+// from state_in and goes, through the block that holds the segment's first supertile, to
+// state_out: no block reads what another block of the same kernel wrote.
+// LEVEL 1 is also the second full pass over the leader's vector for segments in candidate mode
+// whose list the predicted pass did not fill (no prediction, or one that missed): per wave tile,
+// keys above the level-0 bucket are members for sure, keys inside the bucket go to the
+// supertile's slice of the candidate list and are counted here directly.  A slice that overflows
+// (bucket keys clustered in one place) sends the whole segment back to full-pass mode for the
+// kernels that follow; this kernel's counts are complete either way.
+template <typename G, int LEVEL>
+__global__ void __launch_bounds__(kBlock)
+k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+        const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state_in,
+        SegState* __restrict__ state_out, const uint32_t* __restrict__ hist_prev, uint32_t* __restrict__ hist,
+        uint32_t* __restrict__ preds, CollectOut out)
+// in candidate mode out.cand and out.st_cand_cnt are read, when collecting they are written
+{
+    static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_level0");
+    static_assert(kCandSlice == 2 * kBlock, "two slice entries per thread");
+    constexpr int NB = LEVEL == 1 ? kBins1 : kBins2;
+    constexpr int NB_PREV = LEVEL == 1 ? kBins0 : kBins1;
+    constexpr int BITS_PREV = LEVEL == 1 ? kBits0 : kBits1;
+    __shared__ uint32_t lh[NB];
+    __shared__ uint32_t res[4];                             // found, digit, keys above it, its count
+    __shared__ uint32_t above[kWaves];
+
+    const int t = threadIdx.x, wave = t / kLanes, lane = t % kLanes;
+    const int st_lo = hist_block_lo(blockIdx.x, n_st, gridDim.x);
+    const int st_hi = hist_block_lo(static_cast<int64_t>(blockIdx.x) + 1, n_st, gridDim.x);
+
+    auto count = [&](uint32_t key, uint32_t prefix) {
+        if (LEVEL == 1) {
+            if ((key >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
+        } else {
+            if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
+        }
+    };
+
+    bool lh_ready = false;
+    // segment by segment: one that needs nothing from this level costs one look at its state
+    int st = st_lo;
+    while (st < st_hi) {
+        const StDesc d0 = sts[st];
+        const int cur = d0.seg;
+        const int seg_hi = d0.seg_st_end < st_hi ? d0.seg_st_end : st_hi;
+        SegState ss = state_at(state_in, cur);
+        const SegDesc sd = segs[cur];
+        const uint32_t went_full = LEVEL == 2 ? out.full_flag[cur] : 0u;
+        const bool owner = st == sd.st_first;               // this block passes the state on
+        if (went_full) ss.mode = kModeFull;
+        if (ss.done == 0 && ss.pending != 0) {              // block-uniform: the previous level's search
+            if (t == 0) res[0] = 0u;
+            uint32_t digit, n_digit, n_above;               // (search_digit's barrier orders the store above)
+            if (search_digit<NB_PREV>(hist_prev + static_cast<size_t>(cur) * NB_PREV, ss.k_rem, above, digit, n_digit,
+                                      n_above)) {
+                res[1] = digit;
+                res[2] = n_above;
+                res[3] = n_digit;
+                res[0] = 1u;
+            }
+            __syncthreads();
+            if (res[0]) {
+                ss.prefix = (ss.prefix << BITS_PREV) | res[1];
+                ss.k_rem -= res[2];
+                if (LEVEL == 1) {
+                    // the bucket's keys go to the candidate list if its slots can hold them
+                    const uint64_t slots = static_cast<uint64_t>(sd.st_count) * kCandSlice;
+                    ss.mode = res[3] <= slots ? kModeCand : kModeFull;
+                    if (owner && t == 0) preds[cur] = res[1] + 1u;   // prediction for the next step
+                }
+            } else {                                        // only if the counts were corrupted: nothing is selected
+                ss.done = 1;
+                if (LEVEL == 1 && owner && t == 0) preds[cur] = 0u;
+            }
+            ss.pending = 0;
+            __syncthreads();                                // res is reused for the block's next segment
+        }
+        if (ss.done != 0 || (LEVEL == 1 && ss.l1_done != 0)) {   // block-uniform: nothing to count
+            if (owner && t == 0) state_at(state_out, cur) = ss;
+            st = seg_hi;
+            continue;
+        }
+        if (!lh_ready) {                                    // the histogram is only cleared when it is used
+            for (int b = t; b < NB; b += kBlock) lh[b] = 0u;
+            __syncthreads();
+            lh_ready = true;
+        }
+        const uint32_t prefix = ss.prefix;
+        const bool from_list = ss.mode == kModeCand;
+        const bool collect = LEVEL == 1 && from_list && ss.collected == 0;
+        const int64_t begin = d0.begin, end = d0.end;
+        for (int s2 = st; s2 < seg_hi; ++s2) {
+            if (from_list && !collect) {   // keys of this supertile that were copied to the candidate list
+                const uint2* slice = out.cand + static_cast<size_t>(s2) * kCandSlice;
+                const uint32_t listed = out.st_cand_cnt[s2];
+                const uint32_t key0 = slice[t].x, key1 = slice[kBlock + t].x;   // requested with the count, used up to it
+                const uint32_t cnt = listed < kCandSlice ? listed : kCandSlice;
+                if (static_cast<uint32_t>(t) < cnt) count(key0, prefix);
+                if (static_cast<uint32_t>(kBlock + t) < cnt) count(key1, prefix);
+                continue;
+            }
+            const int64_t a0 = s2 == st ? d0.a0 : sts[s2].a0;
+            if constexpr (LEVEL == 1) {
+                if (collect) {   // block-uniform: no list yet, this pass makes it
+                    __shared__ uint32_t fill;
+                    __shared__ CollectStage stg;
+                    if (t == 0) fill = 0u;
+                    __syncthreads();
+                    uint2* slice = out.cand + static_cast<size_t>(s2) * kCandSlice;   // written directly: LDS is the histogram's
+                    for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+                        const int wt = it * kWaves + wave;
+                        const int64_t p0 = a0 + wt * kWaveTile + lane * kVec;
+                        uint32_t key[4] = {0, 0, 0, 0};
+                        bool ok[4] = {false, false, false, false};
+                        if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+                        uint32_t n_above;
+                        collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, nullptr, lh,
+                                            nullptr, 0u, n_above, stg, slice);
+                    }
+                    __syncthreads();
+                    collect_flush(stg, nullptr, static_cast<size_t>(s2) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask,
+                                  out.eq_mask, slice);
+                    if (t == 0) {
+                        const uint32_t n = fill;
+                        out.st_cand_cnt[s2] = n < kCandSlice ? n : kCandSlice;
+                        if (n > kCandSlice) out.full_flag[cur] = 1u;   // every overflowing block stores the same value
+                    }
+                    __syncthreads();   // the staging area is reused for the block's next supertile
+                    continue;
+                }
+            }
+#pragma unroll 2
+            for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+                const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+                if (p0 >= end) continue;
+                uint32_t key[4];
+                bool ok[4];
+                leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (ok[c]) count(key[c], prefix);
+            }
+        }
+        __syncthreads();                                    // flush my counts of the segment
+        uint32_t* h = hist + static_cast<size_t>(cur) * NB;
+        for (int b = t; b < NB; b += kBlock) {
+            const uint32_t v = lh[b];
+            if (v) {
+                atomicAdd(&h[b], v);
+                lh[b] = 0u;
+            }
+        }
+        if (owner && t == 0) {
+            if (LEVEL == 1) ss.pending = 1;                 // the next kernel's blocks search this histogram
+            state_at(state_out, cur) = ss;
+        }
+        __syncthreads();                                    // the histogram is reused for the block's next segment
+        st = seg_hi;
+    }
+}
+
+// The last search as a kernel of its own, one block per segment (see find_threshold for the other way).
+__global__ void __launch_bounds__(kBlock) k_find2(SegState* __restrict__ state, const uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t above[kWaves];
+    const int seg = blockIdx.x;
+    SegState s = state_at(state, seg);
+    if (s.done) return;
     uint32_t digit, n_digit, n_above;
-    if (search_digit<NB>(h, s.k_rem, above, digit, n_digit, n_above)) {
-        s.prefix = (s.prefix << BITS) | digit;
+    if (search_digit<kBins2>(hist + static_cast<size_t>(seg) * kBins2, s.k_rem, above, digit, n_digit, n_above)) {
+        s.prefix = (s.prefix << kBits2) | digit;
         s.k_rem -= n_above;
-        if (LEVEL == 0) {
-            // the bucket's keys go to the candidate list if its slots can hold them
-            const uint64_t slots = static_cast<uint64_t>(segs[seg].st_count) * kCandSlice;
-            s.mode = n_digit <= slots ? kModeCand : kModeFull;
-            preds[seg] = digit + 1;                         // prediction for the next step
-        }
-        if (LEVEL == 2) {
-            s.T = s.prefix;
-            s.q = s.k_rem;
-        }
-        state[seg] = s;
+        s.T = s.prefix;
+        s.q = s.k_rem;
+        state_at(state, seg) = s;
     }
 }
 
 // The last search of the threshold (7 key bits, 128 counters), done by every block that needs the
-// result instead of by a kernel of its own (k_find<2>, which is launched instead when there are so
+// result instead of by a kernel of its own (k_find2, which is launched instead when there are so
 // many blocks that their added barriers cost more than the launch): from the top of the histogram, the bin that holds the
 // k_rem-th largest key of the current 24-bit bucket.  All threads of the block call it; `bcast`
 // is three words of LDS.  Returns the threshold key T and sets q, the number of keys equal to T that
@@ -665,7 +661,7 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const uint2 ce_pre[2] = {slice[threadIdx.x], slice[kBlock + threadIdx.x]};
     const uint32_t cnt_pre = threadIdx.x < kTilesPerSuper ? wt_cnt[tile0 + threadIdx.x] : 0u;
     // second round trip: what the segment number addresses
-    const SegState ss = state[d.seg];
+    const SegState ss = state_at(state, d.seg);
     const uint32_t h2 = (hist2 && threadIdx.x < kBins2) ? hist2[static_cast<size_t>(d.seg) * kBins2 + threadIdx.x] : 0u;
     const int st_first = segs[d.seg].st_first;
     __shared__ uint32_t cnt[kTilesPerSuper];
@@ -674,8 +670,8 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     if (!ss.done && hist2) {                                // block-uniform; without hist2 a kernel has searched already
         T = find_threshold(h2, ss.prefix, ss.k_rem, bcast, q);
         if (st == st_first && threadIdx.x == 0) {           // for the tie quota of the slot pass
-            state[d.seg].T = T;
-            state[d.seg].q = q;
+            state_at(state, d.seg).T = T;
+            state_at(state, d.seg).q = q;
         }
     }
 
@@ -802,7 +798,7 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
     const uint32_t packed = lane < kTilesPerSuper ? wt_cnt[tile] : 0u;
     const int seg0 = OWN_SCAN ? sts[st0].seg : 0;
     const SegDesc sd = segs[d.seg];
-    const uint32_t q = state[d.seg].q;
+    const uint32_t q = state_at(state, d.seg).q;
     if (OWN_SCAN) {
         // all threads: totals of the supertiles between the start of the first supertile's segment and st0
         __shared__ uint32_t part_x[kWavesHere], part_y[kWavesHere];
