@@ -24,11 +24,7 @@ constexpr int kSlotsOwnScanBlock = 1024;         // threads of its blocks then (
 
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
 constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
-constexpr int kHistGridMax = 2048;
-// The histogram kernels split the supertiles evenly over their blocks: block b of g owns the
-// supertiles [hist_block_lo(b), hist_block_lo(b + 1)); g <= n_st, so no block is empty.
-__host__ __device__ inline int hist_block_lo(int64_t b, int n_st, int g) { return static_cast<int>(b * n_st / g); }
-inline int hist_grid(int n_st) { return n_st < kHistGridMax ? n_st : kHistGridMax; }
+constexpr int kHistGridMax = 2048;              // blocks of the search levels' kernels, plus at most one per tensor
 constexpr int kFoldLastSearchMaxSt = 12288;      // up to this many supertiles k_tilecount searches the last level itself
                                                  // (measured: +45 us over 122 K blocks against one launch of 4.5 us)
 constexpr int kCandSlice = 512;                  // candidate slots per supertile (1/16 of its positions)
@@ -51,8 +47,16 @@ struct StDesc {           // one per supertile; carries what the streaming kerne
     int32_t a0;           // first position, a multiple of 4 (may lie up to 3 before begin)
     int32_t begin, end;   // the segment's positions [begin, end)
     int32_t slot_end;     // one past the segment's last output slot
-    int32_t seg_st_end;   // one past the segment's last supertile
-    int32_t pad[2];
+    int32_t pad[3];
+};
+
+struct HistBlock {        // one block of the kernels of the search levels: consecutive supertiles of ONE segment
+    int32_t seg;
+    int32_t st_lo, st_hi; // supertiles [st_lo, st_hi)
+    int32_t owner;        // 1: holds the segment's first supertile; that block passes the segment's state on
+    int32_t a0;           // first position of supertile st_lo
+    int32_t begin, end;   // the segment's positions [begin, end)
+    int32_t pad;
 };
 
 struct ChunkDesc {        // one per scan chunk: up to kChunk consecutive supertiles of one segment

@@ -76,7 +76,7 @@ inline int64_t max_chunks(int64_t numel_max, int n_tensors_max)
 }
 
 struct WsLayout {
-    size_t segs, sts, chunks, preds, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask, eq_mask,
+    size_t segs, sts, chunks, hblocks, preds, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask, eq_mask,
         tile_slot, vals, best, total;
     // per-step counters and histograms: two copies of one zone, used alternately (offsets inside a copy)
     size_t zone[2], zone_bytes, z_overflow, z_p_used, z_full_flag, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
@@ -98,6 +98,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.segs = take(nt * sizeof(SegDesc));
     l.sts = take(nst * sizeof(StDesc));
     l.chunks = take(nch * sizeof(ChunkDesc));
+    l.hblocks = take((kHistGridMax + nt) * sizeof(HistBlock));
     l.preds = take(nt * sizeof(uint32_t));
     l.state = take(3 * nt * kStateStride);               // after level 0, after level 1, after level 2
     {
@@ -154,7 +155,7 @@ struct scalecom_ctx {
     WsLayout lay{};
     // tables of the layout used last, kept on the device until the layout changes
     std::vector<int64_t> cached_offsets, cached_ks, cached_chunks;
-    int n_st = 0, n_chunks = 0;
+    int n_st = 0, n_chunks = 0, n_hblocks = 0;
     int parity = 0;                  // which copy of the scratch zone the next step uses
     bool scratch_clean = false;      // false: both copies must be cleared before the next step
     int best_parity = 0;             // same scheme for the chunk-wise selector's per-chunk maxima
@@ -210,10 +211,11 @@ size_t pinned_bytes_for(int64_t numel_max, int n_tensors_max)
 {
     return align_up(sizeof(SegDesc) * static_cast<size_t>(n_tensors_max), 256) +
            align_up(sizeof(StDesc) * static_cast<size_t>(max_supertiles(numel_max, n_tensors_max)), 256) +
-           sizeof(ChunkDesc) * static_cast<size_t>(max_chunks(numel_max, n_tensors_max));
+           align_up(sizeof(ChunkDesc) * static_cast<size_t>(max_chunks(numel_max, n_tensors_max)), 256) +
+           sizeof(HistBlock) * (kHistGridMax + static_cast<size_t>(n_tensors_max));
 }
 
-// Rebuild and upload the segment, supertile and chunk tables if the layout differs from the cached one.
+// Rebuild and upload the segment, supertile, chunk and block tables if the layout differs from the cached one.
 scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* offsets, const int64_t* ks,
                               const int64_t* sel_chunks = nullptr)
 {
@@ -237,6 +239,8 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     StDesc* sts = reinterpret_cast<StDesc*>(ctx->pinned + st_off);
     const size_t ch_off = st_off + align_up(sizeof(StDesc) * static_cast<size_t>(st_cap), 256);
     ChunkDesc* chunks = reinterpret_cast<ChunkDesc*>(ctx->pinned + ch_off);
+    const size_t hb_off = ch_off + align_up(sizeof(ChunkDesc) * static_cast<size_t>(ch_cap), 256);
+    HistBlock* hblocks = reinterpret_cast<HistBlock*>(ctx->pinned + hb_off);
     int64_t n_st = 0, n_ch = 0, out = 0;
     for (int s = 0; s < n_tensors; ++s) {
         const int64_t b = offsets[s], e = offsets[s + 1];
@@ -249,8 +253,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
                           static_cast<int32_t>(n_ch), static_cast<int32_t>(n_chunks), static_cast<int32_t>(ch[s]), 0};
         for (int64_t j = 0; j < count; ++j)
             sts[n_st + j] = StDesc{s, static_cast<int32_t>(a_first + j * kSuper), static_cast<int32_t>(b),
-                                   static_cast<int32_t>(e), static_cast<int32_t>(out + ks[s]),
-                                   static_cast<int32_t>(n_st + count), {0, 0}};
+                                   static_cast<int32_t>(e), static_cast<int32_t>(out + ks[s]), {0, 0, 0}};
         for (int64_t c = 0; c < n_chunks; ++c)
             chunks[n_ch + c] = ChunkDesc{s, static_cast<int32_t>(n_st + c * kChunk),
                                          static_cast<int32_t>(std::min<int64_t>(kChunk, count - c * kChunk)), 0};
@@ -258,12 +261,30 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
         n_ch += n_chunks;
         out += ks[s];
     }
+    // blocks of the search levels' kernels: every segment's supertiles in runs of equal length, so
+    // that a block never holds supertiles of two segments
+    const int64_t per_block = std::max<int64_t>(1, (n_st + kHistGridMax - 1) / kHistGridMax);
+    int64_t n_hb = 0;
+    for (int s = 0; s < n_tensors; ++s) {
+        const int64_t first = segs[s].st_first, count = segs[s].st_count;
+        for (int64_t j = 0; j < count; j += per_block, ++n_hb)
+            hblocks[n_hb] = HistBlock{s,
+                                      static_cast<int32_t>(first + j),
+                                      static_cast<int32_t>(first + std::min(count, j + per_block)),
+                                      j == 0 ? 1 : 0,
+                                      sts[first + j].a0,
+                                      segs[s].begin,
+                                      segs[s].end,
+                                      0};
+    }
     SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.segs, segs, sizeof(SegDesc) * n_tensors, hipMemcpyHostToDevice,
                                ctx->stream));
     if (n_st > 0) {
         SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.sts, sts, sizeof(StDesc) * n_st, hipMemcpyHostToDevice,
                                    ctx->stream));
         SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.chunks, chunks, sizeof(ChunkDesc) * n_ch, hipMemcpyHostToDevice,
+                                   ctx->stream));
+        SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.hblocks, hblocks, sizeof(HistBlock) * n_hb, hipMemcpyHostToDevice,
                                    ctx->stream));
     }
     // predictions of the previous layout's buckets mean nothing for this one
@@ -274,6 +295,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     ctx->upload_pending = true;
     ctx->n_st = static_cast<int>(n_st);
     ctx->n_chunks = static_cast<int>(n_ch);
+    ctx->n_hblocks = static_cast<int>(n_hb);
     ctx->cached_offsets.assign(offsets, offsets + n_tensors + 1);
     ctx->cached_ks.assign(ks, ks + n_tensors);
     ctx->cached_chunks = ch;
@@ -326,6 +348,7 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     const SegDesc* segs = reinterpret_cast<const SegDesc*>(ws + l.segs);
     const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
     const ChunkDesc* chunks = reinterpret_cast<const ChunkDesc*>(ws + l.chunks);
+    const HistBlock* hblocks = reinterpret_cast<const HistBlock*>(ws + l.hblocks);
     // each level's kernel reads the state the previous one left and writes its own copy
     SegState* state0 = reinterpret_cast<SegState*>(ws + l.state);
     SegState* state1 = &state_at(state0, static_cast<size_t>(ctx->n_tensors_max));
@@ -358,17 +381,17 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
         const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
         k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.zone[0]), words);
     }
-    const int hgrid = hist_grid(n_st);      // the segments' block counts in the tables are those of this grid
+    const int hgrid = ctx->n_hblocks;       // one block per entry of the block table
     ctx->scratch_clean = false;             // until every kernel of this selection has been enqueued
     k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
                                            part, overflow, p_used, hist1_spec, next_zone, zone_words);
-    k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state0, hist0, preds, p_used, part, overflow,
+    k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, hist0, preds, p_used, part, overflow,
                                          hist1_spec);
     mark(1);
     const CollectOut collect_out{wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt, full_flag};
-    k_level<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state0, state1, hist0, hist1, preds,
+    k_level<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, state1, hist0, hist1, preds,
                                            collect_out);
-    k_level<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state1, state, hist1, hist2, preds,
+    k_level<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state1, state, hist1, hist2, preds,
                                            collect_out);
     // the last search: inside k_tilecount's blocks, or a kernel of its own when those are very many
     const bool fold_last = n_st <= kFoldLastSearchMaxSt;

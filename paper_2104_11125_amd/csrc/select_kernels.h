@@ -268,12 +268,13 @@ __device__ __forceinline__ bool search_digit(const uint32_t* __restrict__ h, uin
 // bucket itself, level 1 is searched right away on the counts that pass gathered for it.
 // Otherwise (no prediction, or one that failed) the blocks that hold the segment's supertiles count
 // the top 12 key bits of the leader's vector, and the search of that histogram is left to the
-// blocks of the next kernel (state.pending).  The block that holds the segment's first supertile
-// writes the state either way; no block reads what another block of the same kernel wrote.
+// blocks of the next kernel (state.pending).  One block per entry of the block table (supertiles
+// of one segment); the segment's first block writes the state either way, and no block reads what
+// another block of the same kernel wrote.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-         const StDesc* __restrict__ sts, int n_st, SegState* __restrict__ state, uint32_t* __restrict__ hist,
+         const HistBlock* __restrict__ hblocks, SegState* __restrict__ state, uint32_t* __restrict__ hist,
          uint32_t* __restrict__ preds, const uint32_t* __restrict__ p_used, const uint32_t* __restrict__ part,
          const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec)
 {
@@ -285,125 +286,103 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     static_assert(kPartSlots * kPartWords == 2 * kBlock, "two counter words per thread");
 
     const int t = threadIdx.x, wave = t / kLanes, lane = t % kLanes;
-    const int st_lo = hist_block_lo(blockIdx.x, n_st, gridDim.x);
-    const int st_hi = hist_block_lo(static_cast<int64_t>(blockIdx.x) + 1, n_st, gridDim.x);
-
-    bool lh_ready = false;
-    // walk the block's supertiles segment by segment: a segment that needs no histogram (the
-    // steady state) costs one look at its counters, not one per supertile
-    int st = st_lo;
-    while (st < st_hi) {
-        const StDesc d0 = sts[st];
-        const int cur = d0.seg;
-        const int seg_hi = d0.seg_st_end < st_hi ? d0.seg_st_end : st_hi;
-        // everything the segment number addresses is requested at once
-        const uint32_t* my_part = part + static_cast<size_t>(cur) * kPartSlots * kPartWords;
-        const SegDesc sd = segs[cur];
-        const uint32_t p = p_used[cur];
-        const uint32_t ov = overflow[cur];
-        const uint32_t w0 = my_part[t], w1 = my_part[kBlock + t];
-        const bool owner = st == sd.st_first;               // this block writes the state if no histogram is needed
-        const uint32_t k = static_cast<uint32_t>(sd.k);
-        SegState s{};                                       // every field is written each step
-        s.k_rem = k;
-        s.T = 0xffffffffu;                                  // above every key: nothing is a member
-        s.mode = kModeFull;
-        if (k == 0) {                                       // block-uniform: an empty index set
-            if (owner && t == 0) {
-                s.done = 1;
-                state_at(state, cur) = s;
-            }
-            st = seg_hi;
-            continue;
-        }
-        if (t == 0) {
-            res[0] = 0u;
-            flag = 0u;
-        }
-        if (p != 0) {                                       // block-uniform: sum the slotted copies of the counters
-            if (t < kPartWords) tot_s[t] = 0u;
-            __syncthreads();
-            if (w0) atomicAdd(&tot_s[t % kPartWords], w0);
-            if (w1) atomicAdd(&tot_s[(kBlock + t) % kPartWords], w1);
-            __syncthreads();
-            if (t == 0) {
-                uint32_t tot[1 + kWindow], digit = 0, k_rem = 0;
-                for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
-                if (spec_resolve(tot, ov != 0, p, k, digit, k_rem)) {
-                    res[0] = 1u;
-                    res[1] = digit;
-                    res[2] = k_rem;
-                }
-            }
-        }
-        __syncthreads();
-        if (res[0]) {                                       // block-uniform: the prediction held
-            if (owner) {
-                s.prefix = res[1];
-                s.k_rem = res[2];
-                s.mode = kModeCand;
-                s.collected = 1;
-                if (s.prefix == p - 1u) {                   // the predicted bucket: its second digits are counted
-                    uint32_t digit, n_digit, n_above;
-                    if (search_digit<kBins1>(hist1_spec + static_cast<size_t>(cur) * kBins1, s.k_rem, above, digit,
-                                                    n_digit, n_above)) {
-                        res[1] = (s.prefix << kBits1) | digit;
-                        res[2] = s.k_rem - n_above;
-                        flag = 1u;
-                    }
-                    __syncthreads();
-                }
-                if (t == 0) {
-                    preds[cur] = s.prefix + 1u;             // prediction for the next step
-                    if (flag) {   // (no thread finds the bin only if the counts were corrupted: then level 1 runs from the list)
-                        s.prefix = res[1];
-                        s.k_rem = res[2];
-                        s.l1_done = 1;
-                    }
-                    state_at(state, cur) = s;
-                }
-            }
-            __syncthreads();                                // the LDS words are reused for the block's next segment
-            st = seg_hi;
-            continue;
-        }
-
-        // no prediction, or one that failed: count the top digits of my part of the segment
-        if (!lh_ready) {                                    // the histogram is only cleared when it is used
-            for (int b = t; b < kBins0; b += kBlock) lh[b] = 0u;
-            __syncthreads();
-            lh_ready = true;
-        }
-        const int64_t begin = sd.begin, end = sd.end;
-        for (int s2 = st; s2 < seg_hi; ++s2) {
-            const int64_t a0 = s2 == st ? d0.a0 : sts[s2].a0;
-#pragma unroll 2
-            for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-                const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
-                if (p0 >= end) continue;
-                uint32_t key[4];
-                bool ok[4];
-                leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
-            }
-        }
-        __syncthreads();
-        uint32_t* h = hist + static_cast<size_t>(cur) * kBins0;
-        for (int b = t; b < kBins0; b += kBlock) {
-            const uint32_t v = lh[b];
-            if (v) {
-                atomicAdd(&h[b], v);
-                lh[b] = 0u;
-            }
-        }
+    const HistBlock hb = hblocks[blockIdx.x];
+    const int cur = hb.seg;
+    const bool owner = hb.owner != 0;                       // this block writes the segment's state
+    // everything the segment number addresses is requested at once
+    const uint32_t* my_part = part + static_cast<size_t>(cur) * kPartSlots * kPartWords;
+    const SegDesc sd = segs[cur];
+    const uint32_t p = p_used[cur];
+    const uint32_t ov = overflow[cur];
+    const uint32_t w0 = my_part[t], w1 = my_part[kBlock + t];
+    const uint32_t k = static_cast<uint32_t>(sd.k);
+    SegState s{};                                           // every field is written each step
+    s.k_rem = k;
+    s.T = 0xffffffffu;                                      // above every key: nothing is a member
+    s.mode = kModeFull;
+    if (k == 0) {                                           // block-uniform: an empty index set
         if (owner && t == 0) {
-            s.pending = 1;                                  // the next kernel's blocks search the histogram
+            s.done = 1;
             state_at(state, cur) = s;
         }
-        __syncthreads();                                    // the LDS words are reused for the block's next segment
-        st = seg_hi;
+        return;
+    }
+    if (t == 0) {
+        res[0] = 0u;
+        flag = 0u;
+    }
+    if (p != 0) {                                           // block-uniform: sum the slotted copies of the counters
+        if (t < kPartWords) tot_s[t] = 0u;
+        __syncthreads();
+        if (w0) atomicAdd(&tot_s[t % kPartWords], w0);
+        if (w1) atomicAdd(&tot_s[(kBlock + t) % kPartWords], w1);
+        __syncthreads();
+        if (t == 0) {
+            uint32_t tot[1 + kWindow], digit = 0, k_rem = 0;
+            for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
+            if (spec_resolve(tot, ov != 0, p, k, digit, k_rem)) {
+                res[0] = 1u;
+                res[1] = digit;
+                res[2] = k_rem;
+            }
+        }
+    }
+    __syncthreads();
+    if (res[0]) {                                           // block-uniform: the prediction held
+        if (!owner) return;
+        s.prefix = res[1];
+        s.k_rem = res[2];
+        s.mode = kModeCand;
+        s.collected = 1;
+        if (s.prefix == p - 1u) {                           // the predicted bucket: its second digits are counted
+            uint32_t digit, n_digit, n_above;
+            if (search_digit<kBins1>(hist1_spec + static_cast<size_t>(cur) * kBins1, s.k_rem, above, digit, n_digit,
+                                     n_above)) {
+                res[1] = (s.prefix << kBits1) | digit;
+                res[2] = s.k_rem - n_above;
+                flag = 1u;
+            }
+            __syncthreads();
+        }
+        if (t == 0) {
+            preds[cur] = s.prefix + 1u;                     // prediction for the next step
+            if (flag) {   // (no thread finds the bin only if the counts were corrupted: then level 1 runs from the list)
+                s.prefix = res[1];
+                s.k_rem = res[2];
+                s.l1_done = 1;
+            }
+            state_at(state, cur) = s;
+        }
+        return;
+    }
+
+    // no prediction, or one that failed: count the top digits of my part of the segment
+    for (int b = t; b < kBins0; b += kBlock) lh[b] = 0u;
+    __syncthreads();
+    const int64_t begin = hb.begin, end = hb.end;
+    for (int s2 = hb.st_lo; s2 < hb.st_hi; ++s2) {
+        const int64_t a0 = static_cast<int64_t>(hb.a0) + static_cast<int64_t>(s2 - hb.st_lo) * kSuper;
+#pragma unroll 2
+        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
+            const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+            if (p0 >= end) continue;
+            uint32_t key[4];
+            bool ok[4];
+            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t* h = hist + static_cast<size_t>(cur) * kBins0;
+    for (int b = t; b < kBins0; b += kBlock) {
+        const uint32_t v = lh[b];
+        if (v) atomicAdd(&h[b], v);
+    }
+    if (owner && t == 0) {
+        s.pending = 1;                                      // the next kernel's blocks search the histogram
+        state_at(state, cur) = s;
     }
 }
 
@@ -417,16 +396,16 @@ struct CollectOut {
     uint32_t* full_flag;     // per segment: a slice overflowed, the kernels that follow work in full mode
 };
 
-// Levels 1 and 2 of the search, per segment: first the search of the previous level's histogram
-// if it is still pending (every block that holds supertiles of the segment does it for itself:
-// the histogram is complete since the previous kernel ended, and re-reading its 16 KB costs less
-// than a launch), then the histogram of the next digit of the leader's magnitude keys.
+// Levels 1 and 2 of the search, one block per entry of the block table: first the search of the
+// previous level's histogram if it is still pending (every block of the segment does it for
+// itself: the histogram is complete since the previous kernel ended, and re-reading its 16 KB
+// costs less than a launch), then the histogram of the next digit of the leader's magnitude keys.
 // LEVEL 1: bits 18..7 of keys whose top 12 bits equal the chosen bucket; a segment whose level 1
 // was searched by k_level0 already (the steady state) is skipped.  LEVEL 2: last 7 bits of keys
 // matching 24 bits; the search follows in k_tilecount or k_find2.  Candidate mode reads the keys
 // from the candidate list, full mode recomputes them from the leader's vector.  The state comes
-// from state_in and goes, through the block that holds the segment's first supertile, to
-// state_out: no block reads what another block of the same kernel wrote.
+// from state_in and goes, through the segment's first block, to state_out: no block reads what
+// another block of the same kernel wrote.
 // LEVEL 1 is also the second full pass over the leader's vector for segments in candidate mode
 // whose list the predicted pass did not fill (no prediction, or one that missed): per wave tile,
 // keys above the level-0 bucket are members for sure, keys inside the bucket go to the
@@ -436,23 +415,28 @@ struct CollectOut {
 template <typename G, int LEVEL>
 __global__ void __launch_bounds__(kBlock)
 k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-        const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state_in,
-        SegState* __restrict__ state_out, const uint32_t* __restrict__ hist_prev, uint32_t* __restrict__ hist,
-        uint32_t* __restrict__ preds, CollectOut out)
+        const HistBlock* __restrict__ hblocks, const SegState* __restrict__ state_in, SegState* __restrict__ state_out,
+        const uint32_t* __restrict__ hist_prev, uint32_t* __restrict__ hist, uint32_t* __restrict__ preds,
+        CollectOut out)
 // in candidate mode out.cand and out.st_cand_cnt are read, when collecting they are written
 {
     static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_level0");
-    static_assert(kCandSlice == 2 * kBlock, "two slice entries per thread");
     constexpr int NB = LEVEL == 1 ? kBins1 : kBins2;
     constexpr int NB_PREV = LEVEL == 1 ? kBins0 : kBins1;
     constexpr int BITS_PREV = LEVEL == 1 ? kBits0 : kBits1;
     __shared__ uint32_t lh[NB];
     __shared__ uint32_t res[4];                             // found, digit, keys above it, its count
     __shared__ uint32_t above[kWaves];
+    __shared__ uint32_t cnt_s[kBlock];                      // candidate counts of up to kBlock supertiles
 
     const int t = threadIdx.x, wave = t / kLanes, lane = t % kLanes;
-    const int st_lo = hist_block_lo(blockIdx.x, n_st, gridDim.x);
-    const int st_hi = hist_block_lo(static_cast<int64_t>(blockIdx.x) + 1, n_st, gridDim.x);
+    const HistBlock hb = hblocks[blockIdx.x];
+    const int cur = hb.seg;
+    const bool owner = hb.owner != 0;                       // this block passes the segment's state on
+    SegState ss = state_at(state_in, cur);
+    const int st_count = segs[cur].st_count;
+    const uint32_t went_full = LEVEL == 2 ? out.full_flag[cur] : 0u;
+    if (went_full) ss.mode = kModeFull;
 
     auto count = [&](uint32_t key, uint32_t prefix) {
         if (LEVEL == 1) {
@@ -462,70 +446,59 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
         }
     };
 
-    bool lh_ready = false;
-    // segment by segment: one that needs nothing from this level costs one look at its state
-    int st = st_lo;
-    while (st < st_hi) {
-        const StDesc d0 = sts[st];
-        const int cur = d0.seg;
-        const int seg_hi = d0.seg_st_end < st_hi ? d0.seg_st_end : st_hi;
-        SegState ss = state_at(state_in, cur);
-        const SegDesc sd = segs[cur];
-        const uint32_t went_full = LEVEL == 2 ? out.full_flag[cur] : 0u;
-        const bool owner = st == sd.st_first;               // this block passes the state on
-        if (went_full) ss.mode = kModeFull;
-        if (ss.done == 0 && ss.pending != 0) {              // block-uniform: the previous level's search
-            if (t == 0) res[0] = 0u;
-            uint32_t digit, n_digit, n_above;               // (search_digit's barrier orders the store above)
-            if (search_digit<NB_PREV>(hist_prev + static_cast<size_t>(cur) * NB_PREV, ss.k_rem, above, digit, n_digit,
-                                      n_above)) {
-                res[1] = digit;
-                res[2] = n_above;
-                res[3] = n_digit;
-                res[0] = 1u;
+    if (ss.done == 0 && ss.pending != 0) {                  // block-uniform: the previous level's search
+        if (t == 0) res[0] = 0u;
+        uint32_t digit, n_digit, n_above;                   // (search_digit's barrier orders the store above)
+        if (search_digit<NB_PREV>(hist_prev + static_cast<size_t>(cur) * NB_PREV, ss.k_rem, above, digit, n_digit,
+                                  n_above)) {
+            res[1] = digit;
+            res[2] = n_above;
+            res[3] = n_digit;
+            res[0] = 1u;
+        }
+        __syncthreads();
+        if (res[0]) {
+            ss.prefix = (ss.prefix << BITS_PREV) | res[1];
+            ss.k_rem -= res[2];
+            if (LEVEL == 1) {
+                // the bucket's keys go to the candidate list if its slots can hold them
+                const uint64_t slots = static_cast<uint64_t>(st_count) * kCandSlice;
+                ss.mode = res[3] <= slots ? kModeCand : kModeFull;
+                if (owner && t == 0) preds[cur] = res[1] + 1u;   // prediction for the next step
             }
+        } else {                                            // only if the counts were corrupted: nothing is selected
+            ss.done = 1;
+            if (LEVEL == 1 && owner && t == 0) preds[cur] = 0u;
+        }
+        ss.pending = 0;
+    }
+    if (ss.done != 0 || (LEVEL == 1 && ss.l1_done != 0)) {  // block-uniform: nothing to count
+        if (owner && t == 0) state_at(state_out, cur) = ss;
+        return;
+    }
+    for (int b = t; b < NB; b += kBlock) lh[b] = 0u;
+    __syncthreads();
+    const uint32_t prefix = ss.prefix;
+    const bool from_list = ss.mode == kModeCand;
+    const bool collect = LEVEL == 1 && from_list && ss.collected == 0;
+    const int64_t begin = hb.begin, end = hb.end;
+    if (from_list && !collect) {
+        // keys that were copied to the candidate list: the slices of consecutive supertiles are
+        // consecutive in memory, so the block's supertiles are one array of slots; the supertiles'
+        // counts are fetched first (one per thread), and then no load waits for another
+        for (int b0 = hb.st_lo; b0 < hb.st_hi; b0 += kBlock) {
+            const int nb = hb.st_hi - b0 < kBlock ? hb.st_hi - b0 : kBlock;
+            if (t < nb) cnt_s[t] = out.st_cand_cnt[b0 + t];             // at most kCandSlice (stored clamped)
             __syncthreads();
-            if (res[0]) {
-                ss.prefix = (ss.prefix << BITS_PREV) | res[1];
-                ss.k_rem -= res[2];
-                if (LEVEL == 1) {
-                    // the bucket's keys go to the candidate list if its slots can hold them
-                    const uint64_t slots = static_cast<uint64_t>(sd.st_count) * kCandSlice;
-                    ss.mode = res[3] <= slots ? kModeCand : kModeFull;
-                    if (owner && t == 0) preds[cur] = res[1] + 1u;   // prediction for the next step
-                }
-            } else {                                        // only if the counts were corrupted: nothing is selected
-                ss.done = 1;
-                if (LEVEL == 1 && owner && t == 0) preds[cur] = 0u;
-            }
-            ss.pending = 0;
-            __syncthreads();                                // res is reused for the block's next segment
-        }
-        if (ss.done != 0 || (LEVEL == 1 && ss.l1_done != 0)) {   // block-uniform: nothing to count
-            if (owner && t == 0) state_at(state_out, cur) = ss;
-            st = seg_hi;
-            continue;
-        }
-        if (!lh_ready) {                                    // the histogram is only cleared when it is used
-            for (int b = t; b < NB; b += kBlock) lh[b] = 0u;
+            const uint2* sl = out.cand + static_cast<size_t>(b0) * kCandSlice;
+#pragma unroll 4
+            for (int i = t; i < nb * kCandSlice; i += kBlock)
+                if (static_cast<uint32_t>(i % kCandSlice) < cnt_s[i / kCandSlice]) count(sl[i].x, prefix);
             __syncthreads();
-            lh_ready = true;
         }
-        const uint32_t prefix = ss.prefix;
-        const bool from_list = ss.mode == kModeCand;
-        const bool collect = LEVEL == 1 && from_list && ss.collected == 0;
-        const int64_t begin = d0.begin, end = d0.end;
-        for (int s2 = st; s2 < seg_hi; ++s2) {
-            if (from_list && !collect) {   // keys of this supertile that were copied to the candidate list
-                const uint2* slice = out.cand + static_cast<size_t>(s2) * kCandSlice;
-                const uint32_t listed = out.st_cand_cnt[s2];
-                const uint32_t key0 = slice[t].x, key1 = slice[kBlock + t].x;   // requested with the count, used up to it
-                const uint32_t cnt = listed < kCandSlice ? listed : kCandSlice;
-                if (static_cast<uint32_t>(t) < cnt) count(key0, prefix);
-                if (static_cast<uint32_t>(kBlock + t) < cnt) count(key1, prefix);
-                continue;
-            }
-            const int64_t a0 = s2 == st ? d0.a0 : sts[s2].a0;
+    } else {
+        for (int s2 = hb.st_lo; s2 < hb.st_hi; ++s2) {
+            const int64_t a0 = static_cast<int64_t>(hb.a0) + static_cast<int64_t>(s2 - hb.st_lo) * kSuper;
             if constexpr (LEVEL == 1) {
                 if (collect) {   // block-uniform: no list yet, this pass makes it
                     __shared__ uint32_t fill;
@@ -567,21 +540,16 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                     if (ok[c]) count(key[c], prefix);
             }
         }
-        __syncthreads();                                    // flush my counts of the segment
-        uint32_t* h = hist + static_cast<size_t>(cur) * NB;
-        for (int b = t; b < NB; b += kBlock) {
-            const uint32_t v = lh[b];
-            if (v) {
-                atomicAdd(&h[b], v);
-                lh[b] = 0u;
-            }
-        }
-        if (owner && t == 0) {
-            if (LEVEL == 1) ss.pending = 1;                 // the next kernel's blocks search this histogram
-            state_at(state_out, cur) = ss;
-        }
-        __syncthreads();                                    // the histogram is reused for the block's next segment
-        st = seg_hi;
+    }
+    __syncthreads();                                        // flush my counts of the segment
+    uint32_t* h = hist + static_cast<size_t>(cur) * NB;
+    for (int b = t; b < NB; b += kBlock) {
+        const uint32_t v = lh[b];
+        if (v) atomicAdd(&h[b], v);
+    }
+    if (owner && t == 0) {
+        if (LEVEL == 1) ss.pending = 1;                     // the next kernel's blocks search this histogram
+        state_at(state_out, cur) = ss;
     }
 }
 
