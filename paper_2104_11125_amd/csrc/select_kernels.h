@@ -28,13 +28,14 @@ struct CollectStage {       // LDS staging of one supertile's masks and tile cou
 // digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice
 // `cand_dst` (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if
 // `wc` is given, counted per digit there, and, if `lh1` is given (then lo == hi), per second digit
-// there, and, if `h1_spec` is given, those with top digit `center` per second digit there (in
-// memory: the atomics return nothing and drain behind the streaming loads).  Called by all lanes
-// of a wave; n_above is the same in every lane.
+// there, and, if `h1_spec` is given (then `wc` is too), those of the 2^19 keys from `spec_base` on
+// per 128 keys there (in memory: the atomics return nothing and drain behind the streaming loads),
+// and those beyond these in wc[kWindow].  Called by all lanes of a wave; n_above is the same in
+// every lane.
 template <bool ALL_OK>
 __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
                                              uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* wc,
-                                             uint32_t* lh1, uint32_t* h1_spec, uint32_t center, uint32_t& n_above,
+                                             uint32_t* lh1, uint32_t* h1_spec, uint32_t spec_base, uint32_t& n_above,
                                              CollectStage& stg, uint2* cand_dst)
 {
     // top digit > hi  <=>  key >= (hi + 1) << 19;  lo <= top digit <= hi  <=>  key - (lo << 19) < span
@@ -71,8 +72,13 @@ __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool o
             if (rank < kCandSlice) cand_dst[rank] = make_uint2(key[c], p0 + c);
             if (wc) atomicAdd(&wc[(key[c] >> (kBits1 + kBits2)) - lo], 1u);
             if (lh1) atomicAdd(&lh1[(key[c] >> kBits2) & (kBins1 - 1)], 1u);   // counted whether or not it is listed
-            if (h1_spec && (key[c] >> (kBits1 + kBits2)) == center)
-                atomicAdd(&h1_spec[(key[c] >> kBits2) & (kBins1 - 1)], 1u);
+            if (h1_spec && key[c] >= spec_base) {
+                const uint32_t r = key[c] - spec_base;
+                if (r < kSpecSpan)
+                    atomicAdd(&h1_spec[r >> kBits2], 1u);
+                else
+                    atomicAdd(&wc[kWindow], 1u);
+            }
             ++rank;
         }
     }
@@ -108,7 +114,7 @@ __device__ __forceinline__ void collect_flush(const CollectStage& stg, const uin
 template <typename G, bool INSIDE>
 __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                                                     const StDesc& d, uint32_t lo, uint32_t hi, int wave, int lane,
-                                                    uint32_t* fill, uint32_t* wc, uint32_t* h1_spec, uint32_t center,
+                                                    uint32_t* fill, uint32_t* wc, uint32_t* h1_spec, uint32_t spec_base,
                                                     CollectStage& stg, uint2* cand_stage)
 {
     constexpr int kIters = kTilesPerSuper / kWaves;
@@ -143,7 +149,7 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
             }
         }
         uint32_t n_above;
-        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, h1_spec, center, n_above, stg,
+        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, h1_spec, spec_base, n_above, stg,
                              cand_stage);
         above_acc += n_above;
         m_cur = m_nxt;
@@ -157,10 +163,11 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
 // that carry a prediction of their threshold bucket (the bucket found in the previous step).
 // ONE pass, no histogram: keys whose top digit lies above a 5-digit window around the
 // prediction are members for sure (counted per tile, marked in the mask), keys inside the
-// window go to the candidate list and are counted per digit; those of the predicted bucket
-// itself, where the threshold lies in most steps, are also counted per second digit.  If the
-// counts show afterwards that the k-th largest key fell inside the window, the threshold bucket
-// is known exactly and no other full pass over the leader is needed.  The prediction only decides
+// window go to the candidate list and are counted per digit; those of the 2^19 keys around the
+// previous step's threshold, where the threshold lies again in most steps, are also counted per
+// 128 keys (the resolution of the search's second level).  If the counts show afterwards that the
+// k-th largest key fell inside the window, the threshold bucket is known exactly and no other full
+// pass over the leader is needed; if it fell among those 2^19 keys, level 1 is known too.  The prediction only decides
 // how much work is done, never what is selected.  One block per supertile.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
@@ -180,15 +187,25 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
 
     const int st = blockIdx.x;
     const StDesc d = sts[st];
-    const uint32_t p = preds[d.seg];                        // 0: none, else predicted bucket + 1
+    const uint32_t p = preds[2 * d.seg];                    // 0: none, else predicted bucket + 1
+    const uint32_t t24 = preds[2 * d.seg + 1];              // the previous threshold's top 24 bits
     const SegDesc sd = segs[d.seg];
     if (p == 0 || sd.k == 0) return;
-    // the prediction this step works with, for the kernel that checks it (preds is rewritten there)
-    if (st == sd.st_first && threadIdx.x == 0) p_used[d.seg] = p;
     const uint32_t lo = window_lo(p), hi = window_hi(p);
+    // the 2^19 keys counted per 128: centred on the previous threshold, inside the window
+    const uint32_t mid = (t24 << kBits2) | (kBins2 / 2);
+    const uint32_t spec_base = mid > kSpecSpan / 2 ? (mid - kSpecSpan / 2) & ~static_cast<uint32_t>(kBins2 - 1) : 0u;
+    const bool spec_ok = spec_base >= (lo << (kBits1 + kBits2)) &&
+                         static_cast<uint64_t>(spec_base) + kSpecSpan <= (static_cast<uint64_t>(hi) + 1u) << (kBits1 + kBits2);
+    // the prediction this step works with, for the kernel that checks it (preds is rewritten there)
+    if (st == sd.st_first && threadIdx.x == 0) {
+        p_used[2 * d.seg] = p;
+        p_used[2 * d.seg + 1] = spec_ok ? spec_base : kNoSpec;
+    }
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
     __shared__ uint32_t fill;
-    __shared__ uint32_t acc[kPartWords];                    // [0] above the window, [1 + d] per window digit
+    __shared__ uint32_t acc[kPartWords];                    // [0] above the window, [1 + d] per window digit, ...
+    static_assert(kWindow + 2 <= kPartWords, "above, the window's digits, beyond the finely counted keys");
     __shared__ CollectStage stg;
     __shared__ uint2 cand_stage[kCandSlice];
     if (threadIdx.x == 0) fill = 0u;
@@ -196,13 +213,13 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     __syncthreads();
 
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-    uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1;
+    uint32_t* h1 = spec_ok ? hist1_spec + static_cast<size_t>(d.seg) * kBins1 : nullptr;
     uint32_t above_acc;
     if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
-        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, p - 1u, stg,
+        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, spec_base, stg,
                                              cand_stage);
     else
-        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, p - 1u, stg,
+        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, spec_base, stg,
                                               cand_stage);
     if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
     __syncthreads();
@@ -212,7 +229,7 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
         st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
         if (n > kCandSlice) overflow[d.seg] = 1u;           // every overflowing block stores the same value
     }
-    if (threadIdx.x <= kWindow) {
+    if (threadIdx.x <= kWindow + 1) {                       // [1 + kWindow]: beyond the keys counted per 128
         const uint32_t v = acc[threadIdx.x];
         if (v)
             atomicAdd(&part[(static_cast<size_t>(d.seg) * kPartSlots + st % kPartSlots) * kPartWords + threadIdx.x], v);
@@ -264,8 +281,8 @@ __device__ __forceinline__ bool search_digit(const uint32_t* __restrict__ h, uin
 }
 
 // Level 0 of the search, for every segment: did the predicted pass see the k-th largest key inside
-// its window?  Then the segment's bucket is known without a histogram, and if it is the predicted
-// bucket itself, level 1 is searched right away on the counts that pass gathered for it.
+// its window?  Then the segment's bucket is known without a histogram, and if the key is one of the
+// 2^19 keys that pass counted per 128, level 1 is searched right away on those counts.
 // Otherwise (no prediction, or one that failed) the blocks that hold the segment's supertiles count
 // the top 12 key bits of the leader's vector, and the search of that histogram is left to the
 // blocks of the next kernel (state.pending).  One block per entry of the block table (supertiles
@@ -292,7 +309,8 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     // everything the segment number addresses is requested at once
     const uint32_t* my_part = part + static_cast<size_t>(cur) * kPartSlots * kPartWords;
     const SegDesc sd = segs[cur];
-    const uint32_t p = p_used[cur];
+    const uint32_t p = p_used[2 * cur];
+    const uint32_t spec_base = p_used[2 * cur + 1];
     const uint32_t ov = overflow[cur];
     const uint32_t w0 = my_part[t], w1 = my_part[kBlock + t];
     const uint32_t k = static_cast<uint32_t>(sd.k);
@@ -334,22 +352,25 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         s.k_rem = res[2];
         s.mode = kModeCand;
         s.collected = 1;
-        if (s.prefix == p - 1u) {                           // the predicted bucket: its second digits are counted
-            uint32_t digit, n_digit, n_above;
-            if (search_digit<kBins1>(hist1_spec + static_cast<size_t>(cur) * kBins1, s.k_rem, above, digit, n_digit,
+        // keys beyond the finely counted ones: those above the window and those inside it past the 2^19
+        const uint32_t beyond = tot_s[0] + tot_s[1 + kWindow];
+        if (spec_base != kNoSpec && k > beyond) {           // block-uniform: is the key among the finely counted ones?
+            uint32_t bin, n_bin, n_above;
+            if (search_digit<kBins1>(hist1_spec + static_cast<size_t>(cur) * kBins1, k - beyond, above, bin, n_bin,
                                      n_above)) {
-                res[1] = (s.prefix << kBits1) | digit;
-                res[2] = s.k_rem - n_above;
+                res[1] = (spec_base >> kBits2) + bin;       // the key's top 24 bits
+                res[2] = k - beyond - n_above;
                 flag = 1u;
             }
             __syncthreads();
         }
         if (t == 0) {
-            preds[cur] = s.prefix + 1u;                     // prediction for the next step
-            if (flag) {   // (no thread finds the bin only if the counts were corrupted: then level 1 runs from the list)
+            preds[2 * cur] = s.prefix + 1u;                 // prediction for the next step
+            if (flag) {   // otherwise the key lies elsewhere in the window: level 1 runs from the list
                 s.prefix = res[1];
                 s.k_rem = res[2];
                 s.l1_done = 1;
+                preds[2 * cur + 1] = res[1];
             }
             state_at(state, cur) = s;
         }
@@ -427,9 +448,8 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     __shared__ uint32_t lh[NB];
     __shared__ uint32_t res[4];                             // found, digit, keys above it, its count
     __shared__ uint32_t above[kWaves];
-    __shared__ uint32_t cnt_s[kBlock];                      // candidate counts of up to kBlock supertiles
 
-    const int t = threadIdx.x, wave = t / kLanes, lane = t % kLanes;
+    const int t = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(t / kLanes), lane = t % kLanes;
     const HistBlock hb = hblocks[blockIdx.x];
     const int cur = hb.seg;
     const bool owner = hb.owner != 0;                       // this block passes the segment's state on
@@ -464,11 +484,13 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                 // the bucket's keys go to the candidate list if its slots can hold them
                 const uint64_t slots = static_cast<uint64_t>(st_count) * kCandSlice;
                 ss.mode = res[3] <= slots ? kModeCand : kModeFull;
-                if (owner && t == 0) preds[cur] = res[1] + 1u;   // prediction for the next step
+                if (owner && t == 0) preds[2 * cur] = res[1] + 1u;   // prediction for the next step
+            } else if (owner && t == 0) {
+                preds[2 * cur + 1] = ss.prefix;             // where the next step counts finely
             }
         } else {                                            // only if the counts were corrupted: nothing is selected
             ss.done = 1;
-            if (LEVEL == 1 && owner && t == 0) preds[cur] = 0u;
+            if (LEVEL == 1 && owner && t == 0) preds[2 * cur] = 0u;
         }
         ss.pending = 0;
     }
@@ -483,18 +505,25 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     const bool collect = LEVEL == 1 && from_list && ss.collected == 0;
     const int64_t begin = hb.begin, end = hb.end;
     if (from_list && !collect) {
-        // keys that were copied to the candidate list: the slices of consecutive supertiles are
-        // consecutive in memory, so the block's supertiles are one array of slots; the supertiles'
-        // counts are fetched first (one per thread), and then no load waits for another
-        for (int b0 = hb.st_lo; b0 < hb.st_hi; b0 += kBlock) {
-            const int nb = hb.st_hi - b0 < kBlock ? hb.st_hi - b0 : kBlock;
-            if (t < nb) cnt_s[t] = out.st_cand_cnt[b0 + t];             // at most kCandSlice (stored clamped)
-            __syncthreads();
-            const uint2* sl = out.cand + static_cast<size_t>(b0) * kCandSlice;
-#pragma unroll 4
-            for (int i = t; i < nb * kCandSlice; i += kBlock)
-                if (static_cast<uint32_t>(i % kCandSlice) < cnt_s[i / kCandSlice]) count(sl[i].x, prefix);
-            __syncthreads();
+        // keys that were copied to the candidate list, one wave per supertile: the count and the first
+        // 64 slots (most supertiles list fewer keys) of four supertiles are requested at once, so
+        // that a block with many supertiles does not wait for one round trip after the other
+        constexpr int kAhead = 4;
+        for (int s0 = hb.st_lo + wave; s0 < hb.st_hi; s0 += kAhead * kWaves) {
+            uint32_t cnt[kAhead], key0[kAhead];
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) {
+                const int s2 = s0 + j * kWaves;
+                const bool have = s2 < hb.st_hi;            // wave-uniform
+                cnt[j] = have ? out.st_cand_cnt[s2] : 0u;   // at most kCandSlice (stored clamped)
+                key0[j] = have ? out.cand[static_cast<size_t>(s2) * kCandSlice + lane].x : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) {
+                const uint2* sl = out.cand + static_cast<size_t>(s0 + j * kWaves) * kCandSlice;
+                if (static_cast<uint32_t>(lane) < cnt[j]) count(key0[j], prefix);
+                for (uint32_t e = kLanes + lane; e < cnt[j]; e += kLanes) count(sl[e].x, prefix);
+            }
         }
     } else {
         for (int s2 = hb.st_lo; s2 < hb.st_hi; ++s2) {
@@ -620,13 +649,15 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
     const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper;
     // Everything the block index alone addresses is requested before the first dependent load returns: the
-    // supertile's descriptor, its candidate count and whole slice (used up to the count, in candidate mode only)
-    // and the tiles' running counts.
+    // supertile's descriptor, its candidate count, the first kEarly slots of its slice (used up to the count,
+    // in candidate mode only; slices are a quarter to a tenth full, and reading all of them whole would be
+    // half a gigabyte at a billion elements) and the tiles' running counts.
     static_assert(kCandSlice == 2 * kBlock, "two slice entries per thread");
+    constexpr int kEarly = kBlock / 2;
     const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
     const StDesc d = sts[st];
     const uint32_t n_listed = st_cand_cnt[st];
-    const uint2 ce_pre[2] = {slice[threadIdx.x], slice[kBlock + threadIdx.x]};
+    const uint2 ce_early = threadIdx.x < kEarly ? slice[threadIdx.x] : make_uint2(0u, 0u);
     const uint32_t cnt_pre = threadIdx.x < kTilesPerSuper ? wt_cnt[tile0 + threadIdx.x] : 0u;
     // second round trip: what the segment number addresses
     const SegState ss = state_at(state, d.seg);
@@ -651,9 +682,11 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
         uint32_t* eq32 = reinterpret_cast<uint32_t*>(eq_mask);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const uint2 ce = ce_pre[j];
+            const uint32_t e = j * kBlock + threadIdx.x;
+            uint2 ce = ce_early;
+            if (e >= kEarly && e < n) ce = slice[e];
             const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
-            if (j * kBlock + threadIdx.x < n && ce.x >= T && rel < kSuper) {   // a listed position lies in its supertile
+            if (e < n && ce.x >= T && rel < kSuper) {       // a listed position lies in its supertile
                 const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
                 const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
                 if (ce.x > T) {
