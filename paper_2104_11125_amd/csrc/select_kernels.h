@@ -27,16 +27,12 @@ struct CollectStage {       // LDS staging of one supertile's masks and tile cou
 // `hi` are members for sure (their count and ballots are staged for the tile); keys with a top
 // digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice
 // `cand_dst` (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if
-// `wc` is given, counted per digit there, and, if `lh1` is given (then lo == hi), per second digit
-// there, and, if `h1_spec` is given (then `wc` is too), those of the 2^19 keys from `spec_base` on
-// per 128 keys there (in memory: the atomics return nothing and drain behind the streaming loads),
-// and those beyond these in wc[kWindow].  Called by all lanes of a wave; n_above is the same in
-// every lane.
+// `lh1` is given (then lo == hi), counted per second digit there.  Called by all lanes of a wave;
+// n_above is the same in every lane.
 template <bool ALL_OK>
 __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
-                                             uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* wc,
-                                             uint32_t* lh1, uint32_t* h1_spec, uint32_t spec_base, uint32_t& n_above,
-                                             CollectStage& stg, uint2* cand_dst)
+                                             uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* lh1,
+                                             uint32_t& n_above, CollectStage& stg, uint2* cand_dst)
 {
     // top digit > hi  <=>  key >= (hi + 1) << 19;  lo <= top digit <= hi  <=>  key - (lo << 19) < span
     const uint32_t lo_key = lo << (kBits1 + kBits2);
@@ -70,15 +66,7 @@ __device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool o
     for (int c = 0; c < 4; ++c) {
         if (in[c]) {
             if (rank < kCandSlice) cand_dst[rank] = make_uint2(key[c], p0 + c);
-            if (wc) atomicAdd(&wc[(key[c] >> (kBits1 + kBits2)) - lo], 1u);
             if (lh1) atomicAdd(&lh1[(key[c] >> kBits2) & (kBins1 - 1)], 1u);   // counted whether or not it is listed
-            if (h1_spec && key[c] >= spec_base) {
-                const uint32_t r = key[c] - spec_base;
-                if (r < kSpecSpan)
-                    atomicAdd(&h1_spec[r >> kBits2], 1u);
-                else
-                    atomicAdd(&wc[kWindow], 1u);
-            }
             ++rank;
         }
     }
@@ -114,8 +102,7 @@ __device__ __forceinline__ void collect_flush(const CollectStage& stg, const uin
 template <typename G, bool INSIDE>
 __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                                                     const StDesc& d, uint32_t lo, uint32_t hi, int wave, int lane,
-                                                    uint32_t* fill, uint32_t* wc, uint32_t* h1_spec, uint32_t spec_base,
-                                                    CollectStage& stg, uint2* cand_stage)
+                                                    uint32_t* fill, CollectStage& stg, uint2* cand_stage)
 {
     constexpr int kIters = kTilesPerSuper / kWaves;
     constexpr uint32_t kStride = kWaves * kWaveTile;
@@ -149,8 +136,7 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
             }
         }
         uint32_t n_above;
-        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, wc, nullptr, h1_spec, spec_base, n_above, stg,
-                             cand_stage);
+        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, nullptr, n_above, stg, cand_stage);
         above_acc += n_above;
         m_cur = m_nxt;
         g_cur = g_nxt;
@@ -213,22 +199,46 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     __syncthreads();
 
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-    uint32_t* h1 = spec_ok ? hist1_spec + static_cast<size_t>(d.seg) * kBins1 : nullptr;
+    uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1;
     uint32_t above_acc;
     if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
-        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, spec_base, stg,
-                                             cand_stage);
+        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, stg, cand_stage);
     else
-        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, acc + 1, h1, spec_base, stg,
-                                              cand_stage);
+        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, stg, cand_stage);
     if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
     __syncthreads();
-    collect_flush(stg, cand_stage, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
-    if (threadIdx.x == 0) {
-        const uint32_t n = fill;
-        st_cand_cnt[st] = n < kCandSlice ? n : kCandSlice;
-        if (n > kCandSlice) overflow[d.seg] = 1u;           // every overflowing block stores the same value
+    collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
+    // The staged candidates go to the supertile's slice and are counted on the way, outside the
+    // streaming loop: per window digit (ballots, one LDS atomic per wave and digit) and, those among
+    // the 2^19 finely counted keys, per 128 keys in memory.  (If the slice overflowed the counts are
+    // incomplete, and nothing reads them.)
+    static_assert(kCandSlice == 2 * kBlock, "two staged candidates per thread");
+    const uint32_t n = fill < kCandSlice ? fill : kCandSlice;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint32_t e = j * kBlock + threadIdx.x;
+        const bool have = e < n;
+        const uint2 ce = have ? cand_stage[e] : make_uint2(0u, 0u);
+        if (have) slice[e] = ce;
+        const uint32_t digit = ce.x >> (kBits1 + kBits2);
+#pragma unroll
+        for (uint32_t w = 0; w < kWindow; ++w) {
+            const uint64_t b = __builtin_amdgcn_ballot_w64(have && digit == lo + w);
+            if (lane == 0 && b) atomicAdd(&acc[1 + w], static_cast<uint32_t>(__popcll(b)));
+        }
+        if (spec_ok) {                                      // block-uniform
+            const bool at_or_above = have && ce.x >= spec_base;
+            const uint32_t r = ce.x - spec_base;
+            if (at_or_above && r < kSpecSpan) atomicAdd(&h1[r >> kBits2], 1u);
+            const uint64_t b = __builtin_amdgcn_ballot_w64(at_or_above && r >= kSpecSpan);
+            if (lane == 0 && b) atomicAdd(&acc[1 + kWindow], static_cast<uint32_t>(__popcll(b)));
+        }
     }
+    if (threadIdx.x == 0) {
+        st_cand_cnt[st] = n;
+        if (fill > kCandSlice) overflow[d.seg] = 1u;        // every overflowing block stores the same value
+    }
+    __syncthreads();
     if (threadIdx.x <= kWindow + 1) {                       // [1 + kWindow]: beyond the keys counted per 128
         const uint32_t v = acc[threadIdx.x];
         if (v)
@@ -542,8 +552,8 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                         bool ok[4] = {false, false, false, false};
                         if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
                         uint32_t n_above;
-                        collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, nullptr, lh,
-                                            nullptr, 0u, n_above, stg, slice);
+                        collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, lh, n_above,
+                                            stg, slice);
                     }
                     __syncthreads();
                     collect_flush(stg, nullptr, static_cast<size_t>(s2) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask,
