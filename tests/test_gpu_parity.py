@@ -477,6 +477,27 @@ def test_randomized_prediction_walk(gu, seed):
     ctx.close()
 
 
+@pytest.mark.parametrize("scale", [1e-44, 3e-39, 1e-30, 1.0, 1e30, 5e36])
+def test_prediction_at_the_ends_of_the_key_range(gu, scale):
+    """The same scale for several steps, so that the prediction and the finely counted keys around
+    the previous threshold are in use, with thresholds among the subnormals (the counted range is
+    cut off at key 0, and few distinct values exist), at the smallest normal numbers and close to
+    the largest finite ones."""
+    rng = np.random.default_rng(77)
+    numel, n, k = 50_021, 3, 500
+    ctx = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    shared = rng.standard_normal(numel)
+    for step in range(5):
+        grads = []
+        for i in range(n):
+            g = ((shared + 0.5 * rng.standard_normal(numel)) * scale).astype(np.float32)
+            grads.append(torch.from_numpy(g).to(gu.DEV))
+        gu.compare_step(ctx, mem, grads, ref, step, 0.3, 1.0, k=k, what=f"scale {scale} step {step}")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
