@@ -64,7 +64,7 @@ typedef enum {
  * Bytes of device workspace needed for up to n_learners_max learners with vectors of up to
  * numel_max elements each, split into at most n_tensors_max segments (1 for whole-vector
  * use), with index sets of at most k_max positions in total per step.  Pure host arithmetic
- * (about 0.8 * numel_max + (4 * n_learners_max + 16) * k_max + 125 KB * n_tensors_max bytes).
+ * (about 0.8 * numel_max + (4 * n_learners_max + 16) * k_max + 105 KB * n_tensors_max bytes).
  * Returns 0 if an argument is out of range (numel_max < 0 or > 2^31 - 1, n_tensors_max < 1,
  * n_learners_max outside 1 .. SCALECOM_MAX_LEARNERS, k_max < 0 or > numel_max).
  */

@@ -7,19 +7,23 @@
 // magnitude key |x_L| of the leader's x_L = fma(lr, grad_L, mem_L) (recomputed on the fly, never
 // stored) is resolved 12 + 12 + 7 bits at a time (radix select):
 //
-//   predicted   leader, ONE pass, for segments that carry the threshold bucket of the previous
-//               step as a prediction: keys whose top 12 bits lie above a 5-bucket window around
-//               it are members for sure (counted per 256-element wave tile, marked in the
+//   predicted   leader, ONE pass, for segments that carry the threshold of the previous step as
+//               a prediction: keys whose top 12 bits lie above a 5-bucket window around its
+//               bucket are members for sure (counted per 256-element wave tile, marked in the
 //               membership bitmask); keys inside the window are copied, with their positions,
-//               to a small candidate list and counted per bucket
-//   hist0       leader, histogram of the top 12 key bits -- only for segments without a
-//               prediction or whose window missed the k-th largest key (exact check on counts)
-//   find<0>     per segment: the bucket holding the k-th largest key  (Eq. 2)
-//   hist<1>     the next 12 key bits, histogrammed over the candidate list; for segments that
-//               went through hist0 this is the second leader pass that makes the list
-//   find<1>, hist<2>   the last 7 key bits
+//               to a small candidate list and counted per bucket, and the 2^19 keys around the
+//               previous threshold also per 128 keys
+//   level0      per segment: did the k-th largest key fall inside the window (exact check on
+//               counts)?  Then its bucket is known (Eq. 2), and its top 24 bits too if it fell
+//               among the finely counted keys.  Otherwise (no prediction, or a miss): histogram
+//               of the top 12 key bits of the leader's vector
+//   level<1>    a histogram of level0 is searched by every block that needs the result; then the
+//               next 12 key bits, histogrammed over the candidate list -- nothing to do if they
+//               are known already; for segments that went through the level-0 histogram this is
+//               the second leader pass that makes the list
+//   level<2>    (search of level 1's histogram, then) the last 7 key bits
 //   tilecount   the exact threshold key T and the number q of keys equal to T that still belong
-//               to the set (searched in every block; by find<2> when the blocks are very many);
+//               to the set (searched in every block; by find2 when the blocks are very many);
 //               candidates above / equal to T are added to the per-tile counts and bitmasks
 //               (a segment whose bucket does not fit the candidate list -- many equal keys --
 //               takes levels 1, 2 and this step as full leader passes instead of the list)
@@ -30,8 +34,9 @@
 //               [learner][slot] staging array and learner 0 writes the index (Eq. 3)
 //   reduce      reduced[t] = x_0[t] + x_1[t] + ... in learner order  (Alg. 1 line 10)
 //
-// In the steady state (predictions hold) hist0 finds nothing to do, and the leader's vector is
-// read exactly once before the all-learner pass.  The prediction only decides how much work is
+// In the steady state (predictions hold) the leader's vector is read exactly once before the
+// all-learner pass, and 8 kernels make a step.  No kernel reads what another block of the same
+// launch wrote, so there are no fences or waits between blocks.  The prediction only decides how much work is
 // done, never what is selected.  The output is ascending by position and deterministic.
 // Nothing here is a dense contraction, so there is no MFMA; the kernels are bound by HBM traffic
 // (update, predicted) and by launch latency (the small ones).
