@@ -25,8 +25,6 @@ constexpr int kSlotsOwnScanBlock = 1024;         // threads of its blocks then (
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7
 constexpr int kBins0 = 1 << kBits0, kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
 constexpr int kHistGridMax = 2048;              // blocks of the search levels' kernels, plus at most one per tensor
-constexpr int kFoldLastSearchMaxSt = 12288;      // up to this many supertiles k_tilecount searches the last level itself
-                                                 // (measured: +45 us over 122 K blocks against one launch of 4.5 us)
 constexpr int kCandSlice = 512;                  // candidate slots per supertile (1/16 of its positions)
 constexpr uint32_t kModeFull = 0, kModeCand = 1;
 

@@ -23,7 +23,7 @@
 //               the second leader pass that makes the list
 //   level<2>    (search of level 1's histogram, then) the last 7 key bits
 //   tilecount   the exact threshold key T and the number q of keys equal to T that still belong
-//               to the set (searched in every block; by find2 when the blocks are very many);
+//               to the set (every wave searches the last 128 counters for itself);
 //               candidates above / equal to T are added to the per-tile counts and bitmasks
 //               (a segment whose bucket does not fit the candidate list -- many equal keys --
 //               takes levels 1, 2 and this step as full leader passes instead of the list)
@@ -398,12 +398,9 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
                                            collect_out);
     k_level<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state1, state, hist1, hist2, preds,
                                            collect_out);
-    // the last search: inside k_tilecount's blocks, or a kernel of its own when those are very many
-    const bool fold_last = n_st <= kFoldLastSearchMaxSt;
-    if (!fold_last) k_find2<<<n_tensors, kBlock, 0, s>>>(state, hist2);
     mark(2);
-    k_tilecount<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, state, fold_last ? hist2 : nullptr, wt_cnt, cand,
-                                           st_cand_cnt, sel_mask, eq_mask, st_sum);
+    k_tilecount<G><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2, wt_cnt,
+                                                                   cand, st_cand_cnt, sel_mask, eq_mask, st_sum);
     if (n_st <= kOwnScanMaxSt) {   // few supertiles: the slot kernel adds up the totals before each block itself
         constexpr int per_block = kSlotsOwnScanBlock / kLanes;
         k_slots<true><<<(n_st + per_block - 1) / per_block, kSlotsOwnScanBlock, 0, s>>>(

@@ -1,6 +1,6 @@
 // Exact top-k selection on the leader's vector x_L = fma(lr, grad_L, mem_L) (Eq. 2, Alg. 1 line 6):
 // radix select over the 31-bit magnitude key, 12 + 12 + 7 bits.  Kernels in the order a step runs
-// them: k_predicted, k_level0, k_level<1>, k_level<2>, (k_find2,) k_tilecount, (k_scan,) k_slots.
+// them: k_predicted, k_level0, k_level<1>, k_level<2>, k_tilecount, (k_scan,) k_slots.
 // Part of scalecom.hip's single translation unit.
 #pragma once
 
@@ -433,7 +433,7 @@ struct CollectOut {
 // costs less than a launch), then the histogram of the next digit of the leader's magnitude keys.
 // LEVEL 1: bits 18..7 of keys whose top 12 bits equal the chosen bucket; a segment whose level 1
 // was searched by k_level0 already (the steady state) is skipped.  LEVEL 2: last 7 bits of keys
-// matching 24 bits; the search follows in k_tilecount or k_find2.  Candidate mode reads the keys
+// matching 24 bits; the search follows in k_tilecount.  Candidate mode reads the keys
 // from the candidate list, full mode recomputes them from the leader's vector.  The state comes
 // from state_in and goes, through the segment's first block, to state_out: no block reads what
 // another block of the same kernel wrote.
@@ -592,111 +592,106 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     }
 }
 
-// The last search as a kernel of its own, one block per segment (see find_threshold for the other way).
-__global__ void __launch_bounds__(kBlock) k_find2(SegState* __restrict__ state, const uint32_t* __restrict__ hist)
+// The last search of the threshold (7 key bits, 128 counters), done by every wave that needs the
+// result instead of by a kernel of its own: from the top of the histogram, the bin that holds the
+// k_rem-th largest key of the current 24-bit bucket.  Each lane brings the counts of bins `lane`
+// and `64 + lane`; all 64 lanes call it.  Returns the threshold key T and sets q, the number of
+// keys equal to T that are members.  The histogram is 512 bytes, so re-reading it in every wave is
+// cheap (the 16 KB histograms of the earlier levels are searched once per block of the kernel
+// that follows them).
+__device__ __forceinline__ uint32_t find_threshold(uint32_t h_lo, uint32_t h_hi, uint32_t prefix24, uint32_t k_rem,
+                                                   int lane, uint32_t& q)
 {
-    __shared__ uint32_t above[kWaves];
-    const int seg = blockIdx.x;
-    SegState s = state_at(state, seg);
-    if (s.done) return;
-    uint32_t digit, n_digit, n_above;
-    if (search_digit<kBins2>(hist + static_cast<size_t>(seg) * kBins2, s.k_rem, above, digit, n_digit, n_above)) {
-        s.prefix = (s.prefix << kBits2) | digit;
-        s.k_rem -= n_above;
-        s.T = s.prefix;
-        s.q = s.k_rem;
-        state_at(state, seg) = s;
-    }
-}
-
-// The last search of the threshold (7 key bits, 128 counters), done by every block that needs the
-// result instead of by a kernel of its own (k_find2, which is launched instead when there are so
-// many blocks that their added barriers cost more than the launch): from the top of the histogram, the bin that holds the
-// k_rem-th largest key of the current 24-bit bucket.  All threads of the block call it; `bcast`
-// is three words of LDS.  Returns the threshold key T and sets q, the number of keys equal to T that
-// are members.  The histogram is 512 bytes, so re-reading it in every block is cheap (the 16 KB
-// histograms of the earlier levels are not: those searches stay kernels).
-__device__ __forceinline__ uint32_t find_threshold(uint32_t mine, uint32_t prefix24, uint32_t k_rem, uint32_t* bcast,
-                                                   uint32_t& q)
-{
-    static_assert(kBins2 == 2 * kLanes, "two waves hold the last level's counters");
-    const int t = threadIdx.x, lane = t % kLanes;
-    uint32_t suf = mine;                                    // inclusive suffix sum inside the wave
+    static_assert(kBins2 == 2 * kLanes, "two counters of the last level per lane");
+    uint32_t suf_lo = h_lo, suf_hi = h_hi;                  // inclusive suffix sums over the lanes
 #pragma unroll
     for (int off = 1; off < kLanes; off <<= 1) {
-        const uint32_t v = __shfl_down(suf, off, kLanes);
-        if (lane + off < kLanes) suf += v;
+        const uint32_t a = __shfl_down(suf_lo, off, kLanes), b = __shfl_down(suf_hi, off, kLanes);
+        if (lane + off < kLanes) {
+            suf_lo += a;
+            suf_hi += b;
+        }
     }
-    if (t == kLanes) bcast[0] = suf;                        // total of bins 64..127
-    if (t == kBins2) {                                      // if the counts were corrupted: nothing is a member
-        bcast[1] = 0xffffffffu;
-        bcast[2] = 0u;
+    suf_lo += __builtin_amdgcn_readfirstlane(suf_hi);       // bins 64..127 lie above every bin of the low half
+    const uint32_t above_lo = suf_lo - h_lo, above_hi = suf_hi - h_hi;   // keys in higher bins
+    // exactly one bin qualifies, unless the counts were corrupted: then nothing is a member
+    const uint64_t hit_hi = __builtin_amdgcn_ballot_w64(above_hi < k_rem && k_rem <= suf_hi);
+    const uint64_t hit_lo = __builtin_amdgcn_ballot_w64(above_lo < k_rem && k_rem <= suf_lo);
+    uint32_t T = 0xffffffffu;
+    q = 0u;
+    if (hit_hi) {                                           // wave-uniform
+        const int src = __ffsll(static_cast<unsigned long long>(hit_hi)) - 1;
+        T = (prefix24 << kBits2) | static_cast<uint32_t>(kLanes + src);
+        q = k_rem - __shfl(above_hi, src, kLanes);
+    } else if (hit_lo) {
+        const int src = __ffsll(static_cast<unsigned long long>(hit_lo)) - 1;
+        T = (prefix24 << kBits2) | static_cast<uint32_t>(src);
+        q = k_rem - __shfl(above_lo, src, kLanes);
     }
-    __syncthreads();
-    if (t < kLanes) suf += bcast[0];
-    const uint32_t excl = suf - mine;                       // keys in higher bins
-    if (t < kBins2 && excl < k_rem && k_rem <= suf) {       // exactly one bin qualifies
-        bcast[1] = (prefix24 << kBits2) | static_cast<uint32_t>(t);
-        bcast[2] = k_rem - excl;
-    }
-    __syncthreads();
-    q = bcast[2];
-    return bcast[1];
+    return T;
+}
+
+// Orders one wave's LDS accesses: what its lanes wrote or added before is seen by its lanes after.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 // Per wave tile of the leader's vector: number of keys above the threshold (low half of the
 // packed counter) and equal to it (high half), and the two bitmasks that go with them.
-// Full-pass mode recomputes every key; candidate mode adds the listed keys to what k_collect
-// started.  Also leaves the supertile's totals for the prefix scan.
+// Full-pass mode recomputes every key; candidate mode adds the listed keys to what the collecting
+// pass started.  Also leaves the supertile's totals for the prefix scan.  One WAVE per supertile
+// and no barrier between the waves of a block: a block per supertile spent its time waiting at
+// barriers with most of its threads idle (a supertile lists a few dozen to a few hundred keys).
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-            const StDesc* __restrict__ sts, SegState* __restrict__ state, const uint32_t* __restrict__ hist2,
+            const StDesc* __restrict__ sts, int n_st, SegState* __restrict__ state, const uint32_t* __restrict__ hist2,
             uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt,
             uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
 {
-    const int st = blockIdx.x;
-    const int wave = threadIdx.x / kLanes, lane = threadIdx.x % kLanes;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
+    const int st = blockIdx.x * kWaves + wave;
+    if (st >= n_st) return;                                 // whole wave
+    __shared__ uint32_t cnt_s[kWaves][kTilesPerSuper];
+    uint32_t* cnt = cnt_s[wave];
     const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper;
-    // Everything the block index alone addresses is requested before the first dependent load returns: the
-    // supertile's descriptor, its candidate count, the first kEarly slots of its slice (used up to the count,
-    // in candidate mode only; slices are a quarter to a tenth full, and reading all of them whole would be
-    // half a gigabyte at a billion elements) and the tiles' running counts.
-    static_assert(kCandSlice == 2 * kBlock, "two slice entries per thread");
-    constexpr int kEarly = kBlock / 2;
+    // Everything the supertile's number alone addresses is requested before the first dependent load
+    // returns: its descriptor, its candidate count, the first 64 slots of its slice (used up to the
+    // count, in candidate mode only; slices are a quarter to a tenth full, and reading all of them
+    // whole would be half a gigabyte at a billion elements) and the tiles' running counts.
     const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
     const StDesc d = sts[st];
     const uint32_t n_listed = st_cand_cnt[st];
-    const uint2 ce_early = threadIdx.x < kEarly ? slice[threadIdx.x] : make_uint2(0u, 0u);
-    const uint32_t cnt_pre = threadIdx.x < kTilesPerSuper ? wt_cnt[tile0 + threadIdx.x] : 0u;
+    const uint2 ce_early = slice[lane];
+    const uint32_t cnt_pre = lane < kTilesPerSuper ? wt_cnt[tile0 + lane] : 0u;
     // second round trip: what the segment number addresses
     const SegState ss = state_at(state, d.seg);
-    const uint32_t h2 = (hist2 && threadIdx.x < kBins2) ? hist2[static_cast<size_t>(d.seg) * kBins2 + threadIdx.x] : 0u;
+    const uint32_t* h2 = hist2 + static_cast<size_t>(d.seg) * kBins2;
+    const uint32_t h_lo = h2[lane], h_hi = h2[kLanes + lane];
     const int st_first = segs[d.seg].st_first;
-    __shared__ uint32_t cnt[kTilesPerSuper];
-    __shared__ uint32_t bcast[3];
-    uint32_t T = ss.T, q = ss.q;                            // an empty index set keeps T above every key
-    if (!ss.done && hist2) {                                // block-uniform; without hist2 a kernel has searched already
-        T = find_threshold(h2, ss.prefix, ss.k_rem, bcast, q);
-        if (st == st_first && threadIdx.x == 0) {           // for the tie quota of the slot pass
+    uint32_t T = ss.T, q = 0u;                              // an empty index set keeps T above every key
+    if (!ss.done) {                                         // wave-uniform
+        T = find_threshold(h_lo, h_hi, ss.prefix, ss.k_rem, lane, q);
+        if (st == st_first && lane == 0) {                  // for the tie quota of the slot pass
             state_at(state, d.seg).T = T;
             state_at(state, d.seg).q = q;
         }
     }
 
+    uint32_t v = 0u;                                        // lanes 0..31: the packed counter of one tile each
     if (!ss.done && ss.mode == kModeCand) {
-        if (threadIdx.x < kTilesPerSuper) cnt[threadIdx.x] = cnt_pre;
-        __syncthreads();
+        if (lane < kTilesPerSuper) cnt[lane] = cnt_pre;
+        wave_lds_fence();
         const uint32_t n = n_listed < kCandSlice ? n_listed : kCandSlice;   // never use what lies past the count
         uint32_t* sel32 = reinterpret_cast<uint32_t*>(sel_mask);
         uint32_t* eq32 = reinterpret_cast<uint32_t*>(eq_mask);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint32_t e = j * kBlock + threadIdx.x;
-            uint2 ce = ce_early;
-            if (e >= kEarly && e < n) ce = slice[e];
+        for (uint32_t e = lane; e < n; e += kLanes) {
+            const uint2 ce = e < kLanes ? ce_early : slice[e];
             const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
-            if (e < n && ce.x >= T && rel < kSuper) {       // a listed position lies in its supertile
+            if (ce.x >= T && rel < kSuper) {                // a listed position lies in its supertile
                 const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
                 const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
                 if (ce.x > T) {
@@ -708,15 +703,16 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                 }
             }
         }
-        __syncthreads();
+        wave_lds_fence();
+        if (lane < kTilesPerSuper) v = cnt[lane];
     } else {
         const int64_t begin = d.begin, end = d.end;
-        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-            const int wt = it * kWaves + wave;
+#pragma unroll 2
+        for (int wt = 0; wt < kTilesPerSuper; ++wt) {
             const int64_t p0 = static_cast<int64_t>(d.a0) + wt * kWaveTile + lane * kVec;
             uint32_t key[4] = {0, 0, 0, 0};
             bool ok[4] = {false, false, false, false};
-            if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+            if (!ss.done && p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);   // (no members: nothing is read)
             uint64_t gt[4], eq[4];
             uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
@@ -726,20 +722,16 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                 n_gt += __popcll(gt[c]);
                 n_eq += __popcll(eq[c]);
             }
+            if (lane == wt) v = n_gt | (n_eq << 16);        // at most 256 each
             if (lane == 0) {
-                cnt[wt] = n_gt | (n_eq << 16);             // at most 256 each
                 store_tile_masks(sel_mask, tile0 + wt, gt);
                 store_tile_masks(eq_mask, tile0 + wt, eq);
             }
         }
-        __syncthreads();
     }
-    if (threadIdx.x < kLanes) {
-        const uint32_t v = threadIdx.x < kTilesPerSuper ? cnt[threadIdx.x] : 0u;
-        if (threadIdx.x < kTilesPerSuper) wt_cnt[tile0 + threadIdx.x] = v;
-        const uint32_t s2 = wave_sum(v);                   // at most 8192 each: no carry between halves
-        if (threadIdx.x == 0) st_sum[st] = make_uint2(s2 & 0xffffu, s2 >> 16);
-    }
+    if (lane < kTilesPerSuper) wt_cnt[tile0 + lane] = v;
+    const uint32_t s2 = wave_sum(v);                        // at most 8192 each: no carry between halves
+    if (lane == 0) st_sum[st] = make_uint2(s2 & 0xffffu, s2 >> 16);
 }
 
 // Prefix scan, level 1: one block per chunk of up to 1024 supertiles of one segment; exclusive
