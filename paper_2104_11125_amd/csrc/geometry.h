@@ -93,8 +93,9 @@ constexpr uint32_t kWindow = 5;                  // predicted window: previous b
 constexpr uint32_t kSpecSpan = 1u << (kBits1 + kBits2);   // keys the predicted pass counts per 128, around the last threshold
 constexpr uint32_t kNoSpec = 0xffffffffu;        // (as their first key: none were counted)
 // Counts of the predicted pass, per segment: [0] keys above the window, [1 + d] keys with the
-// d-th digit of the window, [1 + kWindow] keys of the window beyond the finely counted ones.  Blocks add into one of kPartSlots copies (same-address atomics from
-// thousands of blocks would serialise); readers sum the copies.
+// d-th digit of the window, [1 + kWindow] keys of the window beyond the finely counted ones.
+// Blocks add into one of kPartSlots copies (same-address atomics from thousands of blocks would
+// serialise); readers sum the copies.
 constexpr int kPartSlots = 64;
 constexpr int kPartWords = 8;
 

@@ -153,8 +153,8 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
 // previous step's threshold, where the threshold lies again in most steps, are also counted per
 // 128 keys (the resolution of the search's second level).  If the counts show afterwards that the
 // k-th largest key fell inside the window, the threshold bucket is known exactly and no other full
-// pass over the leader is needed; if it fell among those 2^19 keys, level 1 is known too.  The prediction only decides
-// how much work is done, never what is selected.  One block per supertile.
+// pass over the leader is needed; if it fell among those 2^19 keys, level 1 is known too.  The
+// prediction only decides how much work is done, never what is selected.  One block per supertile.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
