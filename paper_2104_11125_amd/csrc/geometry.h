@@ -72,7 +72,7 @@ struct SegState {         // selection state of one segment after a level; every
     uint32_t done;        // 1: empty index set, nothing to refine
     uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
     uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
-    uint32_t l1_done;     // 1: level 1 was searched already, on the counts the predicted pass gathered for its bucket
+    uint32_t l1_done;     // 1: level 1 was searched already, on the fine counts of the predicted pass
     uint32_t pending;     // 1: the last histogram was counted but not searched yet (the next kernel's blocks do that)
 };
 static_assert(sizeof(SegState) == 36, "nine words, no padding to carry along in copies");
