@@ -174,3 +174,33 @@ def test_maximum_size_full(gu):
 def test_maximum_size_chunked_full(gu):
     """The same length with the chunk-wise selector, the last chunk shorter than the others."""
     _streamed_parity(gu, _maximum_size_workload(), step=0, seed=960, chunk=400)
+
+
+def test_large_vector_fallback_paths(gu):
+    """Blocks of the search-level kernels that hold several supertiles each (more than 2048
+    supertiles) on every path of the selection: no prediction, prediction and fine counts hit,
+    threshold moved inside the window, window missed (scale jump), few distinct magnitudes (lists
+    overflow, full passes), and back."""
+    rng = np.random.default_rng(4242)
+    numel, n, k = 40_000_003, 2, 100_000
+    ctx = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV, k_max=k)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    shared = rng.standard_normal(numel, dtype=np.float32)
+    scale = 1e-3
+    for step, move in enumerate(["first", "same", "drift", "jump_up", "ties", "same", "jump_down"]):
+        print(f"[fullsize] fallback paths step {step} ({move})", flush=True)
+        if move == "drift":
+            scale *= 1.08
+        elif move == "jump_up":
+            scale *= 64.0
+        elif move == "jump_down":
+            scale /= 64.0
+        grads = []
+        for i in range(n):
+            g = (shared + 0.5 * rng.standard_normal(numel, dtype=np.float32)) * np.float32(scale)
+            if move == "ties":
+                g = np.sign(g) * np.float32(scale)
+            grads.append(torch.from_numpy(g).to(gu.DEV))
+        gu.compare_step(ctx, mem, grads, ref, step, 0.3, 1.0, k=k, what=f"fallback paths step {step} {move}")
+    ctx.close()
