@@ -30,6 +30,14 @@
  *  - All work is enqueued on the HIP stream given to scalecom_init; calls do not wait for
  *    the GPU.  Outputs are valid once that stream has reached the end of the call's work.
  *    A context must not be used from two threads at once.
+ *  - HIP graphs: once a layout (numel or offsets, k or ks or chunk sizes) has been used in one
+ *    call, further steps with it enqueue kernels only (no copies, memsets, events or waits;
+ *    scalecom_timing_begin must not be in effect), so they can be captured on the context's
+ *    stream.  Two things are decided on the host when a step is enqueued and are therefore frozen
+ *    in a graph: the leader (step mod n_learners) and which of two alternating copies of the
+ *    per-step scratch memory the step uses.  Capture lcm(2, n_learners) consecutive steps,
+ *    starting at a step index that is a multiple of that number; such a graph ends in the state
+ *    it began in and may be replayed any number of times.
  *  - Errors are return codes; nothing is thrown.  scalecom_last_error gives the detail.
  */
 #ifndef SCALECOM_H
