@@ -1,6 +1,6 @@
 // Device helpers shared by all kernels: magnitude keys, nontemporal 16-byte accesses, guarded
-// accesses at segment boundaries, ballots and wave reductions, the exact check of a predicted
-// threshold window.  Part of scalecom.hip's single translation unit.
+// accesses at segment boundaries, ballots and wave reductions.  Part of scalecom.hip's single
+// translation unit.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -168,34 +168,6 @@ __device__ __forceinline__ void leader_keys(const float* mem, const G* grad, flo
     float4 m, g;
     leader_load(mem, grad, p0, begin, end, m, g);
     keys_from(m, g, lr, p0, begin, end, key, ok);
-}
-
-// first and last top digit of the window collected around a predicted bucket (p = bucket + 1)
-__device__ __forceinline__ uint32_t window_lo(uint32_t p) { return p >= 3 ? p - 3 : 0u; }
-__device__ __forceinline__ uint32_t window_hi(uint32_t p)
-{
-    return p + 1 < static_cast<uint32_t>(kBins0) ? p + 1 : kBins0 - 1u;
-}
-
-// Did the predicted single pass see the k-th largest key inside its window?  If so: the key's
-// top digit and how many members remain to be found inside that digit's bucket.  Exact: uses
-// only counts gathered over the whole segment.
-__device__ __forceinline__ bool spec_resolve(const uint32_t tot[1 + kWindow], bool overflow, uint32_t p, uint32_t k,
-                                             uint32_t& digit, uint32_t& k_rem)
-{
-    if (p == 0 || overflow || k <= tot[0]) return false;
-    const uint32_t lo = window_lo(p), hi = window_hi(p);
-    uint32_t c = tot[0];
-    for (uint32_t d = hi + 1; d-- > lo;) {
-        const uint32_t n = tot[1 + d - lo];
-        if (c + n >= k) {
-            digit = d;
-            k_rem = k - c;
-            return true;
-        }
-        c += n;
-    }
-    return false;
 }
 
 // Membership bitmask layout: per wave tile four 64-bit words; bit l of word c belongs to

@@ -72,7 +72,7 @@ struct SegState {         // selection state of one segment after a level; every
     uint32_t done;        // 1: empty index set, nothing to refine
     uint32_t mode;        // kModeCand: levels 1, 2 and the tile counts work on the candidate list
     uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
-    uint32_t l1_done;     // 1: level 1 was searched already, on the fine counts of the predicted pass
+    uint32_t l1_done;     // 1: levels 0 and 1 are known from the counts of the predicted pass
     uint32_t pending;     // 1: the last histogram was counted but not searched yet (the next kernel's blocks do that)
 };
 static_assert(sizeof(SegState) == 36, "nine words, no padding to carry along in copies");
@@ -89,11 +89,18 @@ __host__ __device__ inline const SegState& state_at(const SegState* base, size_t
     return *reinterpret_cast<const SegState*>(reinterpret_cast<const char*>(base) + seg * kStateStride);
 }
 
-constexpr uint32_t kWindow = 5;                  // predicted window: previous bucket +- 2 digits
-constexpr uint32_t kSpecSpan = 1u << (kBits1 + kBits2);   // keys the predicted pass counts per 128, around the last threshold
-constexpr uint32_t kNoSpec = 0xffffffffu;        // (as their first key: none were counted)
-// Counts of the predicted pass, per segment: [0] keys above the window, [1 + d] keys with the
-// d-th digit of the window, [1 + kWindow] keys of the window beyond the finely counted ones.
+// The predicted pass works on a RANGE of keys around the previous step's threshold: 2^w keys,
+// aligned to 128, counted per 128 keys (at most 4096 counts).  w follows the density of keys around
+// the threshold: with error feedback the magnitudes pile up just below it (after some hundred
+// steps a twelve-bit bucket around the threshold holds 7 % of all elements), so a fixed range
+// would come to hold far more keys than the index set has members.
+constexpr int kSpecBitsMax = kBits1 + kBits2;    // 19: 2^19 keys, one twelve-bit bucket wide (+-3 % of the threshold)
+constexpr int kSpecBitsMin = kBits2 + 3;         // 10: 2^10 keys, 8 counts
+// The prediction kept per segment between steps, and the one a step works with.
+constexpr int kPredWords = 4;                    // [0] 1 if there is one, [1] top 24 bits of the last threshold, [2] w,
+                                                 // [3] steps in a row in which the threshold fell into the range's middle half
+constexpr uint32_t kCalmSteps = 8;               // so many of those before the range is made narrower
+// Counts of the predicted pass, per segment: [0] keys above the range, [1] keys inside it.
 // Blocks add into one of kPartSlots copies (same-address atomics from thousands of blocks would
 // serialise); readers sum the copies.
 constexpr int kPartSlots = 64;

@@ -104,7 +104,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.sts = take(nst * sizeof(StDesc));
     l.chunks = take(nch * sizeof(ChunkDesc));
     l.hblocks = take((kHistGridMax + nt) * sizeof(HistBlock));
-    l.preds = take(2 * nt * sizeof(uint32_t));           // per segment: bucket + 1, top 24 bits of the threshold
+    l.preds = take(kPredWords * nt * sizeof(uint32_t));  // per segment: the prediction for the next step
     l.state = take(3 * nt * kStateStride);               // after level 0, after level 1, after level 2
     {
         size_t z = 0;
@@ -114,7 +114,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
             return at;
         };
         l.z_overflow = ztake(nt * sizeof(uint32_t));
-        l.z_p_used = ztake(2 * nt * sizeof(uint32_t));
+        l.z_p_used = ztake(kPredWords * nt * sizeof(uint32_t));
         l.z_full_flag = ztake(nt * sizeof(uint32_t));
         l.z_part = ztake(nt * kPartSlots * kPartWords * sizeof(uint32_t));
         l.z_hist0 = ztake(nt * kBins0 * sizeof(uint32_t));
@@ -294,7 +294,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     }
     // predictions of the previous layout's buckets mean nothing for this one
     k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds),
-                                          2 * static_cast<size_t>(ctx->n_tensors_max));
+                                          kPredWords * static_cast<size_t>(ctx->n_tensors_max));
     ctx->scratch_clean = false;
     SC_HIP(ctx, hipEventRecord(ctx->upload_done, ctx->stream));
     ctx->upload_pending = true;
@@ -581,7 +581,7 @@ DiagLayout diag_layout(int64_t numel_max, int n_tensors_max)
     d.y = 0;
     d.mask = align_up(static_cast<size_t>(numel_max) * sizeof(float), 256);
     d.preds = d.mask + align_up(ntile * 4 * sizeof(uint64_t), 256);
-    d.total = d.preds + align_up(2 * static_cast<size_t>(n_tensors_max) * sizeof(uint32_t), 256);
+    d.total = d.preds + align_up(kPredWords * static_cast<size_t>(n_tensors_max) * sizeof(uint32_t), 256);
     return d;
 }
 
@@ -604,7 +604,7 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     k_set_ks<<<(n_tensors + kBlock - 1) / kBlock, kBlock, 0, s>>>(segs, n_tensors, d_out);
     if (ctx->n_st > 0) {
         // the leader's index set (Eq. 3)
-        k_init<<<1, kBlock, 0, s>>>(preds, 2 * static_cast<size_t>(n_tensors));
+        k_init<<<1, kBlock, 0, s>>>(preds, kPredWords * static_cast<size_t>(n_tensors));
         launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, no_mark);
         SC_HIP(ctx, hipMemcpyAsync(mask_a, sel_mask, mask_bytes, hipMemcpyDeviceToDevice, s));
         // the top-k of the summed error-feedback gradients
@@ -612,7 +612,7 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         const unsigned gx = static_cast<unsigned>(std::min<int64_t>(blocks, 1 << 20));
         const dim3 grid(gx, static_cast<unsigned>((blocks + gx - 1) / gx));
         k_sum_x<G><<<grid, kBlock, 0, s>>>(lp, n_learners, lr, begin, end, y);
-        k_init<<<1, kBlock, 0, s>>>(preds, 2 * static_cast<size_t>(n_tensors));
+        k_init<<<1, kBlock, 0, s>>>(preds, kPredWords * static_cast<size_t>(n_tensors));
         launch_select<NoGrad>(ctx, y, static_cast<const NoGrad*>(nullptr), 0.0f, n_tensors, preds, no_mark);
         k_mask_overlap<<<(ctx->n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(sts, ctx->n_st, mask_a, sel_mask, d_out);
     }

@@ -23,23 +23,20 @@ struct CollectStage {       // LDS staging of one supertile's masks and tile cou
     uint32_t cnt[kTilesPerSuper];
 };
 
-// The per-tile work of the "collect" pass, given the tile's keys: keys whose top digit lies above
-// `hi` are members for sure (their count and ballots are staged for the tile); keys with a top
-// digit in [lo, hi] are appended, with their positions, to the supertile's candidate slice
-// `cand_dst` (in LDS or in memory; slots handed out through the block's LDS counter `fill`) and, if
-// `lh1` is given (then lo == hi), counted per second digit there.  Called by all lanes of a wave;
-// n_above is the same in every lane.
+// The per-tile work of the "collect" pass, given the tile's keys: keys from lo_key + span on are
+// members for sure (their count and ballots are staged for the tile); the `span` keys from lo_key
+// on are appended, with their positions, to the supertile's candidate slice `cand_dst` (in LDS or
+// in memory; slots handed out through the block's LDS counter `fill`) and, if `lh1` is given (then
+// the range is one twelve-bit bucket), counted per second digit there.  Called by all lanes of a
+// wave; n_above and n_in are the same in every lane.
 template <bool ALL_OK>
-__device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo,
-                                             uint32_t hi, int wt, int lane, uint32_t* fill, uint32_t* lh1,
-                                             uint32_t& n_above, CollectStage& stg, uint2* cand_dst)
+__device__ __forceinline__ void collect_tile(const uint32_t key[4], const bool ok[4], uint32_t p0, uint32_t lo_key,
+                                             uint32_t span, int wt, int lane, uint32_t* fill, uint32_t* lh1,
+                                             uint32_t& n_above, uint32_t& n_in, CollectStage& stg, uint2* cand_dst)
 {
-    // top digit > hi  <=>  key >= (hi + 1) << 19;  lo <= top digit <= hi  <=>  key - (lo << 19) < span
-    const uint32_t lo_key = lo << (kBits1 + kBits2);
-    const uint32_t above_key = (hi + 1u) << (kBits1 + kBits2);   // 2^31 for the last digit: no key reaches it
-    const uint32_t span = above_key - lo_key;
+    const uint32_t above_key = lo_key + span;               // at most 2^31, which no key reaches
     n_above = 0;
-    uint32_t n_in = 0;
+    n_in = 0;
     bool in[4];
     uint64_t above[4], inside[4];
 #pragma unroll
@@ -101,8 +98,8 @@ __device__ __forceinline__ void collect_flush(const CollectStage& stg, const uin
 // checked per element.  Positions stay below 2^31 + 8192 and are kept in 32 bits.
 template <typename G, bool INSIDE>
 __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
-                                                    const StDesc& d, uint32_t lo, uint32_t hi, int wave, int lane,
-                                                    uint32_t* fill, CollectStage& stg, uint2* cand_stage)
+                                                    const StDesc& d, uint32_t lo_key, uint32_t span, int wave, int lane,
+                                                    uint32_t* fill, uint32_t& in_acc, CollectStage& stg, uint2* cand_stage)
 {
     constexpr int kIters = kTilesPerSuper / kWaves;
     constexpr uint32_t kStride = kWaves * kWaveTile;
@@ -121,6 +118,7 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
     };
     fetch(p_cur, m_cur, g_cur);
     uint32_t above_acc = 0;
+    in_acc = 0;
 #pragma unroll 1
     for (int it = 0; it < kIters; ++it) {
         const int wt = it * kWaves + wave;
@@ -135,9 +133,10 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
                 ok[c] = pos >= begin && pos < end;
             }
         }
-        uint32_t n_above;
-        collect_tile<INSIDE>(key, ok, p_cur, lo, hi, wt, lane, fill, nullptr, n_above, stg, cand_stage);
+        uint32_t n_above, n_in;
+        collect_tile<INSIDE>(key, ok, p_cur, lo_key, span, wt, lane, fill, nullptr, n_above, n_in, stg, cand_stage);
         above_acc += n_above;
+        in_acc += n_in;
         m_cur = m_nxt;
         g_cur = g_nxt;
         p_cur += kStride;
@@ -146,15 +145,14 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
 }
 
 // First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
-// that carry a prediction of their threshold bucket (the bucket found in the previous step).
-// ONE pass, no histogram: keys whose top digit lies above a 5-digit window around the
-// prediction are members for sure (counted per tile, marked in the mask), keys inside the
-// window go to the candidate list and are counted per digit; those of the 2^19 keys around the
-// previous step's threshold, where the threshold lies again in most steps, are also counted per
-// 128 keys (the resolution of the search's second level).  If the counts show afterwards that the
-// k-th largest key fell inside the window, the threshold bucket is known exactly and no other full
-// pass over the leader is needed; if it fell among those 2^19 keys, level 1 is known too.  The
-// prediction only decides how much work is done, never what is selected.  One block per supertile.
+// that carry a prediction: the top 24 bits of the previous step's threshold and a width w.
+// ONE pass, no histogram in LDS: keys above the 2^w keys centred on the previous threshold are
+// members for sure (counted per tile, marked in the mask); keys among those 2^w go to the
+// candidate list and are counted per 128 keys (the resolution of the search's second level) with
+// atomics in memory.  If the counts show afterwards that the k-th largest key fell inside the
+// range, the top 24 bits of the threshold are known exactly and no other full pass over the
+// leader is needed.  The prediction only decides how much work is done, never what is selected.
+// One block per supertile.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
@@ -173,73 +171,66 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
 
     const int st = blockIdx.x;
     const StDesc d = sts[st];
-    const uint32_t p = preds[2 * d.seg];                    // 0: none, else predicted bucket + 1
-    const uint32_t t24 = preds[2 * d.seg + 1];              // the previous threshold's top 24 bits
+    const uint32_t* pred = preds + static_cast<size_t>(d.seg) * kPredWords;
+    const uint32_t have = pred[0], t24 = pred[1], w = pred[2];
     const SegDesc sd = segs[d.seg];
-    if (p == 0 || sd.k == 0) return;
-    const uint32_t lo = window_lo(p), hi = window_hi(p);
-    // the 2^19 keys counted per 128: centred on the previous threshold, inside the window
+    if (have == 0 || sd.k == 0) return;
+    // the range: 2^w keys centred on the middle of the previous threshold's 128 keys, aligned to 128,
+    // cut off at key 0 and at 2^31
+    const uint32_t span = 1u << w;
     const uint32_t mid = (t24 << kBits2) | (kBins2 / 2);
-    const uint32_t spec_base = mid > kSpecSpan / 2 ? (mid - kSpecSpan / 2) & ~static_cast<uint32_t>(kBins2 - 1) : 0u;
-    const bool spec_ok = spec_base >= (lo << (kBits1 + kBits2)) &&
-                         static_cast<uint64_t>(spec_base) + kSpecSpan <= (static_cast<uint64_t>(hi) + 1u) << (kBits1 + kBits2);
+    uint32_t base = mid > span / 2 ? (mid - span / 2) & ~static_cast<uint32_t>(kBins2 - 1) : 0u;
+    if (base > (1u << 31) - span) base = (1u << 31) - span;
     // the prediction this step works with, for the kernel that checks it (preds is rewritten there)
     if (st == sd.st_first && threadIdx.x == 0) {
-        p_used[2 * d.seg] = p;
-        p_used[2 * d.seg + 1] = spec_ok ? spec_base : kNoSpec;
+        uint32_t* used = p_used + static_cast<size_t>(d.seg) * kPredWords;
+        used[0] = 1u;
+        used[1] = base;
+        used[2] = w;
+        used[3] = pred[3];                                  // steps in a row with the threshold in the range's middle half
     }
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
     __shared__ uint32_t fill;
-    __shared__ uint32_t acc[kPartWords];                    // [0] above the window, [1 + d] per window digit, ...
-    static_assert(kWindow + 2 <= kPartWords, "above, the window's digits, beyond the finely counted keys");
+    __shared__ uint32_t acc[2];                             // keys above the range, keys inside it
     __shared__ CollectStage stg;
     __shared__ uint2 cand_stage[kCandSlice];
     if (threadIdx.x == 0) fill = 0u;
-    if (threadIdx.x < kPartWords) acc[threadIdx.x] = 0u;
+    if (threadIdx.x < 2) acc[threadIdx.x] = 0u;
     __syncthreads();
 
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-    uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1;
-    uint32_t above_acc;
+    // the range's 2^(w-7) counts exist in 2^(19-w) copies (4096 words in all), one copy per residue of the
+    // supertile number: with a narrow range all the atomics of a step would otherwise hit a few cache lines
+    uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1 +
+                   ((static_cast<uint32_t>(st) & ((1u << (kSpecBitsMax - w)) - 1u)) << (w - kBits2));
+    uint32_t above_acc, in_acc;
     if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
-        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, lo, hi, wave, lane, &fill, stg, cand_stage);
+        above_acc = predicted_tiles<G, true>(mem, grad, lr, d, base, span, wave, lane, &fill, in_acc, stg, cand_stage);
     else
-        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, lo, hi, wave, lane, &fill, stg, cand_stage);
+        above_acc = predicted_tiles<G, false>(mem, grad, lr, d, base, span, wave, lane, &fill, in_acc, stg, cand_stage);
     if (lane == 0 && above_acc) atomicAdd(&acc[0], above_acc);
+    if (lane == 0 && in_acc) atomicAdd(&acc[1], in_acc);
     __syncthreads();
     collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
-    // The staged candidates go to the supertile's slice and are counted on the way, outside the
-    // streaming loop: per window digit (ballots, one LDS atomic per wave and digit) and, those among
-    // the 2^19 finely counted keys, per 128 keys in memory.  (If the slice overflowed the counts are
-    // incomplete, and nothing reads them.)
+    // The staged candidates go to the supertile's slice and are counted per 128 keys on the way,
+    // outside the streaming loop.  (If the slice overflowed the counts are incomplete, and nothing
+    // reads them.)
     static_assert(kCandSlice == 2 * kBlock, "two staged candidates per thread");
     const uint32_t n = fill < kCandSlice ? fill : kCandSlice;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const uint32_t e = j * kBlock + threadIdx.x;
-        const bool have = e < n;
-        const uint2 ce = have ? cand_stage[e] : make_uint2(0u, 0u);
-        if (have) slice[e] = ce;
-        const uint32_t digit = ce.x >> (kBits1 + kBits2);
-#pragma unroll
-        for (uint32_t w = 0; w < kWindow; ++w) {
-            const uint64_t b = __builtin_amdgcn_ballot_w64(have && digit == lo + w);
-            if (lane == 0 && b) atomicAdd(&acc[1 + w], static_cast<uint32_t>(__popcll(b)));
-        }
-        if (spec_ok) {                                      // block-uniform
-            const bool at_or_above = have && ce.x >= spec_base;
-            const uint32_t r = ce.x - spec_base;
-            if (at_or_above && r < kSpecSpan) atomicAdd(&h1[r >> kBits2], 1u);
-            const uint64_t b = __builtin_amdgcn_ballot_w64(at_or_above && r >= kSpecSpan);
-            if (lane == 0 && b) atomicAdd(&acc[1 + kWindow], static_cast<uint32_t>(__popcll(b)));
+        if (e < n) {
+            const uint2 ce = cand_stage[e];
+            slice[e] = ce;
+            atomicAdd(&h1[(ce.x - base) >> kBits2], 1u);
         }
     }
     if (threadIdx.x == 0) {
         st_cand_cnt[st] = n;
         if (fill > kCandSlice) overflow[d.seg] = 1u;        // every overflowing block stores the same value
     }
-    __syncthreads();
-    if (threadIdx.x <= kWindow + 1) {                       // [1 + kWindow]: beyond the keys counted per 128
+    if (threadIdx.x < 2) {
         const uint32_t v = acc[threadIdx.x];
         if (v)
             atomicAdd(&part[(static_cast<size_t>(d.seg) * kPartSlots + st % kPartSlots) * kPartWords + threadIdx.x], v);
@@ -291,13 +282,13 @@ __device__ __forceinline__ bool search_digit(const uint32_t* __restrict__ h, uin
 }
 
 // Level 0 of the search, for every segment: did the predicted pass see the k-th largest key inside
-// its window?  Then the segment's bucket is known without a histogram, and if the key is one of the
-// 2^19 keys that pass counted per 128, level 1 is searched right away on those counts.
-// Otherwise (no prediction, or one that failed) the blocks that hold the segment's supertiles count
-// the top 12 key bits of the leader's vector, and the search of that histogram is left to the
-// blocks of the next kernel (state.pending).  One block per entry of the block table (supertiles
-// of one segment); the segment's first block writes the state either way, and no block reads what
-// another block of the same kernel wrote.
+// its range?  Then the top 24 bits of the threshold follow from a search of that pass's counts, and
+// the width of the next step's range is chosen from how many keys this one held and where the
+// threshold fell in it.  Otherwise (no prediction, or a miss) the blocks that hold the segment's
+// supertiles count the top 12 key bits of the leader's vector, and the search of that histogram is
+// left to the blocks of the next kernel (state.pending).  One block per entry of the block table
+// (supertiles of one segment); the segment's first block writes the state either way, and no
+// block reads what another block of the same kernel wrote.
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
@@ -319,11 +310,12 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     // everything the segment number addresses is requested at once
     const uint32_t* my_part = part + static_cast<size_t>(cur) * kPartSlots * kPartWords;
     const SegDesc sd = segs[cur];
-    const uint32_t p = p_used[2 * cur];
-    const uint32_t spec_base = p_used[2 * cur + 1];
+    const uint32_t* used = p_used + static_cast<size_t>(cur) * kPredWords;
+    const uint32_t have = used[0], base = used[1], w = used[2];
     const uint32_t ov = overflow[cur];
     const uint32_t w0 = my_part[t], w1 = my_part[kBlock + t];
     const uint32_t k = static_cast<uint32_t>(sd.k);
+    uint32_t* pred = preds + static_cast<size_t>(cur) * kPredWords;
     SegState s{};                                           // every field is written each step
     s.k_rem = k;
     s.T = 0xffffffffu;                                      // above every key: nothing is a member
@@ -335,52 +327,82 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         }
         return;
     }
-    if (t == 0) {
-        res[0] = 0u;
-        flag = 0u;
-    }
-    if (p != 0) {                                           // block-uniform: sum the slotted copies of the counters
+    if (t == 0) flag = 0u;
+    bool hit = false;
+    if (have != 0) {                                        // block-uniform: sum the slotted copies of the counters
         if (t < kPartWords) tot_s[t] = 0u;
         __syncthreads();
         if (w0) atomicAdd(&tot_s[t % kPartWords], w0);
         if (w1) atomicAdd(&tot_s[(kBlock + t) % kPartWords], w1);
         __syncthreads();
-        if (t == 0) {
-            uint32_t tot[1 + kWindow], digit = 0, k_rem = 0;
-            for (uint32_t j = 0; j <= kWindow; ++j) tot[j] = tot_s[j];
-            if (spec_resolve(tot, ov != 0, p, k, digit, k_rem)) {
-                res[0] = 1u;
-                res[1] = digit;
-                res[2] = k_rem;
-            }
-        }
+        // exact: the range holds the k-th largest key iff fewer than k keys lie above it and at least k
+        // above or inside it (and every key inside it was listed)
+        hit = ov == 0 && tot_s[0] < k && k - tot_s[0] <= tot_s[1];
     }
-    __syncthreads();
-    if (res[0]) {                                           // block-uniform: the prediction held
+    if (hit) {                                              // block-uniform: the prediction held
         if (!owner) return;
-        s.prefix = res[1];
-        s.k_rem = res[2];
-        s.mode = kModeCand;
-        s.collected = 1;
-        // keys beyond the finely counted ones: those above the window and those inside it past the 2^19
-        const uint32_t beyond = tot_s[0] + tot_s[1 + kWindow];
-        if (spec_base != kNoSpec && k > beyond) {           // block-uniform: is the key among the finely counted ones?
-            uint32_t bin, n_bin, n_above;
-            if (search_digit<kBins1>(hist1_spec + static_cast<size_t>(cur) * kBins1, k - beyond, above, bin, n_bin,
-                                     n_above)) {
-                res[1] = (spec_base >> kBits2) + bin;       // the key's top 24 bits
-                res[2] = k - beyond - n_above;
-                flag = 1u;
-            }
-            __syncthreads();
+        const uint32_t above_range = tot_s[0], in_range = tot_s[1];
+        // add up the copies of the range's counts (word = copy * n_bins + bin) in LDS, then search there
+        const uint32_t n_bins = 1u << (w - kBits2);
+        const uint32_t* h1 = hist1_spec + static_cast<size_t>(cur) * kBins1;
+        constexpr int kPer = kBins1 / kBlock;
+        uint32_t mine[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) mine[j] = h1[j * kBlock + t];
+        for (int b = t; b < kBins1; b += kBlock) lh[b] = 0u;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (mine[j]) atomicAdd(&lh[(j * kBlock + t) & (n_bins - 1u)], mine[j]);
+        __syncthreads();
+        uint32_t bin, n_bin, n_above;
+        if (search_digit<kBins1>(lh, k - above_range, above, bin, n_bin, n_above)) {
+            res[1] = (base >> kBits2) + bin;                // the key's top 24 bits
+            res[2] = k - above_range - n_above;
+            res[0] = bin;
+            flag = 1u;
         }
+        __syncthreads();
         if (t == 0) {
-            preds[2 * cur] = s.prefix + 1u;                 // prediction for the next step
-            if (flag) {   // otherwise the key lies elsewhere in the window: level 1 runs from the list
+            if (flag) {
                 s.prefix = res[1];
                 s.k_rem = res[2];
+                s.mode = kModeCand;
+                s.collected = 1;
                 s.l1_done = 1;
-                preds[2 * cur + 1] = res[1];
+                // The next step's range.  Wider at once if the threshold fell outside the middle half of
+                // this one, or if this one held few keys.  Narrower only after kCalmSteps steps in a row
+                // with the threshold in the middle half, if the range holds many more keys than needed (the
+                // index set's size, and enough for the spread of an order statistic of that rank), and at
+                // once if it holds more than half of what the candidate list can take.
+                const uint64_t slots = static_cast<uint64_t>(sd.st_count) * kCandSlice;
+                uint64_t want = k > 64u ? k : 64u;
+                if (static_cast<uint64_t>(k) < 256u * 256u) {   // 16 * sqrt(k) > k
+                    uint32_t r = 1;
+                    while (r * r < k) ++r;
+                    if (16u * r > want) want = 16u * r;
+                }
+                if (want > slots / 4) want = slots / 4;
+                const bool middle = res[0] >= n_bins / 4 && res[0] < n_bins - n_bins / 4;
+                uint32_t calm = middle ? used[3] + 1u : 0u;
+                uint32_t w_next = w;
+                if (in_range > slots / 2 && w > kSpecBitsMin) {
+                    w_next = w - 1;
+                    calm = 0u;
+                } else if ((!middle || 5ull * in_range < 3 * want) && w < kSpecBitsMax) {
+                    w_next = w + 1;
+                    calm = 0u;
+                } else if (calm >= kCalmSteps && 2ull * in_range > 3 * want && w > kSpecBitsMin) {
+                    w_next = w - 1;
+                    calm = 0u;
+                }
+                pred[3] = calm;
+                pred[0] = 1u;
+                pred[1] = res[1];
+                pred[2] = w_next;
+            } else {                                        // only if the counts were corrupted: nothing is selected
+                s.done = 1;
+                pred[0] = 0u;
             }
             state_at(state, cur) = s;
         }
@@ -414,6 +436,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     if (owner && t == 0) {
         s.pending = 1;                                      // the next kernel's blocks search the histogram
         state_at(state, cur) = s;
+        pred[0] = 0u;                                       // until the levels that follow have found the threshold
     }
 }
 
@@ -494,13 +517,15 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                 // the bucket's keys go to the candidate list if its slots can hold them
                 const uint64_t slots = static_cast<uint64_t>(st_count) * kCandSlice;
                 ss.mode = res[3] <= slots ? kModeCand : kModeFull;
-                if (owner && t == 0) preds[2 * cur] = res[1] + 1u;   // prediction for the next step
-            } else if (owner && t == 0) {
-                preds[2 * cur + 1] = ss.prefix;             // where the next step counts finely
+            } else if (owner && t == 0) {                   // the prediction for the next step: widest range
+                uint32_t* pred = preds + static_cast<size_t>(cur) * kPredWords;
+                pred[0] = 1u;
+                pred[1] = ss.prefix;
+                pred[2] = kSpecBitsMax;
+                pred[3] = 0u;
             }
         } else {                                            // only if the counts were corrupted: nothing is selected
             ss.done = 1;
-            if (LEVEL == 1 && owner && t == 0) preds[2 * cur] = 0u;
         }
         ss.pending = 0;
     }
@@ -551,9 +576,9 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                         uint32_t key[4] = {0, 0, 0, 0};
                         bool ok[4] = {false, false, false, false};
                         if (p0 < end) leader_keys(mem, grad, lr, p0, begin, end, key, ok);
-                        uint32_t n_above;
-                        collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix, prefix, wt, lane, &fill, lh, n_above,
-                                            stg, slice);
+                        uint32_t n_above, n_in;
+                        collect_tile<false>(key, ok, static_cast<uint32_t>(p0), prefix << (kBits1 + kBits2),
+                                            1u << (kBits1 + kBits2), wt, lane, &fill, lh, n_above, n_in, stg, slice);
                     }
                     __syncthreads();
                     collect_flush(stg, nullptr, static_cast<size_t>(s2) * kTilesPerSuper, fill, out.wt_cnt, out.sel_mask,

@@ -4,6 +4,8 @@ import numpy as np
 import pytest
 import torch
 
+import oracle
+
 from paper_2104_11125_amd import binding, workloads
 
 pytestmark = pytest.mark.gpu
@@ -495,6 +497,40 @@ def test_prediction_at_the_ends_of_the_key_range(gu, scale):
             g = ((shared + 0.5 * rng.standard_normal(numel)) * scale).astype(np.float32)
             grads.append(torch.from_numpy(g).to(gu.DEV))
         gu.compare_step(ctx, mem, grads, ref, step, 0.3, 1.0, k=k, what=f"scale {scale} step {step}")
+    ctx.close()
+
+
+def test_long_run_into_the_piled_up_state(gu):
+    """Several hundred steps from zero memory: error feedback lets the magnitudes pile up just below
+    the threshold (a twelve-bit bucket around it comes to hold several per cent of all elements), the
+    range of finely counted keys narrows step by step, and its counts go to several slotted copies.
+    Index set and reduced values are compared at every step, the memories every 25 steps."""
+    rng = np.random.default_rng(9)
+    n, beta, lr = 3, 0.1, 0.1
+    sizes = [150_001, 37, 20_000, 3_000]
+    offsets = np.concatenate([[2], 2 + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1] + 1
+    ks = [1_500, 1, 200, 30]
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes), gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    pool = [[((rng.standard_normal(numel) + 0.5 * rng.standard_normal(numel)) * 1e-3).astype(np.float32)
+             for _ in range(n)] for _ in range(5)]
+    pool_dev = [[torch.from_numpy(g).to(gu.DEV) for g in gs] for gs in pool]
+    for step in range(400):
+        host, dev = pool[step % 5], pool_dev[step % 5]
+        idx, red = ctx.scalecom_step_layers(mem, dev, offsets, ks, beta, lr, step)
+        want_idx, want_red = oracle.step_layers(ref, host, offsets, ks, beta, lr, step)
+        gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"long run step {step}")
+        gu.assert_same("reduced", red.cpu().numpy(), want_red, 1e-5, f"long run step {step}")
+        if step % 25 == 24:
+            for i in range(n):
+                gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], 1e-6, f"long run step {step} learner {i}")
+    # the state the test is about was reached: the leader's bucket around the threshold is crowded
+    x = np.abs(ref[0][offsets[0]:offsets[1]] + np.float32(lr) * pool[0][0][offsets[0]:offsets[1]])
+    t = np.sort(x)[-ks[0]]
+    crowd = np.mean((x >= t * 0.97) & (x <= t * 1.03))
+    assert crowd > 3 * ks[0] / sizes[0], f"no pile-up around the threshold ({crowd:.4f})"
     ctx.close()
 
 
