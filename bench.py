@@ -7,7 +7,12 @@
 A "step" is one call of scalecom_step (scalecom_step_layers for the per-layer workload): the
 whole path -- accumulate, exact top-k on the cyclic leader, gather, sum over learners,
 low-pass memory update -- over one batch of synthetic gradients that already sit in HBM.
-Memories are carried from step to step, the leader rotates with the step index.
+Memories are carried from step to step, the leader rotates with the step index.  Memories start
+at zero (Alg. 1), and the default of 300 warm-up steps takes the run into the state a training
+job spends its time in: error feedback lets the magnitudes pile up just below the selection
+threshold (after a few hundred steps a twelve-bit bucket of keys around it holds several per
+cent of all elements), which is the hard case for finding the threshold; the first steps of a
+run are the easy one.
 
 `--select chunk` times the chunk-wise selector of the paper's own implementation (one position
 per `rate` consecutive elements: scalecom_step_chunked, or scalecom_step_layers_chunked for the
@@ -113,8 +118,9 @@ def cpu_baseline(w, select, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed steps from zero memories before the timed ones (see the module docstring)")
     ap.add_argument("--workload", default="resnet50_sized")
     ap.add_argument("--select", choices=["exact", "chunk"], default="exact")
     ap.add_argument("--no-cpu-baseline", action="store_true")

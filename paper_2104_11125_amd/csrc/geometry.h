@@ -74,8 +74,11 @@ struct SegState {         // selection state of one segment after a level; every
     uint32_t collected;   // 1: the candidate list was filled by the predicted single pass
     uint32_t l1_done;     // 1: levels 0 and 1 are known from the counts of the predicted pass
     uint32_t pending;     // 1: the last histogram was counted but not searched yet (the next kernel's blocks do that)
+    uint32_t l2_done;     // 1: T and q are final already, and the tile counts and masks are written (a segment of
+                          //    one supertile is searched and counted by one block)
+    uint32_t w_next;      // width of the next step's range, for the kernel that ends a search without prediction
 };
-static_assert(sizeof(SegState) == 36, "nine words, no padding to carry along in copies");
+static_assert(sizeof(SegState) == 44, "eleven words, no padding to carry along in copies");
 // One state per 128-byte line: blocks that work on different segments run on different XCDs, and
 // four states in one line made the per-segment searches three times slower with 200 segments.
 // (The stride is kept out of the struct so that copies of a state stay in registers.)

@@ -391,7 +391,7 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
                                            part, overflow, p_used, hist1_spec, next_zone, zone_words);
     k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, hist0, preds, p_used, part, overflow,
-                                         hist1_spec);
+                                         hist1_spec, wt_cnt, sel_mask, eq_mask, st_sum);
     mark(1);
     const CollectOut collect_out{wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt, full_flag};
     k_level<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, state1, hist0, hist1, preds,

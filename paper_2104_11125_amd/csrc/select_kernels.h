@@ -23,6 +23,53 @@ struct CollectStage {       // LDS staging of one supertile's masks and tile cou
     uint32_t cnt[kTilesPerSuper];
 };
 
+// The magnitude keys of the 8 wave tiles a wave owns in one supertile (tile it * kWaves + wave,
+// 4 keys per lane and tile; bit 4*it + c of okm says whether the element belongs to the segment).
+// All loads are issued before the first value is used: lanes whose four elements lie inside the
+// segment first (no branch between their loads), then the at most two lanes of the segment that
+// straddle its ends, element by element.  For the passes where few blocks work (fallbacks, small
+// segments) and nothing else hides a round trip to memory.
+template <typename G>
+__device__ __forceinline__ void supertile_keys(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
+                                               int64_t a0, int64_t begin, int64_t end, int wave, int lane,
+                                               uint32_t (&key)[kTilesPerSuper / kWaves * kVec], uint32_t& okm)
+{
+    constexpr int kIters = kTilesPerSuper / kWaves;
+    float4 m4[kIters], g4[kIters];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+        m4[it] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        g4[it] = m4[it];
+        if (p0 >= begin && p0 + 3 < end) {
+            m4[it] = load4(mem + p0);
+            g4[it] = load4(grad + p0);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+        const bool straddles = !(p0 >= begin && p0 + 3 < end) && p0 + 3 >= begin && p0 < end;
+        if (straddles) {
+            m4[it] = load_guarded(mem, p0, begin, end, false);
+            g4[it] = load_guarded(grad, p0, begin, end, false);
+        }
+    }
+    okm = 0;
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
+        uint32_t k4[4];
+        bool ok[4];
+        keys_from(m4[it], g4[it], lr, p0, begin, end, k4, ok);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            key[4 * it + c] = k4[c];
+            okm |= (ok[c] ? 1u : 0u) << (4 * it + c);
+        }
+    }
+}
+
 // The per-tile work of the "collect" pass, given the tile's keys: keys from lo_key + span on are
 // members for sure (their count and ballots are staged for the tile); the `span` keys from lo_key
 // on are appended, with their positions, to the supertile's candidate slice `cand_dst` (in LDS or
@@ -174,7 +221,7 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const uint32_t* pred = preds + static_cast<size_t>(d.seg) * kPredWords;
     const uint32_t have = pred[0], t24 = pred[1], w = pred[2];
     const SegDesc sd = segs[d.seg];
-    if (have == 0 || sd.k == 0) return;
+    if (have == 0 || sd.k == 0 || sd.st_count == 1) return;   // (one supertile: k_level0 searches it directly)
     // the range: 2^w keys centred on the middle of the previous threshold's 128 keys, aligned to 128,
     // cut off at key 0 and at 2^31
     const uint32_t span = 1u << w;
@@ -281,6 +328,63 @@ __device__ __forceinline__ bool search_digit(const uint32_t* __restrict__ h, uin
     return found;
 }
 
+// How many of the block's keys are >= cand: each thread brings NK keys (bit j of `valid` says
+// whether v[j] counts); `partial` is kWaves words of LDS that nobody else touches until the next
+// barrier.  All threads call it; the result is the same in every thread.
+template <int NK>
+__device__ __forceinline__ uint32_t block_count_at_least(const uint32_t (&v)[NK], uint32_t valid, uint32_t cand,
+                                                         uint32_t* partial, int lane, int wave)
+{
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) c += (((valid >> j) & 1u) && v[j] >= cand) ? 1u : 0u;
+    c = wave_sum(c);
+    if (lane == 0) partial[wave] = c;
+    __syncthreads();
+    uint32_t total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) total += partial[w];
+    return total;
+}
+
+// The k-th largest of the block's keys (1 <= k <= number of valid keys), bit by bit from the top:
+// T keeps a bit if at least k keys are >= T with that bit set.  One barrier per bit, the waves'
+// partial counts in alternating halves of `partial` (2 * kWaves words of LDS).  q = how many keys
+// equal to T belong to the k largest.  No histogram: its atomics would all hit the few top digits
+// that gradient-like keys share.
+template <int NK>
+__device__ __forceinline__ uint32_t block_kth_largest(const uint32_t (&v)[NK], uint32_t valid, uint32_t k,
+                                                      uint32_t* partial, int lane, int wave, uint32_t& q)
+{
+    uint32_t T = 0;
+    for (int bit = 30; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        if (block_count_at_least<NK>(v, valid, cand, partial + (bit & 1) * kWaves, lane, wave) >= k) T = cand;
+    }
+    q = T == 0x7fffffffu ? k : k - block_count_at_least<NK>(v, valid, T + 1u, partial + kWaves, lane, wave);
+    return T;
+}
+
+// The same search by ONE wave over keys that its lanes hold (a few hundred keys): no LDS and no
+// barrier per bit, only a reduction over the lanes.  All 64 lanes of the wave call it.
+template <int NK>
+__device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&v)[NK], uint32_t valid, uint32_t k, uint32_t& q)
+{
+    auto count_at_least = [&](uint32_t cand) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int j = 0; j < NK; ++j) c += (((valid >> j) & 1u) && v[j] >= cand) ? 1u : 0u;
+        return wave_sum(c);
+    };
+    uint32_t T = 0;
+    for (int bit = 30; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        if (count_at_least(cand) >= k) T = cand;
+    }
+    q = T == 0x7fffffffu ? k : k - count_at_least(T + 1u);
+    return T;
+}
+
 // Level 0 of the search, for every segment: did the predicted pass see the k-th largest key inside
 // its range?  Then the top 24 bits of the threshold follow from a search of that pass's counts, and
 // the width of the next step's range is chosen from how many keys this one held and where the
@@ -294,7 +398,8 @@ __global__ void __launch_bounds__(kBlock)
 k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
          const HistBlock* __restrict__ hblocks, SegState* __restrict__ state, uint32_t* __restrict__ hist,
          uint32_t* __restrict__ preds, const uint32_t* __restrict__ p_used, const uint32_t* __restrict__ part,
-         const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec)
+         const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec, uint32_t* __restrict__ wt_cnt,
+         uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
 {
     __shared__ uint32_t lh[kBins0];
     __shared__ uint32_t tot_s[kPartWords];
@@ -324,6 +429,137 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         if (owner && t == 0) {
             s.done = 1;
             state_at(state, cur) = s;
+        }
+        return;
+    }
+    if (sd.st_count == 1) {
+        // A segment of one supertile (up to 8192 elements; with hundreds of tensors, half of them): its one
+        // block finds the threshold here and now on the keys it holds in registers, and counts the tiles.  No prediction: the k-th largest of so few values moves by several per cent from
+        // step to step, more than any range of finely counted keys covers.
+        constexpr int kIters = kTilesPerSuper / kWaves;
+        constexpr int kMine = kIters * kVec;                // 32 keys per thread
+        constexpr uint32_t kListMax = 8 * kBlock;           // keys near the threshold, 8 per thread
+        static_assert(kListMax <= kBins0, "the list lives in the histogram's words");
+        uint32_t key[kMine];
+        uint32_t okm;                                       // bit 4*it + c: the element belongs to the segment
+        supertile_keys(mem, grad, lr, static_cast<int64_t>(hb.a0), static_cast<int64_t>(hb.begin),
+                       static_cast<int64_t>(hb.end), wave, lane, key, okm);
+        // The search runs over the few keys near the previous step's threshold if the k largest are
+        // among them (one count tells), over all keys otherwise.
+        uint32_t* partial = tot_s;                          // 2 x kWaves words
+        static_assert(kPartWords >= 2 * kWaves, "room for the partial counts");
+        const uint32_t t_prev = pred[1] << kBits2;          // 0 before the first step
+        const uint32_t n_seg = static_cast<uint32_t>(hb.end - hb.begin);
+        uint32_t lo = t_prev > (1u << (kBits1 + kBits2)) ? t_prev - (1u << (kBits1 + kBits2)) : 0u;
+        uint32_t n_near = n_seg;
+        if (lo != 0u) {                                     // block-uniform
+            n_near = block_count_at_least<kMine>(key, okm, lo, partial + kWaves, lane, wave);   // (the search starts in the other half)
+            if (n_near < k) {                               // the threshold fell by more than that: every key is a candidate
+                lo = 0u;
+                n_near = n_seg;
+                __syncthreads();                            // (the partial counts have been read)
+            }
+        }
+        uint32_t T, q;
+        if (n_near <= kListMax) {                           // block-uniform (n_near >= k holds)
+            // my keys >= lo go to consecutive words of the list: exclusive prefix of the threads' counts
+            uint32_t near = 0;
+#pragma unroll
+            for (int j = 0; j < kMine; ++j) near |= (((okm >> j) & 1u) && key[j] >= lo ? 1u : 0u) << j;
+            uint32_t incl = __popc(near);
+#pragma unroll
+            for (int off = 1; off < kLanes; off <<= 1) {
+                const uint32_t a = __shfl_up(incl, off, kLanes);
+                if (lane >= off) incl += a;
+            }
+            if (lane == kLanes - 1) above[wave] = incl;     // the wave's total
+            __syncthreads();
+            uint32_t slot = incl - __popc(near);
+            for (int w2 = 0; w2 < wave; ++w2) slot += above[w2];
+#pragma unroll
+            for (int j = 0; j < kMine; ++j)
+                if ((near >> j) & 1u) lh[slot++] = key[j];
+            __syncthreads();
+            // the first wave searches the list by itself (8 keys per lane if they are few, else 32)
+            if (wave == 0) {
+                if (n_near <= 8u * kLanes) {
+                    uint32_t mine[8];
+                    uint32_t have_mask = 0;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t e = j * kLanes + lane;
+                        mine[j] = e < n_near ? lh[e] : 0u;
+                        have_mask |= (e < n_near ? 1u : 0u) << j;
+                    }
+                    T = wave_kth_largest<8>(mine, have_mask, k, q);
+                } else {
+                    uint32_t mine[kListMax / kLanes];
+                    uint32_t have_mask = 0;
+#pragma unroll
+                    for (int j = 0; j < static_cast<int>(kListMax / kLanes); ++j) {
+                        const uint32_t e = j * kLanes + lane;
+                        mine[j] = e < n_near ? lh[e] : 0u;
+                        have_mask |= (e < n_near ? 1u : 0u) << j;
+                    }
+                    T = wave_kth_largest<kListMax / kLanes>(mine, have_mask, k, q);
+                }
+                if (lane == 0) {
+                    res[0] = T;
+                    res[1] = q;
+                }
+            }
+            __syncthreads();
+            T = res[0];
+            q = res[1];
+        } else {
+            T = block_kth_largest<kMine>(key, okm, k, partial, lane, wave, q);
+        }
+        const uint32_t prefix = T, k_rem = q;
+        const bool found_all = true;
+        // the tile counts and masks of the supertile, from the keys at hand (what k_tilecount does otherwise)
+        const size_t tile0 = static_cast<size_t>(hb.st_lo) * kTilesPerSuper;
+        __syncthreads();                                    // (the last partial counts have been read)
+        uint32_t* cnt = lh;                                 // the histogram's words: unused on this path
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const int wt = it * kWaves + wave;
+            uint64_t gt[4], eq[4];
+            uint32_t n_gt = 0, n_eq = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool ok = (okm >> (4 * it + c)) & 1u;
+                gt[c] = __ballot(ok && key[4 * it + c] > T);
+                eq[c] = __ballot(ok && key[4 * it + c] == T);
+                n_gt += __popcll(gt[c]);
+                n_eq += __popcll(eq[c]);
+            }
+            if (lane == 0) {
+                cnt[wt] = n_gt | (n_eq << 16);             // at most 256 each
+                store_tile_masks(sel_mask, tile0 + wt, gt);
+                store_tile_masks(eq_mask, tile0 + wt, eq);
+            }
+        }
+        __syncthreads();
+        if (t < kLanes) {
+            const uint32_t v = t < kTilesPerSuper ? cnt[t] : 0u;
+            if (t < kTilesPerSuper) wt_cnt[tile0 + t] = v;
+            const uint32_t s2 = wave_sum(v);               // at most 8192 each: no carry between halves
+            if (t == 0) st_sum[hb.st_lo] = make_uint2(s2 & 0xffffu, s2 >> 16);
+        }
+        if (t == 0) {
+            if (found_all) {
+                s.prefix = prefix;
+                s.k_rem = k_rem;
+                s.T = prefix;
+                s.q = k_rem;
+                s.l1_done = 1;
+                s.l2_done = 1;
+            } else {
+                s.done = 1;
+            }
+            state_at(state, cur) = s;
+            pred[0] = 0u;                                   // no range for the predicted pass ...
+            pred[1] = T >> kBits2;                          // ... but where to look first in the next step
         }
         return;
     }
@@ -371,10 +607,11 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
                 s.collected = 1;
                 s.l1_done = 1;
                 // The next step's range.  Wider at once if the threshold fell outside the middle half of
-                // this one, or if this one held few keys.  Narrower only after kCalmSteps steps in a row
-                // with the threshold in the middle half, if the range holds many more keys than needed (the
-                // index set's size, and enough for the spread of an order statistic of that rank), and at
-                // once if it holds more than half of what the candidate list can take.
+                // this one, or if this one held few keys -- unless twice as many keys would crowd the
+                // candidate list.  Narrower only after kCalmSteps steps in a row with the threshold in the
+                // middle half, if the range holds many more keys than needed (the index set's size, and
+                // enough for the spread of an order statistic of that rank), and at once if it holds more
+                // than three quarters of what the candidate list can take.
                 const uint64_t slots = static_cast<uint64_t>(sd.st_count) * kCandSlice;
                 uint64_t want = k > 64u ? k : 64u;
                 if (static_cast<uint64_t>(k) < 256u * 256u) {   // 16 * sqrt(k) > k
@@ -384,12 +621,13 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
                 }
                 if (want > slots / 4) want = slots / 4;
                 const bool middle = res[0] >= n_bins / 4 && res[0] < n_bins - n_bins / 4;
+                const bool room = 8ull * in_range <= 3 * slots;   // twice as many still below 3/4 of the slots
                 uint32_t calm = middle ? used[3] + 1u : 0u;
                 uint32_t w_next = w;
-                if (in_range > slots / 2 && w > kSpecBitsMin) {
+                if (4ull * in_range > 3 * slots && w > kSpecBitsMin) {
                     w_next = w - 1;
                     calm = 0u;
-                } else if ((!middle || 5ull * in_range < 3 * want) && w < kSpecBitsMax) {
+                } else if ((!middle || 5ull * in_range < 3 * want) && room && w < kSpecBitsMax) {
                     w_next = w + 1;
                     calm = 0u;
                 } else if (calm >= kCalmSteps && 2ull * in_range > 3 * want && w > kSpecBitsMin) {
@@ -409,23 +647,36 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         return;
     }
 
+    // The width of the next step's range, once the levels that follow have found the threshold: the
+    // widest, or if this step had a range that missed, the widest that would have held at most half
+    // of what the candidate list can take (the density around the threshold changes slowly).
+    s.w_next = kSpecBitsMax;
+    if (have != 0) {
+        const uint64_t half = static_cast<uint64_t>(sd.st_count) * kCandSlice / 2;
+        uint64_t would = tot_s[1];                          // keys the missed range held, of width w
+        uint32_t fit = w;
+        while (would > half && fit > kSpecBitsMin) {
+            would >>= 1;
+            --fit;
+        }
+        while (2 * would <= half && fit < kSpecBitsMax) {
+            would <<= 1;
+            ++fit;
+        }
+        s.w_next = fit;
+    }
     // no prediction, or one that failed: count the top digits of my part of the segment
     for (int b = t; b < kBins0; b += kBlock) lh[b] = 0u;
     __syncthreads();
     const int64_t begin = hb.begin, end = hb.end;
     for (int s2 = hb.st_lo; s2 < hb.st_hi; ++s2) {
         const int64_t a0 = static_cast<int64_t>(hb.a0) + static_cast<int64_t>(s2 - hb.st_lo) * kSuper;
-#pragma unroll 2
-        for (int it = 0; it < kTilesPerSuper / kWaves; ++it) {
-            const int64_t p0 = a0 + (it * kWaves + wave) * kWaveTile + lane * kVec;
-            if (p0 >= end) continue;
-            uint32_t key[4];
-            bool ok[4];
-            leader_keys(mem, grad, lr, p0, begin, end, key, ok);
+        uint32_t key[kTilesPerSuper / kWaves * kVec];
+        uint32_t okm;
+        supertile_keys(mem, grad, lr, a0, begin, end, wave, lane, key, okm);
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (ok[c]) atomicAdd(&lh[key[c] >> (kBits1 + kBits2)], 1u);
-        }
+        for (int j = 0; j < kTilesPerSuper / kWaves * kVec; ++j)
+            if ((okm >> j) & 1u) atomicAdd(&lh[key[j] >> (kBits1 + kBits2)], 1u);
     }
     __syncthreads();
     uint32_t* h = hist + static_cast<size_t>(cur) * kBins0;
@@ -521,7 +772,7 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                 uint32_t* pred = preds + static_cast<size_t>(cur) * kPredWords;
                 pred[0] = 1u;
                 pred[1] = ss.prefix;
-                pred[2] = kSpecBitsMax;
+                pred[2] = ss.w_next;
                 pred[3] = 0u;
             }
         } else {                                            // only if the counts were corrupted: nothing is selected
@@ -529,7 +780,7 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
         }
         ss.pending = 0;
     }
-    if (ss.done != 0 || (LEVEL == 1 && ss.l1_done != 0)) {  // block-uniform: nothing to count
+    if (ss.done != 0 || (LEVEL == 1 ? ss.l1_done != 0 : ss.l2_done != 0)) {  // block-uniform: nothing to count
         if (owner && t == 0) state_at(state_out, cur) = ss;
         return;
     }
@@ -697,7 +948,8 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const uint32_t* h2 = hist2 + static_cast<size_t>(d.seg) * kBins2;
     const uint32_t h_lo = h2[lane], h_hi = h2[kLanes + lane];
     const int st_first = segs[d.seg].st_first;
-    uint32_t T = ss.T, q = 0u;                              // an empty index set keeps T above every key
+    if (ss.l2_done) return;                                 // whole wave: counted by the block that searched it
+    uint32_t T = ss.T, q = ss.q;                            // an empty index set keeps T above every key
     if (!ss.done) {                                         // wave-uniform
         T = find_threshold(h_lo, h_hi, ss.prefix, ss.k_rem, lane, q);
         if (st == st_first && lane == 0) {                  // for the tie quota of the slot pass
