@@ -7,16 +7,17 @@
 // magnitude key |x_L| of the leader's x_L = fma(lr, grad_L, mem_L) (recomputed on the fly, never
 // stored) is resolved 12 + 12 + 7 bits at a time (radix select):
 //
-//   predicted   leader, ONE pass, for segments that carry the threshold of the previous step as
-//               a prediction: keys whose top 12 bits lie above a 5-bucket window around its
-//               bucket are members for sure (counted per 256-element wave tile, marked in the
-//               membership bitmask); keys inside the window are copied, with their positions,
-//               to a small candidate list and counted per bucket, and the 2^19 keys around the
-//               previous threshold also per 128 keys
-//   level0      per segment: did the k-th largest key fall inside the window (exact check on
-//               counts)?  Then its bucket is known (Eq. 2), and its top 24 bits too if it fell
-//               among the finely counted keys.  Otherwise (no prediction, or a miss): histogram
-//               of the top 12 key bits of the leader's vector
+//   predicted   leader, ONE pass, for segments that carry a prediction: a range of keys around the
+//               previous step's threshold, whose width follows how densely the keys lie there
+//               (with error feedback they pile up below the threshold).  Keys above the range
+//               are members for sure (counted per 256-element wave tile, marked in the
+//               membership bitmask); keys inside it are copied, with their positions, to a small
+//               candidate list and counted per 128 keys
+//   level0      per segment: did the k-th largest key fall inside the range (exact check on
+//               counts)?  Then the top 24 bits of the threshold follow from the range's counts
+//               (Eq. 2).  Otherwise (no prediction, or a miss): histogram of the top 12 key bits
+//               of the leader's vector.  A segment of one supertile is finished here by its one
+//               block, without prediction
 //   level<1>    a histogram of level0 is searched by every block that needs the result; then the
 //               next 12 key bits, histogrammed over the candidate list -- nothing to do if they
 //               are known already; for segments that went through the level-0 histogram this is
