@@ -434,8 +434,9 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     }
     if (sd.st_count == 1) {
         // A segment of one supertile (up to 8192 elements; with hundreds of tensors, half of them): its one
-        // block finds the threshold here and now on the keys it holds in registers, and counts the tiles.  No prediction: the k-th largest of so few values moves by several per cent from
-        // step to step, more than any range of finely counted keys covers.
+        // block finds the threshold here and now on the keys it holds in registers, and counts the tiles.
+        // No range from the predicted pass: the k-th largest of so few values moves by several per cent
+        // from step to step, more than a range that the candidate list can hold covers.
         constexpr int kIters = kTilesPerSuper / kWaves;
         constexpr int kMine = kIters * kVec;                // 32 keys per thread
         constexpr uint32_t kListMax = 8 * kBlock;           // keys near the threshold, 8 per thread
@@ -453,7 +454,8 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         uint32_t lo = t_prev > (1u << (kBits1 + kBits2)) ? t_prev - (1u << (kBits1 + kBits2)) : 0u;
         uint32_t n_near = n_seg;
         if (lo != 0u) {                                     // block-uniform
-            n_near = block_count_at_least<kMine>(key, okm, lo, partial + kWaves, lane, wave);   // (the search starts in the other half)
+            // (counted in the second half of `partial`: the search starts in the first)
+            n_near = block_count_at_least<kMine>(key, okm, lo, partial + kWaves, lane, wave);
             if (n_near < k) {                               // the threshold fell by more than that: every key is a candidate
                 lo = 0u;
                 n_near = n_seg;
@@ -514,8 +516,6 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         } else {
             T = block_kth_largest<kMine>(key, okm, k, partial, lane, wave, q);
         }
-        const uint32_t prefix = T, k_rem = q;
-        const bool found_all = true;
         // the tile counts and masks of the supertile, from the keys at hand (what k_tilecount does otherwise)
         const size_t tile0 = static_cast<size_t>(hb.st_lo) * kTilesPerSuper;
         __syncthreads();                                    // (the last partial counts have been read)
@@ -547,16 +547,12 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
             if (t == 0) st_sum[hb.st_lo] = make_uint2(s2 & 0xffffu, s2 >> 16);
         }
         if (t == 0) {
-            if (found_all) {
-                s.prefix = prefix;
-                s.k_rem = k_rem;
-                s.T = prefix;
-                s.q = k_rem;
-                s.l1_done = 1;
-                s.l2_done = 1;
-            } else {
-                s.done = 1;
-            }
+            s.prefix = T;
+            s.k_rem = q;
+            s.T = T;
+            s.q = q;
+            s.l1_done = 1;
+            s.l2_done = 1;
             state_at(state, cur) = s;
             pred[0] = 0u;                                   // no range for the predicted pass ...
             pred[1] = T >> kBits2;                          // ... but where to look first in the next step
