@@ -204,3 +204,27 @@ def test_large_vector_fallback_paths(gu):
             grads.append(torch.from_numpy(g).to(gu.DEV))
         gu.compare_step(ctx, mem, grads, ref, step, 0.3, 1.0, k=k, what=f"fallback paths step {step} {move}")
     ctx.close()
+
+
+def test_resnet50_sized_piled_up_full(gu):
+    """The state a long run is in, at the benchmark's size: memories drawn (from a seeded recipe,
+    not from earlier GPU steps) with magnitudes crowded just below a common level, so that the
+    threshold's neighbourhood holds many times k elements.  Over the steps the predicted pass's
+    range misses, is re-sized from the density it saw, narrows, and its counts spread over slotted
+    copies; every step is compared element by element."""
+    w = workloads.by_name("resnet50_sized")
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV, k_max=w.k)
+    gen = torch.Generator(device=gu.DEV)
+    mem = []
+    for i in range(w.n_learners):
+        gen.manual_seed(970 + i)
+        u = torch.rand(w.numel, generator=gen, device=gu.DEV)
+        sign = torch.where(torch.rand(w.numel, generator=gen, device=gu.DEV) < 0.5, -1.0, 1.0)
+        mem.append((4e-3 * (1.0 - 0.5 * u * u * u) * sign).to(torch.float32))   # a third of them within 10 % of 4e-3
+        del u, sign
+    ref = [m.cpu().numpy().copy() for m in mem]
+    for step in range(12):
+        print(f"[fullsize] {w.name} piled up, step {step}", flush=True)
+        grad = workloads.gradients(w, step, gu.DEV)
+        gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, k=w.k, what=w.name + " piled up")
+    ctx.close()

@@ -534,6 +534,27 @@ def test_long_run_into_the_piled_up_state(gu):
     ctx.close()
 
 
+def test_long_run_bf16_flat(gu):
+    """The same for one flat vector with bf16 gradients (300 steps)."""
+    rng = np.random.default_rng(10)
+    n, numel, k, beta, lr = 4, 200_003, 2_000, 0.1, 0.1
+    ctx = binding.scalecom_init(numel, n, torch.bfloat16, 1, gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    pool_dev = [[torch.from_numpy(((rng.standard_normal(numel) + 0.5 * rng.standard_normal(numel)) * 1e-3)
+                                  .astype(np.float32)).to(gu.DEV).to(torch.bfloat16) for _ in range(n)]
+                for _ in range(6)]
+    pool = [[gu.to_host(g) for g in gs] for gs in pool_dev]
+    for step in range(300):
+        idx, red = ctx.scalecom_step(mem, pool_dev[step % 6], k, beta, lr, step)
+        want_idx, want_red = oracle.step(ref, pool[step % 6], k, beta, lr, step)
+        gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"long bf16 run step {step}")
+        gu.assert_same("reduced", red.cpu().numpy(), want_red, 1e-5, f"long bf16 run step {step}")
+    for i in range(n):
+        gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], 1e-6, f"long bf16 run learner {i}")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
