@@ -53,7 +53,7 @@ def index_set_size(w, select):
 
 
 def algorithmic_bytes(w, k):
-    """Bytes one step must move (stated in the design doc): read every learner's mem and grad,
+    """Bytes one step must move: read every learner's mem and grad,
     write every mem, one extra look at the leader's (mem, grad) to find the threshold, write
     idx + reduced values."""
     gb = 2 if w.grad_dtype == "bf16" else 4
