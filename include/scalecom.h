@@ -23,7 +23,7 @@
  *    pointers marked [host] are ordinary process memory, read before the call returns.
  *  - The caller owns every buffer, including the workspace; the library allocates no
  *    device memory.  Per context it keeps pinned host staging for its tile tables
- *    (about numel_max / 1000 + 64 * n_tensors_max bytes).
+ *    (about numel_max / 256 + 140 * n_tensors_max + 64 KB bytes).
  *  - The result of a call depends only on its arguments.  The context remembers, per tensor,
  *    where the previous step's threshold fell and uses it to skip a pass over the leader when
  *    the guess holds (checked exactly); this changes the time a step takes, never its result.
