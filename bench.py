@@ -118,7 +118,7 @@ def cpu_baseline(w, select, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=300,
                     help="untimed steps from zero memories before the timed ones (see the module docstring)")
     ap.add_argument("--workload", default="resnet50_sized")
