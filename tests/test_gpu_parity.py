@@ -555,6 +555,46 @@ def test_long_run_bf16_flat(gu):
     ctx.close()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_randomized_long_runs(gu, seed):
+    """120 steps on a random layout (tensors of one and of several supertiles, any learner count,
+    rate, beta, lr, gradient type): the ranges of the predicted pass adapt while the magnitudes pile
+    up, and every step's index set and reduced values are compared."""
+    rng = np.random.default_rng(50_000 + seed)
+    n = int(rng.integers(2, 6))
+    nt = int(rng.integers(1, 7))
+    sizes = [int(rng.choice([300, 5000, 8192, 9000, 40_000, 150_000])) for _ in range(nt)]
+    off0 = int(rng.integers(0, 5))
+    offsets = np.concatenate([[off0], off0 + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1] + int(rng.integers(0, 3))
+    rate = int(rng.choice([25, 100, 400]))
+    ks = [max(1, s // rate) for s in sizes]
+    bf16 = bool(rng.integers(0, 2))
+    beta = float(rng.choice([0.1, 0.3, 1.0]))
+    lr = float(rng.choice([0.1, 1.0]))
+    ctx = binding.scalecom_init(numel, n, torch.bfloat16 if bf16 else torch.float32, nt, gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    shared = rng.standard_normal(numel)
+    pool_dev = []
+    for _ in range(4):
+        gs = []
+        for _ in range(n):
+            g = torch.from_numpy(((shared + 0.5 * rng.standard_normal(numel)) * 1e-3).astype(np.float32)).to(gu.DEV)
+            gs.append(g.to(torch.bfloat16) if bf16 else g)
+        pool_dev.append(gs)
+    pool = [[gu.to_host(g) for g in gs] for gs in pool_dev]
+    what = f"seed {seed} sizes={sizes} ks={ks} n={n} bf16={bf16} beta={beta} lr={lr}"
+    for step in range(120):
+        idx, red = ctx.scalecom_step_layers(mem, pool_dev[step % 4], offsets, ks, beta, lr, step)
+        want_idx, want_red = oracle.step_layers(ref, pool[step % 4], offsets, ks, beta, lr, step)
+        gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"{what} step {step}")
+        gu.assert_same("reduced", red.cpu().numpy(), want_red, 1e-5, f"{what} step {step}")
+    for i in range(n):
+        gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], 1e-6, f"{what} learner {i}")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
