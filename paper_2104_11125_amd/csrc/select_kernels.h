@@ -385,6 +385,145 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&v)[NK], ui
     return T;
 }
 
+// A segment of one supertile (up to 8192 elements; with hundreds of tensors, half of them) is
+// finished by its one block: the threshold is found on the keys the block holds in registers, and
+// the tile counts and masks are written.  No range from the predicted pass: the k-th largest of so
+// few values moves by several per cent from step to step, more than a range that the candidate list
+// can hold covers; what is kept from the previous step is where to look first.  `s` arrives with
+// k_rem = k and nothing found; lh (kBins0 words), tot_s (kPartWords), res (2), above (kWaves) are
+// LDS of the calling kernel.  All threads of the block call it.
+template <typename G>
+__device__ __forceinline__ void select_one_supertile(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
+                                                     const HistBlock& hb, uint32_t k, SegState s,
+                                                     SegState* __restrict__ state, uint32_t* __restrict__ pred,
+                                                     uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask,
+                                                     uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum,
+                                                     uint32_t* lh, uint32_t* tot_s, uint32_t* res, uint32_t* above)
+{
+    const int t = threadIdx.x, wave = t / kLanes, lane = t % kLanes;
+    const int cur = hb.seg;
+    constexpr int kIters = kTilesPerSuper / kWaves;
+    constexpr int kMine = kIters * kVec;                // 32 keys per thread
+    constexpr uint32_t kListMax = 8 * kBlock;           // keys near the threshold, 8 per thread
+    static_assert(kListMax <= kBins0, "the list lives in the histogram's words");
+    uint32_t key[kMine];
+    uint32_t okm;                                       // bit 4*it + c: the element belongs to the segment
+    supertile_keys(mem, grad, lr, static_cast<int64_t>(hb.a0), static_cast<int64_t>(hb.begin),
+                   static_cast<int64_t>(hb.end), wave, lane, key, okm);
+    // The search runs over the few keys near the previous step's threshold if the k largest are
+    // among them (one count tells), over all keys otherwise.
+    uint32_t* partial = tot_s;                          // 2 x kWaves words
+    static_assert(kPartWords >= 2 * kWaves, "room for the partial counts");
+    const uint32_t t_prev = pred[1] << kBits2;          // 0 before the first step
+    const uint32_t n_seg = static_cast<uint32_t>(hb.end - hb.begin);
+    uint32_t lo = t_prev > (1u << (kBits1 + kBits2)) ? t_prev - (1u << (kBits1 + kBits2)) : 0u;
+    uint32_t n_near = n_seg;
+    if (lo != 0u) {                                     // block-uniform
+        // (counted in the second half of `partial`: the search starts in the first)
+        n_near = block_count_at_least<kMine>(key, okm, lo, partial + kWaves, lane, wave);
+        if (n_near < k) {                               // the threshold fell by more than that: every key is a candidate
+            lo = 0u;
+            n_near = n_seg;
+            __syncthreads();                            // (the partial counts have been read)
+        }
+    }
+    uint32_t T, q;
+    if (n_near <= kListMax) {                           // block-uniform (n_near >= k holds)
+        // my keys >= lo go to consecutive words of the list: exclusive prefix of the threads' counts
+        uint32_t near = 0;
+#pragma unroll
+        for (int j = 0; j < kMine; ++j) near |= (((okm >> j) & 1u) && key[j] >= lo ? 1u : 0u) << j;
+        uint32_t incl = __popc(near);
+#pragma unroll
+        for (int off = 1; off < kLanes; off <<= 1) {
+            const uint32_t a = __shfl_up(incl, off, kLanes);
+            if (lane >= off) incl += a;
+        }
+        if (lane == kLanes - 1) above[wave] = incl;     // the wave's total
+        __syncthreads();
+        uint32_t slot = incl - __popc(near);
+        for (int w2 = 0; w2 < wave; ++w2) slot += above[w2];
+#pragma unroll
+        for (int j = 0; j < kMine; ++j)
+            if ((near >> j) & 1u) lh[slot++] = key[j];
+        __syncthreads();
+        // the first wave searches the list by itself (8 keys per lane if they are few, else 32)
+        if (wave == 0) {
+            if (n_near <= 8u * kLanes) {
+                uint32_t mine[8];
+                uint32_t have_mask = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t e = j * kLanes + lane;
+                    mine[j] = e < n_near ? lh[e] : 0u;
+                    have_mask |= (e < n_near ? 1u : 0u) << j;
+                }
+                T = wave_kth_largest<8>(mine, have_mask, k, q);
+            } else {
+                uint32_t mine[kListMax / kLanes];
+                uint32_t have_mask = 0;
+#pragma unroll
+                for (int j = 0; j < static_cast<int>(kListMax / kLanes); ++j) {
+                    const uint32_t e = j * kLanes + lane;
+                    mine[j] = e < n_near ? lh[e] : 0u;
+                    have_mask |= (e < n_near ? 1u : 0u) << j;
+                }
+                T = wave_kth_largest<kListMax / kLanes>(mine, have_mask, k, q);
+            }
+            if (lane == 0) {
+                res[0] = T;
+                res[1] = q;
+            }
+        }
+        __syncthreads();
+        T = res[0];
+        q = res[1];
+    } else {
+        T = block_kth_largest<kMine>(key, okm, k, partial, lane, wave, q);
+    }
+    // the tile counts and masks of the supertile, from the keys at hand (what k_tilecount does otherwise)
+    const size_t tile0 = static_cast<size_t>(hb.st_lo) * kTilesPerSuper;
+    __syncthreads();                                    // (the last partial counts have been read)
+    uint32_t* cnt = lh;                                 // the histogram's words: unused on this path
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int wt = it * kWaves + wave;
+        uint64_t gt[4], eq[4];
+        uint32_t n_gt = 0, n_eq = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool ok = (okm >> (4 * it + c)) & 1u;
+            gt[c] = __ballot(ok && key[4 * it + c] > T);
+            eq[c] = __ballot(ok && key[4 * it + c] == T);
+            n_gt += __popcll(gt[c]);
+            n_eq += __popcll(eq[c]);
+        }
+        if (lane == 0) {
+            cnt[wt] = n_gt | (n_eq << 16);             // at most 256 each
+            store_tile_masks(sel_mask, tile0 + wt, gt);
+            store_tile_masks(eq_mask, tile0 + wt, eq);
+        }
+    }
+    __syncthreads();
+    if (t < kLanes) {
+        const uint32_t v = t < kTilesPerSuper ? cnt[t] : 0u;
+        if (t < kTilesPerSuper) wt_cnt[tile0 + t] = v;
+        const uint32_t s2 = wave_sum(v);               // at most 8192 each: no carry between halves
+        if (t == 0) st_sum[hb.st_lo] = make_uint2(s2 & 0xffffu, s2 >> 16);
+    }
+    if (t == 0) {
+        s.prefix = T;
+        s.k_rem = q;
+        s.T = T;
+        s.q = q;
+        s.l1_done = 1;
+        s.l2_done = 1;
+        state_at(state, cur) = s;
+        pred[0] = 0u;                                   // no range for the predicted pass ...
+        pred[1] = T >> kBits2;                          // ... but where to look first in the next step
+    }
+}
+
 // Level 0 of the search, for every segment: did the predicted pass see the k-th largest key inside
 // its range?  Then the top 24 bits of the threshold follow from a search of that pass's counts, and
 // the width of the next step's range is chosen from how many keys this one held and where the
@@ -432,131 +571,9 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         }
         return;
     }
-    if (sd.st_count == 1) {
-        // A segment of one supertile (up to 8192 elements; with hundreds of tensors, half of them): its one
-        // block finds the threshold here and now on the keys it holds in registers, and counts the tiles.
-        // No range from the predicted pass: the k-th largest of so few values moves by several per cent
-        // from step to step, more than a range that the candidate list can hold covers.
-        constexpr int kIters = kTilesPerSuper / kWaves;
-        constexpr int kMine = kIters * kVec;                // 32 keys per thread
-        constexpr uint32_t kListMax = 8 * kBlock;           // keys near the threshold, 8 per thread
-        static_assert(kListMax <= kBins0, "the list lives in the histogram's words");
-        uint32_t key[kMine];
-        uint32_t okm;                                       // bit 4*it + c: the element belongs to the segment
-        supertile_keys(mem, grad, lr, static_cast<int64_t>(hb.a0), static_cast<int64_t>(hb.begin),
-                       static_cast<int64_t>(hb.end), wave, lane, key, okm);
-        // The search runs over the few keys near the previous step's threshold if the k largest are
-        // among them (one count tells), over all keys otherwise.
-        uint32_t* partial = tot_s;                          // 2 x kWaves words
-        static_assert(kPartWords >= 2 * kWaves, "room for the partial counts");
-        const uint32_t t_prev = pred[1] << kBits2;          // 0 before the first step
-        const uint32_t n_seg = static_cast<uint32_t>(hb.end - hb.begin);
-        uint32_t lo = t_prev > (1u << (kBits1 + kBits2)) ? t_prev - (1u << (kBits1 + kBits2)) : 0u;
-        uint32_t n_near = n_seg;
-        if (lo != 0u) {                                     // block-uniform
-            // (counted in the second half of `partial`: the search starts in the first)
-            n_near = block_count_at_least<kMine>(key, okm, lo, partial + kWaves, lane, wave);
-            if (n_near < k) {                               // the threshold fell by more than that: every key is a candidate
-                lo = 0u;
-                n_near = n_seg;
-                __syncthreads();                            // (the partial counts have been read)
-            }
-        }
-        uint32_t T, q;
-        if (n_near <= kListMax) {                           // block-uniform (n_near >= k holds)
-            // my keys >= lo go to consecutive words of the list: exclusive prefix of the threads' counts
-            uint32_t near = 0;
-#pragma unroll
-            for (int j = 0; j < kMine; ++j) near |= (((okm >> j) & 1u) && key[j] >= lo ? 1u : 0u) << j;
-            uint32_t incl = __popc(near);
-#pragma unroll
-            for (int off = 1; off < kLanes; off <<= 1) {
-                const uint32_t a = __shfl_up(incl, off, kLanes);
-                if (lane >= off) incl += a;
-            }
-            if (lane == kLanes - 1) above[wave] = incl;     // the wave's total
-            __syncthreads();
-            uint32_t slot = incl - __popc(near);
-            for (int w2 = 0; w2 < wave; ++w2) slot += above[w2];
-#pragma unroll
-            for (int j = 0; j < kMine; ++j)
-                if ((near >> j) & 1u) lh[slot++] = key[j];
-            __syncthreads();
-            // the first wave searches the list by itself (8 keys per lane if they are few, else 32)
-            if (wave == 0) {
-                if (n_near <= 8u * kLanes) {
-                    uint32_t mine[8];
-                    uint32_t have_mask = 0;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const uint32_t e = j * kLanes + lane;
-                        mine[j] = e < n_near ? lh[e] : 0u;
-                        have_mask |= (e < n_near ? 1u : 0u) << j;
-                    }
-                    T = wave_kth_largest<8>(mine, have_mask, k, q);
-                } else {
-                    uint32_t mine[kListMax / kLanes];
-                    uint32_t have_mask = 0;
-#pragma unroll
-                    for (int j = 0; j < static_cast<int>(kListMax / kLanes); ++j) {
-                        const uint32_t e = j * kLanes + lane;
-                        mine[j] = e < n_near ? lh[e] : 0u;
-                        have_mask |= (e < n_near ? 1u : 0u) << j;
-                    }
-                    T = wave_kth_largest<kListMax / kLanes>(mine, have_mask, k, q);
-                }
-                if (lane == 0) {
-                    res[0] = T;
-                    res[1] = q;
-                }
-            }
-            __syncthreads();
-            T = res[0];
-            q = res[1];
-        } else {
-            T = block_kth_largest<kMine>(key, okm, k, partial, lane, wave, q);
-        }
-        // the tile counts and masks of the supertile, from the keys at hand (what k_tilecount does otherwise)
-        const size_t tile0 = static_cast<size_t>(hb.st_lo) * kTilesPerSuper;
-        __syncthreads();                                    // (the last partial counts have been read)
-        uint32_t* cnt = lh;                                 // the histogram's words: unused on this path
-#pragma unroll
-        for (int it = 0; it < kIters; ++it) {
-            const int wt = it * kWaves + wave;
-            uint64_t gt[4], eq[4];
-            uint32_t n_gt = 0, n_eq = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const bool ok = (okm >> (4 * it + c)) & 1u;
-                gt[c] = __ballot(ok && key[4 * it + c] > T);
-                eq[c] = __ballot(ok && key[4 * it + c] == T);
-                n_gt += __popcll(gt[c]);
-                n_eq += __popcll(eq[c]);
-            }
-            if (lane == 0) {
-                cnt[wt] = n_gt | (n_eq << 16);             // at most 256 each
-                store_tile_masks(sel_mask, tile0 + wt, gt);
-                store_tile_masks(eq_mask, tile0 + wt, eq);
-            }
-        }
-        __syncthreads();
-        if (t < kLanes) {
-            const uint32_t v = t < kTilesPerSuper ? cnt[t] : 0u;
-            if (t < kTilesPerSuper) wt_cnt[tile0 + t] = v;
-            const uint32_t s2 = wave_sum(v);               // at most 8192 each: no carry between halves
-            if (t == 0) st_sum[hb.st_lo] = make_uint2(s2 & 0xffffu, s2 >> 16);
-        }
-        if (t == 0) {
-            s.prefix = T;
-            s.k_rem = q;
-            s.T = T;
-            s.q = q;
-            s.l1_done = 1;
-            s.l2_done = 1;
-            state_at(state, cur) = s;
-            pred[0] = 0u;                                   // no range for the predicted pass ...
-            pred[1] = T >> kBits2;                          // ... but where to look first in the next step
-        }
+    if (sd.st_count == 1) {                                 // block-uniform
+        select_one_supertile(mem, grad, lr, hb, k, s, state, pred, wt_cnt, sel_mask, eq_mask, st_sum, lh, tot_s, res,
+                             above);
         return;
     }
     if (t == 0) flag = 0u;
