@@ -385,6 +385,42 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&v)[NK], ui
     return T;
 }
 
+// The width of the next step's range of finely counted keys, after a step whose range (2^w keys,
+// holding in_range keys in all) held the threshold in its bin `bin`; `slots` is what the segment's
+// candidate list can take, `calm` the number of steps in a row in which the threshold fell into the
+// range's middle half (updated).  Wider at once if the threshold fell outside the middle half, or
+// if the range held few keys -- unless twice as many keys would crowd the candidate list.
+// Narrower only after kCalmSteps calm steps, if the range holds many more keys than needed (the
+// index set's size, and enough for the spread of an order statistic of that rank), and at once if
+// it holds more than three quarters of what the candidate list can take.
+__device__ __forceinline__ uint32_t next_width(uint32_t w, uint32_t bin, uint32_t in_range, uint32_t k, uint64_t slots,
+                                               uint32_t& calm)
+{
+    const uint32_t n_bins = 1u << (w - kBits2);
+    uint64_t want = k > 64u ? k : 64u;
+    if (static_cast<uint64_t>(k) < 256u * 256u) {           // 16 * sqrt(k) > k
+        uint32_t r = 1;
+        while (r * r < k) ++r;
+        if (16u * r > want) want = 16u * r;
+    }
+    if (want > slots / 4) want = slots / 4;
+    const bool middle = bin >= n_bins / 4 && bin < n_bins - n_bins / 4;
+    const bool room = 8ull * in_range <= 3 * slots;         // twice as many still below 3/4 of the slots
+    calm = middle ? calm + 1u : 0u;
+    uint32_t w_next = w;
+    if (4ull * in_range > 3 * slots && w > kSpecBitsMin) {
+        w_next = w - 1;
+        calm = 0u;
+    } else if ((!middle || 5ull * in_range < 3 * want) && room && w < kSpecBitsMax) {
+        w_next = w + 1;
+        calm = 0u;
+    } else if (calm >= kCalmSteps && 2ull * in_range > 3 * want && w > kSpecBitsMin) {
+        w_next = w - 1;
+        calm = 0u;
+    }
+    return w_next;
+}
+
 // A segment of one supertile (up to 8192 elements; with hundreds of tensors, half of them) is
 // finished by its one block: the threshold is found on the keys the block holds in registers, and
 // the tile counts and masks are written.  No range from the predicted pass: the k-th largest of so
@@ -619,34 +655,9 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
                 s.mode = kModeCand;
                 s.collected = 1;
                 s.l1_done = 1;
-                // The next step's range.  Wider at once if the threshold fell outside the middle half of
-                // this one, or if this one held few keys -- unless twice as many keys would crowd the
-                // candidate list.  Narrower only after kCalmSteps steps in a row with the threshold in the
-                // middle half, if the range holds many more keys than needed (the index set's size, and
-                // enough for the spread of an order statistic of that rank), and at once if it holds more
-                // than three quarters of what the candidate list can take.
-                const uint64_t slots = static_cast<uint64_t>(sd.st_count) * kCandSlice;
-                uint64_t want = k > 64u ? k : 64u;
-                if (static_cast<uint64_t>(k) < 256u * 256u) {   // 16 * sqrt(k) > k
-                    uint32_t r = 1;
-                    while (r * r < k) ++r;
-                    if (16u * r > want) want = 16u * r;
-                }
-                if (want > slots / 4) want = slots / 4;
-                const bool middle = res[0] >= n_bins / 4 && res[0] < n_bins - n_bins / 4;
-                const bool room = 8ull * in_range <= 3 * slots;   // twice as many still below 3/4 of the slots
-                uint32_t calm = middle ? used[3] + 1u : 0u;
-                uint32_t w_next = w;
-                if (4ull * in_range > 3 * slots && w > kSpecBitsMin) {
-                    w_next = w - 1;
-                    calm = 0u;
-                } else if ((!middle || 5ull * in_range < 3 * want) && room && w < kSpecBitsMax) {
-                    w_next = w + 1;
-                    calm = 0u;
-                } else if (calm >= kCalmSteps && 2ull * in_range > 3 * want && w > kSpecBitsMin) {
-                    w_next = w - 1;
-                    calm = 0u;
-                }
+                uint32_t calm = used[3];
+                const uint32_t w_next =
+                    next_width(w, res[0], in_range, k, static_cast<uint64_t>(sd.st_count) * kCandSlice, calm);
                 pred[3] = calm;
                 pred[0] = 1u;
                 pred[1] = res[1];
