@@ -170,6 +170,42 @@ __device__ __forceinline__ void leader_keys(const float* mem, const G* grad, flo
     keys_from(m, g, lr, p0, begin, end, key, ok);
 }
 
+// Where a step expects its threshold (top 24 bits of the key).  Learners whose gradients differ in
+// scale have thresholds that differ as much, so each leader's own last threshold is kept
+// (lead_mine[seg], 0 before its first turn) and moved on by the growth the last leader saw over
+// its cycle; without it, the last step's threshold.  Only a prediction: it decides how much work
+// a step does, never what it selects.
+__device__ __forceinline__ uint32_t predicted_t24(const uint32_t* pred, const uint32_t* lead_mine, int seg)
+{
+    uint32_t t24 = pred[1];
+    if (lead_mine) {
+        const uint32_t mine = lead_mine[seg];
+        if (mine != 0u) {
+            const float growth = pred[4] != 0u ? __uint_as_float(pred[4]) : 1.0f;
+            const float f = __uint_as_float(mine << kBits2) * growth;
+            t24 = (__float_as_uint(f) & 0x7fffffffu) >> kBits2;
+        }
+    }
+    return t24;
+}
+
+// Records the threshold a step found (by one thread, for the next steps' predictions).
+__device__ __forceinline__ void record_t24(uint32_t* pred, uint32_t* lead_mine, int seg, uint32_t t24)
+{
+    pred[1] = t24;
+    if (lead_mine) {
+        const uint32_t old = lead_mine[seg];
+        float growth = 1.0f;
+        if (old != 0u && t24 != 0u) {
+            growth = __uint_as_float(t24 << kBits2) / __uint_as_float(old << kBits2);
+            if (!(growth > 0.5f)) growth = 0.5f;
+            if (!(growth < 2.0f)) growth = 2.0f;
+        }
+        pred[4] = __float_as_uint(growth);
+        lead_mine[seg] = t24;
+    }
+}
+
 // Membership bitmask layout: per wave tile four 64-bit words; bit l of word c belongs to
 // position tile0 + 4*l + c, i.e. word c is the wave ballot of "element c of my lane is a member".
 __device__ __forceinline__ void store_tile_masks(uint64_t* mask, size_t tile, const uint64_t b[4])

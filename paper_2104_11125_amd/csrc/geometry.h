@@ -100,8 +100,9 @@ __host__ __device__ inline const SegState& state_at(const SegState* base, size_t
 constexpr int kSpecBitsMax = kBits1 + kBits2;    // 19: 2^19 keys, one twelve-bit bucket wide (+-3 % of the threshold)
 constexpr int kSpecBitsMin = kBits2 + 3;         // 10: 2^10 keys, 8 counts
 // The prediction kept per segment between steps, and the one a step works with.
-constexpr int kPredWords = 4;                    // [0] 1 if there is one, [1] top 24 bits of the last threshold, [2] w,
-                                                 // [3] steps in a row in which the threshold fell into the range's middle half
+constexpr int kPredWords = 8;                    // [0] 1 if there is one, [1] top 24 bits of the last threshold, [2] w,
+                                                 // [3] steps in a row in which the threshold fell into the range's middle half,
+                                                 // [4] (float) by how much the last leader's threshold grew since its previous turn
 constexpr uint32_t kCalmSteps = 8;               // so many of those before the range is made narrower
 // Counts of the predicted pass, per segment: [0] keys above the range, [1] keys inside it.
 // Blocks add into one of kPartSlots copies (same-address atomics from thousands of blocks would

@@ -105,7 +105,8 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.sts = take(nst * sizeof(StDesc));
     l.chunks = take(nch * sizeof(ChunkDesc));
     l.hblocks = take((kHistGridMax + nt) * sizeof(HistBlock));
-    l.preds = take(kPredWords * nt * sizeof(uint32_t));  // per segment: the prediction for the next step
+    // per segment: the prediction for the next step; then per learner and segment: that leader's last threshold
+    l.preds = take((kPredWords + static_cast<size_t>(n_learners_max)) * nt * sizeof(uint32_t));
     l.state = take(3 * nt * kStateStride);               // after level 0, after level 1, after level 2
     {
         size_t z = 0;
@@ -295,7 +296,8 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     }
     // predictions of the previous layout's buckets mean nothing for this one
     k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds),
-                                          kPredWords * static_cast<size_t>(ctx->n_tensors_max));
+                                          (kPredWords + static_cast<size_t>(ctx->n_learners_max)) *
+                                              static_cast<size_t>(ctx->n_tensors_max));
     ctx->scratch_clean = false;
     SC_HIP(ctx, hipEventRecord(ctx->upload_done, ctx->stream));
     ctx->upload_pending = true;
@@ -347,7 +349,7 @@ void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learne
 // rewritten).  Uses one copy of the scratch zone and leaves the other one cleared.
 template <typename G, typename Mark>
 void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float lr, int n_tensors, uint32_t* preds,
-                   Mark&& mark)
+                   uint32_t* lead_mine, Mark&& mark)
 {
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
@@ -390,14 +392,14 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     const int hgrid = ctx->n_hblocks;       // one block per entry of the block table
     ctx->scratch_clean = false;             // until every kernel of this selection has been enqueued
     k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
-                                           part, overflow, p_used, hist1_spec, next_zone, zone_words);
+                                           part, overflow, p_used, hist1_spec, lead_mine, next_zone, zone_words);
     k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, hist0, preds, p_used, part, overflow,
-                                         hist1_spec, wt_cnt, sel_mask, eq_mask, st_sum);
+                                         hist1_spec, lead_mine, wt_cnt, sel_mask, eq_mask, st_sum);
     mark(1);
     const CollectOut collect_out{wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt, full_flag};
-    k_level<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, state1, hist0, hist1, preds,
+    k_level<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, state1, hist0, hist1, preds, lead_mine,
                                            collect_out);
-    k_level<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state1, state, hist1, hist2, preds,
+    k_level<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state1, state, hist1, hist2, preds, lead_mine,
                                            collect_out);
     mark(2);
     k_tilecount<G><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2, wt_cnt,
@@ -430,8 +432,12 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
     };
     if (ctx->n_st > 0) {
         mark(0);
-        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors,
-                         reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds), mark);
+        uint32_t* preds = reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds);
+        // this leader's own last thresholds, kept behind the per-segment predictions
+        uint32_t* lead_mine = preds + (static_cast<size_t>(kPredWords) + static_cast<size_t>(leader)) *
+                                          static_cast<size_t>(ctx->n_tensors_max);
+        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, lead_mine,
+                         mark);
         mark(3);
         launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
         mark(5);
@@ -606,7 +612,8 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     if (ctx->n_st > 0) {
         // the leader's index set (Eq. 3)
         k_init<<<1, kBlock, 0, s>>>(preds, kPredWords * static_cast<size_t>(n_tensors));
-        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, no_mark);
+        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, nullptr,
+                         no_mark);
         SC_HIP(ctx, hipMemcpyAsync(mask_a, sel_mask, mask_bytes, hipMemcpyDeviceToDevice, s));
         // the top-k of the summed error-feedback gradients
         const int64_t blocks = (end - begin + kBlock - 1) / kBlock;
@@ -614,7 +621,7 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         const dim3 grid(gx, static_cast<unsigned>((blocks + gx - 1) / gx));
         k_sum_x<G><<<grid, kBlock, 0, s>>>(lp, n_learners, lr, begin, end, y);
         k_init<<<1, kBlock, 0, s>>>(preds, kPredWords * static_cast<size_t>(n_tensors));
-        launch_select<NoGrad>(ctx, y, static_cast<const NoGrad*>(nullptr), 0.0f, n_tensors, preds, no_mark);
+        launch_select<NoGrad>(ctx, y, static_cast<const NoGrad*>(nullptr), 0.0f, n_tensors, preds, nullptr, no_mark);
         k_mask_overlap<<<(ctx->n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(sts, ctx->n_st, mask_a, sel_mask, d_out);
     }
     SC_HIP(ctx, hipGetLastError());

@@ -207,7 +207,7 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
             uint32_t* __restrict__ st_cand_cnt, const uint32_t* __restrict__ preds, uint32_t* __restrict__ wt_cnt,
             uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part,
             uint32_t* __restrict__ overflow, uint32_t* __restrict__ p_used, uint32_t* __restrict__ hist1_spec,
-            uint32_t* __restrict__ next_scratch, size_t next_words)
+            const uint32_t* __restrict__ lead_mine, uint32_t* __restrict__ next_scratch, size_t next_words)
 {
     // The counters and histograms of a step live in one of two copies of a scratch zone; this
     // kernel, the first of a step, clears the copy the NEXT step will use (nothing else touches it
@@ -219,7 +219,8 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const int st = blockIdx.x;
     const StDesc d = sts[st];
     const uint32_t* pred = preds + static_cast<size_t>(d.seg) * kPredWords;
-    const uint32_t have = pred[0], t24 = pred[1], w = pred[2];
+    const uint32_t have = pred[0], w = pred[2];
+    const uint32_t t24 = predicted_t24(pred, lead_mine, d.seg);
     const SegDesc sd = segs[d.seg];
     if (have == 0 || sd.k == 0 || sd.st_count == 1) return;   // (one supertile: k_level0 searches it directly)
     // the range: 2^w keys centred on the middle of the previous threshold's 128 keys, aligned to 128,
@@ -432,6 +433,7 @@ template <typename G>
 __device__ __forceinline__ void select_one_supertile(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                                                      const HistBlock& hb, uint32_t k, SegState s,
                                                      SegState* __restrict__ state, uint32_t* __restrict__ pred,
+                                                     uint32_t* __restrict__ lead_mine,
                                                      uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask,
                                                      uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum,
                                                      uint32_t* lh, uint32_t* tot_s, uint32_t* res, uint32_t* above)
@@ -450,7 +452,7 @@ __device__ __forceinline__ void select_one_supertile(const float* __restrict__ m
     // among them (one count tells), over all keys otherwise.
     uint32_t* partial = tot_s;                          // 2 x kWaves words
     static_assert(kPartWords >= 2 * kWaves, "room for the partial counts");
-    const uint32_t t_prev = pred[1] << kBits2;          // 0 before the first step
+    const uint32_t t_prev = predicted_t24(pred, lead_mine, cur) << kBits2;   // 0 before the first step
     const uint32_t n_seg = static_cast<uint32_t>(hb.end - hb.begin);
     uint32_t lo = t_prev > (1u << (kBits1 + kBits2)) ? t_prev - (1u << (kBits1 + kBits2)) : 0u;
     uint32_t n_near = n_seg;
@@ -556,7 +558,7 @@ __device__ __forceinline__ void select_one_supertile(const float* __restrict__ m
         s.l2_done = 1;
         state_at(state, cur) = s;
         pred[0] = 0u;                                   // no range for the predicted pass ...
-        pred[1] = T >> kBits2;                          // ... but where to look first in the next step
+        record_t24(pred, lead_mine, cur, T >> kBits2);  // ... but where to look first in the next steps
     }
 }
 
@@ -573,8 +575,9 @@ __global__ void __launch_bounds__(kBlock)
 k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
          const HistBlock* __restrict__ hblocks, SegState* __restrict__ state, uint32_t* __restrict__ hist,
          uint32_t* __restrict__ preds, const uint32_t* __restrict__ p_used, const uint32_t* __restrict__ part,
-         const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec, uint32_t* __restrict__ wt_cnt,
-         uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
+         const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec, uint32_t* __restrict__ lead_mine,
+         uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
+         uint2* __restrict__ st_sum)
 {
     __shared__ uint32_t lh[kBins0];
     __shared__ uint32_t tot_s[kPartWords];
@@ -608,8 +611,8 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         return;
     }
     if (sd.st_count == 1) {                                 // block-uniform
-        select_one_supertile(mem, grad, lr, hb, k, s, state, pred, wt_cnt, sel_mask, eq_mask, st_sum, lh, tot_s, res,
-                             above);
+        select_one_supertile(mem, grad, lr, hb, k, s, state, pred, lead_mine, wt_cnt, sel_mask, eq_mask, st_sum, lh,
+                             tot_s, res, above);
         return;
     }
     if (t == 0) flag = 0u;
@@ -660,7 +663,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
                     next_width(w, res[0], in_range, k, static_cast<uint64_t>(sd.st_count) * kCandSlice, calm);
                 pred[3] = calm;
                 pred[0] = 1u;
-                pred[1] = res[1];
+                record_t24(pred, lead_mine, cur, res[1]);
                 pred[2] = w_next;
             } else {                                        // only if the counts were corrupted: nothing is selected
                 s.done = 1;
@@ -746,7 +749,7 @@ __global__ void __launch_bounds__(kBlock)
 k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
         const HistBlock* __restrict__ hblocks, const SegState* __restrict__ state_in, SegState* __restrict__ state_out,
         const uint32_t* __restrict__ hist_prev, uint32_t* __restrict__ hist, uint32_t* __restrict__ preds,
-        CollectOut out)
+        uint32_t* __restrict__ lead_mine, CollectOut out)
 // in candidate mode out.cand and out.st_cand_cnt are read, when collecting they are written
 {
     static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_level0");
@@ -795,7 +798,7 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
             } else if (owner && t == 0) {                   // the prediction for the next step: widest range
                 uint32_t* pred = preds + static_cast<size_t>(cur) * kPredWords;
                 pred[0] = 1u;
-                pred[1] = ss.prefix;
+                record_t24(pred, lead_mine, cur, ss.prefix);
                 pred[2] = ss.w_next;
                 pred[3] = 0u;
             }

@@ -595,6 +595,37 @@ def test_randomized_long_runs(gu, seed):
     ctx.close()
 
 
+@pytest.mark.parametrize("spread", [0.1, 0.9, 30.0])
+def test_learners_whose_gradients_differ_in_scale(gu, spread):
+    """Learners on differently distributed data: learner i's gradients are scaled by a factor of its
+    own (up to 1 + spread), so the leaders' thresholds differ from step to step by as much, and a
+    prediction has to follow each leader's own history.  Tensors of one and of several supertiles;
+    after 90 steps the learner count changes, and with it the cycle of leaders."""
+    rng = np.random.default_rng(77)
+    n, beta, lr = 4, 0.1, 0.1
+    sizes = [120_001, 5_000, 30_000]
+    offsets = np.concatenate([[1], 1 + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1]
+    ks = [1_200, 50, 300]
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes), gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    scale = [1.0 + spread * i / (n - 1) for i in range(n)]
+    pool = [[((rng.standard_normal(numel) + 0.5 * rng.standard_normal(numel)) * 1e-3 * scale[i]).astype(np.float32)
+             for i in range(n)] for _ in range(5)]
+    pool_dev = [[torch.from_numpy(g).to(gu.DEV) for g in gs] for gs in pool]
+    for step in range(150):
+        m = n if step < 90 else n - 1
+        host, dev = pool[step % 5][:m], pool_dev[step % 5][:m]
+        idx, red = ctx.scalecom_step_layers(mem[:m], dev, offsets, ks, beta, lr, step)
+        want_idx, want_red = oracle.step_layers(ref[:m], host, offsets, ks, beta, lr, step)
+        gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"spread {spread} step {step}")
+        gu.assert_same("reduced", red.cpu().numpy(), want_red, 1e-5, f"spread {spread} step {step}")
+    for i in range(n):
+        gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], 1e-6, f"spread {spread} learner {i}")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
