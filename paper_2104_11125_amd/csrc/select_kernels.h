@@ -192,8 +192,8 @@ __device__ __forceinline__ uint32_t predicted_tiles(const float* __restrict__ me
 }
 
 // First look at the leader's vector (Eq. 2: finding the k-th largest magnitude), for segments
-// that carry a prediction: the top 24 bits of the previous step's threshold and a width w.
-// ONE pass, no histogram in LDS: keys above the 2^w keys centred on the previous threshold are
+// that carry a prediction: the top 24 bits of the threshold expected (predicted_t24) and a width w.
+// ONE pass, no histogram in LDS: keys above the 2^w keys centred on the expected threshold are
 // members for sure (counted per tile, marked in the mask); keys among those 2^w go to the
 // candidate list and are counted per 128 keys (the resolution of the search's second level) with
 // atomics in memory.  If the counts show afterwards that the k-th largest key fell inside the
@@ -223,7 +223,7 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const uint32_t t24 = predicted_t24(pred, lead_mine, d.seg);
     const SegDesc sd = segs[d.seg];
     if (have == 0 || sd.k == 0 || sd.st_count == 1) return;   // (one supertile: k_level0 searches it directly)
-    // the range: 2^w keys centred on the middle of the previous threshold's 128 keys, aligned to 128,
+    // the range: 2^w keys centred on the middle of the expected threshold's 128 keys, aligned to 128,
     // cut off at key 0 and at 2^31
     const uint32_t span = 1u << w;
     const uint32_t mid = (t24 << kBits2) | (kBins2 / 2);
