@@ -206,6 +206,13 @@ __device__ __forceinline__ void record_t24(uint32_t* pred, uint32_t* lead_mine, 
     }
 }
 
+// The exact value, once known, in place of the estimate that record_t24 was given.
+__device__ __forceinline__ void refine_t24(uint32_t* pred, uint32_t* lead_mine, int seg, uint32_t t24)
+{
+    pred[1] = t24;
+    if (lead_mine) lead_mine[seg] = t24;
+}
+
 // Membership bitmask layout: per wave tile four 64-bit words; bit l of word c belongs to
 // position tile0 + 4*l + c, i.e. word c is the wave ballot of "element c of my lane is a member".
 __device__ __forceinline__ void store_tile_masks(uint64_t* mask, size_t tile, const uint64_t b[4])

@@ -77,8 +77,9 @@ struct SegState {         // selection state of one segment after a level; every
     uint32_t l2_done;     // 1: T and q are final already, and the tile counts and masks are written (a segment of
                           //    one supertile is searched and counted by one block)
     uint32_t w_next;      // width of the next step's range, for the kernel that ends a search without prediction
+    uint32_t l1_bits;     // key bits that level 1 resolves: 12, or the 1..5 bits that a wide range's counts left open
 };
-static_assert(sizeof(SegState) == 44, "eleven words, no padding to carry along in copies");
+static_assert(sizeof(SegState) == 48, "twelve words, no padding to carry along in copies");
 // One state per 128-byte line: blocks that work on different segments run on different XCDs, and
 // four states in one line made the per-segment searches three times slower with 200 segments.
 // (The stride is kept out of the struct so that copies of a state stay in registers.)
@@ -92,13 +93,28 @@ __host__ __device__ inline const SegState& state_at(const SegState* base, size_t
     return *reinterpret_cast<const SegState*>(reinterpret_cast<const char*>(base) + seg * kStateStride);
 }
 
-// The predicted pass works on a RANGE of keys around the previous step's threshold: 2^w keys,
-// aligned to 128, counted per 128 keys (at most 4096 counts).  w follows the density of keys around
-// the threshold: with error feedback the magnitudes pile up just below it (after some hundred
-// steps a twelve-bit bucket around the threshold holds 7 % of all elements), so a fixed range
-// would come to hold far more keys than the index set has members.
-constexpr int kSpecBitsMax = kBits1 + kBits2;    // 19: 2^19 keys, one twelve-bit bucket wide (+-3 % of the threshold)
+// The predicted pass works on a RANGE of keys around the threshold it expects: 2^w keys, counted in
+// bins.  Up to w = 19 a bin is 128 keys (at most 4096 bins; a hit then fixes the key's top 24 bits)
+// and every listed key costs one atomic in memory.  Those are carried out at the memory side, one
+// by one: half a million of them double the time of the pass.  So a wider range has 64 bins only,
+// counted in LDS first (64 atomics in memory per block at most); a hit then leaves w - 13 more bits
+// to level 1, which counts them on the listed keys of that one bin.  The range starts at a multiple
+// of the bin width, and the counts exist in as many slotted copies as fit into 4096 words.
+// w follows the density of keys around the threshold and how far the threshold moves from step to
+// step: with error feedback the magnitudes pile up just below it (after some hundred steps a
+// twelve-bit bucket around the threshold holds 7 % of all elements), so a fixed range would come to
+// hold far more keys than the index set has members; while the memories are still small the
+// threshold follows every batch's gradient norm, and a range of +-3 % would miss it every other step.
+constexpr int kSpecBitsMax = kBits1 + kBits2;    // 19: the widest range with bins of 128 keys (+-3 % of the threshold)
+constexpr int kSpecBitsWide = kSpecBitsMax + 5;  // 24: the widest range, 2^24 keys (two binades)
 constexpr int kSpecBitsMin = kBits2 + 3;         // 10: 2^10 keys, 8 counts
+constexpr int kSpecWideBinsLog = 6;              // a range wider than 2^19 keys has 64 bins
+// log2 of the keys per bin of a range of 2^w keys
+__host__ __device__ constexpr uint32_t spec_bin_shift(uint32_t w)
+{
+    return w > static_cast<uint32_t>(kSpecBitsMax) ? w - kSpecWideBinsLog : static_cast<uint32_t>(kBits2);
+}
+static_assert(kSpecBitsWide - kSpecWideBinsLog - kBits2 <= kBits1, "level 1 resolves at most twelve bits");
 // The prediction kept per segment between steps, and the one a step works with.
 constexpr int kPredWords = 8;                    // [0] 1 if there is one, [1] top 24 bits of the last threshold, [2] w,
                                                  // [3] steps in a row in which the threshold fell into the range's middle half,

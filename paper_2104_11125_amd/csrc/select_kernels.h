@@ -226,8 +226,9 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     // the range: 2^w keys centred on the middle of the expected threshold's 128 keys, aligned to 128,
     // cut off at key 0 and at 2^31
     const uint32_t span = 1u << w;
+    const uint32_t sh = spec_bin_shift(w);                  // bins of 2^sh keys; the range starts at a multiple of that
     const uint32_t mid = (t24 << kBits2) | (kBins2 / 2);
-    uint32_t base = mid > span / 2 ? (mid - span / 2) & ~static_cast<uint32_t>(kBins2 - 1) : 0u;
+    uint32_t base = mid > span / 2 ? (mid - span / 2) & ~((1u << sh) - 1u) : 0u;
     if (base > (1u << 31) - span) base = (1u << 31) - span;
     // the prediction this step works with, for the kernel that checks it (preds is rewritten there)
     if (st == sd.st_first && threadIdx.x == 0) {
@@ -242,15 +243,18 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     __shared__ uint32_t acc[2];                             // keys above the range, keys inside it
     __shared__ CollectStage stg;
     __shared__ uint2 cand_stage[kCandSlice];
+    __shared__ uint32_t wide_cnt[1 << kSpecWideBinsLog];    // the block's counts of a wide range's bins
+    const bool wide = w > kSpecBitsMax;                     // block-uniform
     if (threadIdx.x == 0) fill = 0u;
     if (threadIdx.x < 2) acc[threadIdx.x] = 0u;
+    if (wide && threadIdx.x < (1 << kSpecWideBinsLog)) wide_cnt[threadIdx.x] = 0u;
     __syncthreads();
 
     uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
-    // the range's 2^(w-7) counts exist in 2^(19-w) copies (4096 words in all), one copy per residue of the
-    // supertile number: with a narrow range all the atomics of a step would otherwise hit a few cache lines
-    uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1 +
-                   ((static_cast<uint32_t>(st) & ((1u << (kSpecBitsMax - w)) - 1u)) << (w - kBits2));
+    // the range's 2^(w-sh) counts exist in as many copies as 4096 words hold, one copy per residue of the
+    // supertile number: with few bins all the atomics of a step would otherwise hit a few cache lines
+    const uint32_t copy = static_cast<uint32_t>(st) & ((1u << (kBits1 - (w - sh))) - 1u);
+    uint32_t* h1 = hist1_spec + static_cast<size_t>(d.seg) * kBins1 + (copy << (w - sh));
     uint32_t above_acc, in_acc;
     if (d.a0 >= d.begin && static_cast<int64_t>(d.a0) + kSuper <= d.end)   // block-uniform
         above_acc = predicted_tiles<G, true>(mem, grad, lr, d, base, span, wave, lane, &fill, in_acc, stg, cand_stage);
@@ -260,7 +264,7 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     if (lane == 0 && in_acc) atomicAdd(&acc[1], in_acc);
     __syncthreads();
     collect_flush(stg, nullptr, static_cast<size_t>(st) * kTilesPerSuper, fill, wt_cnt, sel_mask, eq_mask, slice);
-    // The staged candidates go to the supertile's slice and are counted per 128 keys on the way,
+    // The staged candidates go to the supertile's slice and are counted per bin on the way,
     // outside the streaming loop.  (If the slice overflowed the counts are incomplete, and nothing
     // reads them.)
     static_assert(kCandSlice == 2 * kBlock, "two staged candidates per thread");
@@ -271,7 +275,17 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
         if (e < n) {
             const uint2 ce = cand_stage[e];
             slice[e] = ce;
-            atomicAdd(&h1[(ce.x - base) >> kBits2], 1u);
+            if (wide)
+                atomicAdd(&wide_cnt[(ce.x - base) >> sh], 1u);
+            else
+                atomicAdd(&h1[(ce.x - base) >> sh], 1u);
+        }
+    }
+    if (wide) {                                             // block-uniform
+        __syncthreads();
+        if (threadIdx.x < (1 << kSpecWideBinsLog)) {
+            const uint32_t v = wide_cnt[threadIdx.x];
+            if (v) atomicAdd(&h1[threadIdx.x], v);
         }
     }
     if (threadIdx.x == 0) {
@@ -397,7 +411,7 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&v)[NK], ui
 __device__ __forceinline__ uint32_t next_width(uint32_t w, uint32_t bin, uint32_t in_range, uint32_t k, uint64_t slots,
                                                uint32_t& calm)
 {
-    const uint32_t n_bins = 1u << (w - kBits2);
+    const uint32_t n_bins = 1u << (w - spec_bin_shift(w));
     uint64_t want = k > 64u ? k : 64u;
     if (static_cast<uint64_t>(k) < 256u * 256u) {           // 16 * sqrt(k) > k
         uint32_t r = 1;
@@ -412,7 +426,7 @@ __device__ __forceinline__ uint32_t next_width(uint32_t w, uint32_t bin, uint32_
     if (4ull * in_range > 3 * slots && w > kSpecBitsMin) {
         w_next = w - 1;
         calm = 0u;
-    } else if ((!middle || 5ull * in_range < 3 * want) && room && w < kSpecBitsMax) {
+    } else if ((!middle || 5ull * in_range < 3 * want) && room && w < kSpecBitsWide) {
         w_next = w + 1;
         calm = 0u;
     } else if (calm >= kCalmSteps && 2ull * in_range > 3 * want && w > kSpecBitsMin) {
@@ -603,6 +617,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     s.k_rem = k;
     s.T = 0xffffffffu;                                      // above every key: nothing is a member
     s.mode = kModeFull;
+    s.l1_bits = kBits1;
     if (k == 0) {                                           // block-uniform: an empty index set
         if (owner && t == 0) {
             s.done = 1;
@@ -631,7 +646,8 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         if (!owner) return;
         const uint32_t above_range = tot_s[0], in_range = tot_s[1];
         // add up the copies of the range's counts (word = copy * n_bins + bin) in LDS, then search there
-        const uint32_t n_bins = 1u << (w - kBits2);
+        const uint32_t sh = spec_bin_shift(w);
+        const uint32_t n_bins = 1u << (w - sh);
         const uint32_t* h1 = hist1_spec + static_cast<size_t>(cur) * kBins1;
         constexpr int kPer = kBins1 / kBlock;
         uint32_t mine[kPer];
@@ -645,7 +661,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         __syncthreads();
         uint32_t bin, n_bin, n_above;
         if (search_digit<kBins1>(lh, k - above_range, above, bin, n_bin, n_above)) {
-            res[1] = (base >> kBits2) + bin;                // the key's top 24 bits
+            res[1] = (base >> sh) + bin;                    // the key's top 31 - sh bits (24 up to w = 19)
             res[2] = k - above_range - n_above;
             res[0] = bin;
             flag = 1u;
@@ -657,13 +673,16 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
                 s.k_rem = res[2];
                 s.mode = kModeCand;
                 s.collected = 1;
-                s.l1_done = 1;
+                // a wide range's bins leave sh - 7 bits to level 1, which counts them on the listed keys
+                s.l1_done = sh == kBits2 ? 1u : 0u;
+                s.l1_bits = sh - kBits2;
                 uint32_t calm = used[3];
                 const uint32_t w_next =
                     next_width(w, res[0], in_range, k, static_cast<uint64_t>(sd.st_count) * kCandSlice, calm);
                 pred[3] = calm;
                 pred[0] = 1u;
-                record_t24(pred, lead_mine, cur, res[1]);
+                // (of a wide range's bin its middle, until level 1 has resolved it)
+                record_t24(pred, lead_mine, cur, sh == kBits2 ? res[1] : ((res[1] << sh) | (1u << (sh - 1))) >> kBits2);
                 pred[2] = w_next;
             } else {                                        // only if the counts were corrupted: nothing is selected
                 s.done = 1;
@@ -686,7 +705,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
             would >>= 1;
             --fit;
         }
-        while (2 * would <= half && fit < kSpecBitsMax) {
+        while (2 * would <= half && fit < kSpecBitsWide) {
             would <<= 1;
             ++fit;
         }
@@ -769,9 +788,10 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     const uint32_t went_full = LEVEL == 2 ? out.full_flag[cur] : 0u;
     if (went_full) ss.mode = kModeFull;
 
+    const uint32_t l1_bits = ss.l1_bits;                    // 12, or what a wide range's counts left open
     auto count = [&](uint32_t key, uint32_t prefix) {
         if (LEVEL == 1) {
-            if ((key >> (kBits1 + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & (kBins1 - 1)], 1u);
+            if ((key >> (l1_bits + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & ((1u << l1_bits) - 1u)], 1u);
         } else {
             if ((key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins2 - 1)], 1u);
         }
@@ -789,18 +809,22 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
         }
         __syncthreads();
         if (res[0]) {
-            ss.prefix = (ss.prefix << BITS_PREV) | res[1];
+            ss.prefix = (ss.prefix << (LEVEL == 1 ? static_cast<uint32_t>(BITS_PREV) : l1_bits)) | res[1];
             ss.k_rem -= res[2];
             if (LEVEL == 1) {
                 // the bucket's keys go to the candidate list if its slots can hold them
                 const uint64_t slots = static_cast<uint64_t>(st_count) * kCandSlice;
                 ss.mode = res[3] <= slots ? kModeCand : kModeFull;
-            } else if (owner && t == 0) {                   // the prediction for the next step: widest range
+            } else if (owner && t == 0) {
                 uint32_t* pred = preds + static_cast<size_t>(cur) * kPredWords;
-                pred[0] = 1u;
-                record_t24(pred, lead_mine, cur, ss.prefix);
-                pred[2] = ss.w_next;
-                pred[3] = 0u;
+                if (ss.collected == 0) {                    // no prediction held in this step: one for the next
+                    pred[0] = 1u;
+                    record_t24(pred, lead_mine, cur, ss.prefix);
+                    pred[2] = ss.w_next;
+                    pred[3] = 0u;
+                } else {                                    // a wide range held: k_level0 recorded the middle of its bin
+                    refine_t24(pred, lead_mine, cur, ss.prefix);
+                }
             }
         } else {                                            // only if the counts were corrupted: nothing is selected
             ss.done = 1;
@@ -831,11 +855,39 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                 cnt[j] = have ? out.st_cand_cnt[s2] : 0u;   // at most kCandSlice (stored clamped)
                 key0[j] = have ? out.cand[static_cast<size_t>(s2) * kCandSlice + lane].x : 0u;
             }
+            // the second 64 slots where the count says so (a range that holds about as many keys as the
+            // index set has members lists 70 to 150 per supertile), and the rest of all four slices at once
+            // if one of them holds more than 128 (wide ranges): no trip to memory waits for another
+            constexpr int kRounds = kCandSlice / kLanes - 2;
+            uint32_t key1[kAhead], more[kAhead][kRounds];
+            const bool long_slices =
+                cnt[0] > 2 * kLanes || cnt[1] > 2 * kLanes || cnt[2] > 2 * kLanes || cnt[3] > 2 * kLanes;
+            static_assert(kAhead == 4, "the test above names four counts");
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) {              // (a wave without a supertile has count 0 and reads nothing)
+                const uint2* sl = out.cand + static_cast<size_t>(s0 + j * kWaves) * kCandSlice;
+                key1[j] = static_cast<uint32_t>(kLanes + lane) < cnt[j] ? sl[kLanes + lane].x : 0u;
+            }
+            if (long_slices) {                              // wave-uniform
+#pragma unroll
+                for (int j = 0; j < kAhead; ++j) {
+                    const uint2* sl = out.cand + static_cast<size_t>(s0 + j * kWaves) * kCandSlice;
+#pragma unroll
+                    for (int r = 0; r < kRounds; ++r) {
+                        const uint32_t e = (r + 2) * kLanes + lane;
+                        more[j][r] = e < cnt[j] ? sl[e].x : 0u;
+                    }
+                }
+            }
 #pragma unroll
             for (int j = 0; j < kAhead; ++j) {
-                const uint2* sl = out.cand + static_cast<size_t>(s0 + j * kWaves) * kCandSlice;
                 if (static_cast<uint32_t>(lane) < cnt[j]) count(key0[j], prefix);
-                for (uint32_t e = kLanes + lane; e < cnt[j]; e += kLanes) count(sl[e].x, prefix);
+                if (static_cast<uint32_t>(kLanes + lane) < cnt[j]) count(key1[j], prefix);
+                if (long_slices) {
+#pragma unroll
+                    for (int r = 0; r < kRounds; ++r)
+                        if ((r + 2) * kLanes + lane < cnt[j]) count(more[j][r], prefix);
+                }
             }
         }
     } else {
@@ -992,20 +1044,47 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
         const uint32_t n = n_listed < kCandSlice ? n_listed : kCandSlice;   // never use what lies past the count
         uint32_t* sel32 = reinterpret_cast<uint32_t*>(sel_mask);
         uint32_t* eq32 = reinterpret_cast<uint32_t*>(eq_mask);
-        for (uint32_t e = lane; e < n; e += kLanes) {
-            const uint2 ce = e < kLanes ? ce_early : slice[e];
+        // what a listed key means for the masks: 0 nothing; else bit 31, bit 30 = above T, position in the supertile
+        auto classify = [&](const uint2 ce, uint32_t e) {
             const uint32_t rel = ce.y - static_cast<uint32_t>(d.a0);
-            if (ce.x >= T && rel < kSuper) {                // a listed position lies in its supertile
-                const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
-                const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
-                if (ce.x > T) {
-                    atomicAdd(&cnt[wt], 1u);
-                    atomicOr(&sel32[word], 1u << (l & 31));
-                } else {
-                    atomicAdd(&cnt[wt], 0x10000u);
-                    atomicOr(&eq32[word], 1u << (l & 31));
-                }
+            const bool ok = e < n && ce.x >= T && rel < kSuper;   // (a listed position lies in its supertile)
+            return ok ? (0x80000000u | (ce.x > T ? 0x40000000u : 0u) | rel) : 0u;
+        };
+        auto mark = [&](uint32_t what) {
+            const uint32_t rel = what & (kSuper - 1);
+            const uint32_t wt = rel / kWaveTile, l = (rel % kWaveTile) / kVec, c = rel % kVec;
+            const size_t word = ((tile0 + wt) * 4 + c) * 2 + (l >> 5);
+            if (what & 0x40000000u) {
+                atomicAdd(&cnt[wt], 1u);
+                atomicOr(&sel32[word], 1u << (l & 31));
+            } else {
+                atomicAdd(&cnt[wt], 0x10000u);
+                atomicOr(&eq32[word], 1u << (l & 31));
             }
+        };
+        // Of a long slice all keys are requested before the first one is used, and what each means is
+        // worked out before the first atomic is issued: an atomic between a load and its use makes that
+        // use wait for the atomic as well, one trip to memory after the other.
+        if (n <= 2 * kLanes) {                              // wave-uniform: the usual slice, one or two rounds
+            for (uint32_t e = lane; e < n; e += kLanes) {
+                const uint32_t what = classify(e < kLanes ? ce_early : slice[e], e);
+                if (what) mark(what);
+            }
+        } else {                                            // a slice of a wide range: up to 512 keys
+            constexpr int kRounds = kCandSlice / kLanes;
+            uint2 ent[kRounds];
+            ent[0] = ce_early;
+#pragma unroll
+            for (int r = 1; r < kRounds; ++r) {
+                const uint32_t e = r * kLanes + lane;
+                ent[r] = e < n ? slice[e] : make_uint2(0u, 0u);
+            }
+            uint32_t what[kRounds];
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) what[r] = classify(ent[r], r * kLanes + lane);
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r)
+                if (what[r]) mark(what[r]);
         }
         wave_lds_fence();
         if (lane < kTilesPerSuper) v = cnt[lane];

@@ -626,6 +626,35 @@ def test_learners_whose_gradients_differ_in_scale(gu, spread):
     ctx.close()
 
 
+@pytest.mark.parametrize("sigma", [0.05, 0.3])
+def test_gradient_norm_that_changes_from_step_to_step(gu, sigma):
+    """Every step's gradients carry a random common factor (log-normal, applied through lr), as the
+    gradient norm of a minibatch does: while the memories are small the threshold follows it, so
+    the range of finely counted keys grows beyond one twelve-bit bucket (coarser counts, the open
+    bits resolved on the listed keys) and shrinks again as the magnitudes pile up."""
+    rng = np.random.default_rng(88)
+    n, beta, lr = 3, 0.1, 0.1
+    sizes = [200_003, 20_000, 6_000, 70_000]
+    offsets = np.concatenate([[3], 3 + np.cumsum(sizes)]).tolist()
+    numel = offsets[-1] + 2
+    ks = [500, 200, 60, 2_800]
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes), gu.DEV)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    pool = [[((rng.standard_normal(numel) + 0.5 * rng.standard_normal(numel)) * 1e-3).astype(np.float32)
+             for _ in range(n)] for _ in range(5)]
+    pool_dev = [[torch.from_numpy(g).to(gu.DEV) for g in gs] for gs in pool]
+    for step in range(220):
+        lr_t = float(np.float32(lr * np.exp(rng.normal(0.0, sigma))))
+        idx, red = ctx.scalecom_step_layers(mem, pool_dev[step % 5], offsets, ks, beta, lr_t, step)
+        want_idx, want_red = oracle.step_layers(ref, pool[step % 5], offsets, ks, beta, lr_t, step)
+        gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"sigma {sigma} step {step}")
+        gu.assert_same("reduced", red.cpu().numpy(), want_red, 1e-5, f"sigma {sigma} step {step}")
+    for i in range(n):
+        gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], 1e-6, f"sigma {sigma} learner {i}")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ behaviour of the boundary
 def test_deterministic_and_resumable(gu):
     """Same inputs give the same bytes; stopping after 2 steps, saving the memories and
