@@ -800,8 +800,23 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     if (ss.done == 0 && ss.pending != 0) {                  // block-uniform: the previous level's search
         if (t == 0) res[0] = 0u;
         uint32_t digit, n_digit, n_above;                   // (search_digit's barrier orders the store above)
-        if (search_digit<NB_PREV>(hist_prev + static_cast<size_t>(cur) * NB_PREV, ss.k_rem, above, digit, n_digit,
-                                  n_above)) {
+        const uint32_t* hp = hist_prev + static_cast<size_t>(cur) * NB_PREV;
+        if constexpr (LEVEL == 2) {
+            // level 1's counts exist in 2^(12 - l1_bits) slotted copies (word = copy << l1_bits | bin): added up
+            // in LDS, then searched there
+            __shared__ uint32_t sum1[kBins1];
+            for (int b = t; b < kBins1; b += kBlock) sum1[b] = 0u;
+            uint32_t mine[kBins1 / kBlock];
+#pragma unroll
+            for (int j = 0; j < kBins1 / kBlock; ++j) mine[j] = hp[j * kBlock + t];
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < kBins1 / kBlock; ++j)
+                if (mine[j]) atomicAdd(&sum1[(j * kBlock + t) & ((1u << l1_bits) - 1u)], mine[j]);
+            __syncthreads();
+            hp = sum1;
+        }
+        if (search_digit<NB_PREV>(hp, ss.k_rem, above, digit, n_digit, n_above)) {
             res[1] = digit;
             res[2] = n_above;
             res[3] = n_digit;
@@ -937,6 +952,10 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     }
     __syncthreads();                                        // flush my counts of the segment
     uint32_t* h = hist + static_cast<size_t>(cur) * NB;
+    // Level 1 after a hit of a wide range counts few bits: its 2^l1_bits counters exist in as many
+    // copies as 4096 words hold, one per residue of the block number (atomics on the same few lines are
+    // carried out one after the other at the memory side).  Twelve bits: one copy.
+    if (LEVEL == 1) h += (blockIdx.x & ((1u << (kBits1 - l1_bits)) - 1u)) << l1_bits;
     for (int b = t; b < NB; b += kBlock) {
         const uint32_t v = lh[b];
         if (v) atomicAdd(&h[b], v);
