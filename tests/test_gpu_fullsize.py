@@ -206,6 +206,25 @@ def test_large_vector_fallback_paths(gu):
     ctx.close()
 
 
+def test_large_vector_wide_ranges(gu):
+    """The same vector length with a gradient norm that moves by 5 to 15 % from step to step: after the
+    first miss the range of the predicted pass is re-sized to many times a twelve-bit bucket (coarse
+    counts, level 1 on the listed keys, slices of several hundred keys), in blocks of the search
+    kernels that hold several supertiles each."""
+    rng = np.random.default_rng(4343)
+    numel, n, k = 40_000_003, 2, 100_000
+    ctx = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV, k_max=k)
+    mem = [torch.zeros(numel, device=gu.DEV) for _ in range(n)]
+    ref = [np.zeros(numel, np.float32) for _ in range(n)]
+    shared = rng.standard_normal(numel, dtype=np.float32)
+    for step, factor in enumerate([1.0, 1.06, 0.93, 1.1, 0.9, 1.12, 0.85, 1.15, 1.0]):
+        print(f"[fullsize] wide ranges step {step} (gradient norm x {factor})", flush=True)
+        grads = [torch.from_numpy((shared + 0.5 * rng.standard_normal(numel, dtype=np.float32)) *
+                                  np.float32(1e-3 * factor)).to(gu.DEV) for _ in range(n)]
+        gu.compare_step(ctx, mem, grads, ref, step, 0.3, 1.0, k=k, what=f"wide ranges step {step}")
+    ctx.close()
+
+
 def test_resnet50_sized_piled_up_full(gu):
     """The state a long run is in, at the benchmark's size: memories drawn (from a seeded recipe,
     not from earlier GPU steps) with magnitudes crowded just below a common level, so that the
