@@ -27,6 +27,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import re
 import sys
@@ -124,7 +125,9 @@ def main():
     ap.add_argument("--workload", default="resnet50_sized")
     ap.add_argument("--select", choices=["exact", "chunk"], default="exact")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pool", type=int, default=8, help="distinct gradient batches kept in HBM and cycled")
+    ap.add_argument("--pool", type=int, default=7,
+                    help="distinct gradient batches kept in HBM and cycled (lowered until it has no common "
+                         "factor with the learner count, so that no learner leads on the same batch every time)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all learners are buffers on one MI355X); "
@@ -146,7 +149,9 @@ def main():
 
     # inputs resident in HBM before the timed region: a pool of gradient batches, zero memories
     gbytes = w.n_learners * w.numel * (2 if w.grad_dtype == "bf16" else 4)
-    pool_n = max(1, min(args.pool, args.steps + args.warmup, int(40e9 // gbytes)))
+    pool_n = max(1, min(args.pool, args.steps + args.warmup, int(100e9 // gbytes)))
+    while pool_n > 1 and math.gcd(pool_n, w.n_learners) != 1:
+        pool_n -= 1
     pool = [workloads.gradients(w, t, dev) for t in range(pool_n)]
     mem = workloads.zero_memories(w, dev)
     idx = torch.empty(k, dtype=torch.int32, device=dev)
