@@ -238,6 +238,9 @@ def main():
             "algorithmic_bytes_per_launch": fused_bytes,
             "avg_launch_ms": fused_ms,
             "launches_timed": len(timed),
+            # the pass goes over 8 learners per kernel launch; with more learners the figures above are
+            # those of one step's launches together
+            "kernel_launches_per_pass": -(-w.n_learners // 8),
         },
         "step_roofline": {
             "algorithmic_bytes_per_step": step_bytes,

@@ -18,6 +18,7 @@ constexpr int kSuper = kWaveTile * kTilesPerSuper;   // 8192 positions
 constexpr int kBlock = 256;                      // threads per block in the streaming kernels
 constexpr int kWaves = kBlock / kLanes;          // 4
 constexpr int kUpdateBlocksPerSuper = kTilesPerSuper / kWaves;   // update: one wave tile per wave
+constexpr int kUpdateLearnersPerLaunch = 8;      // update: learners streamed side by side (one per XCD)
 constexpr int kChunk = 1024;                     // supertiles per chunk of the prefix scan
 constexpr int kOwnScanMaxSt = 10240;             // up to this many supertiles k_slots scans the supertile totals itself
 constexpr int kSlotsOwnScanBlock = 1024;         // threads of its blocks then (16 waves = 16 supertiles)

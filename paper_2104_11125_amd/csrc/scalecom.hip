@@ -335,8 +335,11 @@ void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learne
     const int64_t groups = static_cast<int64_t>(n_st) * kUpdateBlocksPerSuper;
     const unsigned gz = static_cast<unsigned>((groups + 65534) / 65535);
     const unsigned gy = static_cast<unsigned>((groups + gz - 1) / gz);
-    k_update<G><<<dim3(n_learners, gy, gz), kBlock, 0, s>>>(lp, lr, beta, 1.0f - beta, sts, n_st, sel_mask, tile_slot, vals,
-                                                           k_total, idx_out);
+    for (int l0 = 0; l0 < n_learners; l0 += kUpdateLearnersPerLaunch) {
+        const int nl = std::min(kUpdateLearnersPerLaunch, n_learners - l0);
+        k_update<G><<<dim3(nl, gy, gz), kBlock, 0, s>>>(lp, lr, beta, 1.0f - beta, sts, n_st, sel_mask, tile_slot, vals,
+                                                       k_total, idx_out, l0);
+    }
     mark(4);
     if (k_total > 0)
         k_reduce<<<static_cast<unsigned>((k_total + kBlock - 1) / kBlock), kBlock, 0, s>>>(vals, n_learners, k_total,

@@ -84,11 +84,11 @@ template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDesc* __restrict__ sts, int n_st,
          const uint64_t* __restrict__ sel_mask, const uint32_t* __restrict__ tile_slot, float* __restrict__ vals,
-         int64_t k_total, int32_t* __restrict__ idx_out)
+         int64_t k_total, int32_t* __restrict__ idx_out, int learner0)
 {
     // grid = (learners, groups of 4 wave tiles split over y and z): x runs fastest, so blocks that
     // are scheduled together work on the same positions of different learners
-    const int learner = blockIdx.x;
+    const int learner = learner0 + blockIdx.x;
     const int group = blockIdx.y + blockIdx.z * gridDim.y;
     const int st = group / kUpdateBlocksPerSuper;
     if (st >= n_st) return;                                 // padding of the 3-d grid (whole block)
