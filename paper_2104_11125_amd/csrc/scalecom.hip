@@ -8,14 +8,17 @@
 // stored) is resolved 12 + 12 + 7 bits at a time (radix select):
 //
 //   predicted   leader, ONE pass, for segments that carry a prediction: a range of keys around the
-//               previous step's threshold, whose width follows how densely the keys lie there
-//               (with error feedback they pile up below the threshold).  Keys above the range
-//               are members for sure (counted per 256-element wave tile, marked in the
-//               membership bitmask); keys inside it are copied, with their positions, to a small
-//               candidate list and counted per 128 keys
+//               threshold the step expects (this leader's last one, moved on by the recent
+//               growth), whose width follows how densely the keys lie there (with error feedback
+//               they pile up below the threshold) and how far the threshold moves between steps.
+//               Keys above the range are members for sure (counted per 256-element wave tile,
+//               marked in the membership bitmask); keys inside it are copied, with their
+//               positions, to a small candidate list and counted per 128 keys (in 64 bins if the
+//               range is wider than 2^19 keys)
 //   level0      per segment: did the k-th largest key fall inside the range (exact check on
 //               counts)?  Then the top 24 bits of the threshold follow from the range's counts
-//               (Eq. 2).  Otherwise (no prediction, or a miss): histogram of the top 12 key bits
+//               (Eq. 2; of a wide range the bin, whose open bits level 1 then resolves on the
+//               listed keys).  Otherwise (no prediction, or a miss): histogram of the top 12 key bits
 //               of the leader's vector.  A segment of one supertile is finished here by its one
 //               block, without prediction
 //   level<1>    a histogram of level0 is searched by every block that needs the result; then the
@@ -30,13 +33,13 @@
 //               takes levels 1, 2 and this step as full leader passes instead of the list)
 //   scan, slots prefix sums of the counts over tiles: first output slot of every wave tile;
 //               keys equal to T become members in position order until q are taken
-//   update      every learner, one (learner, 1024 positions) pair per block: one read of
+//   update      every learner (eight per launch), one (learner, 1024 positions) pair per block: one read of
 //               (mem, grad), one write of mem (Eq. 5); members also store x_i into a small
 //               [learner][slot] staging array and learner 0 writes the index (Eq. 3)
 //   reduce      reduced[t] = x_0[t] + x_1[t] + ... in learner order  (Alg. 1 line 10)
 //
 // In the steady state (predictions hold) the leader's vector is read exactly once before the
-// all-learner pass, and 8 kernels make a step.  No kernel reads what another block of the same
+// all-learner pass, and 8 kernels make a step (up to 8 learners and 84 M elements).  No kernel reads what another block of the same
 // launch wrote, so there are no fences or waits between blocks.  The prediction only decides how much work is
 // done, never what is selected.  The output is ascending by position and deterministic.
 // Nothing here is a dense contraction, so there is no MFMA; the kernels are bound by HBM traffic
