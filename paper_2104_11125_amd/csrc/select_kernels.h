@@ -751,9 +751,10 @@ struct CollectOut {
 // previous level's histogram if it is still pending (every block of the segment does it for
 // itself: the histogram is complete since the previous kernel ended, and re-reading its 16 KB
 // costs less than a launch), then the histogram of the next digit of the leader's magnitude keys.
-// LEVEL 1: bits 18..7 of keys whose top 12 bits equal the chosen bucket; a segment whose level 1
-// was searched by k_level0 already (the steady state) is skipped.  LEVEL 2: last 7 bits of keys
-// matching 24 bits; the search follows in k_tilecount.  Candidate mode reads the keys
+// LEVEL 1: bits 18..7 of keys whose top 12 bits equal the chosen bucket -- or, after a hit of a
+// range wider than 2^19 keys, the l1_bits bits that its 64 bins left open, counted on the listed
+// keys; a segment whose top 24 bits k_level0 found already (the steady state) is skipped.
+// LEVEL 2: last 7 bits of keys matching 24 bits; the search follows in k_tilecount.  Candidate mode reads the keys
 // from the candidate list, full mode recomputes them from the leader's vector.  The state comes
 // from state_in and goes, through the segment's first block, to state_out: no block reads what
 // another block of the same kernel wrote.
