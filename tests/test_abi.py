@@ -104,3 +104,14 @@ def test_layer_ks_follows_the_rate_guidance():
     bad = (ctypes.c_double * 1)(0.0); one = (ctypes.c_int64 * 1)(5); out = (ctypes.c_int64 * 1)()
     assert L.scalecom_layer_ks(1, bad, one, None, out, None) == binding.SCALECOM_EINVAL
     assert L.scalecom_apply_update(None, None, 0, None, None, 0, 1.0) == binding.SCALECOM_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU; asked for more it says so and exits non-zero before touching a device."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr
+    assert res.stdout.strip() == ""
