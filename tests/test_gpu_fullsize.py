@@ -111,9 +111,12 @@ def test_large_multi_tensor_layout(gu):
     ctx.close()
 
 
-def _streamed_parity(gu, w, step, seed, chunk=None):
+def _streamed_parity(gu, w, step, seed, chunk=None, second_step=False):
     """One full-size step checked learner by learner with the oracle's primitives (chunk: the
-    chunk-wise selector with that many elements per chunk instead of the exact top-k)."""
+    chunk-wise selector with that many elements per chunk instead of the exact top-k).
+    second_step: one more step on the same context, which then works with the prediction the first
+    step left, from the memories the ORACLE computed for the first step; its index set, reduced
+    values and the new leader's memory are checked."""
     dev = gu.DEV
     gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
     k_max = w.k if chunk is None else -(-w.numel // chunk)
@@ -139,6 +142,7 @@ def _streamed_parity(gu, w, step, seed, chunk=None):
     print(f"[fullsize] {w.name}: oracle selection done at {time.time() - t0:.0f}s", flush=True)
     gu.assert_same("idx", idx_h, want_idx, None, w.name)
     vals = []
+    ref_after = []                                       # the oracle's memories after the step
     for i in range(w.n_learners):
         m_i = before[i].cpu().numpy()
         acc = oracle.accumulate(m_i, gu.to_host(grad[i]), w.lr)
@@ -146,18 +150,44 @@ def _streamed_parity(gu, w, step, seed, chunk=None):
         oracle.memory_update(m_i, acc, want_idx, w.beta)
         del acc
         gu.assert_same("mem", mem[i].cpu().numpy(), m_i, 1e-6, f"{w.name} learner {i}")
+        if second_step:
+            ref_after.append(m_i)
         del m_i
         print(f"[fullsize] {w.name}: learner {i} memory checked at {time.time() - t0:.0f}s", flush=True)
     gu.assert_same("reduced", red_h, oracle.reduce(vals), 1e-5, w.name)
+    if second_step:
+        del grad, before, vals
+        step2 = step + 1
+        shared = workloads.shared_component(w, step2, dev)
+        grad = [workloads.learner_gradient(w, step2, i, dev, shared=shared) for i in range(w.n_learners)]
+        del shared
+        idx, red = ctx.scalecom_step(mem, grad, w.k, w.beta, w.lr, step2)
+        torch.cuda.synchronize()
+        print(f"[fullsize] {w.name}: second GPU step done at {time.time() - t0:.0f}s", flush=True)
+        leader = step2 % w.n_learners
+        acc_l = oracle.accumulate(ref_after[leader], gu.to_host(grad[leader]), w.lr)
+        want_idx = oracle.topk_select(acc_l, w.k)
+        gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"{w.name} second step")
+        print(f"[fullsize] {w.name}: second selection checked at {time.time() - t0:.0f}s", flush=True)
+        vals = []
+        for i in range(w.n_learners):
+            acc = acc_l if i == leader else oracle.accumulate(ref_after[i], gu.to_host(grad[i]), w.lr)
+            vals.append(oracle.gather(acc, want_idx))
+            if i != leader:
+                del acc
+        gu.assert_same("reduced", red.cpu().numpy(), oracle.reduce(vals), 1e-5, f"{w.name} second step")
+        oracle.memory_update(ref_after[leader], acc_l, want_idx, w.beta)
+        gu.assert_same("mem", mem[leader].cpu().numpy(), ref_after[leader], 1e-6, f"{w.name} second step, leader")
+        print(f"[fullsize] {w.name}: second step checked at {time.time() - t0:.0f}s", flush=True)
     ctx.close()
 
 
 def test_transformer_base_sized_full(gu):
-    _streamed_parity(gu, workloads.by_name("transformer_base_sized"), step=5, seed=930)
+    _streamed_parity(gu, workloads.by_name("transformer_base_sized"), step=5, seed=930, second_step=True)
 
 
 def test_large_bf16_full(gu):
-    _streamed_parity(gu, workloads.by_name("large_bf16"), step=2, seed=940)
+    _streamed_parity(gu, workloads.by_name("large_bf16"), step=2, seed=940, second_step=True)
 
 
 def _maximum_size_workload():
