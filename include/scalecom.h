@@ -24,9 +24,10 @@
  *  - The caller owns every buffer, including the workspace; the library allocates no
  *    device memory.  Per context it keeps pinned host staging for its tile tables
  *    (about numel_max / 256 + 140 * n_tensors_max + 64 KB bytes).
- *  - The result of a call depends only on its arguments.  The context remembers, per tensor,
- *    where the previous step's threshold fell and uses it to skip a pass over the leader when
- *    the guess holds (checked exactly); this changes the time a step takes, never its result.
+ *  - The result of a call depends only on its arguments.  The context remembers, per tensor
+ *    (and per learner, for its turns as leader), where the threshold fell in earlier steps and
+ *    uses it to skip a pass over the leader when the guess holds (checked exactly); this changes
+ *    the time a step takes, never its result.
  *  - All work is enqueued on the HIP stream given to scalecom_init; calls do not wait for
  *    the GPU.  Outputs are valid once that stream has reached the end of the call's work.
  *    A context must not be used from two threads at once.
