@@ -40,6 +40,13 @@ def test_many_learners(gu):
     gu.run_workload(workloads.scaled(workloads.by_name("tiny"), 50_001, n_learners=64, steps=2))
 
 
+@pytest.mark.parametrize("n", [8, 9, 17])
+def test_learner_counts_around_the_launch_size(gu, n):
+    """The all-learner pass goes over eight learners per launch: one launch exactly, one more for a
+    single learner, and two full ones plus one; long enough for leaders out of every launch."""
+    gu.run_workload(workloads.scaled(workloads.by_name("tiny"), 30_011, n_learners=n, steps=n + 2))
+
+
 def test_single_learner(gu):
     gu.run_workload(workloads.scaled(workloads.by_name("tiny"), 70_000, n_learners=1, steps=2))
 
