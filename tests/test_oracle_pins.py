@@ -221,6 +221,43 @@ def test_reduction_commutes_with_sparsification():
     assert np.array_equal(red, dense[idx])
 
 
+def test_memory_update_rounds_the_kept_part_then_fuses_the_residual():
+    """Eq. 5 in binary32, rounding by rounding: 1 - beta is rounded once, kept = RN((1 - beta) * m),
+    then m' = RN(kept + beta * r) with the product beta * r exact (one fused multiply-add); r is x off
+    the index set and 0 on it.  Expected values come from exact rational arithmetic, and the sample
+    is checked to tell this evaluation from an unfused multiply-then-add, from a fused kept part,
+    and from the other algebraic form m + beta * (r - m)."""
+    rng = np.random.default_rng(25)
+    numel = 400
+    m = f32(rng.standard_normal(numel) * 1e-3)
+    x = f32(rng.standard_normal(numel) * 1e-3)
+    idx = np.arange(0, numel, 7, dtype=np.int32)                       # members: residual 0 there
+    in_set = np.zeros(numel, bool)
+    in_set[idx] = True
+    for beta in (0.1, 0.2, 0.3, 0.7):
+        b = np.float32(beta)
+        omb = round_fraction_to_f32(Fraction(1) - Fraction(float(b)))  # 1 - beta, one rounding
+        assert omb == np.float32(1.0) - b
+        got = m.copy()
+        oracle.memory_update(got, x, idx, float(b))
+        differs = {"unfused": 0, "kept_fused": 0, "other_form": 0}
+        for j in range(numel):
+            r = np.float32(0.0) if in_set[j] else x[j]
+            kept = round_fraction_to_f32(Fraction(float(omb)) * Fraction(float(m[j])))
+            want = round_fraction_to_f32(Fraction(float(kept)) + Fraction(float(b)) * Fraction(float(r)))
+            assert got[j] == want, (beta, j)
+            # neighbouring evaluations that the pin must tell apart
+            unfused = np.float32(kept + np.float32(b * r))
+            kept_fused = round_fraction_to_f32(Fraction(float(omb)) * Fraction(float(m[j])) +
+                                               Fraction(float(b)) * Fraction(float(r)))
+            other = np.float32(m[j] + np.float32(b * np.float32(r - m[j])))
+            differs["unfused"] += got[j] != unfused
+            differs["kept_fused"] += got[j] != kept_fused
+            differs["other_form"] += got[j] != other
+        assert all(v > 0 for v in differs.values()), (beta, differs)
+        assert np.array_equal(got[idx], (omb * m[idx]).astype(np.float32))   # on the set: (1 - beta) * m, one rounding
+
+
 def test_beta_one_is_plain_error_feedback():
     rng = np.random.default_rng(24)
     n, numel, k = 3, 3000, 30
