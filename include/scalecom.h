@@ -24,6 +24,10 @@
  *  - The caller owns every buffer, including the workspace; the library allocates no
  *    device memory.  Per context it keeps pinned host staging for its tile tables
  *    (about numel_max / 256 + 140 * n_tensors_max + 64 KB bytes).
+ *  - The workspace is the caller's allocation but the library's to use: from scalecom_init until
+ *    scalecom_destroy it holds the library's tables, counters and threshold predictions, and
+ *    the caller must neither write to it nor hand it to anything else.  What it holds never
+ *    changes a result, but kernels follow the tables in it.
  *  - The result of a call depends only on its arguments.  The context remembers, per tensor
  *    (and per learner, for its turns as leader), where the threshold fell in earlier steps and
  *    uses it to skip a pass over the leader when the guess holds (checked exactly); this changes
@@ -34,11 +38,9 @@
  *  - HIP graphs: once a layout (numel or offsets, k or ks or chunk sizes) has been used in one
  *    call, further steps with it enqueue kernels only (no copies, memsets, events or waits;
  *    scalecom_timing_begin must not be in effect), so they can be captured on the context's
- *    stream.  Two things are decided on the host when a step is enqueued and are therefore frozen
- *    in a graph: the leader (step mod n_learners) and which of two alternating copies of the
- *    per-step scratch memory the step uses.  Capture lcm(2, n_learners) consecutive steps,
- *    starting at a step index that is a multiple of that number; such a graph ends in the state
- *    it began in and may be replayed any number of times.
+ *    stream.  One thing is decided on the host when a step is enqueued and is therefore frozen
+ *    in a graph: the leader (step mod n_learners).  A graph of one step may be replayed for every
+ *    step with that leader; a graph of n_learners consecutive steps for every such cycle.
  *  - Errors are return codes; nothing is thrown.  scalecom_last_error gives the detail.
  */
 #ifndef SCALECOM_H
@@ -85,8 +87,9 @@ size_t scalecom_workspace_bytes(int64_t numel_max, int n_tensors_max, int n_lear
  *   device                   HIP device ordinal
  *   hip_stream               hipStream_t on that device, as void* (NULL = the default stream)
  *   workspace       [device] at least scalecom_workspace_bytes(numel_max, n_tensors_max,
- *                            n_learners_max, k_max) bytes, 256-byte aligned; stays the caller's,
- *                            must outlive the context, contents are scratch
+ *                            n_learners_max, k_max) bytes, 256-byte aligned; must outlive the
+ *                            context and is the library's to use until scalecom_destroy (see
+ *                            Conventions); need not be initialised
  *   n_learners_max           1 .. SCALECOM_MAX_LEARNERS
  *   k_max                    0 .. numel_max: largest k (sum of ks for scalecom_step_layers) used later
  *   grad_dtype               element type of every grad buffer passed later
@@ -191,7 +194,10 @@ scalecom_status scalecom_apply_update(scalecom_ctx* ctx, float* theta, int64_t n
  * over learners 0..n-1 left to right in fp32; the 1/n of the mean does not change the set).  Both
  * sets have ks[s] members, the binarised vectors of Eq. 6 differ in 2 d places, and
  * d_out[s] = ks[s] - |intersection| (the paper plots d / k).  Same tie rule as scalecom_step.
- * Reads mem and grad, modifies neither, and leaves the bucket predictions of scalecom_step alone.
+ * Reads mem and grad, modifies neither.  The threshold predictions that scalecom_step_layers keeps
+ * for a layout survive a call with the same offsets and ks; a call with other offsets or ks is
+ * a change of layout like any other, after which the next step starts without predictions (its
+ * result is the same, it takes two more passes over the leader).
  *   mem, grad, n_learners, n_tensors, offsets, ks, lr, step: as for scalecom_step_layers
  *   scratch       [device] at least scalecom_hamming_scratch_bytes(numel_max, n_tensors_max) bytes
  *                 (the context's maxima), 256-byte aligned, caller-owned, contents undefined afterwards
@@ -230,6 +236,32 @@ scalecom_status scalecom_cosine_distance(scalecom_ctx* ctx, const float* a, cons
  */
 scalecom_status scalecom_layer_ks(int n_tensors, const double* flops_per_gradient, const int64_t* sizes,
                                   const uint8_t* uncompressed, int64_t* ks_out, int64_t* rates_out);
+
+/*
+ * How often the exact selection could not finish on its single pass over the leader, counted on
+ * the device since scalecom_init (or the last reset) over the (step, tensor) pairs with a
+ * non-empty index set and a tensor of more than 8192 elements.  The single pass works on a range
+ * of magnitudes around the threshold that the context expects from earlier steps; the counts tell
+ * how often that held.  Results never depend on it, step times do.  Diagnostic: waits for the
+ * context's stream, then copies the counters to the host; nothing in scalecom_step* waits.
+ *   counts_out [host] uint64[SCALECOM_N_STATS]:
+ *     [SCALECOM_STAT_MISSED]        the threshold fell outside the expected range: two more passes
+ *                                   over the leader's vector in that step
+ *     [SCALECOM_STAT_NO_PREDICTION] nothing was expected yet (first step of a layout): same cost
+ *     [SCALECOM_STAT_FULL_MODE]     so many equal or clustered magnitudes at the threshold that the
+ *                                   last two search levels were passes over the leader's vector too
+ *     [SCALECOM_STAT_WIDE_RANGE]    the range was wider than 2^19 magnitudes and held the threshold:
+ *                                   one more pass over the listed magnitudes, none over the vector
+ *     [SCALECOM_STAT_STEPS]         calls of scalecom_step / scalecom_step_layers counted
+ *   reset      non-zero: the counters start again from zero after this call
+ */
+#define SCALECOM_N_STATS 5
+#define SCALECOM_STAT_MISSED 0
+#define SCALECOM_STAT_NO_PREDICTION 1
+#define SCALECOM_STAT_FULL_MODE 2
+#define SCALECOM_STAT_WIDE_RANGE 3
+#define SCALECOM_STAT_STEPS 4
+scalecom_status scalecom_selection_stats(scalecom_ctx* ctx, uint64_t* counts_out, int reset);
 
 /*
  * Optional per-phase GPU timing, for benchmarks.  Not part of the paper's method: it only

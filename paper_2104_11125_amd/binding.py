@@ -18,6 +18,7 @@ SCALECOM_OK, SCALECOM_EINVAL, SCALECOM_ENOMEM, SCALECOM_EHIP, SCALECOM_EUNSUPPOR
 SCALECOM_GRAD_F32, SCALECOM_GRAD_BF16 = 0, 1
 SCALECOM_MAX_LEARNERS = 64
 SCALECOM_N_PHASES = 5
+SCALECOM_N_STATS = 5
 
 _lib = None
 
@@ -54,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.scalecom_timing_begin.restype = i32
         L.scalecom_timing_read.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
         L.scalecom_timing_read.restype = i32
+        L.scalecom_selection_stats.argtypes = [vp, vp, i32]
+        L.scalecom_selection_stats.restype = i32
         L.scalecom_apply_update.argtypes = [vp, vp, i64, vp, vp, i64, f32]
         L.scalecom_apply_update.restype = i32
         L.scalecom_hamming_scratch_bytes.argtypes = [i64, i32]
@@ -134,12 +137,20 @@ class ScaleCom:
         if st != SCALECOM_OK:
             raise ScaleComError(st, lib().scalecom_last_error(self._ctx).decode())
 
-    def _check_buffers(self, mem, grad):
+    def _check_buffers(self, mem, grad, extent=None):
+        """Every learner's buffers have one length (and reach `extent`, the end of the last segment)."""
+        if len(mem) != len(grad) or len(mem) == 0:
+            raise ValueError("one mem and one grad buffer per learner")
+        numel = mem[0].numel()
         for m, g in zip(mem, grad):
             if m.dtype != torch.float32 or g.dtype != self.grad_dtype:
                 raise TypeError("mem must be float32 and grad must have the context's grad_dtype")
             if not (m.is_contiguous() and g.is_contiguous() and m.device == self.device and g.device == self.device):
                 raise ValueError("buffers must be contiguous tensors on the context's device")
+            if m.numel() != numel or g.numel() != numel:
+                raise ValueError("every learner's mem and grad must have the same number of elements")
+        if extent is not None and int(extent) > numel:
+            raise ValueError("the last segment ends beyond the learners' buffers")
 
     def scalecom_step(self, mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor], k: int, beta: float,
                       lr: float, step: int, idx_out: Optional[torch.Tensor] = None,
@@ -178,7 +189,7 @@ class ScaleCom:
                              idx_out: Optional[torch.Tensor] = None,
                              reduced_vals_out: Optional[torch.Tensor] = None):
         """``scalecom_step_layers`` of the C-ABI."""
-        self._check_buffers(mem, grad)
+        self._check_buffers(mem, grad, offsets[-1] if len(offsets) else None)
         n_tensors = len(ks)
         if len(offsets) != n_tensors + 1:
             raise ValueError("offsets must have len(ks) + 1 entries")
@@ -200,7 +211,7 @@ class ScaleCom:
                                      idx_out: Optional[torch.Tensor] = None,
                                      reduced_vals_out: Optional[torch.Tensor] = None):
         """``scalecom_step_layers_chunked`` of the C-ABI: one position per chunk, a chunk size per tensor."""
-        self._check_buffers(mem, grad)
+        self._check_buffers(mem, grad, offsets[-1] if len(offsets) else None)
         n_tensors = len(chunks)
         if len(offsets) != n_tensors + 1:
             raise ValueError("offsets must have len(chunks) + 1 entries")
@@ -228,6 +239,13 @@ class ScaleCom:
         self._check(lib().scalecom_timing_read(self._ctx, buf, capacity_steps, ctypes.byref(n)))
         return [[buf[t * SCALECOM_N_PHASES + p] for p in range(SCALECOM_N_PHASES)] for t in range(n.value)]
 
+    def scalecom_selection_stats(self, reset: bool = False) -> dict:
+        """``scalecom_selection_stats`` of the C-ABI as a dict (waits for the context's stream)."""
+        buf = (ctypes.c_uint64 * SCALECOM_N_STATS)()
+        self._check(lib().scalecom_selection_stats(self._ctx, buf, 1 if reset else 0))
+        names = ("missed", "no_prediction", "full_mode", "wide_range", "steps")
+        return {name: int(buf[j]) for j, name in enumerate(names)}
+
     def scalecom_apply_update(self, theta: torch.Tensor, idx: torch.Tensor, vals: torch.Tensor, scale: float) -> None:
         """``scalecom_apply_update`` of the C-ABI: theta[idx] -= scale * vals, in place."""
         if theta.dtype != torch.float32 or idx.dtype != torch.int32 or vals.dtype != torch.float32:
@@ -242,7 +260,7 @@ class ScaleCom:
                                   offsets: Sequence[int], ks: Sequence[int], lr: float, step: int,
                                   d_out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """``scalecom_hamming_distance`` of the C-ABI; the scratch buffer is allocated on first use and kept."""
-        self._check_buffers(mem, grad)
+        self._check_buffers(mem, grad, offsets[-1] if len(offsets) else None)
         n_tensors = len(ks)
         if len(offsets) != n_tensors + 1:
             raise ValueError("offsets must have len(ks) + 1 entries")

@@ -77,16 +77,14 @@ k_chunk_select(const float* __restrict__ mem, const G* __restrict__ grad, float 
 }
 
 // After the leader pass: position of each chunk's winner to idx_out and to the membership mask;
-// first output slot of every wave tile (chunk j of a segment owns slot out_base + j); and the
-// other copy of best[] is cleared for the next step (the entries its last use may have touched).
+// first output slot of every wave tile (chunk j of a segment owns slot out_base + j).  (best[] is
+// zeroed again by the all-learner pass that follows.)
 __global__ void __launch_bounds__(kBlock)
 k_chunk_marks(const SegDesc* __restrict__ segs, int n_tensors, const StDesc* __restrict__ sts,
-              const unsigned long long* __restrict__ best, unsigned long long* __restrict__ best_next, int64_t clear_next,
-              int64_t k_total, int64_t n_tiles, uint64_t* __restrict__ sel_mask, uint32_t* __restrict__ tile_slot,
-              int32_t* __restrict__ idx_out)
+              const unsigned long long* __restrict__ best, int64_t k_total, int64_t n_tiles,
+              uint64_t* __restrict__ sel_mask, uint32_t* __restrict__ tile_slot, int32_t* __restrict__ idx_out)
 {
     const int64_t t = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
-    if (t < clear_next) best_next[t] = 0ull;               // as many entries as that copy's last use left behind
     if (t < k_total) {
         // the segment that owns output slot t: the last one whose first slot is <= t (a segment without
         // slots shares its first slot with its successor, so it is never the last such one while t < k_total)

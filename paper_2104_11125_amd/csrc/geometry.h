@@ -116,6 +116,12 @@ __host__ __device__ constexpr uint32_t spec_bin_shift(uint32_t w)
     return w > static_cast<uint32_t>(kSpecBitsMax) ? w - kSpecWideBinsLog : static_cast<uint32_t>(kBits2);
 }
 static_assert(kSpecBitsWide - kSpecWideBinsLog - kBits2 <= kBits1, "level 1 resolves at most twelve bits");
+// A width as read from memory, forced into the range the kernels' index arithmetic is made for.
+__host__ __device__ constexpr uint32_t clamp_width(uint32_t w)
+{
+    return w < static_cast<uint32_t>(kSpecBitsMin) ? static_cast<uint32_t>(kSpecBitsMin)
+                                                  : (w > static_cast<uint32_t>(kSpecBitsWide) ? static_cast<uint32_t>(kSpecBitsWide) : w);
+}
 // The prediction kept per segment between steps, and the one a step works with.
 constexpr int kPredWords = 8;                    // [0] 1 if there is one, [1] top 24 bits of the last threshold, [2] w,
                                                  // [3] steps in a row in which the threshold fell into the range's middle half,
@@ -126,6 +132,17 @@ constexpr uint32_t kCalmSteps = 8;               // so many of those before the 
 // serialise); readers sum the copies.
 constexpr int kPartSlots = 64;
 constexpr int kPartWords = 8;
+
+// What the selections of a context ran into, counted on the device (64-bit words), per (step, tensor)
+// pair with a non-empty index set and more than one supertile.  Only events are counted.
+constexpr int kStatWords = 8;
+enum : int {
+    kStatMissed = 0,        // had a prediction and its range did not hold the threshold: two more leader passes
+    kStatNoPrediction = 1,  // had no prediction (first step with a layout, or the step after a miss)
+    kStatFullMode = 2,      // the threshold bucket did not fit the candidate list: refinement by full leader passes
+    kStatWideRange = 3,     // hit with a range wider than 2^19 keys: one more pass over the listed keys
+    kStatSteps = 4          // selections enqueued (one per step, whatever the number of tensors)
+};
 
 struct LearnerPtrs {
     float* mem[SCALECOM_MAX_LEARNERS];

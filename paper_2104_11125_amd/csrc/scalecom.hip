@@ -85,10 +85,10 @@ inline int64_t max_chunks(int64_t numel_max, int n_tensors_max)
 }
 
 struct WsLayout {
-    size_t segs, sts, chunks, hblocks, preds, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask, eq_mask,
-        tile_slot, vals, best, total;
-    // per-step counters and histograms: two copies of one zone, used alternately (offsets inside a copy)
-    size_t zone[2], zone_bytes, z_overflow, z_p_used, z_full_flag, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
+    size_t segs, sts, chunks, hblocks, preds, stats, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask,
+        eq_mask, tile_slot, vals, best, total;
+    // per-step counters and histograms: one zone, all zero between steps (offsets inside the zone)
+    size_t zone, zone_bytes, z_overflow, z_p_used, z_full_flag, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
 };
 
 WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
@@ -110,6 +110,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.hblocks = take((kHistGridMax + nt) * sizeof(HistBlock));
     // per segment: the prediction for the next step; then per learner and segment: that leader's last threshold
     l.preds = take((kPredWords + static_cast<size_t>(n_learners_max)) * nt * sizeof(uint32_t));
+    l.stats = take(kStatWords * sizeof(unsigned long long));   // what the selections of this context ran into
     l.state = take(3 * nt * kStateStride);               // after level 0, after level 1, after level 2
     {
         size_t z = 0;
@@ -128,8 +129,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
         l.z_hist2 = ztake(nt * kBins2 * sizeof(uint32_t));
         l.zone_bytes = z;
     }
-    l.zone[0] = take(l.zone_bytes);
-    l.zone[1] = take(l.zone_bytes);
+    l.zone = take(l.zone_bytes);
     l.wt_cnt = take(ntile * sizeof(uint32_t));
     l.st_sum = take(nst * sizeof(uint2));
     l.st_prefix = take(nst * sizeof(uint2));
@@ -140,7 +140,7 @@ WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, in
     l.eq_mask = take(ntile * 4 * sizeof(uint64_t));
     l.tile_slot = take(ntile * sizeof(uint32_t));
     l.vals = take(static_cast<size_t>(n_learners_max) * static_cast<size_t>(k_max) * sizeof(float));
-    l.best = take(2 * static_cast<size_t>(k_max) * sizeof(unsigned long long));   // chunk-wise selector, two copies
+    l.best = take(static_cast<size_t>(k_max) * sizeof(unsigned long long));       // chunk-wise selector: a word per chunk
     l.total = o;
     return l;
 }
@@ -166,11 +166,9 @@ struct scalecom_ctx {
     // tables of the layout used last, kept on the device until the layout changes
     std::vector<int64_t> cached_offsets, cached_ks, cached_chunks;
     int n_st = 0, n_chunks = 0, n_hblocks = 0;
-    int parity = 0;                  // which copy of the scratch zone the next step uses
-    bool scratch_clean = false;      // false: both copies must be cleared before the next step
-    int best_parity = 0;             // same scheme for the chunk-wise selector's per-chunk maxima
-    bool best_clean = false;
-    int64_t best_used[2] = {0, 0};   // entries of each copy that its last use may have left non-zero
+    bool scratch_clean = false;      // true: the scratch zone is all zero (every step leaves it so)
+    bool best_clean = false;         // same for the chunk-wise selector's per-chunk maxima
+    bool stats_ready = false;        // the selection counters have been zeroed
     char* pinned = nullptr;          // staging for the table upload
     size_t pinned_bytes = 0;
     hipEvent_t upload_done = nullptr;
@@ -258,9 +256,11 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
         const int64_t count = e > b ? (e - a_first + kSuper - 1) / kSuper : 0;
         const int64_t n_chunks = (count + kChunk - 1) / kChunk;
         if (n_st + count > st_cap || n_ch + n_chunks > ch_cap) return fail(ctx, SCALECOM_ENOMEM, "tile table overflow");
+        // a chunk longer than the segment selects like one of the segment's length, and that fits 32 bits
+        const int64_t sel_chunk = std::min<int64_t>(ch[s], std::max<int64_t>(e - b, 1));
         segs[s] = SegDesc{static_cast<int32_t>(b),    static_cast<int32_t>(e),     static_cast<int32_t>(ks[s]),
                           static_cast<int32_t>(out),  static_cast<int32_t>(n_st),  static_cast<int32_t>(count),
-                          static_cast<int32_t>(n_ch), static_cast<int32_t>(n_chunks), static_cast<int32_t>(ch[s]), 0};
+                          static_cast<int32_t>(n_ch), static_cast<int32_t>(n_chunks), static_cast<int32_t>(sel_chunk), 0};
         for (int64_t j = 0; j < count; ++j)
             sts[n_st + j] = StDesc{s, static_cast<int32_t>(a_first + j * kSuper), static_cast<int32_t>(b),
                                    static_cast<int32_t>(e), static_cast<int32_t>(out + ks[s]), {0, 0, 0}};
@@ -301,6 +301,11 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds),
                                           (kPredWords + static_cast<size_t>(ctx->n_learners_max)) *
                                               static_cast<size_t>(ctx->n_tensors_max));
+    if (!ctx->stats_ready) {
+        k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.stats),
+                                              kStatWords * sizeof(unsigned long long) / sizeof(uint32_t));
+        ctx->stats_ready = true;
+    }
     ctx->scratch_clean = false;
     SC_HIP(ctx, hipEventRecord(ctx->upload_done, ctx->stream));
     ctx->upload_pending = true;
@@ -322,9 +327,11 @@ bool timed_step(scalecom_ctx* ctx)
 
 // The all-learner pass and the sum over learners, shared by the exact and the chunk-wise selector:
 // both leave the membership mask and the first output slot of every wave tile behind.
+// The first launch of the pass also zeroes `clear_words` words from `clear_from`: the selection's
+// per-step scratch, which nothing reads any more at that point, so that the next step finds it clean.
 template <typename G, typename Mark>
 void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learners, int64_t k_total, float beta, float lr,
-                          int32_t* idx_out, float* red_out, Mark&& mark)
+                          int32_t* idx_out, float* red_out, uint32_t* clear_from, size_t clear_words, Mark&& mark)
 {
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
@@ -341,7 +348,7 @@ void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learne
     for (int l0 = 0; l0 < n_learners; l0 += kUpdateLearnersPerLaunch) {
         const int nl = std::min(kUpdateLearnersPerLaunch, n_learners - l0);
         k_update<G><<<dim3(nl, gy, gz), kBlock, 0, s>>>(lp, lr, beta, 1.0f - beta, sts, n_st, sel_mask, tile_slot, vals,
-                                                       k_total, idx_out, l0);
+                                                       k_total, idx_out, l0, clear_from, l0 == 0 ? clear_words : 0);
     }
     mark(4);
     if (k_total > 0)
@@ -352,13 +359,17 @@ void launch_update_reduce(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_learne
 // The exact selection on one vector x = fma(lr, grad, mem) (Eq. 2): every kernel from the first
 // look at the vector to the output slot of every wave tile.  Leaves the membership mask, the
 // tile slots and the threshold behind.  `preds` holds one bucket prediction per segment (read and
-// rewritten).  Uses one copy of the scratch zone and leaves the other one cleared.
+// rewritten), `stats` the context's selection counters (null: nothing is counted).  Expects the scratch zone zeroed (clears it first if the context says it is not) and
+// leaves it used: nothing reads the zone after this function's last kernel, and the caller has
+// it cleared (the all-learner pass does that on the way, see launch_update_reduce), or, with
+// `clear_after`, a clearing kernel is enqueued here.
 template <typename G, typename Mark>
 void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float lr, int n_tensors, uint32_t* preds,
-                   uint32_t* lead_mine, Mark&& mark)
+                   uint32_t* lead_mine, unsigned long long* stats, bool clear_after, Mark&& mark)
 {
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
+    hipStream_t s = ctx->stream;
     const SegDesc* segs = reinterpret_cast<const SegDesc*>(ws + l.segs);
     const StDesc* sts = reinterpret_cast<const StDesc*>(ws + l.sts);
     const ChunkDesc* chunks = reinterpret_cast<const ChunkDesc*>(ws + l.chunks);
@@ -367,7 +378,7 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     SegState* state0 = reinterpret_cast<SegState*>(ws + l.state);
     SegState* state1 = &state_at(state0, static_cast<size_t>(ctx->n_tensors_max));
     SegState* state = &state_at(state1, static_cast<size_t>(ctx->n_tensors_max));   // what the kernels after the search read
-    char* zone = ws + l.zone[ctx->parity];
+    char* zone = ws + l.zone;
     uint32_t* overflow = reinterpret_cast<uint32_t*>(zone + l.z_overflow);
     uint32_t* p_used = reinterpret_cast<uint32_t*>(zone + l.z_p_used);
     uint32_t* full_flag = reinterpret_cast<uint32_t*>(zone + l.z_full_flag);
@@ -376,8 +387,11 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     uint32_t* hist1 = reinterpret_cast<uint32_t*>(zone + l.z_hist1);
     uint32_t* hist1_spec = reinterpret_cast<uint32_t*>(zone + l.z_hist1_spec);
     uint32_t* hist2 = reinterpret_cast<uint32_t*>(zone + l.z_hist2);
-    uint32_t* next_zone = reinterpret_cast<uint32_t*>(ws + l.zone[ctx->parity ^ 1]);
     const size_t zone_words = l.zone_bytes / sizeof(uint32_t);
+    auto clear_zone = [&]() {
+        const int grid = static_cast<int>(std::min<size_t>((zone_words + kBlock - 1) / kBlock, 4096));
+        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(zone), zone_words);
+    };
     uint32_t* wt_cnt = reinterpret_cast<uint32_t*>(ws + l.wt_cnt);
     uint2* st_sum = reinterpret_cast<uint2*>(ws + l.st_sum);
     uint2* st_prefix = reinterpret_cast<uint2*>(ws + l.st_prefix);
@@ -387,26 +401,21 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
     uint64_t* eq_mask = reinterpret_cast<uint64_t*>(ws + l.eq_mask);
     uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
-    hipStream_t s = ctx->stream;
     const int n_st = ctx->n_st;
 
-    if (!ctx->scratch_clean) {   // first step, new layout, or a failed step: clear both scratch copies
-        const size_t words = 2 * zone_words;   // the two copies are adjacent
-        const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
-        k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.zone[0]), words);
-    }
+    if (!ctx->scratch_clean) clear_zone();  // first step, new layout, or a step that failed half-way
     const int hgrid = ctx->n_hblocks;       // one block per entry of the block table
-    ctx->scratch_clean = false;             // until every kernel of this selection has been enqueued
+    ctx->scratch_clean = false;             // until the zone has been cleared again
     k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
-                                           part, overflow, p_used, hist1_spec, lead_mine, next_zone, zone_words);
+                                           part, overflow, p_used, hist1_spec, lead_mine);
     k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, hist0, preds, p_used, part, overflow,
-                                         hist1_spec, lead_mine, wt_cnt, sel_mask, eq_mask, st_sum);
+                                         hist1_spec, lead_mine, wt_cnt, sel_mask, eq_mask, st_sum, stats);
     mark(1);
     const CollectOut collect_out{wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt, full_flag};
     k_level<G, 1><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, state1, hist0, hist1, preds, lead_mine,
-                                           collect_out);
+                                           collect_out, stats);
     k_level<G, 2><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state1, state, hist1, hist2, preds, lead_mine,
-                                           collect_out);
+                                           collect_out, stats);
     mark(2);
     k_tilecount<G><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2, wt_cnt,
                                                                    cand, st_cand_cnt, sel_mask, eq_mask, st_sum);
@@ -419,9 +428,9 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
         k_slots<false><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_sum, st_prefix,
                                                                        chunk_tot, sel_mask, eq_mask, tile_slot);
     }
-    if (hipPeekAtLastError() == hipSuccess) {   // the copy for the next selection was cleared by this one
-        ctx->parity ^= 1;
-        ctx->scratch_clean = true;
+    if (clear_after) {
+        clear_zone();
+        if (hipPeekAtLastError() == hipSuccess) ctx->scratch_clean = true;
     }
 }
 
@@ -443,13 +452,16 @@ scalecom_status launch_step(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_lear
         uint32_t* lead_mine = preds + (static_cast<size_t>(kPredWords) + static_cast<size_t>(leader)) *
                                           static_cast<size_t>(ctx->n_tensors_max);
         launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, lead_mine,
-                         mark);
+                         reinterpret_cast<unsigned long long*>(ctx->ws + ctx->lay.stats), false, mark);
         mark(3);
-        launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
+        launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out,
+                                reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.zone), ctx->lay.zone_bytes / sizeof(uint32_t),
+                                mark);
         mark(5);
         if (timed) ++ctx->prof_steps;
     }
     SC_HIP(ctx, hipGetLastError());
+    ctx->scratch_clean = true;               // the all-learner pass has left the scratch zone zeroed
     return SCALECOM_OK;
 }
 
@@ -462,10 +474,7 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     char* ws = ctx->ws;
     const WsLayout& l = ctx->lay;
     hipStream_t s = ctx->stream;
-    unsigned long long* best =
-        reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity) * ctx->k_max;
-    unsigned long long* best_next =
-        reinterpret_cast<unsigned long long*>(ws + l.best) + static_cast<size_t>(ctx->best_parity ^ 1) * ctx->k_max;
+    unsigned long long* best = reinterpret_cast<unsigned long long*>(ws + l.best);
     uint64_t* sel_mask = reinterpret_cast<uint64_t*>(ws + l.sel_mask);
     uint32_t* tile_slot = reinterpret_cast<uint32_t*>(ws + l.tile_slot);
     const SegDesc* segs = reinterpret_cast<const SegDesc*>(ws + l.segs);
@@ -480,11 +489,10 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         return dim3(gx, static_cast<unsigned>((blocks + gx - 1) / gx));
     };
     mark(0);
-    if (!ctx->best_clean) {             // first chunked step of this context, or one failed before: clear both copies
-        const size_t words = 4 * static_cast<size_t>(ctx->k_max);   // 2 copies x 2 words per entry
+    if (!ctx->best_clean) {             // first chunked step of this context, or one that failed half-way
+        const size_t words = 2 * static_cast<size_t>(ctx->k_max);   // 2 words per entry
         const int grid = static_cast<int>(std::min<size_t>((words + kBlock - 1) / kBlock, 4096));
         k_init<<<grid, kBlock, 0, s>>>(reinterpret_cast<uint32_t*>(ws + l.best), words);
-        ctx->best_used[0] = ctx->best_used[1] = 0;
     }
     ctx->best_clean = false;
     const int64_t n_tiles = static_cast<int64_t>(ctx->n_st) * kTilesPerSuper;
@@ -492,18 +500,15 @@ scalecom_status launch_chunked(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
                                                                  segs, sts, ctx->n_st, best, sel_mask);
     mark(1);
     mark(2);
-    // the other copy still holds what its last use wrote (possibly more entries than this call has)
-    const int64_t clear_next = ctx->best_used[ctx->best_parity ^ 1];
-    k_chunk_marks<<<grid2((std::max({n_tiles, k_total, clear_next}) + kBlock - 1) / kBlock), kBlock, 0, s>>>(
-        segs, n_tensors, sts, best, best_next, clear_next, k_total, n_tiles, sel_mask, tile_slot, idx_out);
+    k_chunk_marks<<<grid2((std::max(n_tiles, k_total) + kBlock - 1) / kBlock), kBlock, 0, s>>>(
+        segs, n_tensors, sts, best, k_total, n_tiles, sel_mask, tile_slot, idx_out);
     mark(3);
-    launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, mark);
+    // nothing reads the per-chunk maxima any more: the all-learner pass zeroes this call's entries on the way
+    launch_update_reduce<G>(ctx, lp, n_learners, k_total, beta, lr, idx_out, red_out, reinterpret_cast<uint32_t*>(best),
+                            2 * static_cast<size_t>(k_total), mark);
     mark(5);
     if (timed) ++ctx->prof_steps;
     SC_HIP(ctx, hipGetLastError());
-    ctx->best_used[ctx->best_parity] = k_total;
-    ctx->best_used[ctx->best_parity ^ 1] = 0;
-    ctx->best_parity ^= 1;
     ctx->best_clean = true;
     return SCALECOM_OK;
 }
@@ -618,8 +623,8 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     if (ctx->n_st > 0) {
         // the leader's index set (Eq. 3)
         k_init<<<1, kBlock, 0, s>>>(preds, kPredWords * static_cast<size_t>(n_tensors));
-        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, nullptr,
-                         no_mark);
+        launch_select<G>(ctx, lp.mem[leader], static_cast<const G*>(lp.grad[leader]), lr, n_tensors, preds, nullptr, nullptr,
+                         true, no_mark);
         SC_HIP(ctx, hipMemcpyAsync(mask_a, sel_mask, mask_bytes, hipMemcpyDeviceToDevice, s));
         // the top-k of the summed error-feedback gradients
         const int64_t blocks = (end - begin + kBlock - 1) / kBlock;
@@ -627,7 +632,8 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
         const dim3 grid(gx, static_cast<unsigned>((blocks + gx - 1) / gx));
         k_sum_x<G><<<grid, kBlock, 0, s>>>(lp, n_learners, lr, begin, end, y);
         k_init<<<1, kBlock, 0, s>>>(preds, kPredWords * static_cast<size_t>(n_tensors));
-        launch_select<NoGrad>(ctx, y, static_cast<const NoGrad*>(nullptr), 0.0f, n_tensors, preds, nullptr, no_mark);
+        launch_select<NoGrad>(ctx, y, static_cast<const NoGrad*>(nullptr), 0.0f, n_tensors, preds, nullptr, nullptr, true,
+                              no_mark);
         k_mask_overlap<<<(ctx->n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(sts, ctx->n_st, mask_a, sel_mask, d_out);
     }
     SC_HIP(ctx, hipGetLastError());
@@ -842,6 +848,31 @@ scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* s
     if (gy > 65535) return fail(ctx, SCALECOM_EINVAL, "copy too large");
     k_copy<<<dim3(gx, gy), kBlock, 0, ctx->stream>>>(static_cast<const vf4_t*>(src), static_cast<vf4_t*>(dst), n16);
     SC_HIP(ctx, hipGetLastError());
+    return SCALECOM_OK;
+}
+
+scalecom_status scalecom_selection_stats(scalecom_ctx* ctx, uint64_t* counts_out, int reset)
+{
+    static_assert(SCALECOM_N_STATS <= kStatWords && SCALECOM_STAT_MISSED == kStatMissed &&
+                      SCALECOM_STAT_NO_PREDICTION == kStatNoPrediction && SCALECOM_STAT_FULL_MODE == kStatFullMode &&
+                      SCALECOM_STAT_WIDE_RANGE == kStatWideRange && SCALECOM_STAT_STEPS == kStatSteps,
+                  "the header's indices are the kernels'");
+    if (!ctx) return SCALECOM_EINVAL;
+    ctx->last_error.clear();
+    if (!counts_out) return fail(ctx, SCALECOM_EINVAL, "null argument");
+    for (int j = 0; j < SCALECOM_N_STATS; ++j) counts_out[j] = 0;
+    if (!ctx->stats_ready) return SCALECOM_OK;              // no step yet: the counters were never started
+    DeviceGuard guard;
+    SC_HIP(ctx, guard.enter(ctx->device));
+    SC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    unsigned long long host[kStatWords];
+    SC_HIP(ctx, hipMemcpy(host, ctx->ws + ctx->lay.stats, sizeof host, hipMemcpyDeviceToHost));
+    for (int j = 0; j < SCALECOM_N_STATS; ++j) counts_out[j] = host[j];
+    if (reset) {
+        k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.stats),
+                                              kStatWords * sizeof(unsigned long long) / sizeof(uint32_t));
+        SC_HIP(ctx, hipGetLastError());
+    }
     return SCALECOM_OK;
 }
 

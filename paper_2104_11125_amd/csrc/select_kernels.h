@@ -207,19 +207,13 @@ k_predicted(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
             uint32_t* __restrict__ st_cand_cnt, const uint32_t* __restrict__ preds, uint32_t* __restrict__ wt_cnt,
             uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ part,
             uint32_t* __restrict__ overflow, uint32_t* __restrict__ p_used, uint32_t* __restrict__ hist1_spec,
-            const uint32_t* __restrict__ lead_mine, uint32_t* __restrict__ next_scratch, size_t next_words)
+            const uint32_t* __restrict__ lead_mine)
 {
-    // The counters and histograms of a step live in one of two copies of a scratch zone; this
-    // kernel, the first of a step, clears the copy the NEXT step will use (nothing else touches it
-    // during this step), so no step needs a separate clearing pass.
-    for (size_t i = blockIdx.x * static_cast<size_t>(kBlock) + threadIdx.x; i < next_words;
-         i += static_cast<size_t>(gridDim.x) * kBlock)
-        next_scratch[i] = 0u;
-
     const int st = blockIdx.x;
     const StDesc d = sts[st];
     const uint32_t* pred = preds + static_cast<size_t>(d.seg) * kPredWords;
-    const uint32_t have = pred[0], w = pred[2];
+    const uint32_t have = pred[0];
+    const uint32_t w = clamp_width(pred[2]);                // (whatever the memory holds, the counts stay in their words)
     const uint32_t t24 = predicted_t24(pred, lead_mine, d.seg);
     const SegDesc sd = segs[d.seg];
     if (have == 0 || sd.k == 0 || sd.st_count == 1) return;   // (one supertile: k_level0 searches it directly)
@@ -591,7 +585,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
          uint32_t* __restrict__ preds, const uint32_t* __restrict__ p_used, const uint32_t* __restrict__ part,
          const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec, uint32_t* __restrict__ lead_mine,
          uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
-         uint2* __restrict__ st_sum)
+         uint2* __restrict__ st_sum, unsigned long long* __restrict__ stats)
 {
     __shared__ uint32_t lh[kBins0];
     __shared__ uint32_t tot_s[kPartWords];
@@ -604,11 +598,12 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     const HistBlock hb = hblocks[blockIdx.x];
     const int cur = hb.seg;
     const bool owner = hb.owner != 0;                       // this block writes the segment's state
+    if (stats && blockIdx.x == 0 && t == 0) atomicAdd(&stats[kStatSteps], 1ull);
     // everything the segment number addresses is requested at once
     const uint32_t* my_part = part + static_cast<size_t>(cur) * kPartSlots * kPartWords;
     const SegDesc sd = segs[cur];
     const uint32_t* used = p_used + static_cast<size_t>(cur) * kPredWords;
-    const uint32_t have = used[0], base = used[1], w = used[2];
+    const uint32_t have = used[0], base = used[1], w = clamp_width(used[2]);
     const uint32_t ov = overflow[cur];
     const uint32_t w0 = my_part[t], w1 = my_part[kBlock + t];
     const uint32_t k = static_cast<uint32_t>(sd.k);
@@ -676,6 +671,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
                 // a wide range's bins leave sh - 7 bits to level 1, which counts them on the listed keys
                 s.l1_done = sh == kBits2 ? 1u : 0u;
                 s.l1_bits = sh - kBits2;
+                if (stats && sh != kBits2) atomicAdd(&stats[kStatWideRange], 1ull);
                 uint32_t calm = used[3];
                 const uint32_t w_next =
                     next_width(w, res[0], in_range, k, static_cast<uint64_t>(sd.st_count) * kCandSlice, calm);
@@ -734,6 +730,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         s.pending = 1;                                      // the next kernel's blocks search the histogram
         state_at(state, cur) = s;
         pred[0] = 0u;                                       // until the levels that follow have found the threshold
+        if (stats) atomicAdd(&stats[have != 0 ? kStatMissed : kStatNoPrediction], 1ull);
     }
 }
 
@@ -769,7 +766,7 @@ __global__ void __launch_bounds__(kBlock)
 k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
         const HistBlock* __restrict__ hblocks, const SegState* __restrict__ state_in, SegState* __restrict__ state_out,
         const uint32_t* __restrict__ hist_prev, uint32_t* __restrict__ hist, uint32_t* __restrict__ preds,
-        uint32_t* __restrict__ lead_mine, CollectOut out)
+        uint32_t* __restrict__ lead_mine, CollectOut out, unsigned long long* __restrict__ stats)
 // in candidate mode out.cand and out.st_cand_cnt are read, when collecting they are written
 {
     static_assert(LEVEL == 1 || LEVEL == 2, "level 0 is k_level0");
@@ -789,7 +786,8 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     const uint32_t went_full = LEVEL == 2 ? out.full_flag[cur] : 0u;
     if (went_full) ss.mode = kModeFull;
 
-    const uint32_t l1_bits = ss.l1_bits;                    // 12, or what a wide range's counts left open
+    // 12, or what a wide range's counts left open (never more than 12: the counters are kBins1 words)
+    const uint32_t l1_bits = ss.l1_bits < static_cast<uint32_t>(kBits1) ? ss.l1_bits : static_cast<uint32_t>(kBits1);
     auto count = [&](uint32_t key, uint32_t prefix) {
         if (LEVEL == 1) {
             if ((key >> (l1_bits + kBits2)) == prefix) atomicAdd(&lh[(key >> kBits2) & ((1u << l1_bits) - 1u)], 1u);
@@ -855,6 +853,7 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
     __syncthreads();
     const uint32_t prefix = ss.prefix;
     const bool from_list = ss.mode == kModeCand;
+    if (LEVEL == 2 && stats && owner && t == 0 && !from_list) atomicAdd(&stats[kStatFullMode], 1ull);
     const bool collect = LEVEL == 1 && from_list && ss.collected == 0;
     const int64_t begin = hb.begin, end = hb.end;
     if (from_list && !collect) {

@@ -84,12 +84,20 @@ template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_update(LearnerPtrs lp, float lr, float beta, float one_minus_beta, const StDesc* __restrict__ sts, int n_st,
          const uint64_t* __restrict__ sel_mask, const uint32_t* __restrict__ tile_slot, float* __restrict__ vals,
-         int64_t k_total, int32_t* __restrict__ idx_out, int learner0)
+         int64_t k_total, int32_t* __restrict__ idx_out, int learner0, uint32_t* __restrict__ clear_from,
+         size_t clear_words)
 {
     // grid = (learners, groups of 4 wave tiles split over y and z): x runs fastest, so blocks that
     // are scheduled together work on the same positions of different learners
     const int learner = learner0 + blockIdx.x;
     const int group = blockIdx.y + blockIdx.z * gridDim.y;
+    // The selection's per-step counters and histograms have been read for the last time before this
+    // kernel starts; the blocks of its first learner zero them on the way, so that the next step finds
+    // them clean and no step pays for a clearing launch.
+    if (clear_words != 0 && blockIdx.x == 0) {              // block-uniform
+        const size_t stride = static_cast<size_t>(gridDim.y) * gridDim.z * kBlock;
+        for (size_t i = static_cast<size_t>(group) * kBlock + threadIdx.x; i < clear_words; i += stride) clear_from[i] = 0u;
+    }
     const int st = group / kUpdateBlocksPerSuper;
     if (st >= n_st) return;                                 // padding of the 3-d grid (whole block)
     // the wave's index is the same in all of its lanes: say so, and everything derived from it

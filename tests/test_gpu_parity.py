@@ -153,6 +153,7 @@ def test_bucket_keys_clustered_in_one_place(gu):
     ref = [np.zeros(numel, np.float32) for _ in range(n)]
     for step in range(3):                       # leaders: ascending, descending, random
         gu.compare_step(ctx, mem, grad, ref, step, 0.5, 1.0, k=numel // 100, what="clustered")
+    assert ctx.scalecom_selection_stats()["full_mode"] >= 1      # the sorted leaders did take the full passes
     ctx.close()
 
 
@@ -171,6 +172,43 @@ def test_threshold_jumps_between_steps(gu):
         grad = [g * sc for g in base]
         lr = 0.1 if step % 5 else 1.0
         gu.compare_step(ctx, mem, grad, ref, step, 0.5, lr, k=w.k, what=f"scale {sc}")
+    ctx.close()
+
+
+def test_selection_stats_count_misses(gu):
+    """The device counters behind scalecom_selection_stats: the first step of a layout has no
+    prediction, a gradient scale that jumps by 100 is a sure miss (the widest range spans two
+    binades), and a step repeated on the same inputs from the same state must hit the third time
+    (the leader's own last threshold is the centre of its range).  Results are compared as ever."""
+    w = workloads.scaled(workloads.by_name("resnet50_sized"), 300_007, n_learners=3, steps=1)
+    ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, 1, gu.DEV)
+    assert ctx.scalecom_selection_stats() == {"missed": 0, "no_prediction": 0, "full_mode": 0, "wide_range": 0, "steps": 0}
+    mem = workloads.zero_memories(w, gu.DEV)
+    ref = [m.cpu().numpy().copy() for m in mem]
+    base = workloads.gradients(w, 0, gu.DEV)
+    seen = []
+    for step, sc in enumerate([1.0, 1.0, 100.0]):
+        gu.compare_step(ctx, mem, [g * sc for g in base], ref, step, 0.5, 0.1, k=w.k, what=f"scale {sc}")
+        seen.append(ctx.scalecom_selection_stats())
+    assert [s["steps"] for s in seen] == [1, 2, 3]
+    assert [s["no_prediction"] for s in seen] == [1, 1, 1]
+    assert seen[0]["missed"] == 0 and seen[2]["missed"] == seen[1]["missed"] + 1          # the jump
+    # the same step three times from the same state
+    mem0, ref0 = [m.clone() for m in mem], [r.copy() for r in ref]
+    for rep in range(3):
+        for m, m0, r, r0 in zip(mem, mem0, ref, ref0):
+            m.copy_(m0)
+            r[:] = r0
+        gu.compare_step(ctx, mem, base, ref, 3, 0.5, 0.1, k=w.k, what=f"repeat {rep}")
+        seen.append(ctx.scalecom_selection_stats())
+    assert seen[-1]["steps"] == 6 and seen[-1]["missed"] == seen[-2]["missed"]            # third time: a hit
+    assert seen[-1]["no_prediction"] == 1
+    # a diagnostic selection is not a step and counts nothing; reset starts again from zero
+    ctx.scalecom_hamming_distance(mem, base, [0, w.numel], [w.k], 0.1, 0)
+    assert ctx.scalecom_selection_stats(reset=True)["steps"] == 6
+    gu.compare_step(ctx, mem, base, ref, 4, 0.5, 0.1, k=w.k, what="after reset")
+    after = ctx.scalecom_selection_stats()
+    assert after["steps"] == 1 and after["no_prediction"] == 0      # same layout: the diagnostic left the predictions alone
     ctx.close()
 
 
