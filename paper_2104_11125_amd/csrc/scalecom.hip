@@ -72,14 +72,14 @@ namespace {
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+constexpr size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-inline int64_t max_supertiles(int64_t numel_max, int n_tensors_max)
+constexpr int64_t max_supertiles(int64_t numel_max, int n_tensors_max)
 {
     return numel_max / kSuper + 2 * static_cast<int64_t>(n_tensors_max) + 2;
 }
 
-inline int64_t max_chunks(int64_t numel_max, int n_tensors_max)
+constexpr int64_t max_chunks(int64_t numel_max, int n_tensors_max)
 {
     return max_supertiles(numel_max, n_tensors_max) / kChunk + static_cast<int64_t>(n_tensors_max) + 1;
 }
@@ -91,7 +91,7 @@ struct WsLayout {
     size_t zone, zone_bytes, z_overflow, z_p_used, z_full_flag, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
 };
 
-WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
+constexpr WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learners_max, int64_t k_max)
 {
     const size_t nt = static_cast<size_t>(n_tensors_max);
     const size_t nst = static_cast<size_t>(max_supertiles(numel_max, n_tensors_max));

@@ -689,24 +689,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         return;
     }
 
-    // The width of the next step's range, once the levels that follow have found the threshold: the
-    // widest, or if this step had a range that missed, the widest that would have held at most half
-    // of what the candidate list can take (the density around the threshold changes slowly).
-    s.w_next = kSpecBitsMax;
-    if (have != 0) {
-        const uint64_t half = static_cast<uint64_t>(sd.st_count) * kCandSlice / 2;
-        uint64_t would = tot_s[1];                          // keys the missed range held, of width w
-        uint32_t fit = w;
-        while (would > half && fit > kSpecBitsMin) {
-            would >>= 1;
-            --fit;
-        }
-        while (2 * would <= half && fit < kSpecBitsWide) {
-            would <<= 1;
-            ++fit;
-        }
-        s.w_next = fit;
-    }
+    s.w_next = kSpecBitsMax;                                // (the search of this histogram chooses it)
     // no prediction, or one that failed: count the top digits of my part of the segment
     for (int b = t; b < kBins0; b += kBlock) lh[b] = 0u;
     __syncthreads();
@@ -829,6 +812,20 @@ k_level(const float* __restrict__ mem, const G* __restrict__ grad, float lr, con
                 // the bucket's keys go to the candidate list if its slots can hold them
                 const uint64_t slots = static_cast<uint64_t>(st_count) * kCandSlice;
                 ss.mode = res[3] <= slots ? kModeCand : kModeFull;
+                // The width of the next step's range: the widest that would hold at most half of what the
+                // candidate list can take, judged by how many keys the threshold's bucket of 2^19 keys holds
+                // (the range will lie around the same threshold, and the density there changes slowly).
+                uint64_t would = res[3];
+                uint32_t fit = kSpecBitsMax;
+                while (would > slots / 2 && fit > static_cast<uint32_t>(kSpecBitsMin)) {
+                    would >>= 1;
+                    --fit;
+                }
+                while (2 * would <= slots / 2 && fit < static_cast<uint32_t>(kSpecBitsWide)) {
+                    would <<= 1;
+                    ++fit;
+                }
+                ss.w_next = fit;
             } else if (owner && t == 0) {
                 uint32_t* pred = preds + static_cast<size_t>(cur) * kPredWords;
                 if (ss.collected == 0) {                    // no prediction held in this step: one for the next
