@@ -120,6 +120,32 @@ scalecom_status scalecom_step(scalecom_ctx* ctx, float* const* mem, const void* 
                               int32_t* idx_out, float* reduced_vals_out);
 
 /*
+ * scalecom_step for callers that cannot allocate device memory or pass a workspace along: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  No context and
+ * no workspace argument: the scratch memory is a static device array inside the library
+ * (about 8.5 MB, held by every GPU the library is used on until the process ends), which bounds
+ * the sizes: numel <= SCALECOM_STATIC_NUMEL_MAX, n_learners <= SCALECOM_STATIC_LEARNERS_MAX,
+ * k <= SCALECOM_STATIC_K_MAX; anything larger is EINVAL (the detail names the limit) and belongs
+ * to scalecom_step.  The call allocates nothing, on the device or through any library: it looks up
+ * the array's address once per device (first call), then only enqueues kernels on hip_stream.
+ * Same operation, arithmetic and results as scalecom_step, bit for bit.
+ *   device           HIP device ordinal (0 .. 63) that owns every buffer
+ *   hip_stream       hipStream_t on that device, as void* (NULL = the default stream)
+ *   grad_dtype       element type of the grad buffers of this call
+ *   all other arguments as for scalecom_step
+ * All calls on one GPU share that GPU's array, which also carries the threshold predictions
+ * from one call to the next (they are dropped when numel, k or grad_dtype change): calls on one
+ * GPU must not overlap -- enqueue them on one stream, or order the streams yourself -- or they
+ * race.  The detail of a failure is scalecom_last_error(NULL) on the calling thread.
+ */
+#define SCALECOM_STATIC_NUMEL_MAX 4194304
+#define SCALECOM_STATIC_LEARNERS_MAX 8
+#define SCALECOM_STATIC_K_MAX 131072
+scalecom_status scalecom_step_static(int device, void* hip_stream, float* const* mem, const void* const* grad,
+                                     int n_learners, int64_t numel, int64_t k, float beta, float lr, int64_t step,
+                                     scalecom_grad_dtype grad_dtype, int32_t* idx_out, float* reduced_vals_out);
+
+/*
  * One iteration with a separate index set per tensor (per-layer compression rates, Sec. 4):
  * each learner's vector is cut into n_tensors consecutive segments
  * [offsets[s], offsets[s+1]), and segment s gets the ks[s] largest-magnitude positions of
@@ -302,7 +328,8 @@ scalecom_status scalecom_stream_copy(scalecom_ctx* ctx, void* dst, const void* s
 /* Static text for a status code. */
 const char* scalecom_strerror(scalecom_status status);
 
-/* Detail of the last failure on this context ("" if none); valid until the next call on it. */
+/* Detail of the last failure on this context ("" if none); valid until the next call on it.
+ * With NULL: of the calling thread's last scalecom_step_static. */
 const char* scalecom_last_error(const scalecom_ctx* ctx);
 
 /* Waits for the context's stream, frees the context's host memory.  NULL is allowed. */

@@ -19,6 +19,7 @@ SCALECOM_GRAD_F32, SCALECOM_GRAD_BF16 = 0, 1
 SCALECOM_MAX_LEARNERS = 64
 SCALECOM_N_PHASES = 5
 SCALECOM_N_STATS = 5
+SCALECOM_STATIC_NUMEL_MAX, SCALECOM_STATIC_LEARNERS_MAX, SCALECOM_STATIC_K_MAX = 4_194_304, 8, 131_072
 
 _lib = None
 
@@ -45,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.scalecom_init.restype = i32
         L.scalecom_step.argtypes = [vp, vp, vp, i32, i64, i64, f32, f32, i64, vp, vp]
         L.scalecom_step.restype = i32
+        L.scalecom_step_static.argtypes = [i32, vp, vp, vp, i32, i64, i64, f32, f32, i64, i32, vp, vp]
+        L.scalecom_step_static.restype = i32
         L.scalecom_step_chunked.argtypes = [vp, vp, vp, i32, i64, i64, f32, f32, i64, vp, vp]
         L.scalecom_step_chunked.restype = i32
         L.scalecom_step_layers.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, f32, i64, vp, vp]
@@ -102,6 +105,33 @@ def scalecom_layer_ks(flops_per_gradient: Sequence[float], sizes: Sequence[int],
     if st != SCALECOM_OK:
         raise ScaleComError(st)
     return list(c_k), list(c_rate)
+
+
+def scalecom_step_static(mem: Sequence[torch.Tensor], grad: Sequence[torch.Tensor], k: int, beta: float, lr: float,
+                         step: int, idx_out: torch.Tensor, reduced_vals_out: torch.Tensor,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+    """``scalecom_step_static`` of the C-ABI: no context, no workspace, nothing allocated (so the
+    outputs must be passed in).  Marshalling only; sizes beyond the static limits raise."""
+    dev = mem[0].device
+    numel = mem[0].numel()
+    for m, g in zip(mem, grad):
+        if m.dtype != torch.float32 or g.dtype not in (torch.float32, torch.bfloat16) or g.dtype != grad[0].dtype:
+            raise TypeError("mem must be float32 and grad float32 or bfloat16")
+        if not (m.is_contiguous() and g.is_contiguous() and m.device == dev and g.device == dev):
+            raise ValueError("buffers must be contiguous tensors on one device")
+        if m.numel() != numel or g.numel() != numel:
+            raise ValueError("every learner's mem and grad must have the same number of elements")
+    if idx_out.dtype != torch.int32 or reduced_vals_out.dtype != torch.float32 or \
+            idx_out.numel() < k or reduced_vals_out.numel() < k:
+        raise TypeError("idx_out must be int32[k] and reduced_vals_out float32[k]")
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    index = dev.index if dev.index is not None else torch.cuda.current_device()
+    st = lib().scalecom_step_static(index, ctypes.c_void_p(s.cuda_stream), _ptrs(mem), _ptrs(grad), len(mem), numel, k,
+                                    beta, lr, step,
+                                    SCALECOM_GRAD_BF16 if grad[0].dtype == torch.bfloat16 else SCALECOM_GRAD_F32,
+                                    ctypes.c_void_p(idx_out.data_ptr()), ctypes.c_void_p(reduced_vals_out.data_ptr()))
+    if st != SCALECOM_OK:
+        raise ScaleComError(st, lib().scalecom_last_error(None).decode())
 
 
 class ScaleCom:

@@ -54,6 +54,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -640,6 +641,56 @@ scalecom_status launch_hamming(scalecom_ctx* ctx, const LearnerPtrs& lp, int n_l
     return SCALECOM_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// scalecom_step_static: the whole-vector step for callers that cannot allocate device memory.
+// Its workspace is a static device array of the library, one copy per GPU, laid out like a
+// caller's workspace for the largest sizes the entry point accepts.
+// ------------------------------------------------------------------------------------------
+constexpr int64_t kStaticNumelMax = SCALECOM_STATIC_NUMEL_MAX;
+constexpr int kStaticLearnersMax = SCALECOM_STATIC_LEARNERS_MAX;
+constexpr int64_t kStaticKMax = SCALECOM_STATIC_K_MAX;
+constexpr WsLayout kStaticLayout = layout_for(kStaticNumelMax, 1, kStaticLearnersMax, kStaticKMax);
+constexpr size_t kStaticBytes = kStaticLayout.total;
+static_assert(kStaticBytes <= (size_t{16} << 20), "the static workspace stays modest");
+
+// In host code this name is only a handle for hipGetSymbolAddress: it is not a device address.
+static __device__ __align__(256) unsigned char static_scratch[kStaticBytes];
+
+constexpr int kStaticDevicesMax = 64;
+struct StaticSlot {                 // host side of one GPU's static workspace
+    std::mutex lock;                // the host state below; the GPU work of two calls is ordered by the caller
+    char* ptr = nullptr;            // device address of this GPU's copy of static_scratch
+    scalecom_ctx ctx;               // a context without staging memory: its tables are built on the device
+    int64_t numel = -1, k = -1;     // the layout whose tables and predictions the workspace holds
+    int gdt = -1;
+};
+StaticSlot g_static[kStaticDevicesMax];
+thread_local std::string g_static_error;   // detail of this thread's last failed scalecom_step_static
+
+scalecom_status static_fail(scalecom_status st, const std::string& msg)
+{
+    g_static_error = msg;
+    return st;
+}
+
+// The tables of a whole-vector layout (one segment [0, numel) with an index set of k positions),
+// written by the GPU: what ensure_tables builds on the host and uploads for offsets = {0, numel}.
+__global__ void __launch_bounds__(kBlock)
+k_flat_tables(SegDesc* __restrict__ segs, StDesc* __restrict__ sts, ChunkDesc* __restrict__ chunks,
+              HistBlock* __restrict__ hblocks, int32_t numel, int32_t k, int32_t n_st, int32_t n_ch, int32_t per_block,
+              int32_t n_hb)
+{
+    const int32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i == 0) segs[0] = SegDesc{0, numel, k, 0, 0, n_st, 0, n_ch, 0, 0};
+    if (i < n_st) sts[i] = StDesc{0, i * kSuper, 0, numel, k, {0, 0, 0}};
+    if (i < n_ch) chunks[i] = ChunkDesc{0, i * kChunk, n_st - i * kChunk < kChunk ? n_st - i * kChunk : kChunk, 0};
+    if (i < n_hb) {
+        const int32_t lo = i * per_block, hi = lo + per_block < n_st ? lo + per_block : n_st;
+        hblocks[i] = HistBlock{0, lo, hi, i == 0 ? 1 : 0, lo * kSuper, 0, numel, 0};
+    }
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -700,6 +751,95 @@ scalecom_status scalecom_step(scalecom_ctx* ctx, float* const* mem, const void* 
     if (numel < 0 || numel > ctx->numel_max) return fail(ctx, SCALECOM_EINVAL, "numel out of range");
     const int64_t offsets[2] = {0, numel};
     return step_common(ctx, mem, grad, n_learners, 1, offsets, &k, beta, lr, step, idx_out, reduced_vals_out);
+}
+
+scalecom_status scalecom_step_static(int device, void* hip_stream, float* const* mem, const void* const* grad,
+                                     int n_learners, int64_t numel, int64_t k, float beta, float lr, int64_t step,
+                                     scalecom_grad_dtype grad_dtype, int32_t* idx_out, float* reduced_vals_out)
+{
+    g_static_error.clear();
+    if (device < 0 || device >= kStaticDevicesMax) return static_fail(SCALECOM_EINVAL, "device ordinal out of range");
+    if (grad_dtype != SCALECOM_GRAD_F32 && grad_dtype != SCALECOM_GRAD_BF16)
+        return static_fail(SCALECOM_EINVAL, "unknown grad_dtype");
+    if (numel < 0 || numel > kStaticNumelMax)
+        return static_fail(SCALECOM_EINVAL, "numel exceeds SCALECOM_STATIC_NUMEL_MAX (use scalecom_step with a workspace)");
+    if (n_learners < 1 || n_learners > kStaticLearnersMax)
+        return static_fail(SCALECOM_EINVAL, "n_learners exceeds SCALECOM_STATIC_LEARNERS_MAX (use scalecom_step with a workspace)");
+    if (k < 0 || k > numel) return static_fail(SCALECOM_EINVAL, "k must satisfy 0 <= k <= numel");
+    if (k > kStaticKMax)
+        return static_fail(SCALECOM_EINVAL, "k exceeds SCALECOM_STATIC_K_MAX (use scalecom_step with a workspace)");
+    if (!(beta > 0.0f && beta <= 1.0f)) return static_fail(SCALECOM_EINVAL, "beta must satisfy 0 < beta <= 1");
+    if (!std::isfinite(lr)) return static_fail(SCALECOM_EINVAL, "lr must be finite");
+    if (step < 0) return static_fail(SCALECOM_EINVAL, "step must be >= 0");
+    if (!mem || !grad) return static_fail(SCALECOM_EINVAL, "null argument");
+    if (numel == 0) return SCALECOM_OK;                         // nothing to do
+    if (k > 0 && (!idx_out || !reduced_vals_out)) return static_fail(SCALECOM_EINVAL, "null output");
+
+    StaticSlot& slot = g_static[device];
+    std::lock_guard<std::mutex> hold(slot.lock);
+    scalecom_ctx* ctx = &slot.ctx;
+    auto hip_fail = [&](const char* what, hipError_t e) {
+        return static_fail(SCALECOM_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    };
+    DeviceGuard guard;
+    hipError_t e = guard.enter(device);
+    if (e != hipSuccess) return hip_fail("hipSetDevice", e);
+    if (!slot.ptr) {                                            // first call on this GPU: where its copy of the array lives
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, device);
+        if (e != hipSuccess) return hip_fail("hipGetDeviceProperties", e);
+        if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+            return static_fail(SCALECOM_EUNSUPPORTED, "the device is not a gfx950 GPU");
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch));
+        if (e != hipSuccess || !p) return hip_fail("hipGetSymbolAddress(static_scratch)", e);
+        slot.ptr = static_cast<char*>(p);
+        ctx->device = device;
+        ctx->ws = slot.ptr;
+        ctx->n_learners_max = kStaticLearnersMax;
+        ctx->numel_max = kStaticNumelMax;
+        ctx->k_max = kStaticKMax;
+        ctx->n_tensors_max = 1;
+        ctx->lay = kStaticLayout;
+    }
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->gdt = grad_dtype;
+    LearnerPtrs lp;
+    if (check_learners(ctx, mem, grad, n_learners, lp) != SCALECOM_OK) return static_fail(SCALECOM_EINVAL, ctx->last_error);
+
+    if (slot.numel != numel || slot.k != k || slot.gdt != static_cast<int>(grad_dtype)) {
+        // another layout than the last call's: new tables, no predictions, counters and histograms cleared
+        const WsLayout& l = ctx->lay;
+        const int32_t n_st = static_cast<int32_t>((numel + kSuper - 1) / kSuper);
+        const int32_t n_ch = (n_st + kChunk - 1) / kChunk;
+        const int32_t per_block = std::max<int32_t>(1, (n_st + kHistGridMax - 1) / kHistGridMax);
+        const int32_t n_hb = (n_st + per_block - 1) / per_block;
+        k_flat_tables<<<(n_st + kBlock - 1) / kBlock, kBlock, 0, ctx->stream>>>(
+            reinterpret_cast<SegDesc*>(slot.ptr + l.segs), reinterpret_cast<StDesc*>(slot.ptr + l.sts),
+            reinterpret_cast<ChunkDesc*>(slot.ptr + l.chunks), reinterpret_cast<HistBlock*>(slot.ptr + l.hblocks),
+            static_cast<int32_t>(numel), static_cast<int32_t>(k), n_st, n_ch, per_block, n_hb);
+        k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(slot.ptr + l.preds),
+                                              (kPredWords + static_cast<size_t>(kStaticLearnersMax)));
+        k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(slot.ptr + l.stats),
+                                              kStatWords * sizeof(unsigned long long) / sizeof(uint32_t));
+        ctx->stats_ready = true;
+        ctx->scratch_clean = false;                             // the zone is cleared before the selection starts
+        ctx->n_st = n_st;
+        ctx->n_chunks = n_ch;
+        ctx->n_hblocks = n_hb;
+        slot.numel = slot.k = -1;                               // until the step below has been enqueued
+        slot.gdt = -1;
+    }
+    const int leader = static_cast<int>(step % n_learners);    // Alg. 1 line 6: CLT-k of learner mod(t, n)
+    const scalecom_status st =
+        grad_dtype == SCALECOM_GRAD_BF16
+            ? launch_step<uint16_t>(ctx, lp, n_learners, 1, k, beta, lr, leader, idx_out, reduced_vals_out)
+            : launch_step<float>(ctx, lp, n_learners, 1, k, beta, lr, leader, idx_out, reduced_vals_out);
+    if (st != SCALECOM_OK) return static_fail(st, ctx->last_error);
+    slot.numel = numel;
+    slot.k = k;
+    slot.gdt = static_cast<int>(grad_dtype);
+    return SCALECOM_OK;
 }
 
 scalecom_status scalecom_step_chunked(scalecom_ctx* ctx, float* const* mem, const void* const* grad, int n_learners,
@@ -933,7 +1073,7 @@ const char* scalecom_strerror(scalecom_status status)
     return "unknown status";
 }
 
-const char* scalecom_last_error(const scalecom_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }
+const char* scalecom_last_error(const scalecom_ctx* ctx) { return ctx ? ctx->last_error.c_str() : g_static_error.c_str(); }
 
 void scalecom_destroy(scalecom_ctx* ctx)
 {
