@@ -87,6 +87,44 @@ def test_per_layer_chunked_full(gu):
     ctx.close()
 
 
+def _oracle_hamming(gu, mem, grad, offsets, ks, lr, step):
+    """d per tensor from the oracle, one tensor's slices at a time."""
+    out = []
+    for a, b, k in zip(offsets[:-1], offsets[1:], ks):
+        out.append(oracle.hamming_distance([m[a:b].cpu().numpy() for m in mem], [gu.to_host(g[a:b]) for g in grad],
+                                           k, lr, step))
+    return np.array(out, dtype=np.int32)
+
+
+def test_hamming_distance_full(gu):
+    """The similarity diagnostic of Sec. 3 (Eq. 6) at the benchmark's sizes: 8 x 25.6 M elements as
+    one vector, and the 200-tensor layout, each between two ordinary steps whose results are compared
+    too (the diagnostic must leave nothing behind that a step trips over)."""
+    for name, seed in (("resnet50_sized", 980), ("per_layer", 985)):
+        w = workloads.by_name(name)
+        offsets = list(w.offsets) if w.n_tensors > 1 else [0, w.numel]
+        ks = list(w.ks) if w.n_tensors > 1 else [w.k]
+        ctx = binding.scalecom_init(w.numel, w.n_learners, torch.float32, w.n_tensors, gu.DEV, k_max=w.k)
+        mem = _random_memories(w, gu.DEV, seed)
+        ref = [m.cpu().numpy().copy() for m in mem]
+        for step in (0, 1, 2):
+            print(f"[fullsize] {name}: Hamming distance around step {step}", flush=True)
+            grad = workloads.gradients(w, step, gu.DEV)
+            d = ctx.scalecom_hamming_distance(mem, grad, offsets, ks, w.lr, step)
+            torch.cuda.synchronize()
+            if step != 1:                                # (the oracle's two selections take a while at this size)
+                want = _oracle_hamming(gu, mem, grad, offsets, ks, w.lr, step)
+                gu.assert_same("d", d.cpu().numpy(), want, None, f"{name} step {step}")
+                assert 0 < int(d.sum()) < sum(ks)        # similar, not identical, learners
+            if w.n_tensors == 1:
+                gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, k=w.k, what=name + " after the diagnostic")
+            else:
+                gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, offsets=offsets, ks=ks,
+                                what=name + " after the diagnostic")
+            del grad
+        ctx.close()
+
+
 def test_large_multi_tensor_layout(gu):
     """More than 12288 supertiles split over several tensors: the two-level prefix scan (per-chunk
     prefixes and chunk totals of several segments) instead of the slot kernel's own scan, and the
@@ -116,7 +154,7 @@ def _streamed_parity(gu, w, step, seed, chunk=None, second_step=False):
     chunk-wise selector with that many elements per chunk instead of the exact top-k).
     second_step: one more step on the same context, which then works with the prediction the first
     step left, from the memories the ORACLE computed for the first step; its index set, reduced
-    values and the new leader's memory are checked."""
+    values and the memories of the new leader and of two other learners are checked."""
     dev = gu.DEV
     gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
     k_max = w.k if chunk is None else -(-w.numel // chunk)
@@ -170,9 +208,15 @@ def _streamed_parity(gu, w, step, seed, chunk=None, second_step=False):
         gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"{w.name} second step")
         print(f"[fullsize] {w.name}: second selection checked at {time.time() - t0:.0f}s", flush=True)
         vals = []
+        others = {(leader + 1) % w.n_learners, (leader + w.n_learners // 2) % w.n_learners} - {leader}
         for i in range(w.n_learners):
             acc = acc_l if i == leader else oracle.accumulate(ref_after[i], gu.to_host(grad[i]), w.lr)
             vals.append(oracle.gather(acc, want_idx))
+            if i in others:                              # learners that did not lead in either step
+                oracle.memory_update(ref_after[i], acc, want_idx, w.beta)
+                gu.assert_same("mem", mem[i].cpu().numpy(), ref_after[i], 1e-6, f"{w.name} second step, learner {i}")
+                print(f"[fullsize] {w.name}: second step, learner {i} memory checked at {time.time() - t0:.0f}s",
+                      flush=True)
             if i != leader:
                 del acc
         gu.assert_same("reduced", red.cpu().numpy(), oracle.reduce(vals), 1e-5, f"{w.name} second step")
