@@ -86,7 +86,7 @@ constexpr int64_t max_chunks(int64_t numel_max, int n_tensors_max)
 }
 
 struct WsLayout {
-    size_t segs, sts, chunks, hblocks, preds, stats, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask,
+    size_t segs, sts, chunks, hblocks, small, preds, stats, state, wt_cnt, st_sum, st_prefix, chunk_tot, st_cand_cnt, cand, sel_mask,
         eq_mask, tile_slot, vals, best, total;
     // per-step counters and histograms: one zone, all zero between steps (offsets inside the zone)
     size_t zone, zone_bytes, z_overflow, z_p_used, z_full_flag, z_part, z_hist0, z_hist1, z_hist1_spec, z_hist2;
@@ -109,6 +109,7 @@ constexpr WsLayout layout_for(int64_t numel_max, int n_tensors_max, int n_learne
     l.sts = take(nst * sizeof(StDesc));
     l.chunks = take(nch * sizeof(ChunkDesc));
     l.hblocks = take((kHistGridMax + nt) * sizeof(HistBlock));
+    l.small = take(nt * sizeof(HistBlock));              // the segments of one supertile, one block each
     // per segment: the prediction for the next step; then per learner and segment: that leader's last threshold
     l.preds = take((kPredWords + static_cast<size_t>(n_learners_max)) * nt * sizeof(uint32_t));
     l.stats = take(kStatWords * sizeof(unsigned long long));   // what the selections of this context ran into
@@ -166,7 +167,11 @@ struct scalecom_ctx {
     WsLayout lay{};
     // tables of the layout used last, kept on the device until the layout changes
     std::vector<int64_t> cached_offsets, cached_ks, cached_chunks;
-    int n_st = 0, n_chunks = 0, n_hblocks = 0;
+    int n_st = 0, n_chunks = 0, n_hblocks = 0, n_small = 0;
+    // segments of one supertile are searched by a kernel of their own, on a second stream beside the
+    // leader pass (contexts for more than one tensor only)
+    hipStream_t side = nullptr;
+    hipEvent_t fork_ev = nullptr, join_ev = nullptr;
     bool scratch_clean = false;      // true: the scratch zone is all zero (every step leaves it so)
     bool best_clean = false;         // same for the chunk-wise selector's per-chunk maxima
     bool stats_ready = false;        // the selection counters have been zeroed
@@ -221,7 +226,8 @@ size_t pinned_bytes_for(int64_t numel_max, int n_tensors_max)
     return align_up(sizeof(SegDesc) * static_cast<size_t>(n_tensors_max), 256) +
            align_up(sizeof(StDesc) * static_cast<size_t>(max_supertiles(numel_max, n_tensors_max)), 256) +
            align_up(sizeof(ChunkDesc) * static_cast<size_t>(max_chunks(numel_max, n_tensors_max)), 256) +
-           sizeof(HistBlock) * (kHistGridMax + static_cast<size_t>(n_tensors_max));
+           align_up(sizeof(HistBlock) * (kHistGridMax + static_cast<size_t>(n_tensors_max)), 256) +
+           sizeof(HistBlock) * static_cast<size_t>(n_tensors_max);
 }
 
 // Rebuild and upload the segment, supertile, chunk and block tables if the layout differs from the cached one.
@@ -250,6 +256,9 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     ChunkDesc* chunks = reinterpret_cast<ChunkDesc*>(ctx->pinned + ch_off);
     const size_t hb_off = ch_off + align_up(sizeof(ChunkDesc) * static_cast<size_t>(ch_cap), 256);
     HistBlock* hblocks = reinterpret_cast<HistBlock*>(ctx->pinned + hb_off);
+    const size_t sm_off =
+        hb_off + align_up(sizeof(HistBlock) * (kHistGridMax + static_cast<size_t>(ctx->n_tensors_max)), 256);
+    HistBlock* small = reinterpret_cast<HistBlock*>(ctx->pinned + sm_off);
     int64_t n_st = 0, n_ch = 0, out = 0;
     for (int s = 0; s < n_tensors; ++s) {
         const int64_t b = offsets[s], e = offsets[s + 1];
@@ -275,7 +284,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     // blocks of the search levels' kernels: every segment's supertiles in runs of equal length, so
     // that a block never holds supertiles of two segments
     const int64_t per_block = std::max<int64_t>(1, (n_st + kHistGridMax - 1) / kHistGridMax);
-    int64_t n_hb = 0;
+    int64_t n_hb = 0, n_small = 0;
     for (int s = 0; s < n_tensors; ++s) {
         const int64_t first = segs[s].st_first, count = segs[s].st_count;
         for (int64_t j = 0; j < count; j += per_block, ++n_hb)
@@ -287,6 +296,8 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
                                       segs[s].begin,
                                       segs[s].end,
                                       0};
+        // a segment of one supertile with a non-empty index set: searched by one block of k_small
+        if (count == 1 && ks[s] > 0 && ctx->side) small[n_small++] = hblocks[n_hb - 1];
     }
     SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.segs, segs, sizeof(SegDesc) * n_tensors, hipMemcpyHostToDevice,
                                ctx->stream));
@@ -297,6 +308,9 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
                                    ctx->stream));
         SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.hblocks, hblocks, sizeof(HistBlock) * n_hb, hipMemcpyHostToDevice,
                                    ctx->stream));
+        if (n_small > 0)
+            SC_HIP(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.small, small, sizeof(HistBlock) * n_small, hipMemcpyHostToDevice,
+                                       ctx->stream));
     }
     // predictions of the previous layout's buckets mean nothing for this one
     k_init<<<1, kBlock, 0, ctx->stream>>>(reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.preds),
@@ -313,6 +327,7 @@ scalecom_status ensure_tables(scalecom_ctx* ctx, int n_tensors, const int64_t* o
     ctx->n_st = static_cast<int>(n_st);
     ctx->n_chunks = static_cast<int>(n_ch);
     ctx->n_hblocks = static_cast<int>(n_hb);
+    ctx->n_small = static_cast<int>(n_small);
     ctx->cached_offsets.assign(offsets, offsets + n_tensors + 1);
     ctx->cached_ks.assign(ks, ks + n_tensors);
     ctx->cached_chunks = ch;
@@ -407,9 +422,23 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
     if (!ctx->scratch_clean) clear_zone();  // first step, new layout, or a step that failed half-way
     const int hgrid = ctx->n_hblocks;       // one block per entry of the block table
     ctx->scratch_clean = false;             // until the zone has been cleared again
+    const StateCopies states{state0, state1, state};
+    // Segments of one supertile: their blocks take 15-20 us from first load to last store whatever else
+    // runs, so they run beside the leader pass on the context's second stream instead of holding up one
+    // of the short kernels that follow it.  What they write nobody else touches before the join.
+    const bool fork = ctx->n_small > 0 && ctx->side != nullptr;
+    if (fork) {
+        (void)hipEventRecord(ctx->fork_ev, s);
+        (void)hipStreamWaitEvent(ctx->side, ctx->fork_ev, 0);
+        k_small<G><<<ctx->n_small, kBlock, 0, ctx->side>>>(memL, gradL, lr, segs,
+                                                          reinterpret_cast<const HistBlock*>(ws + l.small), states, preds,
+                                                          lead_mine, wt_cnt, sel_mask, eq_mask, st_sum);
+        (void)hipEventRecord(ctx->join_ev, ctx->side);
+    }
     k_predicted<G><<<n_st, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, cand, st_cand_cnt, preds, wt_cnt, sel_mask, eq_mask,
                                            part, overflow, p_used, hist1_spec, lead_mine);
-    k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, state0, hist0, preds, p_used, part, overflow,
+    if (fork) (void)hipStreamWaitEvent(s, ctx->join_ev, 0);
+    k_level0<G><<<hgrid, kBlock, 0, s>>>(memL, gradL, lr, segs, hblocks, states, fork, hist0, preds, p_used, part, overflow,
                                          hist1_spec, lead_mine, wt_cnt, sel_mask, eq_mask, st_sum, stats);
     mark(1);
     const CollectOut collect_out{wt_cnt, sel_mask, eq_mask, cand, st_cand_cnt, full_flag};
@@ -739,6 +768,16 @@ scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, 
     if (hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), ctx->pinned_bytes, hipHostMallocDefault) != hipSuccess)
         return bail(SCALECOM_ENOMEM);
     if (hipEventCreateWithFlags(&ctx->upload_done, hipEventDisableTiming) != hipSuccess) return bail(SCALECOM_EHIP);
+#ifdef SCALECOM_EXPERIMENT_NO_SIDE
+    if (false) {
+#else
+    if (n_tensors_max > 1) {                // (a whole vector of one supertile is handled in the main chain)
+#endif
+        if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming) != hipSuccess)
+            return bail(SCALECOM_EHIP);
+    }
     *out = ctx;
     return SCALECOM_OK;
 }
@@ -1078,10 +1117,16 @@ const char* scalecom_last_error(const scalecom_ctx* ctx) { return ctx ? ctx->las
 void scalecom_destroy(scalecom_ctx* ctx)
 {
     if (!ctx) return;
-    if (ctx->pinned || ctx->upload_done || !ctx->prof_events.empty()) {
+    if (ctx->pinned || ctx->upload_done || ctx->side || !ctx->prof_events.empty()) {
         DeviceGuard guard;
         if (guard.enter(ctx->device) == hipSuccess) {
             (void)hipStreamSynchronize(ctx->stream);
+            if (ctx->side) {
+                (void)hipStreamSynchronize(ctx->side);
+                (void)hipStreamDestroy(ctx->side);
+            }
+            if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
+            if (ctx->join_ev) (void)hipEventDestroy(ctx->join_ev);
             if (ctx->upload_done) (void)hipEventDestroy(ctx->upload_done);
             for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
             if (ctx->pinned) (void)hipHostFree(ctx->pinned);

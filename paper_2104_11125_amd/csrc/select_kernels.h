@@ -430,6 +430,15 @@ __device__ __forceinline__ uint32_t next_width(uint32_t w, uint32_t bin, uint32_
     return w_next;
 }
 
+// The selection state of a segment exists in three copies, one per level of the search: each
+// level's kernel reads the copy the previous one left and the segment's first block writes the
+// next, so no block reads what another block of the same launch wrote.
+struct StateCopies {
+    SegState* level0;
+    SegState* level1;
+    SegState* level2;           // what the tile counts and the slot pass read
+};
+
 // A segment of one supertile (up to 8192 elements; with hundreds of tensors, half of them) is
 // finished by its one block: the threshold is found on the keys the block holds in registers, and
 // the tile counts and masks are written.  No range from the predicted pass: the k-th largest of so
@@ -440,7 +449,7 @@ __device__ __forceinline__ uint32_t next_width(uint32_t w, uint32_t bin, uint32_
 template <typename G>
 __device__ __forceinline__ void select_one_supertile(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
                                                      const HistBlock& hb, uint32_t k, SegState s,
-                                                     SegState* __restrict__ state, uint32_t* __restrict__ pred,
+                                                     const StateCopies& states, uint32_t* __restrict__ pred,
                                                      uint32_t* __restrict__ lead_mine,
                                                      uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask,
                                                      uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum,
@@ -564,7 +573,9 @@ __device__ __forceinline__ void select_one_supertile(const float* __restrict__ m
         s.q = q;
         s.l1_done = 1;
         s.l2_done = 1;
-        state_at(state, cur) = s;
+        state_at(states.level0, cur) = s;               // final: every level's copy (the level kernels pass it by)
+        state_at(states.level1, cur) = s;
+        state_at(states.level2, cur) = s;
         pred[0] = 0u;                                   // no range for the predicted pass ...
         record_t24(pred, lead_mine, cur, T >> kBits2);  // ... but where to look first in the next steps
     }
@@ -581,7 +592,7 @@ __device__ __forceinline__ void select_one_supertile(const float* __restrict__ m
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
-         const HistBlock* __restrict__ hblocks, SegState* __restrict__ state, uint32_t* __restrict__ hist,
+         const HistBlock* __restrict__ hblocks, StateCopies states, bool small_elsewhere, uint32_t* __restrict__ hist,
          uint32_t* __restrict__ preds, const uint32_t* __restrict__ p_used, const uint32_t* __restrict__ part,
          const uint32_t* __restrict__ overflow, const uint32_t* __restrict__ hist1_spec, uint32_t* __restrict__ lead_mine,
          uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask,
@@ -613,6 +624,7 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
     s.T = 0xffffffffu;                                      // above every key: nothing is a member
     s.mode = kModeFull;
     s.l1_bits = kBits1;
+    SegState* state = states.level0;
     if (k == 0) {                                           // block-uniform: an empty index set
         if (owner && t == 0) {
             s.done = 1;
@@ -621,8 +633,10 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         return;
     }
     if (sd.st_count == 1) {                                 // block-uniform
-        select_one_supertile(mem, grad, lr, hb, k, s, state, pred, lead_mine, wt_cnt, sel_mask, eq_mask, st_sum, lh,
-                             tot_s, res, above);
+        // (a context for several tensors has k_small do this beside the leader pass)
+        if (!small_elsewhere)
+            select_one_supertile(mem, grad, lr, hb, k, s, states, pred, lead_mine, wt_cnt, sel_mask, eq_mask, st_sum, lh,
+                                 tot_s, res, above);
         return;
     }
     if (t == 0) flag = 0u;
@@ -715,6 +729,29 @@ k_level0(const float* __restrict__ mem, const G* __restrict__ grad, float lr, co
         pred[0] = 0u;                                       // until the levels that follow have found the threshold
         if (stats) atomicAdd(&stats[have != 0 ? kStatMissed : kStatNoPrediction], 1ull);
     }
+}
+
+// The segments of one supertile with a non-empty index set, one block each (host-built table):
+// select_one_supertile as a kernel of its own, which the host runs beside the leader pass.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_small(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
+        const HistBlock* __restrict__ small, StateCopies states, uint32_t* __restrict__ preds,
+        uint32_t* __restrict__ lead_mine, uint32_t* __restrict__ wt_cnt, uint64_t* __restrict__ sel_mask,
+        uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
+{
+    __shared__ uint32_t lh[kBins0];
+    __shared__ uint32_t tot_s[kPartWords];
+    __shared__ uint32_t res[3];
+    __shared__ uint32_t above[kWaves];
+    const HistBlock hb = small[blockIdx.x];
+    SegState s{};
+    s.k_rem = static_cast<uint32_t>(segs[hb.seg].k);
+    s.T = 0xffffffffu;
+    s.mode = kModeFull;
+    s.l1_bits = kBits1;
+    select_one_supertile(mem, grad, lr, hb, s.k_rem, s, states, preds + static_cast<size_t>(hb.seg) * kPredWords, lead_mine,
+                         wt_cnt, sel_mask, eq_mask, st_sum, lh, tot_s, res, above);
 }
 
 // What the level-1 pass writes when it also has to collect (see k_level).

@@ -18,13 +18,21 @@ from paper_2104_11125_amd import binding
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("chunk", [None, 100])
-def test_graph_replay_of_single_steps(chunk):
+@pytest.mark.parametrize("chunk,layered", [(None, False), (100, False), (None, True)])
+def test_graph_replay_of_single_steps(chunk, layered):
+    """layered: per-tensor index sets, with tensors of one supertile among them (their search runs
+    on the context's second stream, which the capture has to follow)."""
     import gpu_util as gu
 
     dev = gu.DEV
     rng = np.random.default_rng(31)
     n, numel, k, beta, lr = 3, 300_007, 3_000, 0.3, 1.0
+    sizes = [5_000, 300, 120_000, 8_192, 70_000, 64, 96_451]
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    ks = [-(-sz // 100) for sz in sizes]
+    assert offsets[-1] == numel
+    if layered:
+        k = sum(ks)
     n_out = k if chunk is None else -(-numel // chunk)
     side = torch.cuda.Stream(device=dev)
     shared = rng.standard_normal(numel)
@@ -33,7 +41,7 @@ def test_graph_replay_of_single_steps(chunk):
         return [((shared + 0.5 * rng.standard_normal(numel)) * 1e-3).astype(np.float32) for _ in range(n)]
 
     with torch.cuda.stream(side):
-        ctx = binding.scalecom_init(numel, n, torch.float32, 1, dev, stream=side, k_max=n_out)
+        ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes) if layered else 1, dev, stream=side, k_max=n_out)
         mem = [torch.zeros(numel, device=dev) for _ in range(n)]
         grads = [torch.zeros(numel, device=dev) for _ in range(n)]
         idx = torch.zeros(n_out, dtype=torch.int32, device=dev)
@@ -41,14 +49,18 @@ def test_graph_replay_of_single_steps(chunk):
     ref = [np.zeros(numel, np.float32) for _ in range(n)]
 
     def enqueue(step):
-        if chunk is None:
+        if layered:
+            ctx.scalecom_step_layers(mem, grads, offsets, ks, beta, lr, step, idx, red)
+        elif chunk is None:
             ctx.scalecom_step(mem, grads, k, beta, lr, step, idx, red)
         else:
             ctx.scalecom_step_chunked(mem, grads, chunk, beta, lr, step, idx, red)
 
     def check(host, step, what):
         side.synchronize()
-        if chunk is None:
+        if layered:
+            want_idx, want_red = oracle.step_layers(ref, host, offsets, ks, beta, lr, step)
+        elif chunk is None:
             want_idx, want_red = oracle.step(ref, host, k, beta, lr, step)
         else:
             want_idx, want_red = oracle.step_chunked(ref, host, chunk, beta, lr, step)
