@@ -448,15 +448,17 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
                                            collect_out, stats);
     mark(2);
     k_tilecount<G><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(memL, gradL, lr, segs, sts, n_st, state, hist2, wt_cnt,
-                                                                   cand, st_cand_cnt, sel_mask, eq_mask, st_sum);
+                                                                   cand, st_cand_cnt, sel_mask, eq_mask, st_sum,
+                                                                   n_tensors == 1, n_st > kManySupertiles);
     if (n_st <= kOwnScanMaxSt) {   // few supertiles: the slot kernel adds up the totals before each block itself
         constexpr int per_block = kSlotsOwnScanBlock / kLanes;
         k_slots<true><<<(n_st + per_block - 1) / per_block, kSlotsOwnScanBlock, 0, s>>>(
-            segs, sts, n_st, state, wt_cnt, st_sum, st_prefix, chunk_tot, sel_mask, eq_mask, tile_slot);
+            segs, sts, n_st, state, wt_cnt, st_sum, st_prefix, chunk_tot, sel_mask, eq_mask, tile_slot, n_tensors == 1);
     } else {
         k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
         k_slots<false><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_sum, st_prefix,
-                                                                       chunk_tot, sel_mask, eq_mask, tile_slot);
+                                                                       chunk_tot, sel_mask, eq_mask, tile_slot,
+                                                                       n_tensors == 1);
     }
     if (clear_after) {
         clear_zone();
@@ -768,11 +770,7 @@ scalecom_status scalecom_init(scalecom_ctx** out, int device, void* hip_stream, 
     if (hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), ctx->pinned_bytes, hipHostMallocDefault) != hipSuccess)
         return bail(SCALECOM_ENOMEM);
     if (hipEventCreateWithFlags(&ctx->upload_done, hipEventDisableTiming) != hipSuccess) return bail(SCALECOM_EHIP);
-#ifdef SCALECOM_EXPERIMENT_NO_SIDE
-    if (false) {
-#else
     if (n_tensors_max > 1) {                // (a whole vector of one supertile is handled in the main chain)
-#endif
         if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess ||
             hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming) != hipSuccess)

@@ -1058,7 +1058,8 @@ __global__ void __launch_bounds__(kBlock)
 k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr, const SegDesc* __restrict__ segs,
             const StDesc* __restrict__ sts, int n_st, SegState* __restrict__ state, const uint32_t* __restrict__ hist2,
             uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ cand, const uint32_t* __restrict__ st_cand_cnt,
-            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum)
+            uint64_t* __restrict__ sel_mask, uint64_t* __restrict__ eq_mask, uint2* __restrict__ st_sum, bool one_seg,
+            bool many)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes), lane = threadIdx.x % kLanes;
     const int st = blockIdx.x * kWaves + wave;
@@ -1068,18 +1069,35 @@ k_tilecount(const float* __restrict__ mem, const G* __restrict__ grad, float lr,
     const size_t tile0 = static_cast<size_t>(st) * kTilesPerSuper;
     // Everything the supertile's number alone addresses is requested before the first dependent load
     // returns: its descriptor, its candidate count, the first 64 slots of its slice (used up to the
-    // count, in candidate mode only; slices are a quarter to a tenth full, and reading all of them
-    // whole would be half a gigabyte at a billion elements) and the tiles' running counts.
+    // count, in candidate mode only) and the tiles' running counts.  With very many supertiles
+    // (`many`, the same for the whole grid) the kernel is bound by its traffic, not by round trips:
+    // slices are a quarter to a tenth full, so the slots are then read up to the count only.
     const uint2* slice = cand + static_cast<size_t>(st) * kCandSlice;
     const StDesc d = sts[st];
     const uint32_t n_listed = st_cand_cnt[st];
-    const uint2 ce_early = slice[lane];
+    uint2 ce_early;
+    if (many)
+        ce_early = static_cast<uint32_t>(lane) < n_listed ? slice[lane] : make_uint2(0u, 0u);
+    else
+        ce_early = slice[lane];
     const uint32_t cnt_pre = lane < kTilesPerSuper ? wt_cnt[tile0 + lane] : 0u;
-    // second round trip: what the segment number addresses
-    const SegState ss = state_at(state, d.seg);
-    const uint32_t* h2 = hist2 + static_cast<size_t>(d.seg) * kBins2;
-    const uint32_t h_lo = h2[lane], h_hi = h2[kLanes + lane];
-    const int st_first = segs[d.seg].st_first;
+    // what the segment number addresses: a second round trip, unless the layout has one segment only
+    // (one_seg, the same for the whole grid): then nothing below waits for the descriptor
+    SegState ss;
+    uint32_t h_lo, h_hi;
+    int st_first;
+    if (one_seg) {
+        ss = state_at(state, 0);
+        h_lo = hist2[lane];
+        h_hi = hist2[kLanes + lane];
+        st_first = 0;
+    } else {
+        ss = state_at(state, d.seg);
+        const uint32_t* h2 = hist2 + static_cast<size_t>(d.seg) * kBins2;
+        h_lo = h2[lane];
+        h_hi = h2[kLanes + lane];
+        st_first = segs[d.seg].st_first;
+    }
     if (ss.l2_done) return;                                 // whole wave: counted by the block that searched it
     uint32_t T = ss.T, q = ss.q;                            // an empty index set keeps T above every key
     if (!ss.done) {                                         // wave-uniform
@@ -1219,7 +1237,7 @@ __global__ void __launch_bounds__(OWN_SCAN ? kSlotsOwnScanBlock : kBlock)
 k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state,
         const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_sum, const uint2* __restrict__ st_prefix,
         const uint2* __restrict__ chunk_tot, uint64_t* __restrict__ sel_mask, const uint64_t* __restrict__ eq_mask,
-        uint32_t* __restrict__ tile_slot)
+        uint32_t* __restrict__ tile_slot, bool one_seg)
 {
     constexpr int kThreads = OWN_SCAN ? kSlotsOwnScanBlock : kBlock;
     constexpr int kWavesHere = kThreads / kLanes;
@@ -1235,9 +1253,17 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
     const StDesc d = sts[st_c];
     const size_t tile = static_cast<size_t>(st_c) * kTilesPerSuper + lane;  // lanes 0..31 own one tile each
     const uint32_t packed = lane < kTilesPerSuper ? wt_cnt[tile] : 0u;
-    const int seg0 = OWN_SCAN ? sts[st0].seg : 0;
-    const SegDesc sd = segs[d.seg];
-    const uint32_t q = state_at(state, d.seg).q;
+    // (with one segment only -- one_seg, the same for the whole grid -- nothing here waits for the descriptor)
+    const int seg0 = (OWN_SCAN && !one_seg) ? sts[st0].seg : 0;
+    SegDesc sd;
+    uint32_t q;
+    if (one_seg) {
+        sd = segs[0];
+        q = state_at(state, 0).q;
+    } else {
+        sd = segs[d.seg];
+        q = state_at(state, d.seg).q;
+    }
     if (OWN_SCAN) {
         // all threads: totals of the supertiles between the start of the first supertile's segment and st0
         __shared__ uint32_t part_x[kWavesHere], part_y[kWavesHere];
@@ -1259,7 +1285,7 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
         }
         __syncthreads();
         if (!live) return;                                  // whole wave
-        if (d.seg == seg0) {                                // wave-uniform
+        if (one_seg || d.seg == seg0) {                     // wave-uniform
             for (int w = 0; w < kWavesHere; ++w) {
                 px += part_x[w];
                 py += part_y[w];
