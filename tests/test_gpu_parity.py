@@ -298,9 +298,15 @@ def test_chunked_selector_per_layer(gu):
     for step, ch in ((8, 1), (9, 400), (10, 7), (11, 3)):
         gu.compare_step(ctx, mem, grad, ref, step, 0.3, 0.7, offsets=offsets, chunks=[ch] * len(sizes),
                         what=f"all chunks {ch}")
+    # chunk sizes far beyond the tensors, beyond 32 bits too: one position per non-empty tensor
+    huge = [2 ** 32, 2 ** 40, 2 ** 62, 2 ** 31, 2 ** 32 + 1, 2 ** 33] * 2
+    gu.compare_step(ctx, mem, grad, ref, 12, 0.3, 0.7, offsets=offsets, chunks=huge, what="huge chunks")
     with pytest.raises(binding.ScaleComError):
         ctx.scalecom_step_layers_chunked(mem, grad, offsets, [0] * len(sizes), 0.3, 0.7, 0)
     ctx.close()
+    flat = binding.scalecom_init(numel, n, torch.float32, 1, gu.DEV)
+    gu.compare_step(flat, mem, grad, ref, 13, 0.3, 0.7, chunk=2 ** 40, what="one huge chunk")
+    flat.close()
 
 
 def test_apply_update_after_a_step(gu):
@@ -801,6 +807,14 @@ def test_argument_errors(gu):
     assert status(lambda: ctx.scalecom_step(odd, odd, 10, 0.5, 0.1, 0)) == E
     assert status(lambda: ctx.scalecom_step_layers(mem, grad, [0, 600, 500], [1, 0], 0.5, 0.1, 0)) == E
     assert status(lambda: ctx.scalecom_step_layers(mem, grad, [0, 10, 20, 30], [1, 1, 1], 0.5, 0.1, 0)) == E
+    # the binding refuses learners whose buffers differ in length, and segments that end beyond them
+    short = [mem[0], mem[1][:numel - 4]]
+    with pytest.raises(ValueError):
+        ctx.scalecom_step(short, grad, 10, 0.5, 0.1, 0)
+    with pytest.raises(ValueError):
+        ctx.scalecom_step(mem, [grad[0], grad[1][:numel - 4]], 10, 0.5, 0.1, 0)
+    with pytest.raises(ValueError):
+        ctx.scalecom_step_layers(mem, grad, [0, 500, numel + 1], [1, 1], 0.5, 0.1, 0)
     torch.cuda.synchronize()
     for m, b in zip(mem, before):
         assert torch.equal(m, b)                                                          # a rejected call changes nothing
