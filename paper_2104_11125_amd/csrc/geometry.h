@@ -22,6 +22,7 @@ constexpr int kUpdateLearnersPerLaunch = 8;      // update: learners streamed si
 constexpr int kChunk = 1024;                     // supertiles per chunk of the prefix scan
 constexpr int kOwnScanMaxSt = 10240;             // up to this many supertiles k_slots scans the supertile totals itself
 constexpr int kManySupertiles = 32768;           // beyond: one wave per supertile means several rounds of waves on the chip
+constexpr int kSlotsBatch = 4;                   // supertiles per wave of the slot kernel then
 constexpr int kSlotsOwnScanBlock = 1024;         // threads of its blocks then (16 waves = 16 supertiles)
 
 constexpr int kBits0 = 12, kBits1 = 12, kBits2 = 7;          // 31-bit key = 12 + 12 + 7

@@ -456,9 +456,13 @@ void launch_select(scalecom_ctx* ctx, const float* memL, const G* gradL, float l
             segs, sts, n_st, state, wt_cnt, st_sum, st_prefix, chunk_tot, sel_mask, eq_mask, tile_slot, n_tensors == 1);
     } else {
         k_scan<<<ctx->n_chunks, kChunk, 0, s>>>(chunks, st_sum, st_prefix, chunk_tot);
-        k_slots<false><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_sum, st_prefix,
-                                                                       chunk_tot, sel_mask, eq_mask, tile_slot,
-                                                                       n_tensors == 1);
+        if (n_st > kManySupertiles)
+            k_slots_many<<<(n_st + kWaves * kSlotsBatch - 1) / (kWaves * kSlotsBatch), kBlock, 0, s>>>(
+                segs, sts, n_st, state, wt_cnt, st_prefix, chunk_tot, sel_mask, eq_mask, tile_slot, n_tensors == 1);
+        else
+            k_slots<false><<<(n_st + kWaves - 1) / kWaves, kBlock, 0, s>>>(segs, sts, n_st, state, wt_cnt, st_sum, st_prefix,
+                                                                           chunk_tot, sel_mask, eq_mask, tile_slot,
+                                                                           n_tensors == 1);
     }
     if (clear_after) {
         clear_zone();

@@ -1224,6 +1224,53 @@ k_scan(const ChunkDesc* __restrict__ chunks, const uint2* __restrict__ st_sum, u
     if (i == 0) chunk_tot[blockIdx.x] = total;
 }
 
+// The end of the slot pass for one supertile, by all 64 lanes of a wave (lanes 0..31 own one wave
+// tile each): `packed` is the tile's counter (members / keys equal to the threshold), px and py the
+// members and ties in the segment's earlier supertiles, q the segment's quota of ties.
+__device__ __forceinline__ void finish_slots(size_t tile, uint32_t packed, uint32_t px, uint32_t py, uint32_t q,
+                                             uint32_t out_base, int lane, uint64_t* __restrict__ sel_mask,
+                                             const uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ tile_slot)
+{
+    uint32_t inc = packed;
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) {
+        const uint32_t a = __shfl_up(inc, off, kLanes);
+        if (lane >= off) inc += a;
+    }
+    const uint32_t excl = inc - packed;                     // halves stay below 8192: no carry
+    const uint32_t gt_before = px + (excl & 0xffffu);
+    const uint32_t eq_before = py + (excl >> 16);
+    if (lane >= kTilesPerSuper) return;
+    tile_slot[tile] = out_base + gt_before + (eq_before < q ? eq_before : q);
+
+    const uint32_t own_eq = packed >> 16;
+    uint32_t take = q > eq_before ? q - eq_before : 0u;     // ties of this tile that are members
+    if (take > own_eq) take = own_eq;
+    if (take == 0) return;
+    uint64_t s4[4], e4[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        s4[c] = sel_mask[tile * 4 + c];
+        e4[c] = eq_mask[tile * 4 + c];
+    }
+    if (take == own_eq) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) s4[c] |= e4[c];
+    } else {                                                // the one tile where the quota runs out
+        for (int l = 0; l < kLanes && take > 0; ++l) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (take > 0 && ((e4[c] >> l) & 1ull)) {
+                    s4[c] |= 1ull << l;
+                    --take;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sel_mask[tile * 4 + c] = s4[c];
+}
+
 // Prefix scan, level 2, one wave per supertile: first output slot of each of its 32 wave tiles
 // = members in the segment's earlier supertiles + earlier tiles of the supertile.  Keys equal to
 // the threshold become members here, in position order, until the segment's quota q is used up
@@ -1308,44 +1355,63 @@ k_slots(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_
         py = wave_sum(cy) + sp.y;
     }
 
-    uint32_t inc = packed;
-#pragma unroll
-    for (int off = 1; off < kLanes; off <<= 1) {
-        const uint32_t a = __shfl_up(inc, off, kLanes);
-        if (lane >= off) inc += a;
-    }
-    const uint32_t excl = inc - packed;                     // halves stay below 8192: no carry
-    const uint32_t gt_before = px + (excl & 0xffffu);
-    const uint32_t eq_before = py + (excl >> 16);
-    if (lane >= kTilesPerSuper) return;
-    tile_slot[tile] = static_cast<uint32_t>(sd.out_base) + gt_before + (eq_before < q ? eq_before : q);
+    finish_slots(tile, packed, px, py, q, static_cast<uint32_t>(sd.out_base), lane, sel_mask, eq_mask, tile_slot);
+}
 
-    const uint32_t own_eq = packed >> 16;
-    uint32_t take = q > eq_before ? q - eq_before : 0u;     // ties of this tile that are members
-    if (take > own_eq) take = own_eq;
-    if (take == 0) return;
-    uint64_t s4[4], e4[4];
+
+// The same pass for very many supertiles (always with k_scan's prefixes): a wave takes kSlotsBatch
+// consecutive supertiles and requests what their numbers address all at once, instead of one wave per
+// supertile in a dozen rounds that each wait for their own round trips.
+__global__ void __launch_bounds__(kBlock)
+k_slots_many(const SegDesc* __restrict__ segs, const StDesc* __restrict__ sts, int n_st, const SegState* __restrict__ state,
+             const uint32_t* __restrict__ wt_cnt, const uint2* __restrict__ st_prefix, const uint2* __restrict__ chunk_tot,
+             uint64_t* __restrict__ sel_mask, const uint64_t* __restrict__ eq_mask, uint32_t* __restrict__ tile_slot,
+             bool one_seg)
+{
+    constexpr int B = kSlotsBatch;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);
+    const int lane = threadIdx.x % kLanes;
+    const int st_begin = (blockIdx.x * kWaves + wave) * B;
+    if (st_begin >= n_st) return;                           // whole wave
+    StDesc d[B];
+    uint32_t packed[B];
+    uint2 sp[B];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        s4[c] = sel_mask[tile * 4 + c];
-        e4[c] = eq_mask[tile * 4 + c];
+    for (int j = 0; j < B; ++j) {
+        const int st_c = st_begin + j < n_st ? st_begin + j : n_st - 1;
+        d[j] = sts[st_c];
+        packed[j] = lane < kTilesPerSuper ? wt_cnt[static_cast<size_t>(st_c) * kTilesPerSuper + lane] : 0u;
+        sp[j] = st_prefix[st_c];
     }
-    if (take == own_eq) {
+    SegDesc sd = segs[0];
+    uint32_t q = state_at(state, 0).q;
+    int cur_seg = 0, cur_chunk = -1;
+    uint32_t cx = 0, cy = 0;                                // totals of the segment's chunks before cur_chunk
 #pragma unroll
-        for (int c = 0; c < 4; ++c) s4[c] |= e4[c];
-    } else {                                                // the one tile where the quota runs out
-        for (int l = 0; l < kLanes && take > 0; ++l) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (take > 0 && ((e4[c] >> l) & 1ull)) {
-                    s4[c] |= 1ull << l;
-                    --take;
-                }
-            }
+    for (int j = 0; j < B; ++j) {
+        const int st = st_begin + j;
+        if (st >= n_st) break;                              // whole wave
+        if (!one_seg && d[j].seg != cur_seg) {              // wave-uniform
+            cur_seg = d[j].seg;
+            sd = segs[cur_seg];
+            q = state_at(state, cur_seg).q;
+            cur_chunk = -1;
         }
+        const int my_chunk = (st - sd.st_first) / kChunk;
+        if (my_chunk != cur_chunk) {                        // wave-uniform: once per wave, as a rule
+            uint32_t ax = 0, ay = 0;
+            for (int c = lane; c < my_chunk; c += kLanes) {
+                const uint2 t = chunk_tot[sd.chunk_first + c];
+                ax += t.x;
+                ay += t.y;
+            }
+            cx = wave_sum(ax);
+            cy = wave_sum(ay);
+            cur_chunk = my_chunk;
+        }
+        finish_slots(static_cast<size_t>(st) * kTilesPerSuper + lane, packed[j], cx + sp[j].x, cy + sp[j].y, q,
+                     static_cast<uint32_t>(sd.out_base), lane, sel_mask, eq_mask, tile_slot);
     }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) sel_mask[tile * 4 + c] = s4[c];
 }
 
 }  // namespace

@@ -125,17 +125,23 @@ def test_hamming_distance_full(gu):
         ctx.close()
 
 
-def test_large_multi_tensor_layout(gu):
+@pytest.mark.parametrize("sizes", [[30_000_001, 1, 55_000_000, 24_999_999, 7],
+                                   [140_000_001, 1, 8_190, 9_000, 100_000_000, 7, 45_000_003]],
+                         ids=["110M", "285M"])
+def test_large_multi_tensor_layout(gu, sizes):
     """More than 12288 supertiles split over several tensors: the two-level prefix scan (per-chunk
     prefixes and chunk totals of several segments) instead of the slot kernel's own scan, and the
-    last threshold search as a kernel of its own, with tensors that start and end inside wave tiles."""
+    last threshold search as a kernel of its own, with tensors that start and end inside wave tiles.
+    The longer layout has more than 32768 supertiles: waves of the slot kernel then take several
+    consecutive supertiles each, here also across tensors of one or two supertiles."""
     n = 2
-    sizes = [30_000_001, 1, 55_000_000, 24_999_999, 7]
     offsets = np.concatenate([[5], 5 + np.cumsum(sizes)]).tolist()
     numel = offsets[-1] + 3
-    ks = [sz // 200 for sz in sizes[:-1]] + [7]
+    ks = [7 if sz == 7 else sz // 200 for sz in sizes]      # (the tensor of 7 elements is sent whole)
     w = workloads.scaled(workloads.by_name("resnet50_sized"), numel, n_learners=n, steps=2)
-    ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes), gu.DEV, k_max=sum(ks))
+    chunks = [200, 1, 400, 200, 1] if len(sizes) == 5 else [200, 1, 400, 3, 200, 1, 100]
+    k_max = max(sum(ks), sum(-(-sz // c) for sz, c in zip(sizes, chunks)))
+    ctx = binding.scalecom_init(numel, n, torch.float32, len(sizes), gu.DEV, k_max=k_max)
     mem = _random_memories(w, gu.DEV, 930)
     ref = [m.cpu().numpy().copy() for m in mem]
     for step in (0, 1):
@@ -144,7 +150,7 @@ def test_large_multi_tensor_layout(gu):
         gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, offsets=offsets, ks=ks, what="large multi-tensor")
     # and the chunk-wise selector on the same layout
     grad = workloads.gradients(w, 2, gu.DEV)
-    gu.compare_step(ctx, mem, grad, ref, 2, w.beta, w.lr, offsets=offsets, chunks=[200, 1, 400, 200, 1],
+    gu.compare_step(ctx, mem, grad, ref, 2, w.beta, w.lr, offsets=offsets, chunks=chunks,
                     what="large multi-tensor chunked")
     ctx.close()
 
