@@ -19,10 +19,11 @@ def _both(gu, ctx, w, mem_s, mem_c, step, what):
     grad = workloads.gradients(w, step, gu.DEV)
     idx_s = torch.full((w.k,), -1, dtype=torch.int32, device=gu.DEV)
     red_s = torch.full((w.k,), float("nan"), dtype=torch.float32, device=gu.DEV)
-    before = torch.cuda.memory_allocated(gu.DEV)
+    # (allocation events, not bytes in use: a garbage collection during the call may free earlier tests' tensors)
+    before = torch.cuda.memory_stats(gu.DEV)["allocation.all.allocated"]
     print(f"[static] {what}: n={w.n_learners} numel={w.numel} k={w.k} step={step}", flush=True)
     binding.scalecom_step_static(mem_s, grad, w.k, w.beta, w.lr, step, idx_s, red_s)
-    assert torch.cuda.memory_allocated(gu.DEV) == before
+    assert torch.cuda.memory_stats(gu.DEV)["allocation.all.allocated"] == before
     idx_c, red_c = ctx.scalecom_step(mem_c, grad, w.k, w.beta, w.lr, step)
     torch.cuda.synchronize()
     gu.assert_same("idx", idx_s.cpu().numpy(), idx_c.cpu().numpy(), None, f"{what} step {step}")
