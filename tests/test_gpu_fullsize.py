@@ -2,7 +2,8 @@
 (same entry points, same buffer shapes, workspace from scalecom_workspace_bytes).
 
 Memories start from a seeded random vector (not zero) so that one checked step exercises the
-whole of Eq. 5; they never come from a previous GPU step.  The ResNet-50-sized and per-layer
+whole of Eq. 5; they never come from a previous GPU step (test_recipe_from_zero_memories runs the
+two mid-sized configurations as their recipes state them instead).  The ResNet-50-sized and per-layer
 workloads are compared element by element with oracle.step / oracle.step_layers.  The two
 largest workloads do not fit the oracle's whole-step call in host memory, so the same oracle
 primitives are applied learner by learner (accumulate -> top-k on the leader -> gather ->
@@ -45,6 +46,13 @@ def test_resnet50_sized_full(gu):
         grad = workloads.gradients(w, step, gu.DEV)
         gu.compare_step(ctx, mem, grad, ref, step, w.beta, w.lr, k=w.k, what=w.name)
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["resnet50_sized", "per_layer"])
+def test_recipe_from_zero_memories(gu, name):
+    """The configuration as its recipe states it: memories start at zero and are carried, the leader
+    cycles, 10 steps (8 x 25.6 M elements) and 5 steps (200 tensors); every output of every step compared."""
+    gu.run_workload(workloads.by_name(name))
 
 
 def test_resnet50_sized_chunked_full(gu):
@@ -123,6 +131,20 @@ def test_hamming_distance_full(gu):
                                 what=name + " after the diagnostic")
             del grad
         ctx.close()
+
+
+@pytest.mark.parametrize("numel", [25_557_032, 110_000_000])
+def test_cosine_distance_full(gu, numel):
+    """The memories' pairwise cosine distance (Sec. 2 footnote) at the sizes of the two whole-vector
+    workloads, against the oracle's binary64 sums."""
+    gen = torch.Generator(device=gu.DEV).manual_seed(77)
+    a = torch.randn(numel, generator=gen, device=gu.DEV, dtype=torch.float32).mul_(2e-4)
+    b = (0.8 * a + 1e-4 * torch.randn(numel, generator=gen, device=gu.DEV, dtype=torch.float32))
+    ctx = binding.scalecom_init(16, 1, torch.float32, 1, gu.DEV)
+    out = ctx.scalecom_cosine_distance(a, b).cpu().numpy()
+    want = oracle.cosine_distance(a.cpu().numpy(), b.cpu().numpy())
+    assert abs(out[0] - want) <= 1e-12 * max(1.0, abs(want)), (numel, out[0], want)
+    ctx.close()
 
 
 @pytest.mark.parametrize("sizes", [[30_000_001, 1, 55_000_000, 24_999_999, 7],
