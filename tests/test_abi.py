@@ -79,6 +79,32 @@ def test_argument_checks_that_need_no_device():
     L.scalecom_destroy(None)
 
 
+def test_static_entry_point_checks_that_need_no_device():
+    """scalecom_step_static refuses what its static workspace cannot hold, and malformed arguments,
+    before it touches a device; the reason is the calling thread's scalecom_last_error(NULL)."""
+    L = binding.lib()
+    fake = (ctypes.c_void_p * 8)(*([256] * 8))               # never dereferenced: every call below fails first
+    vp = lambda x: ctypes.c_void_p(x)
+
+    def call(device=0, n=2, numel=1000, k=10, beta=0.5, lr=0.1, step=0, dtype=0, mem=fake, grad=fake, idx=vp(256), red=vp(256)):
+        return L.scalecom_step_static(device, None, mem, grad, n, numel, k, beta, lr, step, dtype, idx, red)
+
+    cases = [(dict(device=-1), b"device"), (dict(device=64), b"device"), (dict(dtype=7), b"grad_dtype"),
+             (dict(numel=binding.SCALECOM_STATIC_NUMEL_MAX + 1), b"SCALECOM_STATIC_NUMEL_MAX"), (dict(numel=-1), b"numel"),
+             (dict(n=binding.SCALECOM_STATIC_LEARNERS_MAX + 1), b"SCALECOM_STATIC_LEARNERS_MAX"), (dict(n=0), b"n_learners"),
+             (dict(k=1001), b"k must"), (dict(k=-1), b"k must"),
+             (dict(numel=binding.SCALECOM_STATIC_NUMEL_MAX, k=binding.SCALECOM_STATIC_K_MAX + 1), b"SCALECOM_STATIC_K_MAX"),
+             (dict(beta=0.0), b"beta"), (dict(beta=1.5), b"beta"), (dict(beta=float("nan")), b"beta"),
+             (dict(lr=float("inf")), b"lr"), (dict(step=-1), b"step"), (dict(mem=None), b"null"), (dict(grad=None), b"null"),
+             (dict(idx=None), b"null output"), (dict(red=None), b"null output")]
+    for kwargs, word in cases:
+        assert call(**kwargs) == binding.SCALECOM_EINVAL, kwargs
+        assert word in L.scalecom_last_error(None), (kwargs, L.scalecom_last_error(None))
+    assert call(numel=0, k=0) == binding.SCALECOM_OK          # nothing to do, nothing touched
+    assert L.scalecom_last_error(None) == b""
+    assert L.scalecom_selection_stats(None, None, 0) == binding.SCALECOM_EINVAL
+
+
 def test_workloads_match_the_benchmark_table():
     from paper_2104_11125_amd import workloads
     cfg = {w.name: w for w in workloads.configs()}
