@@ -351,6 +351,20 @@ def main():
         ctx.scalecom_stream_copy(dst, src)
     torch.cuda.synchronize()
     copy_gbps = 10 * 2 * (1 << 30) / (time.perf_counter() - c0) / 1e9
+    # what one more dependent launch costs the stream when nothing watches it: the 1 GiB copy followed by 0 or 16
+    # copies of 16 bytes (the same kernel with one block), 20 times each way.  A kernel trace of this very command
+    # shows the 16-byte copies at about 4.5 us each: the profiler's own share of every dispatch.
+    def copies_with_small(n_small):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            ctx.scalecom_stream_copy(dst, src)
+            for _ in range(n_small):
+                ctx.scalecom_stream_copy(dst[:16], src[:16])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / 20
+    copies_with_small(16)
+    launch_us = (copies_with_small(16) - copies_with_small(0)) / 16 * 1e6
     del src, dst
     ctx.close()
     torch.cuda.empty_cache()
@@ -401,6 +415,7 @@ def main():
             "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
             "copy_kernel_GBps": copy_gbps,
             "frac_of_copy_kernel": step_gbps / copy_gbps,
+            "dependent_launch_us": launch_us,
             # the extra steps after the timed region, each bracketed by HIP events at every phase boundary
             # (the events themselves add a few microseconds per boundary)
             "event_timed_extra_steps_median_ms": sorted(sum(p) for p in phases)[n_ph // 2] if n_ph else None,
