@@ -96,3 +96,51 @@ def test_static_workspace_step_matches_scalecom_step():
     assert L.scalecom_last_error(None) != b""
     torch.cuda.synchronize()
     assert not big[0].any() and not out_i.any()
+
+
+def test_static_workspace_step_replayed_as_graphs():
+    """One of the callers the entry point is for: code under HIP graph capture.  After one eager cycle
+    (the first call on a device looks the array up, the first call with a layout writes its tables) a
+    step per leader is captured and replayed with new gradients; every step is compared with
+    scalecom_step on a copy of the memories."""
+    import gpu_util as gu
+
+    w = workloads.scaled(workloads.by_name("resnet50_sized"), 300_007, n_learners=3, steps=1)
+    n = w.n_learners
+    side = torch.cuda.Stream(device=gu.DEV)
+    ms, mc, ctx = _start(gu, w, 5)
+    grads = [torch.zeros(w.numel, device=gu.DEV) for _ in range(n)]
+    idx_s = torch.full((w.k,), -1, dtype=torch.int32, device=gu.DEV)
+    red_s = torch.full((w.k,), float("nan"), dtype=torch.float32, device=gu.DEV)
+
+    def upload(step):
+        for dst, src in zip(grads, workloads.gradients(w, step, gu.DEV)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    def check(step, what):
+        side.synchronize()
+        idx_c, red_c = ctx.scalecom_step(mc, grads, w.k, w.beta, w.lr, step)
+        torch.cuda.synchronize()
+        gu.assert_same("idx", idx_s.cpu().numpy(), idx_c.cpu().numpy(), None, f"{what} step {step}")
+        gu.assert_same("reduced", red_s.cpu().numpy(), red_c.cpu().numpy(), 1e-5, f"{what} step {step}")
+        for i, (a, b) in enumerate(zip(ms, mc)):
+            gu.assert_same("mem", a.cpu().numpy(), b.cpu().numpy(), 1e-6, f"{what} step {step} learner {i}")
+
+    for step in range(n):
+        upload(step)
+        print(f"[static] eager step {step} before the capture", flush=True)
+        binding.scalecom_step_static(ms, grads, w.k, w.beta, w.lr, step, idx_s, red_s, stream=side)
+        check(step, "eager")
+    graphs = []
+    for leader in range(n):                             # recorded, not run
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            binding.scalecom_step_static(ms, grads, w.k, w.beta, w.lr, n + leader, idx_s, red_s, stream=side)
+        graphs.append(g)
+    for step in range(n, 4 * n):
+        upload(step)                                    # eager work and a synchronisation between replays
+        print(f"[static] replay of leader {step % n}'s graph, step {step}", flush=True)
+        graphs[step % n].replay()
+        check(step, "replay")
+    ctx.close()
