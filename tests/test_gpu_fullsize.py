@@ -9,6 +9,7 @@ largest workloads do not fit the oracle's whole-step call in host memory, so the
 primitives are applied learner by learner (accumulate -> top-k on the leader -> gather ->
 reduce -> memory update): every output element is still compared.
 """
+import os
 import time
 
 import numpy as np
@@ -260,6 +261,50 @@ def _streamed_parity(gu, w, step, seed, chunk=None, second_step=False):
         gu.assert_same("mem", mem[leader].cpu().numpy(), ref_after[leader], 1e-6, f"{w.name} second step, leader")
         print(f"[fullsize] {w.name}: second step checked at {time.time() - t0:.0f}s", flush=True)
     ctx.close()
+
+
+def _streamed_recipe(gu, w):
+    """The workload as its recipe states it (memories from zero and carried, the leader cycling, all of its
+    steps), the oracle's memories kept on the host and its primitives applied learner by learner: index set
+    and reduced values compared at every step, every learner's memory after the last one."""
+    dev = gu.DEV
+    gd = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    ctx = binding.scalecom_init(w.numel, w.n_learners, gd, 1, dev, k_max=w.k)
+    mem = workloads.zero_memories(w, dev)
+    ref = [np.zeros(w.numel, np.float32) for _ in range(w.n_learners)]
+    t0 = time.time()
+    for step in range(w.steps):
+        shared = workloads.shared_component(w, step, dev)
+        grad = [workloads.learner_gradient(w, step, i, dev, shared=shared) for i in range(w.n_learners)]
+        del shared
+        idx, red = ctx.scalecom_step(mem, grad, w.k, w.beta, w.lr, step)
+        torch.cuda.synchronize()
+        leader = step % w.n_learners
+        acc = oracle.accumulate(ref[leader], gu.to_host(grad[leader]), w.lr)
+        want_idx = oracle.topk_select(acc, w.k)
+        del acc
+        gu.assert_same("idx", idx.cpu().numpy(), want_idx, None, f"{w.name} step {step}")
+        vals = []
+        for i in range(w.n_learners):
+            acc = oracle.accumulate(ref[i], gu.to_host(grad[i]), w.lr)
+            vals.append(oracle.gather(acc, want_idx))
+            oracle.memory_update(ref[i], acc, want_idx, w.beta)
+            del acc
+        gu.assert_same("reduced", red.cpu().numpy(), oracle.reduce(vals), 1e-5, f"{w.name} step {step}")
+        del grad, vals
+        print(f"[fullsize] {w.name}: step {step} of its recipe checked at {time.time() - t0:.0f}s", flush=True)
+    for i in range(w.n_learners):
+        gu.assert_same("mem", mem[i].cpu().numpy(), ref[i], 1e-6, f"{w.name} after {w.steps} steps, learner {i}")
+    ctx.close()
+
+
+@pytest.mark.skipif(not os.environ.get("SCALECOM_LONG_TESTS"), reason="minutes of oracle time; set SCALECOM_LONG_TESTS=1")
+@pytest.mark.parametrize("name", ["transformer_base_sized", "large_bf16"])
+def test_recipe_from_zero_memories_streamed(gu, name):
+    """The two largest configurations as their recipes state them: 10 steps of 16 x 110 M elements, 3 steps of
+    8 x 10^9 with bfloat16 gradients.  Not part of the default run (the tests above check two steps of each from
+    random memories, every output element as well)."""
+    _streamed_recipe(gu, workloads.by_name(name))
 
 
 def test_transformer_base_sized_full(gu):
