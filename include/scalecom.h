@@ -34,10 +34,13 @@
  *    the time a step takes, never its result.
  *  - All work is enqueued on the HIP stream given to scalecom_init; calls do not wait for
  *    the GPU.  Outputs are valid once that stream has reached the end of the call's work.
- *    A context must not be used from two threads at once.
+ *    A context created with n_tensors_max > 1 also owns a second stream: inside a step one
+ *    kernel is forked onto it and joined again with two events, so it never runs ahead of or
+ *    behind the context's stream.  A context must not be used from two threads at once.
  *  - HIP graphs: once a layout (numel or offsets, k or ks or chunk sizes) has been used in one
- *    call, further steps with it enqueue kernels only (no copies, memsets, events or waits;
- *    scalecom_timing_begin must not be in effect), so they can be captured on the context's
+ *    call, further steps with it enqueue kernels only (no copies or memsets, and no events or
+ *    waits besides that fork and join, which a stream capture follows; scalecom_timing_begin
+ *    must not be in effect), so they can be captured on the context's
  *    stream.  One thing is decided on the host when a step is enqueued and is therefore frozen
  *    in a graph: the leader (step mod n_learners).  A graph of one step may be replayed for every
  *    step with that leader; a graph of n_learners consecutive steps for every such cycle.
